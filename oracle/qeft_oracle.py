@@ -1,0 +1,236 @@
+"""CPU oracle for QEFT's mixed-precision linear layer.  TEST INFRASTRUCTURE ONLY.
+
+This file is the slow, plain definition that the HIP library is checked against.
+Only the test-suite, the smoke check and the benchmark's CPU-baseline leg may
+import it; the product path never does, and it shares no code with the HIP path.
+
+What it computes (paper sections in brackets):
+
+* The stored form of one linear layer has three parts [Sec. 3.1]: a dense
+  low-bit code matrix over the IC-k non-weak input channels, one (scale,
+  zero-point) pair per group of g adjacent non-weak channels of a row, and the
+  k weak input channels kept as an FP16 block.  After the offline global
+  reordering the weak channels are contiguous [Sec. 3.2]; here they are the last
+  k input channels.
+* Forward [Sec. 3.2.1]: dequantize the codes, multiply with the activations,
+  then add the product of the FP16 weak block with its activations:
+      Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . W_weak^T
+* Backward [Sec. 3.3, Eq. 5]: dX = dY . W through the full mixed weight, and a
+  weight gradient for the weak block only: dW_weak = dY^T . X[:, Kq:].
+* Quantizer: the paper's data-free fallback, min-max round-to-nearest per group
+  [Sec. 6.1 (70B setting), App. C "Comparison of Quantization Methods",
+  App. C "Quantization Cost"].
+
+Arithmetic: everything that is a real number is float64 here (dequantized
+weights s*(q-z) are exact in float64, sums carry ~1e-16 relative error).  The
+one exception is the quantizer: its decisions (scale, zero-point, code) are
+integers taken from floating point, so they are taken in IEEE float32, the
+precision the kernel uses, with round-half-to-even.
+
+Parity status: every function below is pinned by tests/test_oracle_*.py against
+something other than itself (hand-written bit patterns, closed forms from the
+paper's tables, exact-rational brute force, reductions to a library GEMM,
+adjoint identities, known-answer quantization grids).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "layout", "pack_codes", "unpack_codes", "quantize_rtn", "dequantize",
+    "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
+    "fwd_samples", "bwd_dx_samples", "weak_grad_samples",
+]
+
+
+# --------------------------------------------------------------------------- layout
+def layout(out_features: int, in_features: int, n_weak: int, bits: int, group_size: int) -> dict:
+    """Sizes of the three stored components [Sec. 3.1].
+
+    Kq = IC - k columns are quantized.  Groups of g adjacent quantized columns
+    tile [0, Kq); the last one may be partial.  Codes are bit-packed into 32-bit
+    words, 8 four-bit or 10 three-bit codes per word (two top bits unused), and
+    each row is padded with zero words to a multiple of 4 words.
+    """
+    if bits not in (3, 4):
+        raise ValueError("bits must be 3 or 4")
+    oc, ic, k, g = int(out_features), int(in_features), int(n_weak), int(group_size)
+    if oc <= 0 or ic <= 0 or g <= 0 or not (0 <= k <= ic):
+        raise ValueError("bad shape")
+    per = 8 if bits == 4 else 10
+    kq = ic - k
+    n_groups = -(-kq // g)
+    words = -(-kq // per)
+    stride = -(-words // 4) * 4
+    return {
+        "kq": kq, "n_groups": n_groups, "codes_per_word": per,
+        "words_per_row": words, "row_stride_words": stride,
+        "qweight_bytes": oc * stride * 4,
+        "scales_bytes": oc * n_groups * 2,
+        "zeros_bytes": oc * n_groups * 2,
+        "weak_bytes": oc * k * 2,
+    }
+
+
+# --------------------------------------------------------------------------- bit packing
+def pack_codes(codes: np.ndarray, bits: int, row_stride_words: int) -> np.ndarray:
+    """codes uint8 [OC][Kq] -> uint32 [OC][row_stride_words].
+
+    Code number i of a word sits at bit position bits*i (lowest code first);
+    column j of a row is code j % per of word j // per.
+    """
+    per = 8 if bits == 4 else 10
+    codes = np.asarray(codes, dtype=np.uint8)
+    oc, kq = codes.shape
+    if kq and int(codes.max()) >= (1 << bits):
+        raise ValueError("code out of range")
+    out = np.zeros((oc, row_stride_words), dtype=np.uint32)
+    for j in range(kq):
+        out[:, j // per] |= codes[:, j].astype(np.uint32) << np.uint32(bits * (j % per))
+    return out
+
+
+def unpack_codes(qweight: np.ndarray, kq: int, bits: int) -> np.ndarray:
+    """Inverse of pack_codes: uint32 [OC][stride] -> uint8 [OC][Kq]."""
+    per = 8 if bits == 4 else 10
+    qweight = np.asarray(qweight, dtype=np.uint32)
+    oc = qweight.shape[0]
+    mask = np.uint32((1 << bits) - 1)
+    out = np.zeros((oc, kq), dtype=np.uint8)
+    for j in range(kq):
+        out[:, j] = ((qweight[:, j // per] >> np.uint32(bits * (j % per))) & mask).astype(np.uint8)
+    return out
+
+
+# --------------------------------------------------------------------------- quantizer
+def quantize_rtn(w: np.ndarray, n_weak: int, bits: int, group_size: int):
+    """Min-max round-to-nearest group quantization of the non-weak columns.
+
+    w: float16 [OC][IC].  Returns (codes uint8 [OC][Kq], scales f16 [OC][G],
+    zeros f16 [OC][G], weak f16 [OC][k]).
+
+    Per row and per group J of g adjacent quantized columns, all in float32:
+        lo = min(0, min_J w)    hi = max(0, max_J w)        (range contains 0)
+        s  = fp16((hi - lo) / qmax);   s = 1, z = 0 when hi == lo;
+             the smallest positive fp16 if the rounding gave 0
+        z  = clip(rint(-lo / s), 0, qmax)                   (an integer)
+        q  = clip(rint(w / s) + z, 0, qmax)
+    with rint = round-half-to-even and qmax = 2^bits - 1, so that the stored
+    weight is s * (q - z).
+    """
+    w = np.asarray(w)
+    assert w.dtype == np.float16 and w.ndim == 2
+    oc, ic = w.shape
+    k, g = int(n_weak), int(group_size)
+    kq = ic - k
+    n_groups = -(-kq // g)
+    qmax = np.float32((1 << bits) - 1)
+    wf = w[:, :kq].astype(np.float32)
+    codes = np.zeros((oc, kq), dtype=np.uint8)
+    scales = np.zeros((oc, n_groups), dtype=np.float16)
+    zeros = np.zeros((oc, n_groups), dtype=np.float16)
+    tiny = np.float16(2.0 ** -24)
+    for gi in range(n_groups):
+        blk = wf[:, gi * g:min((gi + 1) * g, kq)]
+        lo = np.minimum(np.float32(0), blk.min(axis=1)).astype(np.float32)
+        hi = np.maximum(np.float32(0), blk.max(axis=1)).astype(np.float32)
+        s32 = ((hi - lo) / qmax).astype(np.float32)
+        flat = s32 == 0
+        s16 = s32.astype(np.float16)
+        s16 = np.where((s16 == 0) & ~flat, tiny, s16)
+        s16 = np.where(flat, np.float16(1.0), s16).astype(np.float16)
+        s = s16.astype(np.float32)
+        z = np.clip(np.rint((-lo / s).astype(np.float32)), np.float32(0), qmax).astype(np.float32)
+        z = np.where(flat, np.float32(0), z).astype(np.float32)
+        q = np.rint((blk / s[:, None]).astype(np.float32)).astype(np.float32) + z[:, None]
+        q = np.clip(q, np.float32(0), qmax)
+        codes[:, gi * g:gi * g + blk.shape[1]] = q.astype(np.uint8)
+        scales[:, gi] = s16
+        zeros[:, gi] = z.astype(np.float16)
+    weak = np.ascontiguousarray(w[:, kq:])
+    return codes, scales, zeros, weak
+
+
+# --------------------------------------------------------------------------- dequantize
+def dequantize(codes: np.ndarray, scales: np.ndarray, zeros: np.ndarray,
+               weak: np.ndarray, group_size: int) -> np.ndarray:
+    """The full mixed weight W = [ s*(q - z) | W_weak ] as float64 [OC][IC]."""
+    codes = np.asarray(codes, dtype=np.uint8)
+    oc, kq = codes.shape
+    k = weak.shape[1]
+    w = np.empty((oc, kq + k), dtype=np.float64)
+    s = np.asarray(scales).astype(np.float64)
+    z = np.asarray(zeros).astype(np.float64)
+    for j in range(kq):
+        gi = j // group_size
+        w[:, j] = s[:, gi] * (codes[:, j].astype(np.float64) - z[:, gi])
+    w[:, kq:] = np.asarray(weak).astype(np.float64)
+    return w
+
+
+# --------------------------------------------------------------------------- the three products
+def linear_fwd(w: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """Y = X . W^T  [Sec. 3.2.1].  w float64 [OC][IC], x [M][IC] -> float64 [M][OC]."""
+    return np.asarray(x).astype(np.float64) @ w.T
+
+
+def linear_bwd_dx(w: np.ndarray, dy: np.ndarray) -> np.ndarray:
+    """dX = dY . W through the full mixed weight [Sec. 3.3].  dy [M][OC] -> [M][IC]."""
+    return np.asarray(dy).astype(np.float64) @ w
+
+
+def weak_grad(dy: np.ndarray, x_weak: np.ndarray) -> np.ndarray:
+    """dW_weak = dY^T . X[:, weak]  [Sec. 3.3, Eq. 5].  -> float64 [OC][k]."""
+    return np.asarray(dy).astype(np.float64).T @ np.asarray(x_weak).astype(np.float64)
+
+
+def round_fp16(a: np.ndarray) -> np.ndarray:
+    """Round-to-nearest-even to float16 (the dtype of Y, dX and optionally dW)."""
+    return np.asarray(a, dtype=np.float64).astype(np.float16)
+
+
+# --------------------------------------------------------------------------- sampled outputs
+# At full benchmark sizes the whole product is too slow for a test; these compute
+# single outputs one by one from the packed arrays: unpack the row (or column),
+# dequantize it, take the dot product.
+def _row(qweight, scales, zeros, weak, o, kq, bits, group_size):
+    codes = unpack_codes(qweight[o:o + 1], kq, bits)
+    return dequantize(codes, scales[o:o + 1], zeros[o:o + 1], weak[o:o + 1], group_size)[0]
+
+
+def fwd_samples(qweight, scales, zeros, weak, kq, bits, group_size, x, pairs):
+    """Y[m, o] for each (m, o) in pairs."""
+    out = np.empty(len(pairs), dtype=np.float64)
+    rows = {}
+    for i, (m, o) in enumerate(pairs):
+        if o not in rows:
+            rows[o] = _row(qweight, scales, zeros, weak, o, kq, bits, group_size)
+        out[i] = np.dot(np.asarray(x[m]).astype(np.float64), rows[o])
+    return out
+
+
+def bwd_dx_samples(qweight, scales, zeros, weak, kq, bits, group_size, dy, pairs):
+    """dX[m, c] for each (m, c) in pairs."""
+    per = 8 if bits == 4 else 10
+    mask = (1 << bits) - 1
+    out = np.empty(len(pairs), dtype=np.float64)
+    cols = {}
+    for i, (m, c) in enumerate(pairs):
+        if c not in cols:
+            if c < kq:
+                q = (np.asarray(qweight[:, c // per]).astype(np.uint32) >> np.uint32(bits * (c % per))) & np.uint32(mask)
+                gi = c // group_size
+                cols[c] = np.asarray(scales[:, gi]).astype(np.float64) * (
+                    q.astype(np.float64) - np.asarray(zeros[:, gi]).astype(np.float64))
+            else:
+                cols[c] = np.asarray(weak[:, c - kq]).astype(np.float64)
+        out[i] = np.dot(np.asarray(dy[m]).astype(np.float64), cols[c])
+    return out
+
+
+def weak_grad_samples(dy, x_weak, pairs):
+    """dW_weak[o, c] for each (o, c) in pairs."""
+    out = np.empty(len(pairs), dtype=np.float64)
+    for i, (o, c) in enumerate(pairs):
+        out[i] = np.dot(np.asarray(dy[:, o]).astype(np.float64), np.asarray(x_weak[:, c]).astype(np.float64))
+    return out
