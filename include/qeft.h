@@ -1,0 +1,143 @@
+/*
+ * qeft.h - C ABI of the MI355X (gfx950) library for QEFT's fused mixed-precision
+ * linear layer (arxiv 2410.08661).
+ *
+ * One linear layer with OC output and IC input channels is stored as three
+ * components (paper Sec. 3.1): a dense low-bit code matrix over the Kq = IC - k
+ * non-weak input channels, one fp16 (scale, zero-point) pair per group of g
+ * adjacent non-weak channels of a row, and the k "weak" input channels kept in
+ * fp16.  After the offline global reordering (Sec. 3.2) the weak channels are
+ * contiguous; in this library they are the LAST k input channels, so that
+ *
+ *     W[o][j]      = scale[o][j/g] * (code[o][j] - zero[o][j/g])     j <  Kq
+ *     W[o][Kq + c] = weak[o][c]                                      c <  k
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers owned by the caller; the library
+ *     allocates nothing, keeps no state and never synchronises.  Work is enqueued
+ *     on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *     ordered only by that stream.
+ *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
+ *     Activations and gradients are fp16; accumulation is fp32.
+ *   - Return value: QEFT_OK or a negative qeft_status.  All argument checks run
+ *     before anything is launched, so a failing call has no effect.  M == 0 is a
+ *     valid no-op.  k == 0 (nothing weak) and k == IC (nothing quantized) are valid.
+ */
+#ifndef QEFT_H
+#define QEFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QEFT_OK = 0,
+    QEFT_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+    QEFT_ERR_SHAPE = -2,       /* OC, IC, g <= 0; k outside [0, IC]; M < 0; ld < row width      */
+    QEFT_ERR_BITS = -3,        /* bits is not 3 or 4                                           */
+    QEFT_ERR_ALIGN = -4,       /* pointer not 16-byte aligned, or ld not a multiple of 8       */
+    QEFT_ERR_WORKSPACE = -5,   /* workspace missing or smaller than qeft_workspace_bytes()     */
+    QEFT_ERR_UNSUPPORTED = -6, /* unknown layout / dtype / op, or a combination not implemented */
+    QEFT_ERR_HIP = -7          /* the HIP runtime reported an error at launch                  */
+} qeft_status;
+
+/* Description of one layer (plain data, passed by pointer, host memory). */
+typedef struct {
+    int32_t out_features; /* OC                                                     */
+    int32_t in_features;  /* IC, in reordered channel order (weak channels last)    */
+    int32_t n_weak;       /* k, number of fp16 weak input channels, 0 <= k <= IC    */
+    int32_t bits;         /* 4 or 3                                                 */
+    int32_t group_size;   /* g, quantized columns sharing one (scale, zero) pair    */
+    int32_t layout;       /* 0 = canonical (the only layout defined so far)         */
+} qeft_desc_t;
+
+/* Sizes derived from a description (host memory). */
+typedef struct {
+    int64_t kq;               /* IC - k                                              */
+    int64_t n_groups;         /* G = ceil(Kq / g)                                    */
+    int64_t words_per_row;    /* ceil(Kq / 8) for 4-bit, ceil(Kq / 10) for 3-bit     */
+    int64_t row_stride_words; /* words_per_row rounded up to a multiple of 4         */
+    size_t qweight_bytes;     /* OC * row_stride_words * 4                           */
+    size_t scales_bytes;      /* OC * G * 2                                          */
+    size_t zeros_bytes;       /* OC * G * 2                                          */
+    size_t weak_bytes;        /* OC * k * 2                                          */
+} qeft_layout_t;
+
+/* The stored layer: four device pointers, borrowed for the duration of a call.
+ *   qweight uint32 [OC][row_stride_words]  code i of a word at bits [b*i, b*i+b), lowest
+ *                                          column first; 8 codes per word for 4-bit,
+ *                                          10 for 3-bit (bits 30..31 zero); row padding
+ *                                          words are zero.
+ *   scales  fp16   [OC][G]
+ *   zeros   fp16   [OC][G]                 any fp16 value; qeft_pack writes integers
+ *   weak    fp16   [OC][k]                 the trainable block; the caller's optimizer
+ *                                          may update it between calls.
+ * A pointer may be NULL only when its component is empty (Kq == 0 or k == 0). */
+typedef struct {
+    void* qweight;
+    void* scales;
+    void* zeros;
+    void* weak;
+} qeft_weight_t;
+
+enum { QEFT_OP_FWD = 0, QEFT_OP_BWD_DX = 1, QEFT_OP_WEAK_GRAD = 2 };
+enum { QEFT_DTYPE_F16 = 0, QEFT_DTYPE_F32 = 1 };
+
+/* Component sizes of the stored form (Sec. 3.1).  Host only, pure. */
+int qeft_layout(const qeft_desc_t* desc, qeft_layout_t* out);
+
+/* Offline conversion of an fp16 weight into the stored form (Sec. 3.1; the data-free
+ * quantizer is the paper's min-max round-to-nearest group quantization, Sec. 6.1 and
+ * App. C).  W is fp16 [OC][ldw] on the device, columns already in reordered order.
+ * Per row and group, in fp32: lo = min(0, min w), hi = max(0, max w),
+ * s = fp16((hi - lo) / qmax) (1 if the group is all zero), z = clip(rint(-lo / s)),
+ * code = clip(rint(w / s) + z), round-half-to-even.  The last k columns are copied to
+ * out->weak.  Writes every byte of the four output buffers, padding included. */
+int qeft_pack(const qeft_desc_t* desc, const void* W, int64_t ldw,
+              const qeft_weight_t* out, void* stream);
+
+/* Build the stored form from already chosen codes (uint8 [OC][Kq], device) and
+ * parameters: bit-packs the codes and copies scales / zeros / weak.  For quantizers
+ * other than the built-in one (the paper's grid search + OPTQ, Sec. 3.1). */
+int qeft_pack_codes(const qeft_desc_t* desc, const uint8_t* codes, const void* scales,
+                    const void* zeros, const void* weak, const qeft_weight_t* out, void* stream);
+
+/* Inverse of qeft_pack_codes: codes uint8 [OC][Kq], scales/zeros fp16 [OC][G], weak fp16
+ * [OC][k], all device buffers of the caller.  Any output pointer may be NULL to skip it. */
+int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
+                void* scales, void* zeros, void* weak, void* stream);
+
+/* Bytes of device workspace an operation needs for M rows (0 if none). */
+size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
+
+/* Forward of the fused layer (Sec. 3.2.1): Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . weak^T in
+ * one pass.  X fp16 [M][ldx] (ldx >= IC), Y fp16 [M][ldy] (ldy >= OC).  Small M runs a
+ * bandwidth-bound matrix-vector kernel, large M a tiled MFMA GEMM. */
+int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* X, int64_t M,
+                    int64_t ldx, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream);
+
+/* Input gradient through the full mixed weight (Sec. 3.3): dX = dY . W, i.e.
+ * dX[:, :Kq] = dY . dq(Q) and dX[:, Kq:] = dY . weak (the weak block's current values).
+ * dY fp16 [M][lddy] (lddy >= OC), dX fp16 [M][lddx] (lddx >= IC). */
+int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M,
+                       int64_t lddy, void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* stream);
+
+/* Weight gradient of the weak block only (Sec. 3.3, Eq. 5): dW[o][c] = sum_m dY[m][o] * Xw[m][c].
+ * Xw fp16 [M][ldxw] holds the k weak activations of each token: either a view into X
+ * (pointer X + Kq, ldxw = ldx) or the compact copy saved for backward (ldxw = k).
+ * dW is [OC][k], fp16 or fp32 by out_dtype; accumulate != 0 adds to dW instead of
+ * overwriting it (gradient accumulation, Tab. 4).  Needs a workspace. */
+int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy,
+                   const void* Xw, int64_t ldxw, void* dW, int out_dtype, int accumulate,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/* Static, never NULL. */
+const char* qeft_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QEFT_H */

@@ -113,7 +113,7 @@ def quantize_rtn(w: np.ndarray, n_weak: int, bits: int, group_size: int):
         lo = min(0, min_J w)    hi = max(0, max_J w)        (range contains 0)
         s  = fp16((hi - lo) / qmax);   s = 1, z = 0 when hi == lo;
              the smallest positive fp16 if the rounding gave 0
-        z  = clip(rint(-lo / s), 0, qmax)                   (an integer)
+        z  = clip(rint((0 - lo) / s), 0, qmax)              (an integer, never -0)
         q  = clip(rint(w / s) + z, 0, qmax)
     with rint = round-half-to-even and qmax = 2^bits - 1, so that the stored
     weight is s * (q - z).
@@ -140,7 +140,7 @@ def quantize_rtn(w: np.ndarray, n_weak: int, bits: int, group_size: int):
         s16 = np.where((s16 == 0) & ~flat, tiny, s16)
         s16 = np.where(flat, np.float16(1.0), s16).astype(np.float16)
         s = s16.astype(np.float32)
-        z = np.clip(np.rint((-lo / s).astype(np.float32)), np.float32(0), qmax).astype(np.float32)
+        z = np.clip(np.rint(((np.float32(0) - lo) / s).astype(np.float32)), np.float32(0), qmax).astype(np.float32)
         z = np.where(flat, np.float32(0), z).astype(np.float32)
         q = np.rint((blk / s[:, None]).astype(np.float32)).astype(np.float32) + z[:, None]
         q = np.clip(q, np.float32(0), qmax)

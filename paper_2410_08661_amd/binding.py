@@ -1,0 +1,197 @@
+"""ctypes binding of libqeft.so: the same entry points as include/qeft.h.
+
+Argument marshalling only.  `raw` exposes the C functions as they are (integers for
+pointers), the functions below take torch tensors and pass `data_ptr()` and the current
+HIP stream.  PyTorch is used for device memory and streams, nothing else; there is no
+fallback path: if the library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch  # imported first on purpose: the library must bind to the HIP runtime torch loaded
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqeft.so")
+
+QEFT_OK = 0
+QEFT_ERR_NULL, QEFT_ERR_SHAPE, QEFT_ERR_BITS, QEFT_ERR_ALIGN = -1, -2, -3, -4
+QEFT_ERR_WORKSPACE, QEFT_ERR_UNSUPPORTED, QEFT_ERR_HIP = -5, -6, -7
+QEFT_OP_FWD, QEFT_OP_BWD_DX, QEFT_OP_WEAK_GRAD = 0, 1, 2
+QEFT_DTYPE_F16, QEFT_DTYPE_F32 = 0, 1
+
+
+class qeft_desc_t(C.Structure):
+    _fields_ = [("out_features", C.c_int32), ("in_features", C.c_int32), ("n_weak", C.c_int32),
+                ("bits", C.c_int32), ("group_size", C.c_int32), ("layout", C.c_int32)]
+
+
+class qeft_layout_t(C.Structure):
+    _fields_ = [("kq", C.c_int64), ("n_groups", C.c_int64), ("words_per_row", C.c_int64),
+                ("row_stride_words", C.c_int64), ("qweight_bytes", C.c_size_t), ("scales_bytes", C.c_size_t),
+                ("zeros_bytes", C.c_size_t), ("weak_bytes", C.c_size_t)]
+
+
+class qeft_weight_t(C.Structure):
+    _fields_ = [("qweight", C.c_void_p), ("scales", C.c_void_p), ("zeros", C.c_void_p), ("weak", C.c_void_p)]
+
+
+EXPORTS = {
+    "qeft_layout": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_layout_t)]),
+    "qeft_pack": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.POINTER(qeft_weight_t), C.c_void_p]),
+    "qeft_pack_codes": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.POINTER(qeft_weight_t), C.c_void_p]),
+    "qeft_unpack": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_void_p, C.c_void_p,
+                              C.c_void_p, C.c_void_p]),
+    "qeft_workspace_bytes": (C.c_size_t, [C.POINTER(qeft_desc_t), C.c_int, C.c_int64]),
+    "qeft_linear_fwd": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64, C.c_int64,
+                                  C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_linear_bwd_dx": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64,
+                                     C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                 C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_status_string": (C.c_char_p, [C.c_int]),
+}
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2410_08661_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    for name, (res, args) in EXPORTS.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+raw = _load()
+
+
+class QeftError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {raw.qeft_status_string(status).decode()} ({status})")
+
+
+def _check(status: int, where: str) -> None:
+    if status != QEFT_OK:
+        raise QeftError(status, where)
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def make_desc(out_features, in_features, n_weak, bits=4, group_size=128, layout=0) -> qeft_desc_t:
+    return qeft_desc_t(out_features, in_features, n_weak, bits, group_size, layout)
+
+
+def qeft_layout(desc: qeft_desc_t) -> qeft_layout_t:
+    out = qeft_layout_t()
+    _check(raw.qeft_layout(C.byref(desc), C.byref(out)), "qeft_layout")
+    return out
+
+
+class Weight:
+    """The four device buffers of one stored layer (torch tensors own the memory)."""
+
+    def __init__(self, desc: qeft_desc_t, device="cuda"):
+        lay = qeft_layout(desc)
+        self.desc, self.lay = desc, lay
+        oc = desc.out_features
+        self.qweight = torch.zeros((oc, lay.row_stride_words), dtype=torch.int32, device=device)
+        self.scales = torch.zeros((oc, lay.n_groups), dtype=torch.float16, device=device)
+        self.zeros = torch.zeros((oc, lay.n_groups), dtype=torch.float16, device=device)
+        self.weak = torch.zeros((oc, desc.n_weak), dtype=torch.float16, device=device)
+
+    def c_struct(self) -> qeft_weight_t:
+        lay, d = self.lay, self.desc
+        return qeft_weight_t(self.qweight.data_ptr() if lay.kq else None, self.scales.data_ptr() if lay.kq else None,
+                             self.zeros.data_ptr() if lay.kq else None, self.weak.data_ptr() if d.n_weak else None)
+
+    def nbytes(self) -> int:
+        lay = self.lay
+        return lay.qweight_bytes + lay.scales_bytes + lay.zeros_bytes + lay.weak_bytes
+
+
+def qeft_pack(desc: qeft_desc_t, W: torch.Tensor, out: Weight | None = None) -> Weight:
+    out = out or Weight(desc, W.device)
+    ws = out.c_struct()
+    _check(raw.qeft_pack(C.byref(desc), _ptr(W), W.stride(0), C.byref(ws), _stream()), "qeft_pack")
+    return out
+
+
+def qeft_pack_codes(desc, codes, scales, zeros, weak, out: Weight | None = None) -> Weight:
+    out = out or Weight(desc, weak.device if weak is not None else codes.device)
+    ws = out.c_struct()
+    _check(raw.qeft_pack_codes(C.byref(desc), _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(weak), C.byref(ws),
+                               _stream()), "qeft_pack_codes")
+    return out
+
+
+def qeft_unpack(desc, w: Weight):
+    lay = w.lay
+    dev = w.qweight.device
+    codes = torch.empty((desc.out_features, lay.kq), dtype=torch.uint8, device=dev)
+    scales, zeros, weak = torch.empty_like(w.scales), torch.empty_like(w.zeros), torch.empty_like(w.weak)
+    ws = w.c_struct()
+    _check(raw.qeft_unpack(C.byref(desc), C.byref(ws), _ptr(codes) if lay.kq else None,
+                           _ptr(scales) if lay.kq else None, _ptr(zeros) if lay.kq else None,
+                           _ptr(weak) if desc.n_weak else None, _stream()), "qeft_unpack")
+    return codes, scales, zeros, weak
+
+
+def _empty_rows(m: int, cols: int, dtype, device) -> torch.Tensor:
+    """[m][cols] tensor whose leading dimension is padded to a multiple of 8 elements."""
+    ld = (max(cols, 1) + 7) // 8 * 8
+    return torch.empty((m, ld), dtype=dtype, device=device)[:, :cols]
+
+
+def qeft_workspace_bytes(desc, op: int, M: int) -> int:
+    return int(raw.qeft_workspace_bytes(C.byref(desc), op, M))
+
+
+def _workspace(desc, op, M, device):
+    n = qeft_workspace_bytes(desc, op, M)
+    return (torch.empty(n, dtype=torch.uint8, device=device), n) if n else (None, 0)
+
+
+def qeft_linear_fwd(desc, w: Weight, X: torch.Tensor, Y: torch.Tensor | None = None, ws=None) -> torch.Tensor:
+    M = X.shape[0]
+    if Y is None:
+        Y = _empty_rows(M, desc.out_features, torch.float16, X.device)
+    wst = w.c_struct()
+    _check(raw.qeft_linear_fwd(C.byref(desc), C.byref(wst), _ptr(X), M, X.stride(0) if M else desc.in_features,
+                               _ptr(Y), Y.stride(0) if M else desc.out_features, _ptr(ws),
+                               ws.numel() if ws is not None else 0, _stream()), "qeft_linear_fwd")
+    return Y
+
+
+def qeft_linear_bwd_dx(desc, w: Weight, dY: torch.Tensor, dX: torch.Tensor | None = None, ws=None) -> torch.Tensor:
+    M = dY.shape[0]
+    if dX is None:
+        dX = _empty_rows(M, desc.in_features, torch.float16, dY.device)
+    wst = w.c_struct()
+    _check(raw.qeft_linear_bwd_dx(C.byref(desc), C.byref(wst), _ptr(dY), M, dY.stride(0) if M else desc.out_features,
+                                  _ptr(dX), dX.stride(0) if M else desc.in_features, _ptr(ws),
+                                  ws.numel() if ws is not None else 0, _stream()), "qeft_linear_bwd_dx")
+    return dX
+
+
+def qeft_weak_grad(desc, dY: torch.Tensor, Xw: torch.Tensor, dW: torch.Tensor | None = None, accumulate=False,
+                   out_dtype=torch.float32, ws=None) -> torch.Tensor:
+    M = dY.shape[0]
+    if dW is None:
+        dW = torch.zeros((desc.out_features, desc.n_weak), dtype=out_dtype, device=dY.device)
+    code = {torch.float16: QEFT_DTYPE_F16, torch.float32: QEFT_DTYPE_F32}[dW.dtype]
+    if ws is None:
+        ws, _ = _workspace(desc, QEFT_OP_WEAK_GRAD, M, dY.device)
+    _check(raw.qeft_weak_grad(C.byref(desc), _ptr(dY), M, dY.stride(0) if M else desc.out_features, _ptr(Xw),
+                              Xw.stride(0) if M else max(desc.n_weak, 8), _ptr(dW), code, int(bool(accumulate)),
+                              _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "qeft_weak_grad")
+    return dW

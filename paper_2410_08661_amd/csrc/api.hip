@@ -1,0 +1,203 @@
+// The C ABI (include/qeft.h): argument checks, layout arithmetic and kernel dispatch.
+// Every check runs on the host before anything is launched.
+#include "qeft_internal.h"
+
+using namespace qeft;
+
+namespace {
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+int check_desc(const qeft_desc_t* d) {
+    if (!d) return QEFT_ERR_NULL;
+    if (d->bits != 3 && d->bits != 4) return QEFT_ERR_BITS;
+    if (d->out_features <= 0 || d->in_features <= 0 || d->group_size <= 0 || d->n_weak < 0 ||
+        d->n_weak > d->in_features)
+        return QEFT_ERR_SHAPE;
+    if (d->layout != 0) return QEFT_ERR_UNSUPPORTED;
+    return QEFT_OK;
+}
+
+void fill_layout(const qeft_desc_t* d, qeft_layout_t* o) {
+    const int64_t per = (d->bits == 4) ? 8 : 10;
+    o->kq = (int64_t)d->in_features - d->n_weak;
+    o->n_groups = (o->kq + d->group_size - 1) / d->group_size;
+    o->words_per_row = (o->kq + per - 1) / per;
+    o->row_stride_words = (o->words_per_row + 3) / 4 * 4;
+    o->qweight_bytes = (size_t)d->out_features * (size_t)o->row_stride_words * 4u;
+    o->scales_bytes = (size_t)d->out_features * (size_t)o->n_groups * 2u;
+    o->zeros_bytes = o->scales_bytes;
+    o->weak_bytes = (size_t)d->out_features * (size_t)d->n_weak * 2u;
+}
+
+// Checks the four component pointers and fills the kernel-side description.
+int make_layer(const qeft_desc_t* d, const qeft_weight_t* w, Layer* L) {
+    int st = check_desc(d);
+    if (st != QEFT_OK) return st;
+    if (!w) return QEFT_ERR_NULL;
+    qeft_layout_t lay;
+    fill_layout(d, &lay);
+    if (lay.kq > 0 && (!w->qweight || !w->scales || !w->zeros)) return QEFT_ERR_NULL;
+    if (d->n_weak > 0 && !w->weak) return QEFT_ERR_NULL;
+    if (lay.kq > 0 && (!aligned16(w->qweight) || !aligned16(w->scales) || !aligned16(w->zeros))) return QEFT_ERR_ALIGN;
+    if (d->n_weak > 0 && !aligned16(w->weak)) return QEFT_ERR_ALIGN;
+    L->oc = d->out_features;
+    L->ic = d->in_features;
+    L->k = d->n_weak;
+    L->bits = d->bits;
+    L->g = d->group_size;
+    L->kq = (int)lay.kq;
+    L->ng = (int)lay.n_groups;
+    L->words = (int)lay.words_per_row;
+    L->stride = (int)lay.row_stride_words;
+    L->qweight = (const uint32_t*)w->qweight;
+    L->scales = (const __half*)w->scales;
+    L->zeros = (const __half*)w->zeros;
+    L->weak = (const __half*)w->weak;
+    return QEFT_OK;
+}
+
+int check_matrix(const void* p, int64_t M, int64_t ld, int64_t width) {
+    if (M < 0) return QEFT_ERR_SHAPE;
+    if (M == 0) return QEFT_OK;
+    if (!p) return QEFT_ERR_NULL;
+    if (ld < width) return QEFT_ERR_SHAPE;
+    if (!aligned16(p) || (ld & 7) != 0) return QEFT_ERR_ALIGN;
+    return QEFT_OK;
+}
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? QEFT_OK : QEFT_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+int qeft_layout(const qeft_desc_t* desc, qeft_layout_t* out) {
+    int st = check_desc(desc);
+    if (st != QEFT_OK) return st;
+    if (!out) return QEFT_ERR_NULL;
+    fill_layout(desc, out);
+    return QEFT_OK;
+}
+
+int qeft_pack(const qeft_desc_t* desc, const void* W, int64_t ldw, const qeft_weight_t* out, void* stream) {
+    Layer L;
+    int st = make_layer(desc, out, &L);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(W, L.oc, ldw, L.ic);
+    if (st != QEFT_OK) return st;
+    return hip_status(pack_rtn(L, (const __half*)W, ldw, (uint32_t*)out->qweight, (__half*)out->scales,
+                               (__half*)out->zeros, (__half*)out->weak, (hipStream_t)stream));
+}
+
+int qeft_pack_codes(const qeft_desc_t* desc, const uint8_t* codes, const void* scales, const void* zeros,
+                    const void* weak, const qeft_weight_t* out, void* stream) {
+    Layer L;
+    int st = make_layer(desc, out, &L);
+    if (st != QEFT_OK) return st;
+    if (L.kq > 0 && (!codes || !scales || !zeros)) return QEFT_ERR_NULL;
+    if (L.k > 0 && !weak) return QEFT_ERR_NULL;
+    return hip_status(pack_codes(L, codes, (const __half*)scales, (const __half*)zeros, (const __half*)weak,
+                                 (uint32_t*)out->qweight, (__half*)out->scales, (__half*)out->zeros,
+                                 (__half*)out->weak, (hipStream_t)stream));
+}
+
+int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes, void* scales, void* zeros,
+                void* weak, void* stream) {
+    Layer L;
+    int st = make_layer(desc, w, &L);
+    if (st != QEFT_OK) return st;
+    return hip_status(unpack(L, codes, (__half*)scales, (__half*)zeros, (__half*)weak, (hipStream_t)stream));
+}
+
+size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
+    if (check_desc(desc) != QEFT_OK || M <= 0) return 0;
+    if (op == QEFT_OP_WEAK_GRAD && weak_grad_mfma_supported(desc->out_features, desc->n_weak, M))
+        return weak_grad_mfma_workspace(desc->out_features, desc->n_weak, M);
+    return 0;
+}
+
+int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* X, int64_t M, int64_t ldx,
+                    void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    Layer L;
+    int st = make_layer(desc, w, &L);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(X, M, ldx, L.ic);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(Y, M, ldy, L.oc);
+    if (st != QEFT_OK) return st;
+    if (M == 0) return QEFT_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const __half* x = (const __half*)X;
+    __half* y = (__half*)Y;
+    if (M > 16 && gemm_fwd_supported(L, M)) return hip_status(gemm_fwd(L, x, M, ldx, y, ldy, s));
+    if (gemv_supported(L, M, ldx)) {
+        // the matrix-vector kernel takes up to 16 rows per pass
+        for (int64_t m0 = 0; m0 < M; m0 += 16) {
+            const int64_t mm = (M - m0 < 16) ? (M - m0) : 16;
+            hipError_t e = gemv_fwd(L, x + m0 * ldx, mm, ldx, y + m0 * ldy, ldy, s);
+            if (e != hipSuccess) return QEFT_ERR_HIP;
+        }
+        return QEFT_OK;
+    }
+    return hip_status(fwd_generic(L, x, M, ldx, y, ldy, s));
+}
+
+int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M, int64_t lddy,
+                       void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* stream) {
+    (void)ws;
+    (void)ws_bytes;
+    Layer L;
+    int st = make_layer(desc, w, &L);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(dY, M, lddy, L.oc);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(dX, M, lddx, L.ic);
+    if (st != QEFT_OK) return st;
+    if (M == 0) return QEFT_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (gemm_dx_supported(L, M)) return hip_status(gemm_dx(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+    return hip_status(bwd_dx_generic(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+}
+
+int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy, const void* Xw, int64_t ldxw,
+                   void* dW, int out_dtype, int accumulate, void* ws, size_t ws_bytes, void* stream) {
+    int st = check_desc(desc);
+    if (st != QEFT_OK) return st;
+    if (out_dtype != QEFT_DTYPE_F16 && out_dtype != QEFT_DTYPE_F32) return QEFT_ERR_UNSUPPORTED;
+    const int oc = desc->out_features, k = desc->n_weak;
+    st = check_matrix(dY, M, lddy, oc);
+    if (st != QEFT_OK) return st;
+    if (k == 0 || M == 0) return (M < 0) ? QEFT_ERR_SHAPE : QEFT_OK;
+    st = check_matrix(Xw, M, ldxw, k);
+    if (st != QEFT_OK) return st;
+    if (!dW) return QEFT_ERR_NULL;
+    if (!aligned16(dW)) return QEFT_ERR_ALIGN;
+    hipStream_t s = (hipStream_t)stream;
+    if (weak_grad_mfma_supported(oc, k, M)) {
+        const size_t need = weak_grad_mfma_workspace(oc, k, M);
+        if (need > 0 && (!ws || ws_bytes < need || !aligned16(ws))) return QEFT_ERR_WORKSPACE;
+        return hip_status(weak_grad_mfma(oc, k, (const __half*)dY, M, lddy, (const __half*)Xw, ldxw, dW,
+                                         out_dtype == QEFT_DTYPE_F32, accumulate != 0, ws, s));
+    }
+    return hip_status(weak_grad_generic(oc, k, (const __half*)dY, M, lddy, (const __half*)Xw, ldxw, dW,
+                                        out_dtype == QEFT_DTYPE_F32, accumulate != 0, s));
+}
+
+const char* qeft_status_string(int status) {
+    switch (status) {
+        case QEFT_OK: return "ok";
+        case QEFT_ERR_NULL: return "a required pointer is NULL";
+        case QEFT_ERR_SHAPE: return "invalid shape or leading dimension";
+        case QEFT_ERR_BITS: return "bits must be 3 or 4";
+        case QEFT_ERR_ALIGN: return "pointer not 16-byte aligned or leading dimension not a multiple of 8";
+        case QEFT_ERR_WORKSPACE: return "workspace missing or too small";
+        case QEFT_ERR_UNSUPPORTED: return "unsupported layout, dtype or operation";
+        case QEFT_ERR_HIP: return "HIP runtime error at launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,54 @@
+// Internal declarations shared by the translation units of libqeft (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "qeft.h"
+
+namespace qeft {
+
+// Everything a kernel needs to know about one stored layer (see qeft.h for the format).
+struct Layer {
+    int oc, ic, k, bits, g;
+    int kq;        // ic - k
+    int ng;        // groups per row
+    int words;     // used words per row
+    int stride;    // words per row incl. padding (multiple of 4)
+    const uint32_t* qweight;
+    const __half* scales;
+    const __half* zeros;
+    const __half* weak;
+};
+
+inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// ---- generic kernels: any shape, bits and alignment; plain loops (generic.hip) ------
+hipError_t fwd_generic(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s);
+hipError_t bwd_dx_generic(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s);
+hipError_t weak_grad_generic(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
+                             void* dW, int out_f32, int accumulate, hipStream_t s);
+
+// ---- format conversion (pack.hip) ----------------------------------------------------
+hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,
+                    __half* weak, hipStream_t s);
+hipError_t pack_codes(const Layer& L, const uint8_t* codes, const __half* scales_in, const __half* zeros_in,
+                      const __half* weak_in, uint32_t* qweight, __half* scales, __half* zeros, __half* weak, hipStream_t s);
+hipError_t unpack(const Layer& L, uint8_t* codes, __half* scales, __half* zeros, __half* weak, hipStream_t s);
+
+// ---- decode path: fused dequant matrix-vector product for M <= 16 (gemv.hip) -------------
+bool gemv_supported(const Layer& L, int64_t M, int64_t ldx);
+hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s);
+
+// ---- prefill / fine-tune path: MFMA GEMMs (gemm.hip) ---------------------------------------
+bool gemm_fwd_supported(const Layer& L, int64_t M);
+hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s);
+bool gemm_dx_supported(const Layer& L, int64_t M);
+hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s);
+bool weak_grad_mfma_supported(int oc, int k, int64_t M);
+size_t weak_grad_mfma_workspace(int oc, int k, int64_t M);
+hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
+                          void* dW, int out_f32, int accumulate, void* ws, hipStream_t s);
+
+}  // namespace qeft

@@ -1,0 +1,111 @@
+"""The C-ABI library loads, exports every symbol include/qeft.h declares, and rejects bad
+arguments before touching the GPU (no GPU needed: every call here fails validation or is
+host-only)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from oracle import qeft_oracle as qo
+from paper_2410_08661_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "qeft.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qeft_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = _declared_functions()
+    assert names == sorted(B.EXPORTS), "binding and header disagree"
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    for n in ("qeft_pack", "qeft_linear_fwd", "qeft_linear_bwd_dx", "qeft_weak_grad"):   # the four named calls
+        assert n in names
+
+
+@pytest.mark.parametrize("shape", [(512, 512, 8, 4), (4096, 11008, 128, 4), (5120, 13824, 128, 3), (7, 32, 32, 4), (3, 9, 0, 3)])
+def test_layout_matches_oracle(shape):
+    oc, ic, k, bits = shape
+    lay = B.qeft_layout(B.make_desc(oc, ic, k, bits, 128))
+    ref = qo.layout(oc, ic, k, bits, 128)
+    for f in ("kq", "n_groups", "words_per_row", "row_stride_words", "qweight_bytes", "scales_bytes", "zeros_bytes", "weak_bytes"):
+        assert getattr(lay, f) == ref[f], f
+
+
+def _w(q=0x1000, s=0x2000, z=0x3000, k=0x4000):
+    return B.qeft_weight_t(q, s, z, k)
+
+
+def test_status_strings():
+    for st in range(0, -8, -1):
+        assert B.raw.qeft_status_string(st) not in (None, b"unknown status")
+    assert B.raw.qeft_status_string(-99) == b"unknown status"
+
+
+def test_descriptor_validation():
+    lay = B.qeft_layout_t()
+    assert B.raw.qeft_layout(None, C.byref(lay)) == B.QEFT_ERR_NULL
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 5)), C.byref(lay)) == B.QEFT_ERR_BITS
+    assert B.raw.qeft_layout(C.byref(B.make_desc(0, 8, 0, 4)), C.byref(lay)) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 9, 4)), C.byref(lay)) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, -1, 4)), C.byref(lay)) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4, 0)), C.byref(lay)) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4, 128, 7)), C.byref(lay)) == B.QEFT_ERR_UNSUPPORTED
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4)), None) == B.QEFT_ERR_NULL
+
+
+def test_forward_and_backward_validation():
+    d = B.make_desc(64, 256, 128, 4)
+    w = _w()
+    fwd, dx = B.raw.qeft_linear_fwd, B.raw.qeft_linear_bwd_dx
+    X, Y = 0x10000, 0x20000
+    assert fwd(C.byref(d), None, X, 1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_NULL
+    assert fwd(C.byref(d), C.byref(_w(q=None)), X, 1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_NULL
+    assert fwd(C.byref(d), C.byref(_w(k=None)), X, 1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_NULL
+    assert fwd(C.byref(d), C.byref(_w(s=0x2002)), X, 1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_ALIGN
+    assert fwd(C.byref(d), C.byref(w), None, 1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_NULL
+    assert fwd(C.byref(d), C.byref(w), X, -1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_SHAPE
+    assert fwd(C.byref(d), C.byref(w), X, 1, 248, Y, 64, None, 0, None) == B.QEFT_ERR_SHAPE      # ldx < IC
+    assert fwd(C.byref(d), C.byref(w), X, 1, 260, Y, 64, None, 0, None) == B.QEFT_ERR_ALIGN      # ldx % 8
+    assert fwd(C.byref(d), C.byref(w), X + 2, 1, 256, Y, 64, None, 0, None) == B.QEFT_ERR_ALIGN
+    assert fwd(C.byref(d), C.byref(w), X, 1, 256, Y, 56, None, 0, None) == B.QEFT_ERR_SHAPE      # ldy < OC
+    assert fwd(C.byref(d), C.byref(w), X, 0, 256, Y, 64, None, 0, None) == B.QEFT_OK             # M = 0: no-op
+    assert fwd(C.byref(d), C.byref(w), None, 0, 0, None, 0, None, 0, None) == B.QEFT_OK
+    assert dx(C.byref(d), C.byref(w), X, 2, 56, Y, 256, None, 0, None) == B.QEFT_ERR_SHAPE       # lddy < OC
+    assert dx(C.byref(d), C.byref(w), X, 2, 64, Y, 248, None, 0, None) == B.QEFT_ERR_SHAPE       # lddx < IC
+    assert dx(C.byref(d), C.byref(w), X, 2, 64, None, 256, None, 0, None) == B.QEFT_ERR_NULL
+    assert dx(C.byref(d), C.byref(w), X, 0, 64, Y, 256, None, 0, None) == B.QEFT_OK
+    # all-weak layer: the quantized pointers may be NULL
+    d2 = B.make_desc(64, 128, 128, 4)
+    assert fwd(C.byref(d2), C.byref(_w(q=None, s=None, z=None)), X, 0, 128, Y, 64, None, 0, None) == B.QEFT_OK
+    d3 = B.make_desc(64, 128, 0, 3)
+    assert fwd(C.byref(d3), C.byref(_w(k=None)), X, 0, 128, Y, 64, None, 0, None) == B.QEFT_OK
+
+
+def test_pack_and_weak_grad_validation():
+    d = B.make_desc(64, 256, 128, 4)
+    w = _w()
+    assert B.raw.qeft_pack(C.byref(d), None, 256, C.byref(w), None) == B.QEFT_ERR_NULL
+    assert B.raw.qeft_pack(C.byref(d), 0x10000, 128, C.byref(w), None) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_pack(C.byref(d), 0x10000, 256, None, None) == B.QEFT_ERR_NULL
+    assert B.raw.qeft_pack_codes(C.byref(d), None, 0x100, 0x200, 0x300, C.byref(w), None) == B.QEFT_ERR_NULL
+    wg = B.raw.qeft_weak_grad
+    dY, Xw, dW = 0x10000, 0x20000, 0x30000
+    assert wg(C.byref(d), dY, 4, 64, Xw, 128, dW, 2, 0, None, 0, None) == B.QEFT_ERR_UNSUPPORTED   # dtype
+    assert wg(C.byref(d), None, 4, 64, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert wg(C.byref(d), dY, 4, 64, Xw, 120, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE         # ldxw < k
+    assert wg(C.byref(d), dY, 4, 64, Xw, 128, None, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert wg(C.byref(d), dY, 0, 64, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_OK
+    assert wg(C.byref(d), dY, -3, 64, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE
+    need = B.qeft_workspace_bytes(B.make_desc(4096, 4096, 128, 4), B.QEFT_OP_WEAK_GRAD, 4096)
+    if need:
+        d4 = B.make_desc(4096, 4096, 128, 4)
+        assert wg(C.byref(d4), dY, 4096, 4096, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_WORKSPACE
+        assert wg(C.byref(d4), dY, 4096, 4096, Xw, 128, dW, 1, 0, 0x40000, need - 1, None) == B.QEFT_ERR_WORKSPACE
+    assert B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 0) == 0
