@@ -59,10 +59,11 @@ typedef struct {
     int64_t kq;               /* IC - k                                              */
     int64_t n_groups;         /* G = ceil(Kq / g)                                    */
     int64_t words_per_row;    /* ceil(Kq / 8) for 4-bit, ceil(Kq / 10) for 3-bit     */
-    int64_t row_stride_words; /* words_per_row rounded up to a multiple of 4         */
+    int64_t row_stride_words; /* words_per_row rounded up to a multiple of 16 (64 B) */
+    int64_t group_stride;     /* G rounded up to a multiple of 8: row pitch of scales/zeros */
     size_t qweight_bytes;     /* OC * row_stride_words * 4                           */
-    size_t scales_bytes;      /* OC * G * 2                                          */
-    size_t zeros_bytes;       /* OC * G * 2                                          */
+    size_t scales_bytes;      /* OC * group_stride * 2                               */
+    size_t zeros_bytes;       /* OC * group_stride * 2                               */
     size_t weak_bytes;        /* OC * k * 2                                          */
 } qeft_layout_t;
 
@@ -71,8 +72,8 @@ typedef struct {
  *                                          column first; 8 codes per word for 4-bit,
  *                                          10 for 3-bit (bits 30..31 zero); row padding
  *                                          words are zero.
- *   scales  fp16   [OC][G]
- *   zeros   fp16   [OC][G]                 any fp16 value; qeft_pack writes integers
+ *   scales  fp16   [OC][group_stride]      entries past G are zero
+ *   zeros   fp16   [OC][group_stride]      any fp16 value; qeft_pack writes integers
  *   weak    fp16   [OC][k]                 the trainable block; the caller's optimizer
  *                                          may update it between calls.
  * A pointer may be NULL only when its component is empty (Kq == 0 or k == 0). */
@@ -100,7 +101,8 @@ int qeft_pack(const qeft_desc_t* desc, const void* W, int64_t ldw,
               const qeft_weight_t* out, void* stream);
 
 /* Build the stored form from already chosen codes (uint8 [OC][Kq], device) and
- * parameters: bit-packs the codes and copies scales / zeros / weak.  For quantizers
+ * parameters (scales, zeros fp16 [OC][G] compact; weak fp16 [OC][k]): bit-packs the codes
+ * and copies scales / zeros / weak into the padded stored arrays.  For quantizers
  * other than the built-in one (the paper's grid search + OPTQ, Sec. 3.1). */
 int qeft_pack_codes(const qeft_desc_t* desc, const uint8_t* codes, const void* scales,
                     const void* zeros, const void* weak, const qeft_weight_t* out, void* stream);

@@ -50,7 +50,10 @@ def layout(out_features: int, in_features: int, n_weak: int, bits: int, group_si
     Kq = IC - k columns are quantized.  Groups of g adjacent quantized columns
     tile [0, Kq); the last one may be partial.  Codes are bit-packed into 32-bit
     words, 8 four-bit or 10 three-bit codes per word (two top bits unused), and
-    each row is padded with zero words to a multiple of 4 words.
+    each row is padded with zero words to a multiple of 16 words (64 bytes: the
+    paper does not describe row padding; one 128-column step of 4-bit codes is 64 bytes).
+    Scales and zero-points are stored as [OC][group_stride] with group_stride = G rounded
+    up to a multiple of 8 (16-byte rows), padding zero.
     """
     if bits not in (3, 4):
         raise ValueError("bits must be 3 or 4")
@@ -61,13 +64,14 @@ def layout(out_features: int, in_features: int, n_weak: int, bits: int, group_si
     kq = ic - k
     n_groups = -(-kq // g)
     words = -(-kq // per)
-    stride = -(-words // 4) * 4
+    stride = -(-words // 16) * 16
+    gstride = -(-n_groups // 8) * 8
     return {
         "kq": kq, "n_groups": n_groups, "codes_per_word": per,
-        "words_per_row": words, "row_stride_words": stride,
+        "words_per_row": words, "row_stride_words": stride, "group_stride": gstride,
         "qweight_bytes": oc * stride * 4,
-        "scales_bytes": oc * n_groups * 2,
-        "zeros_bytes": oc * n_groups * 2,
+        "scales_bytes": oc * gstride * 2,
+        "zeros_bytes": oc * gstride * 2,
         "weak_bytes": oc * k * 2,
     }
 

@@ -29,7 +29,8 @@ class qeft_desc_t(C.Structure):
 
 class qeft_layout_t(C.Structure):
     _fields_ = [("kq", C.c_int64), ("n_groups", C.c_int64), ("words_per_row", C.c_int64),
-                ("row_stride_words", C.c_int64), ("qweight_bytes", C.c_size_t), ("scales_bytes", C.c_size_t),
+                ("row_stride_words", C.c_int64), ("group_stride", C.c_int64), ("qweight_bytes", C.c_size_t),
+                ("scales_bytes", C.c_size_t),
                 ("zeros_bytes", C.c_size_t), ("weak_bytes", C.c_size_t)]
 
 
@@ -105,8 +106,8 @@ class Weight:
         self.desc, self.lay = desc, lay
         oc = desc.out_features
         self.qweight = torch.zeros((oc, lay.row_stride_words), dtype=torch.int32, device=device)
-        self.scales = torch.zeros((oc, lay.n_groups), dtype=torch.float16, device=device)
-        self.zeros = torch.zeros((oc, lay.n_groups), dtype=torch.float16, device=device)
+        self.scales = torch.zeros((oc, lay.group_stride), dtype=torch.float16, device=device)
+        self.zeros = torch.zeros((oc, lay.group_stride), dtype=torch.float16, device=device)
         self.weak = torch.zeros((oc, desc.n_weak), dtype=torch.float16, device=device)
 
     def c_struct(self) -> qeft_weight_t:
@@ -138,7 +139,8 @@ def qeft_unpack(desc, w: Weight):
     lay = w.lay
     dev = w.qweight.device
     codes = torch.empty((desc.out_features, lay.kq), dtype=torch.uint8, device=dev)
-    scales, zeros, weak = torch.empty_like(w.scales), torch.empty_like(w.zeros), torch.empty_like(w.weak)
+    scales = torch.empty((desc.out_features, lay.n_groups), dtype=torch.float16, device=dev)
+    zeros, weak = torch.empty_like(scales), torch.empty_like(w.weak)
     ws = w.c_struct()
     _check(raw.qeft_unpack(C.byref(desc), C.byref(ws), _ptr(codes) if lay.kq else None,
                            _ptr(scales) if lay.kq else None, _ptr(zeros) if lay.kq else None,

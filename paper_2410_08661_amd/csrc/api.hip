@@ -23,9 +23,10 @@ void fill_layout(const qeft_desc_t* d, qeft_layout_t* o) {
     o->kq = (int64_t)d->in_features - d->n_weak;
     o->n_groups = (o->kq + d->group_size - 1) / d->group_size;
     o->words_per_row = (o->kq + per - 1) / per;
-    o->row_stride_words = (o->words_per_row + 3) / 4 * 4;
+    o->row_stride_words = (o->words_per_row + 15) / 16 * 16;
     o->qweight_bytes = (size_t)d->out_features * (size_t)o->row_stride_words * 4u;
-    o->scales_bytes = (size_t)d->out_features * (size_t)o->n_groups * 2u;
+    o->group_stride = (o->n_groups + 7) / 8 * 8;
+    o->scales_bytes = (size_t)d->out_features * (size_t)o->group_stride * 2u;
     o->zeros_bytes = o->scales_bytes;
     o->weak_bytes = (size_t)d->out_features * (size_t)d->n_weak * 2u;
 }
@@ -48,6 +49,7 @@ int make_layer(const qeft_desc_t* d, const qeft_weight_t* w, Layer* L) {
     L->g = d->group_size;
     L->kq = (int)lay.kq;
     L->ng = (int)lay.n_groups;
+    L->gs = (int)lay.group_stride;
     L->words = (int)lay.words_per_row;
     L->stride = (int)lay.row_stride_words;
     L->qweight = (const uint32_t*)w->qweight;

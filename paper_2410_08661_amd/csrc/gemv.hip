@@ -7,161 +7,150 @@
 // instruction lane l supplies 8 contraction elements of row/column l % 16 for the slot
 // l / 16, and one packed 32-bit word holds exactly 8 codes: a lane's 128-bit load (4 words
 // = 32 codes) therefore feeds 4 MFMAs with no cross-lane movement, and the 4 slots of a
-// load cover 128 consecutive columns = one quantization group.  Which column a contraction
-// slot stands for is free as long as A and B agree, so the activations are permuted to the
-// order the nibbles come out of the mask-and-or conversion (pairs (0,4) (1,5) (2,6) (3,7)).
+// load cover 128 consecutive columns = one quantization group ("step").  Which column a
+// contraction slot stands for is free as long as A and B agree, so the activations are
+// permuted to the order the nibbles come out of the mask-and-or conversion
+// (pairs (0,4) (1,5) (2,6) (3,7)).
 //
 // Dequantization never touches the weights: the codes enter the MFMA as the exact fp16
-// numbers 1024 + q (exponent bits or-ed onto the nibble), one extra MFMA against a vector of
-// ones gives Sx = sum of the group's activations, and the group's contribution is
-//     s * (sum x*(1024+q) - (1024 + z) * Sx) = s * sum x*(q - z)
+// numbers 1024 + q (exponent bits or-ed onto the nibble) and the group's contribution is
+//     s * (sum x*(1024+q) - (1024 + z) * Sx) = s * sum x*(q - z),   Sx = sum of the group's x,
 // applied to the 16x16 fp32 accumulator: 2 FMAs per 32 weights and lane, any fp16 zero-point.
 // The weak block is a plain fp16 B operand accumulated into the same tile.
-// The K range is split over the waves of a workgroup (step s -> wave s % KS) and reduced
-// through LDS in a fixed order: no atomics, run-to-run deterministic.
+//
+// Work split.  A workgroup owns whole tiles of 16 output channels; KS waves per tile split
+// the K steps into contiguous ranges and are reduced through LDS in a fixed order (no
+// atomics: run-to-run deterministic).  The inner loop issues weight loads 4 steps ahead and
+// is counted exactly by the hardware load counter (no branches, no bounds tests: rows are
+// padded to whole steps and rows past OC are clamped, never stored).
+//   * small-M kernel (M <= 4 and X fits in LDS): the workgroup stages X once (permuted, with
+//     Sx), one barrier; scales / zero-points come straight from memory, 4 steps per 8-byte load;
+//   * chunked kernel (any M <= 16): each wave stages its own slice, CH steps at a time.
+//
+// Every branch around an MFMA is wave-uniform by construction (the wave index goes through
+// readfirstlane): MFMA executes regardless of the EXEC mask.
 #include "qeft_internal.h"
-#include <cstdlib>
 
 namespace qeft {
 namespace {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef float f4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
 __device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
-
 __device__ __forceinline__ u4 load16(const void* p) { return *reinterpret_cast<const u4*>(p); }
+__device__ __forceinline__ u2 load8(const void* p) { return *reinterpret_cast<const u2*>(p); }
+// element i (0..3) of four packed halfs
+__device__ __forceinline__ float half_at(u2 v, int i) { return (float)__builtin_bit_cast(h2, (i < 2) ? v.x : v.y)[i & 1]; }
+
+// The two constants of the code -> fp16 conversion, held in vector registers the compiler
+// cannot see through: (w & mask) | magic then selects the single v_and_or_b32 (with two
+// literals it would be two instructions).  The instruction itself is compiler-generated on
+// purpose: VALU instructions hidden in inline asm escape the MFMA hazard recognizer.
+struct Consts {
+    uint32_t mask, magic;
+};
+__device__ __forceinline__ Consts make_consts() {
+    Consts c{0x000f000fu, 0x64006400u};
+    asm volatile("" : "+v"(c.mask), "+v"(c.magic));
+    return c;
+}
 
 // 8 codes of one word as fp16 (1024 + q), in slot order (0,4)(1,5)(2,6)(3,7)
-__device__ __forceinline__ h8 codes_to_h8(uint32_t w) {
+__device__ __forceinline__ h8 codes_to_h8(uint32_t w, Consts c) {
     u4 r;
-    r.x = (w & 0x000f000fu) | 0x64006400u;
-    r.y = ((w >> 4) & 0x000f000fu) | 0x64006400u;
-    r.z = ((w >> 8) & 0x000f000fu) | 0x64006400u;
-    r.w = ((w >> 12) & 0x000f000fu) | 0x64006400u;
+    r.x = (w & c.mask) | c.magic;
+    r.y = ((w >> 4) & c.mask) | c.magic;
+    r.z = ((w >> 8) & c.mask) | c.magic;
+    r.w = ((w >> 12) & c.mask) | c.magic;
     return as_h8(r);
 }
 
 // 8 consecutive activations (x0..x7 in 4 registers) to the same slot order
-__device__ __forceinline__ h8 permute_x(u4 v) {
+__device__ __forceinline__ u4 permute_x(u4 v) {
     u4 r;
     r.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);  // (x0, x4)
     r.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);  // (x1, x5)
     r.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);  // (x2, x6)
     r.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);  // (x3, x7)
-    return as_h8(r);
+    return r;
 }
 
-constexpr int PF = 4;  // K steps whose loads are issued together
+// x0 + ... + x7 in fp32
+__device__ __forceinline__ float sum8(u4 v) {
+    const h8 h = as_h8(v);
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += (float)h[i];
+    return s;
+}
 
+// sum over each aligned group of 16 lanes
+__device__ __forceinline__ float sum16(float t) {
+    t += __shfl_xor(t, 1, 64);
+    t += __shfl_xor(t, 2, 64);
+    t += __shfl_xor(t, 4, 64);
+    t += __shfl_xor(t, 8, 64);
+    return t;
+}
+
+__device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
+
+// One quantized step of one 16-row tile: 4 MFMAs on the codes, then the group's scale and
+// zero-point on the accumulator.  c = 1024 + z.
+__device__ __forceinline__ void step_tile(f4& y, const u4 (&xa)[4], u4 w, f4 sx, float sf, float c, Consts magic) {
+    f4 acc = f4{0.f, 0.f, 0.f, 0.f};
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[0]), codes_to_h8(w.x, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[1]), codes_to_h8(w.y, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[2]), codes_to_h8(w.z, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[3]), codes_to_h8(w.w, magic), acc, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = fmaf(sf, fmaf(-c, sx[e], acc[e]), y[e]);
+}
+
+// Weak steps of 32 fp16 columns, dealt to the K-split waves from the last one back (they carry
+// fewer quantized steps when the split is uneven).
 template <int R>
-__global__ __launch_bounds__(256) void gemv_w4_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
-                                                      __half* __restrict__ Y, int64_t ldy) {
-    extern __shared__ float red[];  // [KS-1][R][4][64]
-    // The wave index is made provably wave-uniform: every branch on the K step must be a
-    // scalar branch, because MFMA executes whatever the EXEC mask says.
-    const int lane = threadIdx.x & 63, KS = blockDim.x >> 6;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n = lane & 15, kb = lane >> 4;
-    const int row0 = blockIdx.x * (16 * R);
-    const int nq = L.ng;                       // quantized steps: one group of 128 columns each
-    const int nsteps = nq + (L.k + 31) / 32;   // + weak steps of 32 columns each
-
-    const uint32_t* wrow[R];
-    const __half* srow[R];
-    const __half* zrow[R];
-    const __half* krow[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        const int o = min(row0 + 16 * r + n, L.oc - 1);
-        wrow[r] = L.qweight + (size_t)o * L.stride;
-        srow[r] = L.scales + (size_t)o * L.ng;
-        zrow[r] = L.zeros + (size_t)o * L.ng;
-        krow[r] = L.weak + (size_t)o * L.k;
-    }
-    const bool mvalid = n < M;                 // this lane's activation row exists
-    const __half* xrow = X + (size_t)(mvalid ? n : 0) * ldx;
-
-    f4 y[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) y[r] = f4{0.f, 0.f, 0.f, 0.f};
+__device__ __forceinline__ void weak_steps(const Layer& L, const __half* __restrict__ X, int M, int64_t ldx, int row0,
+                                           int kw, int KS, int n, int kb, f4 (&y)[R]) {
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
-    u4 ones4 = u4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-    const h8 ones = as_h8(ones4);
-
-    for (int s0 = wave; s0 < nsteps; s0 += KS * PF) {
-        u4 wq[PF][R];
-        u4 xa[PF][4];
-        float sc[PF][R], zc[PF][R];
-        // ---- issue every load of this chunk ------------------------------------------------
+    const int nweak = (L.k + 31) / 32;
+    for (int t = KS - 1 - kw; t < nweak; t += KS) {
+        const int c0 = 32 * t + 8 * kb;
+        const u4 xa = (n < M && c0 < L.k) ? load16(X + (size_t)n * ldx + L.kq + c0) : zero4;
 #pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int s = s0 + p * KS;
-            if (s < nq) {
-                const int word = 4 * (4 * s + kb);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    wq[p][r] = (word < L.stride) ? load16(wrow[r] + word) : zero4;
-                    sc[p][r] = __half2float(srow[r][s]);
-                    zc[p][r] = __half2float(zrow[r][s]);
-                }
-                const int col = 128 * s + 32 * kb;
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    xa[p][i] = (mvalid && col + 8 * i < L.kq) ? load16(xrow + col + 8 * i) : zero4;
-            } else if (s < nsteps) {
-                const int c0 = 32 * (s - nq) + 8 * kb;
-#pragma unroll
-                for (int r = 0; r < R; ++r) wq[p][r] = (c0 < L.k) ? load16(krow[r] + c0) : zero4;
-                xa[p][0] = (mvalid && c0 < L.k) ? load16(xrow + L.kq + c0) : zero4;
-            }
-        }
-        // ---- consume ----------------------------------------------------------------------
-#pragma unroll
-        for (int p = 0; p < PF; ++p) {
-            const int s = s0 + p * KS;
-            if (s < nq) {
-                h8 a[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) a[i] = permute_x(xa[p][i]);
-                f4 sx = f4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int i = 0; i < 4; ++i) sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[i], ones, sx, 0, 0, 0);
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    f4 acc = f4{0.f, 0.f, 0.f, 0.f};
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[0], codes_to_h8(wq[p][r].x), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[1], codes_to_h8(wq[p][r].y), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[2], codes_to_h8(wq[p][r].z), acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[3], codes_to_h8(wq[p][r].w), acc, 0, 0, 0);
-                    const float c = 1024.f + zc[p][r];
-                    const float sf = sc[p][r];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) y[r][e] = fmaf(sf, fmaf(-c, sx[e], acc[e]), y[r][e]);
-                }
-            } else if (s < nsteps) {
-                const h8 a = as_h8(xa[p][0]);
-#pragma unroll
-                for (int r = 0; r < R; ++r) y[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, as_h8(wq[p][r]), y[r], 0, 0, 0);
-            }
+        for (int r = 0; r < R; ++r) {
+            const int o = min(row0 + 16 * r + n, L.oc - 1);
+            const u4 wk = (c0 < L.k) ? load16(L.weak + (size_t)o * L.k + c0) : zero4;
+            y[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa), as_h8(wk), y[r], 0, 0, 0);
         }
     }
+}
 
-    // ---- reduce the K split: waves 1..KS-1 hand their tiles to wave 0 through LDS ---------------
-    if (wave > 0) {
+// Reduction over the K split and store.  `slot(w)` is a float[R*4*64] buffer of K-split wave w.
+template <int R, class Slot>
+__device__ __forceinline__ void reduce_store(const Layer& L, f4 (&y)[R], int kw, int KS, int lane, int row0, int M,
+                                             __half* __restrict__ Y, int64_t ldy, Slot slot) {
+    const int n = lane & 15, kb = lane >> 4;
+    if (kw > 0) {
+        float* mine = slot(kw);
 #pragma unroll
         for (int r = 0; r < R; ++r)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) red[(((wave - 1) * R + r) * 4 + e) * 64 + lane] = y[r][e];
+            for (int e = 0; e < 4; ++e) mine[(r * 4 + e) * 64 + lane] = y[r][e];
     }
     __syncthreads();
-    if (wave == 0) {
-        for (int w = 1; w < KS; ++w)
+    if (kw == 0) {
+        for (int w = 1; w < KS; ++w) {
+            const float* other = slot(w);
 #pragma unroll
             for (int r = 0; r < R; ++r)
 #pragma unroll
-                for (int e = 0; e < 4; ++e) y[r][e] += red[(((w - 1) * R + r) * 4 + e) * 64 + lane];
+                for (int e = 0; e < 4; ++e) y[r][e] += other[(r * 4 + e) * 64 + lane];
+        }
         // accumulator element e of lane l is row 4*(l/16)+e, column l%16 of the 16x16 tile
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -175,6 +164,289 @@ __global__ __launch_bounds__(256) void gemv_w4_kernel(Layer L, const __half* __r
     }
 }
 
+// =============================================================================================
+// Small-M kernel: M <= 4.  A workgroup owns TW tiles of 16 rows; its TW*KS waves stage all of X
+// once (one barrier), then wave (t, kw) streams K range kw of tile t.  The K split is in units
+// of 4 steps, so a wave's scales / zero-points arrive as aligned 8-byte loads.
+// LDS: X [M][ng*256 + 16 B] permuted fragments | Sx float [ng][4] | zero bytes | reduction slots
+// =============================================================================================
+struct SmallLds {
+    int xrow, sx_off, zero_off, red_off, total;
+};
+inline SmallLds small_lds(int M, int ng, int tw, int ks) {
+    SmallLds l;
+    l.xrow = ng * 256 + 16;
+    l.sx_off = M * l.xrow;
+    l.zero_off = l.sx_off + ng * 16;  // what lanes without an activation row read, 4 steps deep
+    l.red_off = l.zero_off + 256 * 4;
+    l.total = l.red_off + (ks - 1) * tw * 4 * 64 * (int)sizeof(float);
+    return l;
+}
+
+__global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
+                                                             __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS) {
+    constexpr int D = 4;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int TW = (blockDim.x >> 6) / KS;
+    const int ti = wave / KS, kw = wave - ti * KS;  // tile within the workgroup, K split index
+    const int n = lane & 15, kb = lane >> 4;
+    const int row0 = (blockIdx.x * TW + ti) * 16;
+    const int nq = L.ng;
+    const int units = (nq + 3) >> 2;
+    const int q_beg = 4 * (int)((int64_t)units * kw / KS);
+    const int q_end = min(4 * (int)((int64_t)units * (kw + 1) / KS), nq);
+    const int nj = max(q_end - q_beg, 0);
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+
+    // ---- prefetch first: weights and group parameters do not depend on anything staged below ------
+    const int orow = min(row0 + n, L.oc - 1);
+    const unsigned char* wp =
+        reinterpret_cast<const unsigned char*>(L.qweight + (size_t)orow * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+    const __half* sp = L.scales + (size_t)orow * L.gs + q_beg;
+    const __half* zp = L.zeros + (size_t)orow * L.gs + q_beg;
+    u4 wq[D];
+    u2 sc4 = u2{0u, 0u}, zc4 = u2{0u, 0u};
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < nj) wq[d] = load16(wp + 64 * d);
+    if (nj > 0) {
+        sc4 = load8(sp);
+        zc4 = load8(zp);
+    }
+
+    // ---- stage X: fragment idx -> (row m, fragment f of 8 columns); zero beyond Kq.  Four fragments
+    // per thread and pass, all loads issued before the first use ------------------------------------
+    {
+        const int per_m = nq * 16;
+        const int total = M * per_m;  // multiple of 16: a 16-lane group is all in or all out
+        for (int base = 0; base < total; base += 4 * blockDim.x) {
+            u4 v[4];
+            int mm[4], ff[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int idx = base + u * blockDim.x + threadIdx.x;
+                const int m = (idx >= per_m) + (idx >= 2 * per_m) + (idx >= 3 * per_m);
+                mm[u] = (idx < total) ? m : -1;
+                ff[u] = idx - m * per_m;
+                v[u] = zero4;
+                if (idx < total && 8 * ff[u] < L.kq) v[u] = load16(X + (size_t)m * ldx + 8 * ff[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float t = sum16(sum8(v[u]));
+                if (mm[u] >= 0) {
+                    *reinterpret_cast<u4*>(lds + mm[u] * ld.xrow + ff[u] * 16) = permute_x(v[u]);
+                    if ((ff[u] & 15) == 0) reinterpret_cast<float*>(lds + ld.sx_off)[(ff[u] >> 4) * 4 + mm[u]] = t;
+                }
+            }
+        }
+        // rows of Sx beyond M read as zero
+        for (int i = threadIdx.x; i < nq * 4; i += blockDim.x)
+            if ((i & 3) >= M) reinterpret_cast<float*>(lds + ld.sx_off)[i] = 0.f;
+        for (int i = threadIdx.x; i < 64 * 4; i += blockDim.x) reinterpret_cast<float*>(lds + ld.zero_off)[i] = 0.f;
+    }
+    __syncthreads();
+
+    // ---- stream this wave's steps ---------------------------------------------------------------------
+    f4 y[1];
+    y[0] = f4{0.f, 0.f, 0.f, 0.f};
+    const Consts magic = make_consts();
+    // lanes without an activation row (n >= M), and accumulator rows >= 4 for Sx, read zero bytes
+    const bool has_x = n < M, has_sx = kb == 0;
+    int xa_addr = has_x ? n * ld.xrow + kb * 64 + q_beg * 256 : ld.zero_off;
+    int sx_addr = has_sx ? ld.sx_off + q_beg * 16 : ld.zero_off;
+    const int xa_inc = has_x ? 256 * D : 0, sx_inc = has_sx ? 16 * D : 0;
+
+    auto step = [&](int d) {
+        u4 xa[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const u4*>(lds + xa_addr + d * 256 + 16 * i);
+        const f4 sx = *reinterpret_cast<const f4*>(lds + sx_addr + d * 16);
+        step_tile(y[0], xa, wq[d], sx, half_at(sc4, d), 1024.f + half_at(zc4, d), magic);
+    };
+    auto advance = [&]() {
+        wp += 64 * D;
+        sp += D;
+        zp += D;
+        xa_addr += xa_inc;
+        sx_addr += sx_inc;
+    };
+
+    int j0 = 0;
+    for (; j0 + 2 * D <= nj; j0 += D) {  // steady state: every load is real, no branches
+        const u2 scn = load8(sp + D), zcn = load8(zp + D);
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            step(d);
+            wq[d] = load16(wp + 64 * (d + D));
+            __builtin_amdgcn_sched_barrier(0);  // keep the refill right behind its step: D loads stay in flight
+        }
+        sc4 = scn;
+        zc4 = zcn;
+        advance();
+    }
+    for (; j0 < nj; j0 += D) {  // last < 2*D steps
+        u2 scn = sc4, zcn = zc4;
+        if (j0 + D < nj) {
+            scn = load8(sp + D);
+            zcn = load8(zp + D);
+        }
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (j0 + d < nj) {
+                step(d);
+                if (j0 + d + D < nj) wq[d] = load16(wp + 64 * (d + D));
+            }
+        }
+        sc4 = scn;
+        zc4 = zcn;
+        advance();
+    }
+    weak_steps<1>(L, X, M, ldx, row0, kw, KS, n, kb, y);
+    reduce_store<1>(L, y, kw, KS, lane, row0, M, Y, ldy, [&](int w) {
+        return reinterpret_cast<float*>(lds + ld.red_off) + (size_t)(ti * (KS - 1) + (w - 1)) * 4 * 64;
+    });
+}
+
+// =============================================================================================
+// Chunked kernel: any M <= 16, R tiles per wave share the A fragments; each wave stages CH steps
+// of its own K range at a time into a private LDS region.
+// =============================================================================================
+constexpr int XROW = 272;  // bytes per activation row and step: 16 fragments + 16 B against bank conflicts
+
+template <int R, int CH>
+struct Region {
+    int xstep;  // bytes of X per step
+    __device__ __forceinline__ Region(int M) : xstep(M * XROW) {}
+    __device__ __forceinline__ int x_off(int sl) const { return sl * xstep; }
+    __device__ __forceinline__ int sx_off(int sl) const { return CH * xstep + sl * 64; }
+    __device__ __forceinline__ int s_off(int sl) const { return CH * xstep + CH * 64 + sl * (R * 64); }
+    __device__ __forceinline__ int z_off(int sl) const { return CH * xstep + CH * 64 + CH * R * 64 + sl * (R * 64); }
+};
+inline size_t region_bytes(int R, int CH, int M) {
+    const size_t b = (size_t)CH * ((size_t)M * XROW + 64 + 2 * (size_t)R * 64);
+    const size_t red = (size_t)R * 4 * 64 * sizeof(float);  // the region doubles as the reduction buffer
+    return b > red ? b : red;
+}
+
+// R: row tiles per wave, D: weight loads in flight per tile, CH: steps staged per chunk (multiple of D)
+template <int R, int D, int CH>
+__global__ __launch_bounds__(512) void gemv_w4_chunk_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
+                                                            __half* __restrict__ Y, int64_t ldy, int region_stride) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int lane = threadIdx.x & 63;
+    const int KS = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, kb = lane >> 4;
+    const int row0 = blockIdx.x * (16 * R);
+    unsigned char* my = lds + (size_t)wave * region_stride;
+    const Region<R, CH> rg(M);
+
+    const int nq = L.ng;
+    const int q_beg = (int)((int64_t)nq * wave / KS), q_end = (int)((int64_t)nq * (wave + 1) / KS);
+    const int nj = q_end - q_beg;
+
+    const unsigned char* wrow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int o = min(row0 + 16 * r + n, L.oc - 1);
+        wrow[r] = reinterpret_cast<const unsigned char*>(L.qweight + (size_t)o * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+    }
+    const bool mvalid = n < M;
+    const Consts magic = make_consts();
+
+    f4 y[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) y[r] = f4{0.f, 0.f, 0.f, 0.f};
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+
+    u4 wq[D][R];
+    auto load_w = [&](int d, int j) {  // j: step index local to this wave
+#pragma unroll
+        for (int r = 0; r < R; ++r) wq[d][r] = load16(wrow[r] + 64 * (size_t)j);
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (d < nj) load_w(d, d);
+
+    // rows of Sx that no activation row fills stay zero
+    for (int i = lane; i < CH * 16; i += 64) reinterpret_cast<float*>(my + rg.sx_off(0))[i] = 0.f;
+
+    for (int c0 = 0; c0 < nj; c0 += CH) {
+        const int cs = min(CH, nj - c0);
+        wave_lds_fence();
+        // ---- stage X (permuted), Sx, scales and zero-points of steps [c0, c0+cs) -------------
+        {
+            const int per_m = cs * 16;    // fragments per activation row
+            const int total = M * per_m;  // multiple of 16: a 16-lane group is all in or all out
+            for (int base = 0; base < total; base += 64) {
+                const int idx = base + lane;
+                const bool in = idx < total;
+                const int m = in ? idx / per_m : 0;
+                const int jj = in ? idx % per_m : 0;
+                const int sl = jj >> 4, f = jj & 15;
+                const int col = (q_beg + c0 + sl) * 128 + 8 * f;
+                u4 v = zero4;
+                if (in && col < L.kq) v = load16(X + (size_t)m * ldx + col);
+                const float t = sum16(sum8(v));
+                if (in) {
+                    *reinterpret_cast<u4*>(my + rg.x_off(sl) + m * XROW + f * 16) = permute_x(v);
+                    if (f == 0) reinterpret_cast<float*>(my + rg.sx_off(sl))[m] = t;
+                }
+            }
+            const int totp = R * 16 * cs;
+            for (int idx = lane; idx < totp; idx += 64) {
+                const int sl = idx % cs, ri = idx / cs;
+                const int o = min(row0 + ri, L.oc - 1);
+                const size_t gi = (size_t)o * L.gs + q_beg + c0 + sl;
+                reinterpret_cast<float*>(my + rg.s_off(sl))[ri] = __half2float(L.scales[gi]);
+                reinterpret_cast<float*>(my + rg.z_off(sl))[ri] = 1024.f + __half2float(L.zeros[gi]);
+            }
+        }
+        wave_lds_fence();
+        // ---- stream the weights of the chunk -------------------------------------------------
+        for (int sl0 = 0; sl0 < cs; sl0 += D) {
+#pragma unroll
+            for (int d = 0; d < D; ++d) {
+                const int sl = sl0 + d;
+                if (sl < cs) {
+                    u4 xa[4];
+                    const unsigned char* xp = my + rg.x_off(sl) + n * XROW + kb * 64;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) xa[i] = mvalid ? *reinterpret_cast<const u4*>(xp + 16 * i) : zero4;
+                    const f4 sx = *reinterpret_cast<const f4*>(my + rg.sx_off(sl) + kb * 16);
+#pragma unroll
+                    for (int r = 0; r < R; ++r) {
+                        const float sf = reinterpret_cast<const float*>(my + rg.s_off(sl))[16 * r + n];
+                        const float c = reinterpret_cast<const float*>(my + rg.z_off(sl))[16 * r + n];
+                        step_tile(y[r], xa, wq[d][r], sx, sf, c, magic);
+                    }
+                    const int jn = c0 + sl + D;  // refill this slot with the step D ahead
+                    if (jn < nj) load_w(d, jn);
+                }
+            }
+        }
+    }
+
+    weak_steps<R>(L, X, M, ldx, row0, wave, KS, n, kb, y);
+    wave_lds_fence();
+    reduce_store<R>(L, y, wave, KS, lane, row0, M, Y, ldy,
+                    [&](int w) { return reinterpret_cast<float*>(lds + (size_t)w * region_stride); });
+}
+
+template <int R, int D, int CH>
+hipError_t launch_chunk(const Layer& L, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy, int ks,
+                        hipStream_t s) {
+    const int grid = ceil_div(L.oc, 16 * R);
+    const size_t region = (region_bytes(R, CH, M) + 255) / 256 * 256;
+    gemv_w4_chunk_kernel<R, D, CH><<<grid, 64 * ks, region * ks, s>>>(L, X, M, ldx, Y, ldy, (int)region);
+    return hipGetLastError();
+}
+
+constexpr int SMALL_LDS_LIMIT = 96 * 1024;
+
 }  // namespace
 
 bool gemv_supported(const Layer& L, int64_t M, int64_t ldx) {
@@ -182,14 +454,44 @@ bool gemv_supported(const Layer& L, int64_t M, int64_t ldx) {
     return M >= 1 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0;
 }
 
-hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
-    constexpr int R = 1;
-    const char* e = getenv("QEFT_DBG_KS");
-    const int ks = e ? atoi(e) : 4;
-    const int grid = ceil_div(L.oc, 16 * R);
-    const size_t lds = (size_t)(ks - 1) * R * 4 * 64 * sizeof(float);
-    gemv_w4_kernel<R><<<grid, 64 * ks, lds, s>>>(L, X, (int)M, ldx, Y, ldy);
-    return hipGetLastError();
+hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
+    const int M = (int)M64;
+    const int steps = L.ng + (L.k + 31) / 32;
+    if (M <= 4) {
+        const int tiles = ceil_div(L.oc, 16);
+        const int units = (L.ng + 3) / 4;
+        // ~12 waves per CU over 256 CUs, at most 16 waves per workgroup, K split in units of 4 steps
+        int ks = ceil_div(3072, tiles);
+        const int ks_max = units < 1 ? 1 : (units > 16 ? 16 : units);
+        ks = ks < 1 ? 1 : (ks > ks_max ? ks_max : ks);
+        int tw = 16 / ks;
+        tw = tw < 1 ? 1 : (tw > 4 ? 4 : tw);
+        while (tw > 1 && ceil_div(tiles, tw) < 512) tw >>= 1;  // keep every CU busy
+        const SmallLds ld = small_lds(M, L.ng, tw, ks);
+        if (ld.total <= SMALL_LDS_LIMIT) {
+            static bool attr_set = false;
+            if (!attr_set) {
+                hipError_t e = hipFuncSetAttribute((const void*)gemv_w4_small_kernel,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
+                if (e != hipSuccess) return e;
+                attr_set = true;
+            }
+            gemv_w4_small_kernel<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks);
+            return hipGetLastError();
+        }
+    }
+    const int R = (M <= 4) ? 1 : (M <= 8 ? 2 : 4);
+    const int tiles = ceil_div(L.oc, 16 * R);
+    int ks = ceil_div(2048, tiles);
+    ks = ks < 1 ? 1 : (ks > 8 ? 8 : ks);
+    while (ks > 1 && steps / ks < 2) --ks;
+    if (R == 1) {
+        if (M == 1) return launch_chunk<1, 4, 16>(L, X, M, ldx, Y, ldy, ks, s);
+        if (M == 2) return launch_chunk<1, 4, 8>(L, X, M, ldx, Y, ldy, ks, s);
+        return launch_chunk<1, 4, 4>(L, X, M, ldx, Y, ldy, ks, s);
+    }
+    if (R == 2) return launch_chunk<2, 2, 4>(L, X, M, ldx, Y, ldy, ks > 6 ? 6 : ks, s);
+    return launch_chunk<4, 2, 2>(L, X, M, ldx, Y, ldy, ks > 6 ? 6 : ks, s);
 }
 
 }  // namespace qeft

@@ -14,7 +14,7 @@ __device__ __forceinline__ float weight_at(const Layer& L, int o, int j) {
     const int per = (L.bits == 4) ? 8 : 10;
     const uint32_t word = L.qweight[(size_t)o * L.stride + j / per];
     const uint32_t code = (word >> (L.bits * (j % per))) & ((1u << L.bits) - 1u);
-    const size_t gi = (size_t)o * L.ng + j / L.g;
+    const size_t gi = (size_t)o * L.gs + j / L.g;
     return __half2float(L.scales[gi]) * ((float)code - __half2float(L.zeros[gi]));
 }
 

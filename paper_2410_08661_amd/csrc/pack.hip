@@ -11,10 +11,17 @@ namespace {
 // ---- step 1: (scale, zero) of every (row, group); one wavefront per pair ------------------
 __global__ __launch_bounds__(256) void rtn_params_kernel(Layer L, const __half* __restrict__ W, int64_t ldw,
                                                          __half* __restrict__ scales, __half* __restrict__ zeros) {
-    const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t pair = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // over [OC][group_stride]
     const int lane = threadIdx.x & 63;
-    if (pair >= (int64_t)L.oc * L.ng) return;
-    const int o = (int)(pair / L.ng), gi = (int)(pair % L.ng);
+    if (pair >= (int64_t)L.oc * L.gs) return;
+    const int o = (int)(pair / L.gs), gi = (int)(pair % L.gs);
+    if (gi >= L.ng) {   // padding entry
+        if (lane == 0) {
+            scales[pair] = __float2half_rn(0.f);
+            zeros[pair] = __float2half_rn(0.f);
+        }
+        return;
+    }
     const int j0 = gi * L.g;
     const int len = min(L.g, L.kq - j0);
     float lo = 0.f, hi = 0.f;  // the range always contains 0
@@ -61,7 +68,7 @@ __global__ __launch_bounds__(256) void rtn_words_kernel(Layer L, const __half* _
     for (int i = 0; i < per; ++i) {
         const int j = wd * per + i;
         if (j < L.kq) {
-            const size_t gi = (size_t)o * L.ng + j / L.g;
+            const size_t gi = (size_t)o * L.gs + j / L.g;
             const float s = __half2float(scales[gi]);
             const float z = __half2float(zeros[gi]);
             const float v = __half2float(W[(size_t)o * ldw + j]);
@@ -97,6 +104,18 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(Layer L, uint8_t* __r
     codes[idx] = (uint8_t)((word >> (L.bits * (j % per))) & ((1u << L.bits) - 1u));
 }
 
+// compact [OC][G] parameters into the padded [OC][group_stride] arrays (padding zero)
+__global__ __launch_bounds__(256) void pad_groups_kernel(Layer L, const __half* __restrict__ s_in,
+                                                         const __half* __restrict__ z_in, __half* __restrict__ s_out,
+                                                         __half* __restrict__ z_out) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)L.oc * L.gs) return;
+    const int o = (int)(idx / L.gs), gi = (int)(idx % L.gs);
+    const bool real = gi < L.ng;
+    s_out[idx] = real ? s_in[(size_t)o * L.ng + gi] : __float2half_rn(0.f);
+    z_out[idx] = real ? z_in[(size_t)o * L.ng + gi] : __float2half_rn(0.f);
+}
+
 // rows x cols fp16 copy between two leading dimensions
 __global__ __launch_bounds__(256) void copy2d_kernel(const __half* __restrict__ src, int64_t lds, __half* __restrict__ dst,
                                                      int64_t ldd, int64_t rows, int cols) {
@@ -117,7 +136,7 @@ void copy2d(const __half* src, int64_t lds, __half* dst, int64_t ldd, int64_t ro
 hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,
                     __half* weak, hipStream_t s) {
     if (L.kq > 0) {
-        const int64_t pairs = (int64_t)L.oc * L.ng;
+        const int64_t pairs = (int64_t)L.oc * L.gs;
         rtn_params_kernel<<<ceil_div(pairs, 4), 256, 0, s>>>(L, W, ldw, scales, zeros);
         rtn_words_kernel<<<ceil_div((int64_t)L.oc * L.stride, 256), 256, 0, s>>>(L, W, ldw, scales, zeros, qweight);
     }
@@ -129,8 +148,7 @@ hipError_t pack_codes(const Layer& L, const uint8_t* codes, const __half* scales
                       const __half* weak_in, uint32_t* qweight, __half* scales, __half* zeros, __half* weak, hipStream_t s) {
     if (L.kq > 0) {
         pack_words_kernel<<<ceil_div((int64_t)L.oc * L.stride, 256), 256, 0, s>>>(L, codes, qweight);
-        copy2d(scales_in, L.ng, scales, L.ng, L.oc, L.ng, s);
-        copy2d(zeros_in, L.ng, zeros, L.ng, L.oc, L.ng, s);
+        pad_groups_kernel<<<ceil_div((int64_t)L.oc * L.gs, 256), 256, 0, s>>>(L, scales_in, zeros_in, scales, zeros);
     }
     copy2d(weak_in, L.k, weak, L.k, L.oc, L.k, s);
     return hipGetLastError();
@@ -139,8 +157,8 @@ hipError_t pack_codes(const Layer& L, const uint8_t* codes, const __half* scales
 hipError_t unpack(const Layer& L, uint8_t* codes, __half* scales, __half* zeros, __half* weak, hipStream_t s) {
     if (L.kq > 0) {
         if (codes) unpack_codes_kernel<<<ceil_div((int64_t)L.oc * L.kq, 256), 256, 0, s>>>(L, codes);
-        if (scales) copy2d(L.scales, L.ng, scales, L.ng, L.oc, L.ng, s);
-        if (zeros) copy2d(L.zeros, L.ng, zeros, L.ng, L.oc, L.ng, s);
+        if (scales) copy2d(L.scales, L.gs, scales, L.ng, L.oc, L.ng, s);
+        if (zeros) copy2d(L.zeros, L.gs, zeros, L.ng, L.oc, L.ng, s);
     }
     if (weak) copy2d(L.weak, L.k, weak, L.k, L.oc, L.k, s);
     return hipGetLastError();

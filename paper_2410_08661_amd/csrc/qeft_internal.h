@@ -14,6 +14,7 @@ struct Layer {
     int oc, ic, k, bits, g;
     int kq;        // ic - k
     int ng;        // groups per row
+    int gs;        // row pitch of scales / zeros in elements (ng rounded up to a multiple of 8)
     int words;     // used words per row
     int stride;    // words per row incl. padding (multiple of 4)
     const uint32_t* qweight;

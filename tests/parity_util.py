@@ -55,8 +55,9 @@ class HostLayer:
         w = B.Weight(self.desc)
         if self.kq:
             w.qweight.copy_(torch.from_numpy(self.qweight.view(np.int32)))
-            w.scales.copy_(torch.from_numpy(self.scales))
-            w.zeros.copy_(torch.from_numpy(self.zeros))
+            ng = self.lay["n_groups"]            # stored rows are padded to group_stride with zeros
+            w.scales[:, :ng].copy_(torch.from_numpy(self.scales))
+            w.zeros[:, :ng].copy_(torch.from_numpy(self.zeros))
         if self.k:
             w.weak.copy_(torch.from_numpy(self.weak))
         return w

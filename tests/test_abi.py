@@ -34,7 +34,7 @@ def test_layout_matches_oracle(shape):
     oc, ic, k, bits = shape
     lay = B.qeft_layout(B.make_desc(oc, ic, k, bits, 128))
     ref = qo.layout(oc, ic, k, bits, 128)
-    for f in ("kq", "n_groups", "words_per_row", "row_stride_words", "qweight_bytes", "scales_bytes", "zeros_bytes", "weak_bytes"):
+    for f in ("kq", "n_groups", "words_per_row", "row_stride_words", "group_stride", "qweight_bytes", "scales_bytes", "zeros_bytes", "weak_bytes"):
         assert getattr(lay, f) == ref[f], f
 
 

@@ -46,8 +46,14 @@ def test_pack_rtn_bit_exact(oc, ic, k, bits, g):
     B.qeft_pack(desc, wbuf[:, :ic], out)
     torch.cuda.synchronize()
     assert np.array_equal(out.qweight.cpu().numpy().view(np.uint32), ref_words)
-    assert np.array_equal(out.scales.cpu().numpy().view(np.uint16), scales.view(np.uint16))
-    assert np.array_equal(out.zeros.cpu().numpy().view(np.uint16), zeros.view(np.uint16))
+    ng = lay["n_groups"]
+    out.scales[:, ng:].fill_(1.0)            # padding must be rewritten as zero as well
+    B.qeft_pack(desc, wbuf[:, :ic], out)
+    torch.cuda.synchronize()
+    assert out.scales.shape[1] == lay["group_stride"]
+    assert np.array_equal(out.scales[:, :ng].cpu().numpy().view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(out.zeros[:, :ng].cpu().numpy().view(np.uint16), zeros.view(np.uint16))
+    assert torch.all(out.scales[:, ng:] == 0) and torch.all(out.zeros[:, ng:] == 0)
     assert np.array_equal(out.weak.cpu().numpy().view(np.uint16), weak.view(np.uint16))
 
 
@@ -62,6 +68,11 @@ def test_pack_codes_and_unpack_bit_exact(oc, ic, k, bits, g):
                       dev(h.zeros) if h.kq else None, dev(h.weak) if k else None, out)
     torch.cuda.synchronize()
     assert np.array_equal(out.qweight.cpu().numpy().view(np.uint32), h.qweight)
+    ng = h.lay["n_groups"]
+    if h.kq:
+        assert np.array_equal(out.scales[:, :ng].cpu().numpy().view(np.uint16), h.scales.view(np.uint16))
+        assert np.array_equal(out.zeros[:, :ng].cpu().numpy().view(np.uint16), h.zeros.view(np.uint16))
+        assert torch.all(out.scales[:, ng:] == 0) and torch.all(out.zeros[:, ng:] == 0)
     codes, scales, zeros, weak = B.qeft_unpack(desc, h.to_device())
     torch.cuda.synchronize()
     assert np.array_equal(codes.cpu().numpy(), h.codes)

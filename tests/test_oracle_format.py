@@ -58,15 +58,15 @@ def test_pack_rejects_out_of_range():
 # ---- layout closed forms ------------------------------------------------------------
 # (OC, IC, k, bits) -> (Kq, G, words per row, stride, total stored bytes), worked by hand
 LAYOUT_CASES = [
-    ((512, 512, 8, 4), (504, 4, 63, 64, 147456)),
-    ((4096, 4096, 128, 4), (3968, 31, 496, 496, 9682944)),
-    ((11008, 4096, 128, 4), (3968, 31, 496, 496, 26022912)),
-    ((4096, 11008, 128, 4), (10880, 85, 1360, 1360, 24723456)),
-    ((5120, 5120, 128, 3), (4992, 39, 500, 500, 12349440)),
-    ((5120, 13824, 128, 3), (13696, 107, 1370, 1372, 31600640)),
-    ((5120, 13824, 128, 4), (13696, 107, 1712, 1712, 38563840)),
-    ((28672, 8192, 256, 4), (7936, 62, 992, 992, 135561216)),
-    ((8192, 28672, 256, 4), (28416, 222, 3552, 3552, 127860736)),
+    ((512, 512, 8, 4), (504, 4, 63, 64, 155648)),
+    ((4096, 4096, 128, 4), (3968, 31, 496, 496, 9699328)),
+    ((11008, 4096, 128, 4), (3968, 31, 496, 496, 26066944)),
+    ((4096, 11008, 128, 4), (10880, 85, 1360, 1360, 24772608)),
+    ((5120, 5120, 128, 3), (4992, 39, 500, 512, 12615680)),
+    ((5120, 13824, 128, 3), (13696, 107, 1370, 1376, 31784960)),
+    ((5120, 13824, 128, 4), (13696, 107, 1712, 1712, 38666240)),
+    ((28672, 8192, 256, 4), (7936, 62, 992, 992, 135790592)),
+    ((8192, 28672, 256, 4), (28416, 222, 3552, 3552, 127926272)),
 ]
 
 
@@ -76,15 +76,17 @@ def test_layout_closed_form(shape, expect):
     lay = qo.layout(oc, ic, k, bits, 128)
     total = lay["qweight_bytes"] + lay["scales_bytes"] + lay["zeros_bytes"] + lay["weak_bytes"]
     assert (lay["kq"], lay["n_groups"], lay["words_per_row"], lay["row_stride_words"], total) == expect
-    # bytes = OC * (4*stride + 2*G + 2*G + 2*k)
-    assert total == oc * (4 * expect[3] + 4 * expect[1] + 2 * k)
+    # bytes = OC * (4*stride + 2*Gs + 2*Gs + 2*k) with Gs = G rounded up to a multiple of 8
+    gs = -(-expect[1] // 8) * 8
+    assert lay["group_stride"] == gs
+    assert total == oc * (4 * expect[3] + 4 * gs + 2 * k)
 
 
 def test_layout_degenerate():
     lay = qo.layout(7, 32, 32, 4, 128)          # every column weak: nothing quantized
     assert (lay["kq"], lay["n_groups"], lay["qweight_bytes"], lay["weak_bytes"]) == (0, 0, 0, 7 * 32 * 2)
     lay = qo.layout(7, 32, 0, 3, 128)           # no weak column, one partial group
-    assert (lay["kq"], lay["n_groups"], lay["words_per_row"], lay["row_stride_words"], lay["weak_bytes"]) == (32, 1, 4, 4, 0)
+    assert (lay["kq"], lay["n_groups"], lay["words_per_row"], lay["row_stride_words"], lay["weak_bytes"]) == (32, 1, 4, 16, 0)
     with pytest.raises(ValueError):
         qo.layout(4, 8, 9, 4, 128)
     with pytest.raises(ValueError):
@@ -97,7 +99,9 @@ def _model_sum(golden, name, k, field):
     tot = 0
     for oc, ic in m["linears"]:
         lay = qo.layout(oc, ic, k, 4, 128)
-        tot += lay[field] if field != "group_bytes" else lay["scales_bytes"] + lay["zeros_bytes"]
+        # information content of the group parameters: one fp16 scale + one fp16 zero-point per
+        # group (the 16-byte row padding of the stored arrays is an alignment detail)
+        tot += lay[field] if field != "group_bytes" else 4 * oc * lay["n_groups"]
     return tot * m["blocks"]
 
 
