@@ -167,25 +167,33 @@ __device__ __forceinline__ void reduce_store(const Layer& L, f4 (&y)[R], int kw,
 // =============================================================================================
 // Small-M kernel: M <= 4.  A workgroup owns TW tiles of 16 rows; its TW*KS waves stage all of X
 // once (one barrier), then wave (t, kw) streams K range kw of tile t.  The K split is in units
-// of 4 steps, so a wave's scales / zero-points arrive as aligned 8-byte loads.
-// LDS: X [M][ng*256 + 16 B] permuted fragments | Sx float [ng][4] | zero bytes | reduction slots
+// of 4 steps, so a wave fetches its scales / zero-points as aligned 8-byte loads (16 steps per
+// load instruction: the 4 lanes of a row take 4 steps each) and parks them in its own LDS slice.
+// The wave's share of the weak block is requested first of all and consumed last.
+// LDS: X [M][ng*256 + 16 B] permuted fragments | Sx float [ng][4] | zero bytes |
+//      (s, 1024+z) float2 [waves][steps per wave][16] | reduction slots
 // =============================================================================================
 struct SmallLds {
-    int xrow, sx_off, zero_off, red_off, total;
+    int xrow, sx_off, zero_off, sz_off, sz_wave, red_off, total;
 };
 inline SmallLds small_lds(int M, int ng, int tw, int ks) {
     SmallLds l;
+    const int units = (ng + 3) / 4;
+    const int steps_per_wave = ((4 * ((units + ks - 1) / ks) + 15) / 16) * 16;
     l.xrow = ng * 256 + 16;
     l.sx_off = M * l.xrow;
     l.zero_off = l.sx_off + ng * 16;  // what lanes without an activation row read, 4 steps deep
-    l.red_off = l.zero_off + 256 * 4;
+    l.sz_off = l.zero_off + 256 * 4;
+    l.sz_wave = steps_per_wave * 128;
+    l.red_off = l.sz_off + tw * ks * l.sz_wave;
     l.total = l.red_off + (ks - 1) * tw * 4 * 64 * (int)sizeof(float);
     return l;
 }
 
 __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                              __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS) {
-    constexpr int D = 4;
+    constexpr int D = 4;      // weight loads in flight per lane
+    constexpr int WMAX = 4;   // weak steps per wave kept in registers
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -198,23 +206,56 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     const int q_beg = 4 * (int)((int64_t)units * kw / KS);
     const int q_end = min(4 * (int)((int64_t)units * (kw + 1) / KS), nq);
     const int nj = max(q_end - q_beg, 0);
+    const int nweak = (L.k + 31) / 32;
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    const bool has_x = n < M;
 
-    // ---- prefetch first: weights and group parameters do not depend on anything staged below ------
+    // ---- requests that depend on nothing staged below go out first --------------------------------
     const int orow = min(row0 + n, L.oc - 1);
     const unsigned char* wp =
         reinterpret_cast<const unsigned char*>(L.qweight + (size_t)orow * L.stride) + 64 * (size_t)q_beg + 16 * kb;
-    const __half* sp = L.scales + (size_t)orow * L.gs + q_beg;
-    const __half* zp = L.zeros + (size_t)orow * L.gs + q_beg;
     u4 wq[D];
-    u2 sc4 = u2{0u, 0u}, zc4 = u2{0u, 0u};
 #pragma unroll
     for (int d = 0; d < D; ++d)
         if (d < nj) wq[d] = load16(wp + 64 * d);
-    if (nj > 0) {
-        sc4 = load8(sp);
-        zc4 = load8(zp);
+    // weak steps of 32 fp16 columns are dealt to the K-split waves from the last one back
+    u4 wk[WMAX], xw[WMAX];
+#pragma unroll
+    for (int i = 0; i < WMAX; ++i) {
+        const int c0 = 32 * (KS - 1 - kw + i * KS) + 8 * kb;
+        wk[i] = (c0 < L.k) ? load16(L.weak + (size_t)orow * L.k + c0) : zero4;
+        xw[i] = (has_x && c0 < L.k) ? load16(X + (size_t)n * ldx + L.kq + c0) : zero4;
     }
+    // scales / zero-points: lane (n, kb) takes steps 16*b + 4*kb .. +3 of row n
+    const __half* sp = L.scales + (size_t)orow * L.gs + q_beg;
+    const __half* zp = L.zeros + (size_t)orow * L.gs + q_beg;
+    unsigned char* szw = lds + ld.sz_off + (size_t)wave * ld.sz_wave;
+    auto stage_sz = [&](int b0) {   // 64 steps from local step b0
+        u2 sb[4], zb[4];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int st = b0 + 16 * b + 4 * kb;
+            sb[b] = zb[b] = u2{0u, 0u};
+            if (st < nj) {
+                sb[b] = load8(sp + st);
+                zb[b] = load8(zp + st);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int st = b0 + 16 * b + 4 * kb;
+            if (st < nj) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float2 v;
+                    v.x = half_at(sb[b], e);
+                    v.y = 1024.f + half_at(zb[b], e);
+                    reinterpret_cast<float2*>(szw)[(st + e) * 16 + n] = v;
+                }
+            }
+        }
+    };
+    stage_sz(0);
 
     // ---- stage X: fragment idx -> (row m, fragment f of 8 columns); zero beyond Kq.  Four fragments
     // per thread and pass, all loads issued before the first use ------------------------------------
@@ -247,6 +288,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
             if ((i & 3) >= M) reinterpret_cast<float*>(lds + ld.sx_off)[i] = 0.f;
         for (int i = threadIdx.x; i < 64 * 4; i += blockDim.x) reinterpret_cast<float*>(lds + ld.zero_off)[i] = 0.f;
     }
+    for (int b0 = 64; b0 < nj; b0 += 64) stage_sz(b0);
     __syncthreads();
 
     // ---- stream this wave's steps ---------------------------------------------------------------------
@@ -254,9 +296,10 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     y[0] = f4{0.f, 0.f, 0.f, 0.f};
     const Consts magic = make_consts();
     // lanes without an activation row (n >= M), and accumulator rows >= 4 for Sx, read zero bytes
-    const bool has_x = n < M, has_sx = kb == 0;
+    const bool has_sx = kb == 0;
     int xa_addr = has_x ? n * ld.xrow + kb * 64 + q_beg * 256 : ld.zero_off;
     int sx_addr = has_sx ? ld.sx_off + q_beg * 16 : ld.zero_off;
+    int sz_addr = ld.sz_off + wave * ld.sz_wave + n * 8;
     const int xa_inc = has_x ? 256 * D : 0, sx_inc = has_sx ? 16 * D : 0;
 
     auto step = [&](int d) {
@@ -264,35 +307,27 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
 #pragma unroll
         for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const u4*>(lds + xa_addr + d * 256 + 16 * i);
         const f4 sx = *reinterpret_cast<const f4*>(lds + sx_addr + d * 16);
-        step_tile(y[0], xa, wq[d], sx, half_at(sc4, d), 1024.f + half_at(zc4, d), magic);
+        const float2 sz = *reinterpret_cast<const float2*>(lds + sz_addr + d * 128);
+        step_tile(y[0], xa, wq[d], sx, sz.x, sz.y, magic);
     };
     auto advance = [&]() {
         wp += 64 * D;
-        sp += D;
-        zp += D;
         xa_addr += xa_inc;
         sx_addr += sx_inc;
+        sz_addr += 128 * D;
     };
 
     int j0 = 0;
     for (; j0 + 2 * D <= nj; j0 += D) {  // steady state: every load is real, no branches
-        const u2 scn = load8(sp + D), zcn = load8(zp + D);
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             step(d);
             wq[d] = load16(wp + 64 * (d + D));
             __builtin_amdgcn_sched_barrier(0);  // keep the refill right behind its step: D loads stay in flight
         }
-        sc4 = scn;
-        zc4 = zcn;
         advance();
     }
     for (; j0 < nj; j0 += D) {  // last < 2*D steps
-        u2 scn = sc4, zcn = zc4;
-        if (j0 + D < nj) {
-            scn = load8(sp + D);
-            zcn = load8(zp + D);
-        }
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             if (j0 + d < nj) {
@@ -300,11 +335,19 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
                 if (j0 + d + D < nj) wq[d] = load16(wp + 64 * (d + D));
             }
         }
-        sc4 = scn;
-        zc4 = zcn;
         advance();
     }
-    weak_steps<1>(L, X, M, ldx, row0, kw, KS, n, kb, y);
+    // ---- weak block ---------------------------------------------------------------------------------------
+#pragma unroll
+    for (int i = 0; i < WMAX; ++i)
+        if (KS - 1 - kw + i * KS < nweak)
+            y[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xw[i]), as_h8(wk[i]), y[0], 0, 0, 0);
+    for (int t = KS - 1 - kw + WMAX * KS; t < nweak; t += KS) {   // very wide weak blocks only
+        const int c0 = 32 * t + 8 * kb;
+        const u4 a = (has_x && c0 < L.k) ? load16(X + (size_t)n * ldx + L.kq + c0) : zero4;
+        const u4 w = (c0 < L.k) ? load16(L.weak + (size_t)orow * L.k + c0) : zero4;
+        y[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(w), y[0], 0, 0, 0);
+    }
     reduce_store<1>(L, y, kw, KS, lane, row0, M, Y, ldy, [&](int w) {
         return reinterpret_cast<float*>(lds + ld.red_off) + (size_t)(ti * (KS - 1) + (w - 1)) * 4 * 64;
     });
@@ -445,7 +488,7 @@ hipError_t launch_chunk(const Layer& L, const __half* X, int M, int64_t ldx, __h
     return hipGetLastError();
 }
 
-constexpr int SMALL_LDS_LIMIT = 96 * 1024;
+constexpr int SMALL_LDS_LIMIT = 144 * 1024;   // of the 160 KB a CU has
 
 }  // namespace
 
@@ -467,6 +510,10 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
         int tw = 16 / ks;
         tw = tw < 1 ? 1 : (tw > 4 ? 4 : tw);
         while (tw > 1 && ceil_div(tiles, tw) < 512) tw >>= 1;  // keep every CU busy
+        if (small_lds(M, L.ng, tw, ks).total > 64 * 1024) {     // one workgroup per CU: make it a full one
+            tw = 1;
+            ks = ks_max;
+        }
         const SmallLds ld = small_lds(M, L.ng, tw, ks);
         if (ld.total <= SMALL_LDS_LIMIT) {
             static bool attr_set = false;
