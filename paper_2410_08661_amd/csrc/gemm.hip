@@ -1,88 +1,34 @@
 // Prefill / fine-tune path (paper Sec. 3.3): the large-M products of the fused layer as tiled
-// fp16 MFMA GEMMs with fp32 accumulation.
+// fp16 MFMA GEMMs with fp32 accumulation (tiling and LDS layout: gemm_common.h).
 //
-//   forward   Y [M][OC]  = X  . W^T        contraction over IC  (quantized part + weak block)
-//   backward  dX[M][IC]  = dY . W          contraction over OC  (through the full mixed weight)
+//   forward    Y [M][OC]  = X  . W^T            contraction over IC (quantized part, then weak block)
+//   backward   dX[M][IC]  = dY . W              contraction over OC, through the full mixed weight
+//   weak grad  dW[OC][k]  = dY^T . X[:, weak]   contraction over the M tokens (Eq. 5, weak block only)
 //
-// Both are computed "transposed": the weight side is the MFMA A operand (rows = OC for the
-// forward), the activation side the B operand (columns = tokens).  With the 32x32x16 MFMA a
-// lane then owns 4 consecutive output channels of one token, i.e. 8 contiguous bytes of the
-// row-major result, so the epilogue stores straight from the accumulators.
-//
-// Tiling: a workgroup of 4 waves (2 x 2) owns a 256 x 256 output tile, each wave 128 x 128
-// (4 x 4 MFMA tiles, 256 accumulator registers).  K advances in stages of 64: both operand
-// tiles (256 rows x 64 halfs, rows of 128 bytes, 16-byte chunks XOR-swizzled by the row so
-// fragment reads are conflict-free) are double-buffered in LDS, 128 KB of the CU's 160 KB.
-// The next stage's global loads are issued before the current stage's MFMAs; the weights
-// are dequantized in registers on their way into LDS, so the MFMA loop sees plain fp16.
+// The next stage's global loads are issued before the current stage's MFMAs and converted on
+// their way into LDS afterwards: the 4-bit codes are dequantized in registers, so the MFMA loop
+// only ever sees plain fp16 tiles.
 //
 // Dequantization: codes become the exact fp16 numbers 1024 + q by or-ing exponent bits onto
-// the masked nibbles (two codes per instruction); then ((1024+q) - 1024 - z) * s in packed
-// fp16: the two subtractions keep any fp16 zero-point exact up to one rounding.  The nibbles
-// of a word come out in the order (0,4)(1,5)(2,6)(3,7); the activations of quantized stages
-// are permuted to the same order when they are written to LDS.
-#include "qeft_internal.h"
+// the masked nibbles (two codes per instruction), then ((1024+q) - 1024 - z) * s in packed fp16.
+// Forward: a thread converts whole words of one weight row; the nibbles of a word come out in
+// the order (0,4)(1,5)(2,6)(3,7) and the activations of quantized stages are permuted to match.
+// Backward: the contraction runs across weight rows, so a thread takes the same word column of
+// 8 consecutive rows and pairs the rows with a byte permute before the conversion; the result is
+// already transposed, in natural order.
+#include "gemm_common.h"
 
 namespace qeft {
 namespace {
 
-typedef _Float16 h8 __attribute__((ext_vector_type(8)));
-typedef _Float16 h2 __attribute__((ext_vector_type(2)));
-typedef float f16v __attribute__((ext_vector_type(16)));
-typedef uint32_t u4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+using namespace gemm;
 
-constexpr int BT = 256;                 // tile rows of either operand
-constexpr int BK = 64;                  // K per stage
-constexpr int TILE_BYTES = BT * BK * 2; // 32 KB
-constexpr int GEMM_LDS = 4 * TILE_BYTES;
-
-__device__ __forceinline__ u4 ld16(const void* p) { return *reinterpret_cast<const u4*>(p); }
-__device__ __forceinline__ h8 as_h8(u4 v) { return __builtin_bit_cast(h8, v); }
-__device__ __forceinline__ uint32_t h2_bits(h2 v) { return __builtin_bit_cast(uint32_t, v); }
-__device__ __forceinline__ h2 bits_h2(uint32_t v) { return __builtin_bit_cast(h2, v); }
-
-// byte offset of 16-byte chunk `c` (0..7) of row `r` inside a 256 x 64 half tile
-__device__ __forceinline__ int tile_off(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
-
-struct Consts {
-    uint32_t mask, magic;
-};
-__device__ __forceinline__ Consts make_consts() {
-    Consts c{0x000f000fu, 0x64006400u};
-    asm volatile("" : "+v"(c.mask), "+v"(c.magic));  // opaque: (w & mask) | magic selects v_and_or_b32
-    return c;
-}
-
-// 8 activations x0..x7 -> (x0,x4)(x1,x5)(x2,x6)(x3,x7)
-__device__ __forceinline__ u4 permute_x(u4 v) {
-    u4 r;
-    r.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
-    r.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
-    r.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
-    r.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
-    return r;
-}
-
-// one word of 8 codes -> 8 dequantized fp16 weights in nibble order.  nz = (-1024 - z ... ) is
-// applied as two exact/rounded steps: (h - 1024) is exact, (.. - z) rounds once, (.. * s) once.
-__device__ __forceinline__ u4 dequant_word(uint32_t w, h2 z2, h2 s2, Consts c) {
-    const h2 k1024 = h2{(_Float16)1024.f, (_Float16)1024.f};
-    u4 r;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const h2 h = bits_h2(((w >> (4 * i)) & c.mask) | c.magic);
-        r[i] = h2_bits(((h - k1024) - z2) * s2);
-    }
-    return r;
-}
-
-// ---- forward -----------------------------------------------------------------------------------------
-// Raw global data of one stage, held in registers until the previous stage's MFMAs are issued.
+// ======================================================================================= forward
 struct FwdStage {
-    u4 a[8];        // quantized stage: a[0], a[1] = 4 code words of rows r0 and r0+128; weak stage: 8 fp16 chunks
-    u4 b[8];        // 8 chunks of X
-    uint32_t sz[2]; // (scale, zero) halfs of the two rows
+    u4 qa[2];        // quantized stage: 4 code words of rows r and r+128
+    uint32_t sz[2];  // their (scale, zero-point)
+    RowLoader wk;    // weak stage: fp16 weights
+    RowLoader x;     // activations
 };
 
 __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
@@ -90,43 +36,30 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;   // wave position: OC half, token half
-    // consecutive workgroups walk the OC tiles of one token panel: the panel of X stays in L2
+    const int wm = wave >> 1, wn = wave & 1;
+    // consecutive workgroups walk the OC tiles of one token panel: that panel of X stays in L2
     const int t_oc = blockIdx.x % tiles_oc, t_m = blockIdx.x / tiles_oc;
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const int nq_st = (L.kq + BK - 1) / BK, nw_st = (L.k + BK - 1) / BK, nst = nq_st + nw_st;
     const Consts cst = make_consts();
-    const u4 zero4 = u4{0u, 0u, 0u, 0u};
 
-    // producer coordinates
-    const int ar = tid >> 1, ah = tid & 1;               // quantized A: rows ar, ar+128; half ah of the stage
+    const int ar = tid >> 1, ah = tid & 1;  // quantized A: rows ar and ar+128, half ah of the stage's 8 words
     const int arow0 = min(oc0 + ar, L.oc - 1), arow1 = min(oc0 + ar + 128, L.oc - 1);
 
     auto load_stage = [&](FwdStage& s, int st) {
         if (st < nq_st) {
-            s.a[0] = ld16(L.qweight + (size_t)arow0 * L.stride + 8 * st + 4 * ah);
-            s.a[1] = ld16(L.qweight + (size_t)arow1 * L.stride + 8 * st + 4 * ah);
+            s.qa[0] = ld16(L.qweight + (size_t)arow0 * L.stride + 8 * st + 4 * ah);
+            s.qa[1] = ld16(L.qweight + (size_t)arow1 * L.stride + 8 * st + 4 * ah);
             const int g = st >> 1;
             s.sz[0] = (uint32_t)__half_as_ushort(L.scales[(size_t)arow0 * L.gs + g]) |
                       ((uint32_t)__half_as_ushort(L.zeros[(size_t)arow0 * L.gs + g]) << 16);
             s.sz[1] = (uint32_t)__half_as_ushort(L.scales[(size_t)arow1 * L.gs + g]) |
                       ((uint32_t)__half_as_ushort(L.zeros[(size_t)arow1 * L.gs + g]) << 16);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = tid + 256 * u, r = idx >> 3, c = idx & 7;
-                const int col = BK * st + 8 * c;
-                s.b[u] = (m0 + r < M && col < L.kq) ? ld16(X + (size_t)(m0 + r) * ldx + col) : zero4;
-            }
+            s.x.load(X, ldx, m0, M, BK * st, L.kq, tid, false);   // columns past Kq belong to the weak block
         } else {
             const int c0 = BK * (st - nq_st);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = tid + 256 * u, r = idx >> 3, c = idx & 7;
-                const int col = c0 + 8 * c;
-                const int orow = min(oc0 + r, L.oc - 1);
-                s.a[u] = (col < L.k) ? ld16(L.weak + (size_t)orow * L.k + col) : zero4;
-                s.b[u] = (m0 + r < M && col < L.k) ? ld16(X + (size_t)(m0 + r) * ldx + L.kq + col) : zero4;
-            }
+            s.wk.load(L.weak, L.k, oc0, L.oc, c0, L.k, tid, true);
+            s.x.load(X + L.kq, ldx, m0, M, c0, L.k, tid, false);
         }
     };
     auto store_stage = [&](const FwdStage& s, int st, unsigned char* sA, unsigned char* sB) {
@@ -135,82 +68,191 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
             for (int rr = 0; rr < 2; ++rr) {
                 const _Float16 sc = bits_h2(s.sz[rr])[0], zp = bits_h2(s.sz[rr])[1];
                 const h2 s2 = h2{sc, sc}, z2 = h2{zp, zp};
-                const int r = ar + 128 * rr;
 #pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    *reinterpret_cast<u4*>(sA + tile_off(r, 4 * ah + i)) = dequant_word(s.a[rr][i], z2, s2, cst);
-            }
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t w = s.qa[rr][i];
+                    u4 r;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = tid + 256 * u, r = idx >> 3, c = idx & 7;
-                *reinterpret_cast<u4*>(sB + tile_off(r, c)) = permute_x(s.b[u]);
+                    for (int p = 0; p < 4; ++p) r[p] = dequant_pair(((w >> (4 * p)) & cst.mask) | cst.magic, z2, s2);
+                    *reinterpret_cast<u4*>(sA + tile_off(ar + 128 * rr, 4 * ah + i)) = r;
+                }
             }
+            s.x.store(sB, tid, true);
         } else {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int idx = tid + 256 * u, r = idx >> 3, c = idx & 7;
-                *reinterpret_cast<u4*>(sA + tile_off(r, c)) = s.a[u];
-                *reinterpret_cast<u4*>(sB + tile_off(r, c)) = s.b[u];
-            }
+            s.wk.store(sA, tid, false);
+            s.x.store(sB, tid, false);
         }
     };
 
     f16v acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
+    zero_acc(acc);
     FwdStage stg;
     load_stage(stg, 0);
     store_stage(stg, 0, lds, lds + 2 * TILE_BYTES);
     __syncthreads();
-
-    const int fr = lane & 31, fk = lane >> 5;   // fragment row within a 32-row MFMA tile, k half
     for (int st = 0; st < nst; ++st) {
         const int cur = st & 1;
-        const unsigned char* sA = lds + cur * TILE_BYTES;
-        const unsigned char* sB = lds + 2 * TILE_BYTES + cur * TILE_BYTES;
         if (st + 1 < nst) load_stage(stg, st + 1);
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            h8 a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = *reinterpret_cast<const h8*>(sA + tile_off(wm * 128 + i * 32 + fr, 2 * ks + fk));
-                b[i] = *reinterpret_cast<const h8*>(sB + tile_off(wn * 128 + i * 32 + fr, 2 * ks + fk));
-            }
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (st + 1 < nst)
-            store_stage(stg, st + 1, lds + (cur ^ 1) * TILE_BYTES, lds + 2 * TILE_BYTES + (cur ^ 1) * TILE_BYTES);
+        compute_stage(lds + cur * TILE_BYTES, lds + (2 + cur) * TILE_BYTES, acc, wm, wn, lane);
+        if (st + 1 < nst) store_stage(stg, st + 1, lds + (cur ^ 1) * TILE_BYTES, lds + (2 + (cur ^ 1)) * TILE_BYTES);
         __syncthreads();
     }
+    store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wm, wn, lane);
+}
 
-    // ---- epilogue: accumulator element 4*g + r of a lane is row 8*g + 4*(lane/32) + r, column lane%32
+// ======================================================================================= backward dX
+// A[i = ic][k = oc] = W[oc][ic], B[j = m][k = oc] = dY[m][oc].  Thread (ko = t / 32, io = t % 32)
+// produces the 8 x 8 block of 8 weight rows x one word column (8 input channels).
+struct DxStage {
+    uint32_t qw[8];   // quantized columns: the word of each of the 8 rows
+    uint32_t sz[8];   // (scale, zero-point) of each row for this column's group
+    ColLoader wk;     // weak columns: 8 rows x 8 fp16
+    RowLoader dy;
+};
+
+__global__ __launch_bounds__(256) void gemm_dx_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
+                                                      __half* __restrict__ dX, int64_t lddx, int tiles_ic) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int t_ic = blockIdx.x % tiles_ic, t_m = blockIdx.x / tiles_ic;
+    const int ic0 = t_ic * BT, m0 = t_m * BT;
+    const int nst = (L.oc + BK - 1) / BK;
+    const Consts cst = make_consts();
+
+    const int ko = tid >> 5, io = tid & 31;
+    const int ic = ic0 + 8 * io;          // first of this thread's 8 input channels
+    const bool quant = ic < L.kq;         // Kq is a multiple of 8: a block is all quantized or all weak
+    const int wcol = ic >> 3, grp = ic >> 7;
+
+    auto load_stage = [&](DxStage& s, int st) {
+        const int k0 = BK * st;
+        if (quant) {
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int m = m0 + wn * 128 + j * 32 + fr;
-        if (m >= M) continue;
+            for (int e = 0; e < 8; ++e) {
+                const int row = min(k0 + 8 * ko + e, L.oc - 1);   // rows past OC meet zero columns of dY
+                s.qw[e] = L.qweight[(size_t)row * L.stride + wcol];
+                s.sz[e] = (uint32_t)__half_as_ushort(L.scales[(size_t)row * L.gs + grp]) |
+                          ((uint32_t)__half_as_ushort(L.zeros[(size_t)row * L.gs + grp]) << 16);
+            }
+        } else {
+            s.wk.load(L.weak, L.k, k0, L.oc, ic0 - L.kq, L.k, tid);
+        }
+        s.dy.load(dY, lddy, m0, M, k0, L.oc, tid, false);
+    };
+    auto store_stage = [&](const DxStage& s, unsigned char* sA, unsigned char* sB) {
+        if (quant) {
+            u4 out[8];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+            for (int p = 0; p < 4; ++p) {   // rows 2p and 2p+1 side by side
+                const h2 s2 = h2{bits_h2(s.sz[2 * p])[0], bits_h2(s.sz[2 * p + 1])[0]};
+                const h2 z2 = h2{bits_h2(s.sz[2 * p])[1], bits_h2(s.sz[2 * p + 1])[1]};
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int oc = oc0 + wm * 128 + i * 32 + 8 * g + 4 * fk;
-                if (oc < L.oc) {   // OC is a multiple of 4 on this path
-                    h2 lo = h2{(_Float16)acc[i][j][4 * g + 0], (_Float16)acc[i][j][4 * g + 1]};
-                    h2 hi = h2{(_Float16)acc[i][j][4 * g + 2], (_Float16)acc[i][j][4 * g + 3]};
-                    *reinterpret_cast<u2*>(Y + (size_t)m * ldy + oc) = u2{h2_bits(lo), h2_bits(hi)};
+                for (int b = 0; b < 4; ++b) {   // byte b of both words: codes 2b and 2b+1
+                    const uint32_t sel = 0x0c000c00u | ((4u + b) << 16) | (uint32_t)b;
+                    const uint32_t t = __builtin_amdgcn_perm(s.qw[2 * p + 1], s.qw[2 * p], sel);
+                    out[2 * b][p] = dequant_pair((t & cst.mask) | cst.magic, z2, s2);
+                    out[2 * b + 1][p] = dequant_pair(((t >> 4) & cst.mask) | cst.magic, z2, s2);
                 }
             }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) *reinterpret_cast<u4*>(sA + tile_off(8 * io + j, ko)) = out[j];
+        } else {
+            s.wk.store(sA, tid);
         }
+        s.dy.store(sB, tid, false);
+    };
+
+    f16v acc[4][4];
+    zero_acc(acc);
+    DxStage stg;
+    load_stage(stg, 0);
+    store_stage(stg, lds, lds + 2 * TILE_BYTES);
+    __syncthreads();
+    for (int st = 0; st < nst; ++st) {
+        const int cur = st & 1;
+        if (st + 1 < nst) load_stage(stg, st + 1);
+        compute_stage(lds + cur * TILE_BYTES, lds + (2 + cur) * TILE_BYTES, acc, wm, wn, lane);
+        if (st + 1 < nst) store_stage(stg, lds + (cur ^ 1) * TILE_BYTES, lds + (2 + (cur ^ 1)) * TILE_BYTES);
+        __syncthreads();
     }
+    store_f16(acc, dX, lddx, ic0, L.ic, m0, M, wm, wn, lane);
+}
+
+// ======================================================================================= weak gradient
+// A[i = c][k = m] = Xw[m][c], B[j = oc][k = m] = dY[m][oc]: both operands are read transposed.
+// The tokens are split over `splits` workgroups per OC tile; each writes an fp32 partial
+// [OC][k] slab, summed in slab order by a second kernel (no atomics: deterministic).
+__global__ __launch_bounds__(256) void weak_grad_kernel(int oc_total, int k, const __half* __restrict__ dY, int M,
+                                                        int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
+                                                        float* __restrict__ part, int splits, int chunk) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int split = blockIdx.x % splits, t_oc = blockIdx.x / splits;
+    const int oc0 = t_oc * BT;
+    const int mb = split * chunk, me = min(mb + chunk, M);
+    const int nst = (me - mb + BK - 1) / BK;
+
+    f16v acc[4][4];
+    zero_acc(acc);
+    ColLoader la, lb;
+    if (nst > 0) {
+        la.load(Xw, ldxw, mb, me, 0, k, tid);
+        lb.load(dY, lddy, mb, me, oc0, oc_total, tid);
+        la.store(lds, tid);
+        lb.store(lds + 2 * TILE_BYTES, tid);
+    }
+    __syncthreads();
+    for (int st = 0; st < nst; ++st) {
+        const int cur = st & 1;
+        if (st + 1 < nst) {
+            la.load(Xw, ldxw, mb + BK * (st + 1), me, 0, k, tid);
+            lb.load(dY, lddy, mb + BK * (st + 1), me, oc0, oc_total, tid);
+        }
+        compute_stage(lds + cur * TILE_BYTES, lds + (2 + cur) * TILE_BYTES, acc, wm, wn, lane);
+        if (st + 1 < nst) {
+            la.store(lds + (cur ^ 1) * TILE_BYTES, tid);
+            lb.store(lds + (2 + (cur ^ 1)) * TILE_BYTES, tid);
+        }
+        __syncthreads();
+    }
+    store_f32(acc, part + (size_t)split * oc_total * k, k, 0, k, oc0, oc_total, wm, wn, lane);
+}
+
+__global__ __launch_bounds__(256) void weak_grad_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
+                                                               void* dW, int out_f32, int accumulate) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float s = 0.f;
+    for (int p = 0; p < splits; ++p) s += part[(size_t)p * n + i];
+    if (out_f32) {
+        float* o = (float*)dW + i;
+        *o = accumulate ? *o + s : s;
+    } else {
+        __half* o = (__half*)dW + i;
+        *o = __float2half_rn(accumulate ? __half2float(*o) + s : s);
+    }
+}
+
+hipError_t raise_lds_limit(const void* fn, bool& done) {
+    if (done) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
+    if (e == hipSuccess) done = true;
+    return e;
+}
+
+// tokens per split: whole stages, enough workgroups to cover the CUs
+void weak_grad_split(int oc, int64_t M, int& splits, int& chunk) {
+    const int oc_tiles = ceil_div(oc, BT);
+    const int stages = ceil_div(M, BK);
+    int want = ceil_div(256, oc_tiles);
+    if (want > stages) want = stages;
+    if (want < 1) want = 1;
+    chunk = ceil_div(stages, want) * BK;
+    splits = ceil_div(M, chunk);
 }
 
 }  // namespace
@@ -220,23 +262,50 @@ bool gemm_fwd_supported(const Layer& L, int64_t M) {
 }
 
 hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void*)gemm_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    static bool attr = false;
+    hipError_t e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);
+    if (e != hipSuccess) return e;
     const int tiles_oc = ceil_div(L.oc, BT), tiles_m = ceil_div(M, BT);
     gemm_fwd_kernel<<<tiles_oc * tiles_m, 256, GEMM_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
     return hipGetLastError();
 }
 
-bool gemm_dx_supported(const Layer&, int64_t) { return false; }
-hipError_t gemm_dx(const Layer&, const __half*, int64_t, int64_t, __half*, int64_t, hipStream_t) { return hipErrorNotSupported; }
-bool weak_grad_mfma_supported(int, int, int64_t) { return false; }
-size_t weak_grad_mfma_workspace(int, int, int64_t) { return 0; }
-hipError_t weak_grad_mfma(int, int, const __half*, int64_t, int64_t, const __half*, int64_t, void*, int, int, void*, hipStream_t) {
-    return hipErrorNotSupported;
+bool gemm_dx_supported(const Layer& L, int64_t M) {
+    return M > 16 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0 && (L.oc % 8) == 0 &&
+           (L.ic % 8) == 0;
+}
+
+hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s) {
+    static bool attr = false;
+    hipError_t e = raise_lds_limit((const void*)gemm_dx_kernel, attr);
+    if (e != hipSuccess) return e;
+    const int tiles_ic = ceil_div(L.ic, BT), tiles_m = ceil_div(M, BT);
+    gemm_dx_kernel<<<tiles_ic * tiles_m, 256, GEMM_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic);
+    return hipGetLastError();
+}
+
+bool weak_grad_mfma_supported(int oc, int k, int64_t M) {
+    return M >= 64 && k >= 8 && k <= BT && (k % 8) == 0 && (oc % 8) == 0;
+}
+
+size_t weak_grad_mfma_workspace(int oc, int k, int64_t M) {
+    int splits, chunk;
+    weak_grad_split(oc, M, splits, chunk);
+    return (size_t)splits * oc * k * sizeof(float);
+}
+
+hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
+                          void* dW, int out_f32, int accumulate, void* ws, hipStream_t s) {
+    static bool attr = false;
+    hipError_t e = raise_lds_limit((const void*)weak_grad_kernel, attr);
+    if (e != hipSuccess) return e;
+    int splits, chunk;
+    weak_grad_split(oc, M, splits, chunk);
+    weak_grad_kernel<<<ceil_div(oc, BT) * splits, 256, GEMM_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws,
+                                                                     splits, chunk);
+    const int64_t n = (int64_t)oc * k;
+    weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
+    return hipGetLastError();
 }
 
 }  // namespace qeft

@@ -1,0 +1,200 @@
+// Shared pieces of the tiled MFMA GEMM kernels (forward, input gradient, weak-column gradient).
+//
+// A workgroup of 4 waves (2 x 2) owns a 256 x 256 output tile C[i][j] = sum_k A[i][k] * B[j][k],
+// each wave 128 x 128 (4 x 4 MFMA 32x32x16 tiles, 256 fp32 accumulators per lane).  K advances
+// in stages of 64: both operand tiles are 256 rows x 64 halfs in LDS, rows of 128 bytes whose
+// 16-byte chunks are XOR-swizzled with the row number so that fragment reads and the producers'
+// writes are free of bank conflicts; two buffers per operand (128 KB of the CU's 160 KB).
+// The operand roles are chosen per kernel so that "i" runs along the contiguous dimension of
+// the result: a lane owns 4 consecutive i for one j, i.e. 8 (fp16) or 16 (fp32) contiguous bytes.
+#pragma once
+
+#include "qeft_internal.h"
+
+namespace qeft {
+namespace gemm {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+
+constexpr int BT = 256;                  // tile rows of either operand
+constexpr int BK = 64;                   // K per stage
+constexpr int TILE_BYTES = BT * BK * 2;  // 32 KB
+constexpr int GEMM_LDS = 4 * TILE_BYTES; // A0 A1 B0 B1
+
+__device__ __forceinline__ u4 ld16(const void* p) { return *reinterpret_cast<const u4*>(p); }
+__device__ __forceinline__ uint32_t h2_bits(h2 v) { return __builtin_bit_cast(uint32_t, v); }
+__device__ __forceinline__ h2 bits_h2(uint32_t v) { return __builtin_bit_cast(h2, v); }
+
+// byte offset of 16-byte chunk `c` (0..7) of row `r` inside a 256 x 64 half tile
+__device__ __forceinline__ int tile_off(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+
+// The two constants of the code -> fp16 conversion in vector registers the compiler cannot
+// see through, so that (w & mask) | magic selects the single v_and_or_b32.
+struct Consts {
+    uint32_t mask, magic;
+};
+__device__ __forceinline__ Consts make_consts() {
+    Consts c{0x000f000fu, 0x64006400u};
+    asm volatile("" : "+v"(c.mask), "+v"(c.magic));
+    return c;
+}
+
+// two codes (as 1024 + q in packed fp16) -> two weights: ((h - 1024) - z) * s.  The first
+// subtraction is exact, the second rounds once (exact for integer zero-points), the product once.
+__device__ __forceinline__ uint32_t dequant_pair(uint32_t hbits, h2 z2, h2 s2) {
+    const h2 k1024 = h2{(_Float16)1024.f, (_Float16)1024.f};
+    return h2_bits(((bits_h2(hbits) - k1024) - z2) * s2);
+}
+
+// 8 halfs x0..x7 -> (x0,x4)(x1,x5)(x2,x6)(x3,x7): the order nibbles leave the mask-and-or conversion
+__device__ __forceinline__ u4 permute_x(u4 v) {
+    u4 r;
+    r.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
+    r.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
+    r.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
+    r.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
+    return r;
+}
+
+// 8 x 8 half transpose in registers: in[e] holds 8 consecutive columns of row e; out[j] holds
+// column j of the 8 rows (rows ascending).
+__device__ __forceinline__ void transpose8x8(const u4 (&in)[8], u4 (&out)[8]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t sel = (j & 1) ? 0x07060302u : 0x05040100u;
+#pragma unroll
+        for (int p = 0; p < 4; ++p) out[j][p] = __builtin_amdgcn_perm(in[2 * p + 1][j >> 1], in[2 * p][j >> 1], sel);
+    }
+}
+
+__device__ __forceinline__ void zero_acc(f16v (&acc)[4][4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+}
+
+// The 64 MFMAs of one stage for wave (wm, wn).
+__device__ __forceinline__ void compute_stage(const unsigned char* sA, const unsigned char* sB, f16v (&acc)[4][4], int wm,
+                                              int wn, int lane) {
+    const int fr = lane & 31, fk = lane >> 5;  // fragment row within a 32-row MFMA tile, k half
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+        h8 a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i] = *reinterpret_cast<const h8*>(sA + tile_off(wm * 128 + i * 32 + fr, 2 * ks + fk));
+            b[i] = *reinterpret_cast<const h8*>(sB + tile_off(wn * 128 + i * 32 + fr, 2 * ks + fk));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+}
+
+// Producer of an operand tile whose k dimension is contiguous in memory: row r of the tile is
+// src[(row0 + r) * ld + col0 ...], 64 columns per stage.  Thread t takes chunks t + 256*u.
+struct RowLoader {
+    u4 v[8];
+    template <class Valid>
+    __device__ __forceinline__ void load(const __half* src, int64_t ld, int row0, int nrows, int col0, int ncols, int tid,
+                                         Valid clamp_rows) {
+        const u4 zero4 = u4{0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = tid + 256 * u, r = idx >> 3, c = idx & 7;
+            const int col = col0 + 8 * c;
+            int row = row0 + r;
+            bool ok = col < ncols;
+            if (clamp_rows) row = min(row, nrows - 1); else ok = ok && row < nrows;
+            v[u] = ok ? ld16(src + (size_t)row * ld + col) : zero4;
+        }
+    }
+    __device__ __forceinline__ void store(unsigned char* tile, int tid, bool permute) const {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int idx = tid + 256 * u, r = idx >> 3, c = idx & 7;
+            *reinterpret_cast<u4*>(tile + tile_off(r, c)) = permute ? permute_x(v[u]) : v[u];
+        }
+    }
+};
+
+// Producer of an operand tile whose k dimension is the ROW index of a row-major matrix:
+// tile row i, stage column kk is src[(k0 + kk) * ld + i0 + i].  Thread (ko = t / 32, io = t % 32)
+// loads an 8 x 8 block and transposes it in registers.
+struct ColLoader {
+    u4 v[8];
+    __device__ __forceinline__ void load(const __half* src, int64_t ld, int k0, int k_end, int i0, int i_end, int tid) {
+        const u4 zero4 = u4{0u, 0u, 0u, 0u};
+        const int ko = tid >> 5, io = tid & 31;
+        const int col = i0 + 8 * io;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = k0 + 8 * ko + e;
+            v[e] = (k < k_end && col < i_end) ? ld16(src + (size_t)k * ld + col) : zero4;
+        }
+    }
+    __device__ __forceinline__ void store(unsigned char* tile, int tid) const {
+        const int ko = tid >> 5, io = tid & 31;
+        u4 t[8];
+        transpose8x8(v, t);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) *reinterpret_cast<u4*>(tile + tile_off(8 * io + j, ko)) = t[j];
+    }
+};
+
+// Epilogue for fp16 results out[j][i]: accumulator element 4*g + r of a lane is i = 8*g + 4*(lane/32) + r,
+// j = lane % 32 of its 32 x 32 tile.  ni must be a multiple of 4.
+__device__ __forceinline__ void store_f16(const f16v (&acc)[4][4], __half* out, int64_t ld, int i0, int ni, int j0, int nj,
+                                          int wm, int wn, int lane) {
+    const int fr = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+        const int j = j0 + wn * 128 + tj * 32 + fr;
+        if (j >= nj) continue;
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int i = i0 + wm * 128 + ti * 32 + 8 * g + 4 * fk;
+                if (i < ni) {
+                    const h2 lo = h2{(_Float16)acc[ti][tj][4 * g + 0], (_Float16)acc[ti][tj][4 * g + 1]};
+                    const h2 hi = h2{(_Float16)acc[ti][tj][4 * g + 2], (_Float16)acc[ti][tj][4 * g + 3]};
+                    *reinterpret_cast<u2*>(out + (size_t)j * ld + i) = u2{h2_bits(lo), h2_bits(hi)};
+                }
+            }
+        }
+    }
+}
+
+// Same for fp32 results (16-byte stores).
+__device__ __forceinline__ void store_f32(const f16v (&acc)[4][4], float* out, int64_t ld, int i0, int ni, int j0, int nj,
+                                          int wm, int wn, int lane) {
+    const int fr = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+        const int j = j0 + wn * 128 + tj * 32 + fr;
+        if (j >= nj) continue;
+#pragma unroll
+        for (int ti = 0; ti < 4; ++ti) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int i = i0 + wm * 128 + ti * 32 + 8 * g + 4 * fk;
+                if (i < ni)
+                    *reinterpret_cast<f4*>(out + (size_t)j * ld + i) =
+                        f4{acc[ti][tj][4 * g + 0], acc[ti][tj][4 * g + 1], acc[ti][tj][4 * g + 2], acc[ti][tj][4 * g + 3]};
+            }
+        }
+    }
+}
+
+}  // namespace gemm
+}  // namespace qeft
