@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused mixed-precision linear layer on one MI355X.
+
+One step = one pass of the whole hot path over synthetic inputs with the Llama-2 7B layer
+shapes (4-bit, group 128, k = 128 weak columns):
+
+  decode     one decoder block at M = 1: 7 matrix-vector launches (q, k, v, o, gate, up, down),
+             each step on a different packed copy of the block (> 1 GB in rotation, so the
+             weights come from HBM, not from the 256 MB last-level cache); the 7 launches are
+             replayed from a HIP graph so that the GPU, not Python, sets the pace
+  fine-tune  M = 4096 tokens on the three layer shapes: forward, dX through the full mixed
+             weight, dW of the weak columns
+  pack       min-max round-to-nearest quantization + packing of one 4096 x 4096 layer
+
+`value` is the decode figure of the metric (stored weight bytes of the block / time of the
+decode segment); the fine-tune TFLOP/s is reported beside it.  Everything is timed with HIP
+events on the stream the kernels run on.  Prints one JSON line.
+"""
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_08661_amd import binding as B
+    from paper_2410_08661_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+    bits, g, k = 4, 128, 128
+    block_shapes = synth.LLAMA_7B_BLOCK            # 7 launches of one decoder block
+    ft_shapes = synth.LLAMA_7B                     # the three distinct shapes
+    M_ft = 4096
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.seed_for(2, 0))
+
+    def synth_weight(oc, ic):
+        return (torch.randn((oc, ic), generator=gen, device=dev, dtype=torch.float32) * 0.02).half()
+
+    def synth_x(m, ic):
+        x = torch.randn((m, ic), generator=gen, device=dev, dtype=torch.float32)
+        x[:, ic - k:] *= 20.0                      # the outlier channels that make columns weak
+        return x.half()
+
+    # ---- decode: enough distinct packed blocks to exceed 1 GB ------------------------------------
+    descs = {s: B.make_desc(s[0], s[1], k, bits, g) for s in set(block_shapes)}
+    block_bytes = 0
+    blocks = []
+    n_blocks = 10
+    for b in range(n_blocks):
+        layers = []
+        for s in block_shapes:
+            layers.append(B.qeft_pack(descs[s], synth_weight(*s)))
+        blocks.append(layers)
+    block_bytes = sum(l.nbytes() for l in blocks[0])
+    x1 = {ic: synth_x(1, ic) for ic in {s[1] for s in block_shapes}}
+    y1 = {oc: torch.empty((1, oc), dtype=torch.float16, device=dev) for oc in {s[0] for s in block_shapes}}
+
+    def decode_block(layers):
+        for s, l in zip(block_shapes, layers):
+            B.qeft_linear_fwd(descs[s], l, x1[s[1]], y1[s[0]])
+
+    decode_block(blocks[0])                        # first launch sets kernel attributes: outside capture
+    torch.cuda.synchronize()
+    graphs = []
+    cap_stream = torch.cuda.Stream()
+    for layers in blocks:
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=cap_stream):
+            decode_block(layers)
+        graphs.append(gr)
+
+    # ---- fine-tune operands -----------------------------------------------------------------------
+    ft = []
+    for s in ft_shapes:
+        oc, ic = s
+        d = descs[s]
+        x = synth_x(M_ft, ic)
+        dy = (torch.randn((M_ft, oc), generator=gen, device=dev, dtype=torch.float32) * 0.01).half()
+        ws_n = B.qeft_workspace_bytes(d, B.QEFT_OP_WEAK_GRAD, M_ft)
+        ft.append(dict(shape=s, desc=d, w=blocks[0][block_shapes.index(s)], x=x, dy=dy,
+                       y=torch.empty((M_ft, oc), dtype=torch.float16, device=dev),
+                       dx=torch.empty((M_ft, ic), dtype=torch.float16, device=dev),
+                       dw=torch.zeros((oc, k), dtype=torch.float32, device=dev),
+                       ws=torch.empty(max(ws_n, 1), dtype=torch.uint8, device=dev) if ws_n else None))
+    pack_w = synth_weight(4096, 4096)
+    pack_out = B.Weight(descs[(4096, 4096)])
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    records = []
+
+    def one_step(i, timed):
+        marks = [ev()]
+        marks[0].record()
+        graphs[i % n_blocks].replay()
+        marks.append(ev()); marks[-1].record()
+        for f in ft:
+            B.qeft_linear_fwd(f["desc"], f["w"], f["x"], f["y"])
+            marks.append(ev()); marks[-1].record()
+            B.qeft_linear_bwd_dx(f["desc"], f["w"], f["dy"], f["dx"])
+            marks.append(ev()); marks[-1].record()
+            B.qeft_weak_grad(f["desc"], f["dy"], f["x"][:, f["shape"][1] - k:], dW=f["dw"], ws=f["ws"])
+            marks.append(ev()); marks[-1].record()
+        B.qeft_pack(descs[(4096, 4096)], pack_w, pack_out)
+        marks.append(ev()); marks[-1].record()
+        if timed:
+            records.append(marks)
+
+    for i in range(args.warmup):
+        one_step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(args.warmup + i, True)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+
+    seg = np.array([[m[j].elapsed_time(m[j + 1]) for j in range(len(m) - 1)] for m in records])   # ms
+    mean = seg.mean(axis=0)
+    decode_ms = mean[0]
+    gemv_gbs = block_bytes / (decode_ms * 1e-3) / 1e9
+    kernels = []
+    flops_tot, ms_tot = 0.0, 0.0
+    for fi, f in enumerate(ft):
+        oc, ic = f["shape"]
+        t_fwd, t_dx, t_dw = mean[1 + 3 * fi], mean[2 + 3 * fi], mean[3 + 3 * fi]
+        fl = 2.0 * M_ft * oc * ic
+        fl_dw = 2.0 * M_ft * oc * k
+        flops_tot += 2 * fl + fl_dw
+        ms_tot += t_fwd + t_dx + t_dw
+        kernels.append(dict(shape=f"{oc}x{ic}", fwd_us=round(t_fwd * 1e3, 1), fwd_tflops=round(fl / t_fwd / 1e9, 1),
+                            dx_us=round(t_dx * 1e3, 1), dx_tflops=round(fl / t_dx / 1e9, 1),
+                            dw_us=round(t_dw * 1e3, 1), dw_dy_gbs=round(M_ft * oc * 2 / t_dw / 1e6, 1)))
+    ft_tflops = flops_tot / ms_tot / 1e9
+    # dominant kernel of the timed region: the dX GEMM (largest share of a step)
+    dx_fl = sum(2.0 * M_ft * f["shape"][0] * f["shape"][1] for f in ft)
+    dx_ms = sum(mean[2 + 3 * fi] for fi in range(len(ft)))
+    dx_tf = dx_fl / dx_ms / 1e9
+
+    out = {
+        "metric": "M=1 weight GB/s (% HBM peak); M=4096 fwd+bwd TFLOP/s (% MFMA peak)",
+        "value": round(gemv_gbs, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall_ms / args.steps, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {"workload": "Llama-2-7B layer shapes, w4 g128 k=128: decode block M=1 (7 launches, "
+                               f"{n_blocks} distinct packed blocks in rotation) + fine-tune M=4096 fwd+dX+dW_weak + pack",
+                   "block_bytes": block_bytes, "M_decode": 1, "M_finetune": M_ft},
+        "pct_hbm_peak": round(100 * gemv_gbs / HBM_PEAK_GBS, 2),
+        "decode_us_per_block": round(decode_ms * 1e3, 2),
+        "finetune_tflops": round(ft_tflops, 1),
+        "pct_mfma_peak": round(100 * ft_tflops / MFMA_F16_PEAK_TF, 2),
+        "pack_us": round(mean[-1] * 1e3, 1),
+        "finetune_kernels": kernels,
+        "roofline": {"kernel": "gemm_dx_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
+                     "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": None},
+        "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_gbs, 1),
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
+                          "traffic": None, "note": "per-block average over 7 graph-replayed launches, launch gaps included"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(np, synth, k, bits, g)
+    print(json.dumps(out))
+
+
+def cpu_baseline(np, synth, k, bits, g):
+    """The oracle as it stands, timed on the host: one 4096 x 4096 layer at M = 1
+    (unpack -> dequantize -> float64 product), scaled to the metric's unit."""
+    from oracle import qeft_oracle as qo
+    oc, ic = 4096, 4096
+    seed = synth.seed_for(2, 0)
+    w16 = synth.make_weight(oc, ic, seed)
+    x = synth.make_activations(1, ic, k, seed)
+    lay = qo.layout(oc, ic, k, bits, g)
+    codes, scales, zeros, weak = qo.quantize_rtn(w16, k, bits, g)
+    qweight = qo.pack_codes(codes, bits, lay["row_stride_words"])
+    nbytes = lay["qweight_bytes"] + lay["scales_bytes"] + lay["zeros_bytes"] + lay["weak_bytes"]
+    reps, t_wall, t_cpu = 0, 0.0, 0.0
+    while t_wall < 10.0 and reps < 50:
+        c0, w0 = time.process_time(), time.perf_counter()
+        w64 = qo.dequantize(qo.unpack_codes(qweight, lay["kq"], bits), scales, zeros, weak, g)
+        y = qo.round_fp16(qo.linear_fwd(w64, x))
+        t_wall += time.perf_counter() - w0
+        t_cpu += time.process_time() - c0
+        reps += 1
+    return {"value": round(nbytes * reps / t_wall / 1e9, 4), "unit": "GB/s",
+            "cores": max(1, int(math.ceil(t_cpu / t_wall - 0.05))), "kind": "oracle",
+            "sample": f"{reps} x (unpack + dequantize + fp64 product) of one 4096x4096 w4 g128 k128 layer at M=1, "
+                      f"{t_wall:.1f} s of host time"}
+
+
+if __name__ == "__main__":
+    main()

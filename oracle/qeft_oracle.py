@@ -101,8 +101,11 @@ def unpack_codes(qweight: np.ndarray, kq: int, bits: int) -> np.ndarray:
     oc = qweight.shape[0]
     mask = np.uint32((1 << bits) - 1)
     out = np.zeros((oc, kq), dtype=np.uint8)
-    for j in range(kq):
-        out[:, j] = ((qweight[:, j // per] >> np.uint32(bits * (j % per))) & mask).astype(np.uint8)
+    j = np.arange(kq)
+    word_of, shift_of = j // per, (bits * (j % per)).astype(np.uint32)
+    for r0 in range(0, oc, 1024):          # row blocks only bound the temporary's size
+        blk = qweight[r0:r0 + 1024]
+        out[r0:r0 + 1024] = ((blk[:, word_of] >> shift_of[None, :]) & mask).astype(np.uint8)
     return out
 
 
