@@ -16,6 +16,8 @@
 // Backward: the contraction runs across weight rows, so a thread takes the same word column of
 // 8 consecutive rows and pairs the rows with a byte permute before the conversion; the result is
 // already transposed, in natural order.
+#include <type_traits>
+
 #include "gemm_common.h"
 
 namespace qeft {
@@ -37,8 +39,9 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    // consecutive workgroups walk the OC tiles of one token panel: that panel of X stays in L2
-    const int t_oc = blockIdx.x % tiles_oc, t_m = blockIdx.x / tiles_oc;
+    const int tile = xcd_tile(tiles_oc * ((M + BT - 1) / BT));
+    if (tile < 0) return;
+    const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const int nq_st = (L.kq + BK - 1) / BK, nw_st = (L.k + BK - 1) / BK, nst = nq_st + nw_st;
     const Consts cst = make_consts();
@@ -100,6 +103,162 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
     store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wm, wn, lane);
 }
 
+// ------------------------------------------------------------------------- forward, software-pipelined
+// Same tiles, for Kq a multiple of 64.  A stage's 64 MFMAs run in four blocks of 16; between
+// the blocks the thread converts a quarter of the NEXT stage's raw data (already in registers)
+// into the other LDS buffer and immediately re-issues the global loads of the stage after that
+// into the registers just freed, so every load has a whole stage of MFMAs to land and the
+// conversion hides under the matrix pipe.  Fragment reads of block ks+1 are issued before the
+// MFMAs of block ks.  No load is conditional (rows are clamped, never masked), so the compiler's
+// load-counter waits are exact.  The weak block's k/64 stages follow unpipelined.
+__global__ __launch_bounds__(256) void gemm_fwd_pipe_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
+                                                            __half* __restrict__ Y, int64_t ldy, int tiles_oc) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tile = xcd_tile(tiles_oc * ((M + BT - 1) / BT));
+    if (tile < 0) return;
+    const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
+    const int oc0 = t_oc * BT, m0 = t_m * BT;
+    const int nq = L.kq / BK;
+    const Consts cst = make_consts();
+
+    // quantized A: rows ar and ar+128, half ah of the stage's 8 words
+    const int ar = tid >> 1, ah = tid & 1;
+    const int arow[2] = {min(oc0 + ar, L.oc - 1), min(oc0 + ar + 128, L.oc - 1)};
+    const uint32_t* wp[2] = {L.qweight + (size_t)arow[0] * L.stride + 4 * ah, L.qweight + (size_t)arow[1] * L.stride + 4 * ah};
+    const __half* sp[2] = {L.scales + (size_t)arow[0] * L.gs, L.scales + (size_t)arow[1] * L.gs};
+    const __half* zp[2] = {L.zeros + (size_t)arow[0] * L.gs, L.zeros + (size_t)arow[1] * L.gs};
+    // X: chunk u of this thread is tile row (tid >> 3) + 32 u, chunk column tid & 7
+    const int xr = tid >> 3, xc = tid & 7;
+    const __half* xp[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) xp[u] = X + (size_t)min(m0 + xr + 32 * u, M - 1) * ldx + 8 * xc;
+
+    u4 xv[8], av[2];
+    __half sraw[2], zraw[2];   // kept as loaded: combining them here would wait for the loads at once
+    auto load_a = [&](int rr, int st) {
+        av[rr] = ld16(wp[rr] + 8 * st);
+        sraw[rr] = sp[rr][st >> 1];
+        zraw[rr] = zp[rr][st >> 1];
+    };
+    auto load_x = [&](int u, int st) { xv[u] = ld16(xp[u] + BK * st); };
+    auto conv_a = [&](int rr, unsigned char* sA) {
+        const _Float16 sc = __builtin_bit_cast(_Float16, sraw[rr]), zv = __builtin_bit_cast(_Float16, zraw[rr]);
+        const h2 s2 = h2{sc, sc}, z2 = h2{zv, zv};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t w = av[rr][i];
+            u4 r;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) r[p] = dequant_pair(((w >> (4 * p)) & cst.mask) | cst.magic, z2, s2);
+            *reinterpret_cast<u4*>(sA + tile_off(ar + 128 * rr, 4 * ah + i)) = r;
+        }
+    };
+    auto conv_x = [&](int u, unsigned char* sB) {
+        *reinterpret_cast<u4*>(sB + tile_off(xr + 32 * u, xc)) = permute_x(xv[u]);
+    };
+
+    f16v acc[4][4];
+    zero_acc(acc);
+    Frags f, fn;
+
+    if (nq > 0) {
+        // prologue: stage 0 into LDS buffer 0, stage 1 into the registers
+#pragma unroll
+        for (int u = 0; u < 8; ++u) load_x(u, 0);
+        load_a(0, 0);
+        load_a(1, 0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) conv_x(u, lds + 2 * TILE_BYTES);
+        conv_a(0, lds);
+        conv_a(1, lds);
+        if (nq > 1) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) load_x(u, 1);
+            load_a(0, 1);
+            load_a(1, 1);
+        }
+        __syncthreads();
+        load_frags(f, lds, lds + 2 * TILE_BYTES, wm, wn, lane, 0);
+
+        // one stage: registers hold stage st+1; LOAD re-fills them with stage st+2 as they are converted
+        auto stage = [&](int st, auto flags) {
+            constexpr bool CONVERT = (decltype(flags)::value & 1) != 0, LOAD = (decltype(flags)::value & 2) != 0;
+            const int cur = st & 1;
+            const unsigned char* sA = lds + cur * TILE_BYTES;
+            const unsigned char* sB = lds + (2 + cur) * TILE_BYTES;
+            unsigned char* nA = lds + (cur ^ 1) * TILE_BYTES;
+            unsigned char* nB = lds + (2 + (cur ^ 1)) * TILE_BYTES;
+            // block 0
+            load_frags(fn, sA, sB, wm, wn, lane, 1);
+            mfma_block(f, acc);
+            if (CONVERT) {
+#pragma unroll
+                for (int u = 0; u < 3; ++u) {
+                    conv_x(u, nB);
+                    if (LOAD) load_x(u, st + 2);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);   // loads stay in the block that frees their registers
+            // block 1
+            load_frags(f, sA, sB, wm, wn, lane, 2);
+            mfma_block(fn, acc);
+            if (CONVERT) {
+#pragma unroll
+                for (int u = 3; u < 6; ++u) {
+                    conv_x(u, nB);
+                    if (LOAD) load_x(u, st + 2);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // block 2
+            load_frags(fn, sA, sB, wm, wn, lane, 3);
+            mfma_block(f, acc);
+            if (CONVERT) {
+#pragma unroll
+                for (int u = 6; u < 8; ++u) {
+                    conv_x(u, nB);
+                    if (LOAD) load_x(u, st + 2);
+                }
+                conv_a(0, nA);
+                if (LOAD) load_a(0, st + 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            // block 3
+            mfma_block(fn, acc);
+            if (CONVERT) {
+                conv_a(1, nA);
+                if (LOAD) load_a(1, st + 2);
+            }
+            __syncthreads();
+            if (CONVERT) load_frags(f, nA, nB, wm, wn, lane, 0);
+        };
+        int st = 0;
+        for (; st + 2 < nq; ++st) stage(st, std::integral_constant<int, 3>{});   // convert st+1, load st+2
+        if (st + 1 < nq) {
+            stage(st, std::integral_constant<int, 1>{});                        // convert the last stage
+            ++st;
+        }
+        stage(st, std::integral_constant<int, 0>{});
+    }
+
+    // ---- weak block: plain fp16 stages, one at a time --------------------------------------------
+    const int nw = (L.k + BK - 1) / BK;
+    for (int w = 0; w < nw; ++w) {
+        RowLoader la, lb;
+        la.load(L.weak, L.k, oc0, L.oc, BK * w, L.k, tid, true);
+        lb.load(X + L.kq, ldx, m0, M, BK * w, L.k, tid, false);
+        la.store(lds, tid, false);
+        lb.store(lds + 2 * TILE_BYTES, tid, false);
+        __syncthreads();
+        compute_stage(lds, lds + 2 * TILE_BYTES, acc, wm, wn, lane);
+        __syncthreads();
+    }
+    store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wm, wn, lane);
+}
+
 // ======================================================================================= backward dX
 // A[i = ic][k = oc] = W[oc][ic], B[j = m][k = oc] = dY[m][oc].  Thread (ko = t / 32, io = t % 32)
 // produces the 8 x 8 block of 8 weight rows x one word column (8 input channels).
@@ -116,7 +275,9 @@ __global__ __launch_bounds__(256) void gemm_dx_kernel(Layer L, const __half* __r
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
-    const int t_ic = blockIdx.x % tiles_ic, t_m = blockIdx.x / tiles_ic;
+    const int tile = xcd_tile(tiles_ic * ((M + BT - 1) / BT));
+    if (tile < 0) return;
+    const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
     const int ic0 = t_ic * BT, m0 = t_m * BT;
     const int nst = (L.oc + BK - 1) / BK;
     const Consts cst = make_consts();
@@ -266,7 +427,14 @@ hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __h
     hipError_t e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);
     if (e != hipSuccess) return e;
     const int tiles_oc = ceil_div(L.oc, BT), tiles_m = ceil_div(M, BT);
-    gemm_fwd_kernel<<<tiles_oc * tiles_m, 256, GEMM_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
+    if (L.kq > 0 && L.kq % BK == 0) {   // whole quantized stages: the software-pipelined kernel
+        static bool attr2 = false;
+        e = raise_lds_limit((const void*)gemm_fwd_pipe_kernel, attr2);
+        if (e != hipSuccess) return e;
+        gemm_fwd_pipe_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, GEMM_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
+    } else {
+        gemm_fwd_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, GEMM_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
+    }
     return hipGetLastError();
 }
 
@@ -280,7 +448,7 @@ hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __
     hipError_t e = raise_lds_limit((const void*)gemm_dx_kernel, attr);
     if (e != hipSuccess) return e;
     const int tiles_ic = ceil_div(L.ic, BT), tiles_m = ceil_div(M, BT);
-    gemm_dx_kernel<<<tiles_ic * tiles_m, 256, GEMM_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic);
+    gemm_dx_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, GEMM_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic);
     return hipGetLastError();
 }
 

@@ -30,8 +30,13 @@ __device__ __forceinline__ u4 ld16(const void* p) { return *reinterpret_cast<con
 __device__ __forceinline__ uint32_t h2_bits(h2 v) { return __builtin_bit_cast(uint32_t, v); }
 __device__ __forceinline__ h2 bits_h2(uint32_t v) { return __builtin_bit_cast(h2, v); }
 
-// byte offset of 16-byte chunk `c` (0..7) of row `r` inside a 256 x 64 half tile
-__device__ __forceinline__ int tile_off(int r, int c) { return r * 128 + ((c ^ (r & 7)) << 4); }
+// Byte offset of 16-byte chunk `c` (0..7) of row `r` inside a 256 x 64 half tile.  A row is one
+// 128-byte line = one pass over the LDS banks, which a 128-bit access makes with 8 lanes at a
+// time.  The chunk slot is XOR-ed with row bits 0..2 and 3..5 so that 8 neighbouring lanes hit 8
+// different slots in every access pattern the kernels use: fragment reads (8 consecutive rows, one
+// chunk), row-wise producer stores (one row x 8 chunks, or 4 rows x 2 half-rows) and transposing
+// producer stores (rows 8 apart, one chunk).  (Measured: SQ_LDS_BANK_CONFLICT.)
+__device__ __forceinline__ int tile_off(int r, int c) { return r * 128 + ((c ^ (r & 7) ^ ((r >> 3) & 7)) << 4); }
 
 // The two constants of the code -> fp16 conversion in vector registers the compiler cannot
 // see through, so that (w & mask) | magic selects the single v_and_or_b32.
@@ -72,6 +77,19 @@ __device__ __forceinline__ void transpose8x8(const u4 (&in)[8], u4 (&out)[8]) {
     }
 }
 
+// XCD-aware tile order.  Workgroup b runs on XCD b % 8, and each XCD has its own L2.  Tile v of
+// a row-major (slow index = activation panel) enumeration goes to the workgroup (v % per_xcd) * 8
+// + v / per_xcd, so that every XCD walks a contiguous range of tiles: the 32 workgroups resident
+// on an XCD then share one or two activation panels in that XCD's L2 instead of sixteen.
+// The grid is 8 * per_xcd workgroups; returns -1 for the few that have no tile.
+constexpr int N_XCD = 8;
+__device__ __forceinline__ int xcd_tile(int n_tiles) {
+    const int per_xcd = (n_tiles + N_XCD - 1) / N_XCD;
+    const int v = (int)(blockIdx.x % N_XCD) * per_xcd + (int)(blockIdx.x / N_XCD);
+    return v < n_tiles ? v : -1;
+}
+inline int xcd_grid(int n_tiles) { return N_XCD * ((n_tiles + N_XCD - 1) / N_XCD); }
+
 __device__ __forceinline__ void zero_acc(f16v (&acc)[4][4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -98,6 +116,26 @@ __device__ __forceinline__ void compute_stage(const unsigned char* sA, const uns
 #pragma unroll
             for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
+}
+
+// The same, split so that a caller can interleave other work between the four k blocks of a stage.
+struct Frags {
+    h8 a[4], b[4];
+};
+__device__ __forceinline__ void load_frags(Frags& f, const unsigned char* sA, const unsigned char* sB, int wm, int wn,
+                                           int lane, int ks) {
+    const int fr = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f.a[i] = *reinterpret_cast<const h8*>(sA + tile_off(wm * 128 + i * 32 + fr, 2 * ks + fk));
+        f.b[i] = *reinterpret_cast<const h8*>(sB + tile_off(wn * 128 + i * 32 + fr, 2 * ks + fk));
+    }
+}
+__device__ __forceinline__ void mfma_block(const Frags& f, f16v (&acc)[4][4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
 }
 
 // Producer of an operand tile whose k dimension is contiguous in memory: row r of the tile is
