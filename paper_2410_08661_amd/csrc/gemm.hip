@@ -103,160 +103,238 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
     store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wm, wn, lane);
 }
 
-// ------------------------------------------------------------------------- forward, software-pipelined
-// Same tiles, for Kq a multiple of 64.  A stage's 64 MFMAs run in four blocks of 16; between
-// the blocks the thread converts a quarter of the NEXT stage's raw data (already in registers)
-// into the other LDS buffer and immediately re-issues the global loads of the stage after that
-// into the registers just freed, so every load has a whole stage of MFMAs to land and the
-// conversion hides under the matrix pipe.  Fragment reads of block ks+1 are issued before the
-// MFMAs of block ks.  No load is conditional (rows are clamped, never masked), so the compiler's
-// load-counter waits are exact.  The weak block's k/64 stages follow unpipelined.
-__global__ __launch_bounds__(256) void gemm_fwd_pipe_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
+// ------------------------------------------------------------------------- forward, weights in registers
+// One packed word is 8 consecutive columns of one output channel - exactly the 8 k-values one
+// lane feeds into a 32x32x16 MFMA as its A operand.  So the quantized weights never touch LDS:
+// lane (fr, fk) of a wave fetches, for each of its four 32-row blocks, the 16 bytes holding words
+// 4 fk .. 4 fk + 3 of its row for the stage, and dequantizes word ks straight into the A fragment
+// of k-block ks (the k-blocks of a stage are numbered so that this works: block ks covers the
+// columns of words ks and 4 + ks; the X fragments are read from LDS chunk 4 fk + ks to match).
+// LDS holds only the activations (two 32 KB buffers), which halves the LDS traffic per MFMA of
+// the LDS-staged kernels; the price is that the two waves sharing a row block both convert it.
+//  * 4 waves (2 x 2), each 128 x 128; a stage is 16 slots of four MFMAs (one row block against
+//    the four X fragments); every slot also converts one word for the next k-block, reads one X
+//    fragment for it, and carries a share of the X staging (global -> registers -> nibble order
+//    -> LDS) and of the fetches; a scheduling barrier after each slot keeps that interleaving.
+//  * one workgroup barrier per stage, after slot 11; the last four slots read the next stage's
+//    first X fragments behind it.
+//  * scales / zero-points: 8 bytes (four groups) per row and array every 8 stages, latched into a
+//    packed register per row when the group changes.
+struct RegConsts {
+    uint32_t m0, m1, g0, g1;
+};
+__device__ __forceinline__ RegConsts make_reg_consts() {
+    RegConsts c{0x000f000fu, 0x00f000f0u, 0x64006400u, 0x54005400u};
+    asm volatile("" : "+v"(c.m0), "+v"(c.m1), "+v"(c.g0), "+v"(c.g1));
+    return c;
+}
+// word -> 8 weights in the order (c0,c4)(c1,c5)(c2,c6)(c3,c7).  Codes at bits 0..3 of a half
+// become 1024 + q, codes at bits 4..7 become 64 + q (exponent chosen so that mantissa bit 4
+// weighs 1); (h - base) is exact, then - z and * s as everywhere else.
+__device__ __forceinline__ h8 dequant_word(uint32_t w, uint32_t zs, const RegConsts& c) {
+    const h2 v = bits_h2(zs);
+    const h2 z2 = h2{v.x, v.x}, s2 = h2{v.y, v.y};
+    const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
+    const uint32_t w8 = w >> 8;
+    u4 r;
+    r.x = h2_bits(((bits_h2((w & c.m0) | c.g0) - b0) - z2) * s2);
+    r.y = h2_bits(((bits_h2((w & c.m1) | c.g1) - b1) - z2) * s2);
+    r.z = h2_bits(((bits_h2((w8 & c.m0) | c.g0) - b0) - z2) * s2);
+    r.w = h2_bits(((bits_h2((w8 & c.m1) | c.g1) - b1) - z2) * s2);
+    return __builtin_bit_cast(h8, r);
+}
+
+constexpr int REGA_LDS = 3 * TILE_BYTES;   // X0 X1, and one tile for the weak block's weights
+
+__global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                             __half* __restrict__ Y, int64_t ldy, int tiles_oc) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wr = wave >> 1, wc = wave & 1;
     const int tile = xcd_tile(tiles_oc * ((M + BT - 1) / BT));
     if (tile < 0) return;
     const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const int nq = L.kq / BK;
-    const Consts cst = make_consts();
+    const RegConsts cst = make_reg_consts();
+    using lds_u4 = __attribute__((address_space(3))) u4;
+    using lds_h8 = __attribute__((address_space(3))) h8;
+    using gptr = const __attribute__((address_space(1))) char*;
+    using g_u4 = const __attribute__((address_space(1))) u4;
+    using g_u2 = const __attribute__((address_space(1))) u2;
+    const int fr = lane & 31, fk = lane >> 5;
 
-    // quantized A: rows ar and ar+128, half ah of the stage's 8 words
-    const int ar = tid >> 1, ah = tid & 1;
-    const int arow[2] = {min(oc0 + ar, L.oc - 1), min(oc0 + ar + 128, L.oc - 1)};
-    const uint32_t* wp[2] = {L.qweight + (size_t)arow[0] * L.stride + 4 * ah, L.qweight + (size_t)arow[1] * L.stride + 4 * ah};
-    const __half* sp[2] = {L.scales + (size_t)arow[0] * L.gs, L.scales + (size_t)arow[1] * L.gs};
-    const __half* zp[2] = {L.zeros + (size_t)arow[0] * L.gs, L.zeros + (size_t)arow[1] * L.gs};
-    // X: chunk u of this thread is tile row (tid >> 3) + 32 u, chunk column tid & 7
-    const int xr = tid >> 3, xc = tid & 7;
-    const __half* xp[8];
+    // global addresses: wave-uniform 64-bit base (scalar registers) + 32-bit lane offset
+    const char* wt = reinterpret_cast<const char*>(L.qweight + (size_t)oc0 * L.stride);
+    const char* st_ = reinterpret_cast<const char*>(L.scales + (size_t)oc0 * L.gs);
+    const char* zt = reinterpret_cast<const char*>(L.zeros + (size_t)oc0 * L.gs);
+    const char* xt = reinterpret_cast<const char*>(X + (size_t)m0 * ldx);
+    uint32_t aoff[4], szoff[4], xoff[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) xp[u] = X + (size_t)min(m0 + xr + 32 * u, M - 1) * ldx + 8 * xc;
-
-    u4 xv[8], av[2];
-    __half sraw[2], zraw[2];   // kept as loaded: combining them here would wait for the loads at once
-    auto load_a = [&](int rr, int st) {
-        av[rr] = ld16(wp[rr] + 8 * st);
-        sraw[rr] = sp[rr][st >> 1];
-        zraw[rr] = zp[rr][st >> 1];
+    for (int i = 0; i < 4; ++i) {
+        const uint32_t row = (uint32_t)min(wr * 128 + 32 * i + fr, L.oc - 1 - oc0);
+        aoff[i] = (row * (uint32_t)L.stride + 4u * fk) * 4u;
+        szoff[i] = row * (uint32_t)L.gs * 2u;
+    }
+    const int xr = tid >> 3, xc = tid & 7;   // X chunk u of this thread: tile row xr + 32 u, chunk column xc
+#pragma unroll
+    for (int u = 0; u < 8; ++u) xoff[u] = ((uint32_t)min(xr + 32 * u, M - 1 - m0) * (uint32_t)ldx + 8u * xc) * 2u;
+    auto sbase = [](const char* p) {
+        asm volatile("" : "+s"(p));
+        return (gptr)p;
     };
-    auto load_x = [&](int u, int st) { xv[u] = ld16(xp[u] + BK * st); };
-    auto conv_a = [&](int rr, unsigned char* sA) {
-        const _Float16 sc = __builtin_bit_cast(_Float16, sraw[rr]), zv = __builtin_bit_cast(_Float16, zraw[rr]);
-        const h2 s2 = h2{sc, sc}, z2 = h2{zv, zv};
+
+    // LDS addresses: base register + compile-time offset.  Rows 64 apart share the swizzle, rows
+    // 32 apart differ in bit 2 of it, so chunk writes use two bases and fragment reads one base
+    // per XOR constant.
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    uint32_t xw[2] = {lds0 + (uint32_t)tile_off(xr, xc), lds0 + (uint32_t)tile_off(xr + 32, xc)};
+    uint32_t fb[8];
+    {
+        const uint32_t base = (uint32_t)((4 * fk) ^ (fr & 7) ^ (fr >> 3));
+#pragma unroll
+        for (int x = 0; x < 8; ++x) fb[x] = lds0 + (uint32_t)(wc * 128 + fr) * 128u + ((base ^ (uint32_t)x) << 4);
+    }
+
+    u4 araw[2][4];      // codes: set = stage parity, row block i; word ks of the stage in component ks
+    u4 xv[8];           // X of the stage after the current one
+    u2 szs[4], szz[4];  // scales / zero-points of four consecutive groups, per row block
+    uint32_t lsz[4];    // latched group: zero-point in the low half, scale in the high half
+    h8 afr[2][4], bfr[2][4];
+    auto load_a = [&](int set, int i, int st) { araw[set][i] = *reinterpret_cast<g_u4*>(sbase(wt + 32 * st) + aoff[i]); };
+    auto load_x = [&](int u, int st) { xv[u] = *reinterpret_cast<g_u4*>(sbase(xt + 2 * BK * st) + xoff[u]); };
+    auto load_sz = [&](int g4) {   // groups g4 .. g4 + 3 (g4 a multiple of 4; the arrays are padded to a multiple of 8 groups)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const uint32_t w = av[rr][i];
-            u4 r;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) r[p] = dequant_pair(((w >> (4 * p)) & cst.mask) | cst.magic, z2, s2);
-            *reinterpret_cast<u4*>(sA + tile_off(ar + 128 * rr, 4 * ah + i)) = r;
+            szs[i] = *reinterpret_cast<g_u2*>(sbase(st_ + 2 * g4) + szoff[i]);
+            szz[i] = *reinterpret_cast<g_u2*>(sbase(zt + 2 * g4) + szoff[i]);
         }
     };
-    auto conv_x = [&](int u, unsigned char* sB) {
-        *reinterpret_cast<u4*>(sB + tile_off(xr + 32 * u, xc)) = permute_x(xv[u]);
+    auto latch = [&](int g) {
+        const int sh = 16 * (g & 3);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint64_t s64 = ((uint64_t)szs[i].y << 32) | szs[i].x, z64 = ((uint64_t)szz[i].y << 32) | szz[i].x;
+            lsz[i] = ((uint32_t)(z64 >> sh) & 0xffffu) | ((uint32_t)(s64 >> sh) << 16);
+        }
+    };
+    auto put_x = [&](int u, int buf) {
+        *reinterpret_cast<lds_u4*>(xw[u & 1] + (uint32_t)((u >> 1) * 8192 + buf * TILE_BYTES)) = permute_x(xv[u]);
+    };
+    auto read_b = [&](int set, int j, int buf, int kn) {
+        bfr[set][j] = *reinterpret_cast<const lds_h8*>(fb[kn ^ (4 * (j & 1))] + (uint32_t)(j * 4096 + buf * TILE_BYTES));
     };
 
     f16v acc[4][4];
     zero_acc(acc);
-    Frags f, fn;
 
     if (nq > 0) {
-        // prologue: stage 0 into LDS buffer 0, stage 1 into the registers
+        const int s1 = min(1, nq - 1);
 #pragma unroll
         for (int u = 0; u < 8; ++u) load_x(u, 0);
-        load_a(0, 0);
-        load_a(1, 0);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) conv_x(u, lds + 2 * TILE_BYTES);
-        conv_a(0, lds);
-        conv_a(1, lds);
-        if (nq > 1) {
+        for (int i = 0; i < 4; ++i) load_a(0, i, 0);
+        load_sz(0);
 #pragma unroll
-            for (int u = 0; u < 8; ++u) load_x(u, 1);
-            load_a(0, 1);
-            load_a(1, 1);
+        for (int i = 0; i < 4; ++i) load_a(1, i, s1);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            put_x(u, 0);
+            load_x(u, s1);
         }
+        latch(0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) afr[0][i] = dequant_word(araw[0][i].x, lsz[i], cst);
         __syncthreads();
-        load_frags(f, lds, lds + 2 * TILE_BYTES, wm, wn, lane, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) read_b(0, j, 0, 0);
 
-        // one stage: registers hold stage st+1; LOAD re-fills them with stage st+2 as they are converted
-        auto stage = [&](int st, auto flags) {
-            constexpr bool CONVERT = (decltype(flags)::value & 1) != 0, LOAD = (decltype(flags)::value & 2) != 0;
-            const int cur = st & 1;
-            const unsigned char* sA = lds + cur * TILE_BYTES;
-            const unsigned char* sB = lds + (2 + cur) * TILE_BYTES;
-            unsigned char* nA = lds + (cur ^ 1) * TILE_BYTES;
-            unsigned char* nB = lds + (2 + (cur ^ 1)) * TILE_BYTES;
-            // block 0
-            load_frags(fn, sA, sB, wm, wn, lane, 1);
-            mfma_block(f, acc);
-            if (CONVERT) {
-#pragma unroll
-                for (int u = 0; u < 3; ++u) {
-                    conv_x(u, nB);
-                    if (LOAD) load_x(u, st + 2);
+        // stage st: X in buffer CUR, codes in set CUR
+        auto stage = [&](int st, auto cur_c) {
+            constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+            const int sl = min(st + 2, nq - 1);
+            // keep "base + constant" from being hoisted out of the loop into a register per constant:
+            // inside the stage it folds into the instruction's offset field
+            asm volatile("" : "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]), "+v"(fb[4]), "+v"(fb[5]), "+v"(fb[6]), "+v"(fb[7]));
+            asm volatile("" : "+v"(xw[0]), "+v"(xw[1]), "+v"(aoff[0]), "+v"(aoff[1]), "+v"(aoff[2]), "+v"(aoff[3]));
+            asm volatile("" : "+v"(xoff[0]), "+v"(xoff[1]), "+v"(xoff[2]), "+v"(xoff[3]), "+v"(xoff[4]), "+v"(xoff[5]), "+v"(xoff[6]), "+v"(xoff[7]));
+            auto slot = [&](auto s_c) {
+                constexpr int S = decltype(s_c)::value, ks = S >> 2, i = S & 3, kn = (ks + 1) & 3;
+                constexpr int SRC = ks < 3 ? CUR : NXT;   // where the next k-block comes from
+                if (S == 12 && CUR == 1) {
+                    // the next stage opens a new group: latch it, and when it was the last of the four
+                    // held in registers fetch the following four (needed two stages from now)
+                    const int g = min(st + 1, nq - 1) >> 1;
+                    latch(g);
+                    if ((g & 3) == 3 && 2 * (g + 1) < nq) load_sz(g + 1);
                 }
-            }
-            __builtin_amdgcn_sched_barrier(0);   // loads stay in the block that frees their registers
-            // block 1
-            load_frags(f, sA, sB, wm, wn, lane, 2);
-            mfma_block(fn, acc);
-            if (CONVERT) {
 #pragma unroll
-                for (int u = 3; u < 6; ++u) {
-                    conv_x(u, nB);
-                    if (LOAD) load_x(u, st + 2);
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                read_b(kn & 1, i, SRC, kn);
+                afr[kn & 1][i] = dequant_word(araw[SRC][i][kn], lsz[i], cst);
+                if (S < 8) {
+                    put_x(S, NXT);
+                    load_x(S, sl);
                 }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // block 2
-            load_frags(fn, sA, sB, wm, wn, lane, 3);
-            mfma_block(f, acc);
-            if (CONVERT) {
-#pragma unroll
-                for (int u = 6; u < 8; ++u) {
-                    conv_x(u, nB);
-                    if (LOAD) load_x(u, st + 2);
-                }
-                conv_a(0, nA);
-                if (LOAD) load_a(0, st + 2);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            // block 3
-            mfma_block(fn, acc);
-            if (CONVERT) {
-                conv_a(1, nA);
-                if (LOAD) load_a(1, st + 2);
-            }
-            __syncthreads();
-            if (CONVERT) load_frags(f, nA, nB, wm, wn, lane, 0);
+                if (S >= 12) load_a(CUR, i, sl);
+                if (S == 11) __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            slot(std::integral_constant<int, 0>{});
+            slot(std::integral_constant<int, 1>{});
+            slot(std::integral_constant<int, 2>{});
+            slot(std::integral_constant<int, 3>{});
+            slot(std::integral_constant<int, 4>{});
+            slot(std::integral_constant<int, 5>{});
+            slot(std::integral_constant<int, 6>{});
+            slot(std::integral_constant<int, 7>{});
+            slot(std::integral_constant<int, 8>{});
+            slot(std::integral_constant<int, 9>{});
+            slot(std::integral_constant<int, 10>{});
+            slot(std::integral_constant<int, 11>{});
+            slot(std::integral_constant<int, 12>{});
+            slot(std::integral_constant<int, 13>{});
+            slot(std::integral_constant<int, 14>{});
+            slot(std::integral_constant<int, 15>{});
         };
         int st = 0;
-        for (; st + 2 < nq; ++st) stage(st, std::integral_constant<int, 3>{});   // convert st+1, load st+2
-        if (st + 1 < nq) {
-            stage(st, std::integral_constant<int, 1>{});                        // convert the last stage
-            ++st;
+        for (; st + 1 < nq; st += 2) {
+            stage(st, std::integral_constant<int, 0>{});
+            stage(st + 1, std::integral_constant<int, 1>{});
         }
-        stage(st, std::integral_constant<int, 0>{});
+        if (nq & 1) stage(st, std::integral_constant<int, 0>{});
+        __syncthreads();
     }
 
-    // ---- weak block: plain fp16 stages, one at a time --------------------------------------------
+    // ---- weak block: plain fp16 stages with both operands through LDS, one at a time ----------------
     const int nw = (L.k + BK - 1) / BK;
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    unsigned char* sA = lds + 2 * TILE_BYTES;
     for (int w = 0; w < nw; ++w) {
-        RowLoader la, lb;
-        la.load(L.weak, L.k, oc0, L.oc, BK * w, L.k, tid, true);
-        lb.load(X + L.kq, ldx, m0, M, BK * w, L.k, tid, false);
-        la.store(lds, tid, false);
-        lb.store(lds + 2 * TILE_BYTES, tid, false);
+        u4 wa[8], wb[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = xr + 32 * u, col = BK * w + 8 * xc;
+            wa[u] = (col < L.k) ? ld16(L.weak + (size_t)min(oc0 + r, L.oc - 1) * L.k + col) : zero4;
+            wb[u] = (col < L.k) ? ld16(X + (size_t)min(m0 + r, M - 1) * ldx + L.kq + col) : zero4;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            *reinterpret_cast<u4*>(sA + tile_off(xr + 32 * u, xc)) = wa[u];
+            *reinterpret_cast<u4*>(lds + tile_off(xr + 32 * u, xc)) = wb[u];
+        }
         __syncthreads();
-        compute_stage(lds, lds + 2 * TILE_BYTES, acc, wm, wn, lane);
+        Frags f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            load_frags(f, sA, lds, wr, wc, lane, ks);
+            mfma_block(f, acc);
+        }
         __syncthreads();
     }
-    store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wm, wn, lane);
+    store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wr, wc, lane);
 }
 
 // ======================================================================================= backward dX
@@ -423,16 +501,20 @@ bool gemm_fwd_supported(const Layer& L, int64_t M) {
 }
 
 hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
-    static bool attr = false;
-    hipError_t e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);
-    if (e != hipSuccess) return e;
     const int tiles_oc = ceil_div(L.oc, BT), tiles_m = ceil_div(M, BT);
-    if (L.kq > 0 && L.kq % BK == 0) {   // whole quantized stages: the software-pipelined kernel
-        static bool attr2 = false;
-        e = raise_lds_limit((const void*)gemm_fwd_pipe_kernel, attr2);
-        if (e != hipSuccess) return e;
-        gemm_fwd_pipe_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, GEMM_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
+    hipError_t e;
+    if (L.kq > 0 && L.kq % BK == 0) {   // whole quantized stages: weights dequantized in registers
+        static bool attr = false;
+        if (!attr) {
+            e = hipFuncSetAttribute((const void*)gemm_fwd_rega_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, REGA_LDS);
+            if (e != hipSuccess) return e;
+            attr = true;
+        }
+        gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
     } else {
+        static bool attr = false;
+        e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);
+        if (e != hipSuccess) return e;
         gemm_fwd_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, GEMM_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
     }
     return hipGetLastError();

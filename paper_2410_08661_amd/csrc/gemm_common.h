@@ -138,6 +138,51 @@ __device__ __forceinline__ void mfma_block(const Frags& f, f16v (&acc)[4][4]) {
         for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
 }
 
+// Generic wave tile of TI x TJ MFMA tiles whose first rows in the operand tiles are ra0 / rb0.
+template <int TI, int TJ>
+struct FragsT {
+    h8 a[TI], b[TJ];
+};
+template <int TI, int TJ>
+__device__ __forceinline__ void load_frags_t(FragsT<TI, TJ>& f, const unsigned char* sA, const unsigned char* sB, int ra0,
+                                             int rb0, int lane, int ks) {
+    const int fr = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < TI; ++i) f.a[i] = *reinterpret_cast<const h8*>(sA + tile_off(ra0 + i * 32 + fr, 2 * ks + fk));
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) f.b[j] = *reinterpret_cast<const h8*>(sB + tile_off(rb0 + j * 32 + fr, 2 * ks + fk));
+}
+template <int TI, int TJ>
+__device__ __forceinline__ void mfma_block_t(const FragsT<TI, TJ>& f, f16v (&acc)[TI][TJ]) {
+#pragma unroll
+    for (int i = 0; i < TI; ++i)
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+}
+// fp16 epilogue of such a wave tile: out[j][i], i0/j0 = global index of the wave tile's first row of A / B
+template <int TI, int TJ>
+__device__ __forceinline__ void store_f16_t(const f16v (&acc)[TI][TJ], __half* out, int64_t ld, int i0, int ni, int j0,
+                                            int nj, int lane) {
+    const int fr = lane & 31, fk = lane >> 5;
+#pragma unroll
+    for (int tj = 0; tj < TJ; ++tj) {
+        const int j = j0 + tj * 32 + fr;
+        if (j >= nj) continue;
+#pragma unroll
+        for (int ti = 0; ti < TI; ++ti) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int i = i0 + ti * 32 + 8 * g + 4 * fk;
+                if (i < ni) {
+                    const h2 lo = h2{(_Float16)acc[ti][tj][4 * g + 0], (_Float16)acc[ti][tj][4 * g + 1]};
+                    const h2 hi = h2{(_Float16)acc[ti][tj][4 * g + 2], (_Float16)acc[ti][tj][4 * g + 3]};
+                    *reinterpret_cast<u2*>(out + (size_t)j * ld + i) = u2{h2_bits(lo), h2_bits(hi)};
+                }
+            }
+        }
+    }
+}
+
 // Producer of an operand tile whose k dimension is contiguous in memory: row r of the tile is
 // src[(row0 + r) * ld + col0 ...], 64 columns per stage.  Thread t takes chunks t + 256*u.
 struct RowLoader {
