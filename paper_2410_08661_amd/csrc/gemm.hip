@@ -16,6 +16,7 @@
 // Backward: the contraction runs across weight rows, so a thread takes the same word column of
 // 8 consecutive rows and pairs the rows with a byte permute before the conversion; the result is
 // already transposed, in natural order.
+#include <cstdlib>
 #include <type_traits>
 
 #include "gemm_common.h"
@@ -348,7 +349,7 @@ struct DxStage {
 };
 
 __global__ __launch_bounds__(256) void gemm_dx_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
-                                                      __half* __restrict__ dX, int64_t lddx, int tiles_ic) {
+                                                      __half* __restrict__ dX, int64_t lddx, int tiles_ic, int ic_start) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -356,7 +357,7 @@ __global__ __launch_bounds__(256) void gemm_dx_kernel(Layer L, const __half* __r
     const int tile = xcd_tile(tiles_ic * ((M + BT - 1) / BT));
     if (tile < 0) return;
     const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
-    const int ic0 = t_ic * BT, m0 = t_m * BT;
+    const int ic0 = ic_start + t_ic * BT, m0 = t_m * BT;
     const int nst = (L.oc + BK - 1) / BK;
     const Consts cst = make_consts();
 
@@ -417,6 +418,424 @@ __global__ __launch_bounds__(256) void gemm_dx_kernel(Layer L, const __half* __r
         __syncthreads();
     }
     store_f16(acc, dX, lddx, ic0, L.ic, m0, M, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------- backward dX, weights in registers
+// C[i = ic][j = m] = sum_oc W[oc][ic] dY[m][oc].  The A operand of a 32x32x16 MFMA wants, per
+// lane, 8 consecutive k = 8 consecutive weight ROWS of one input channel, while the stored
+// matrices run along the channels.  Both kinds of weight therefore pass through LDS as "lines":
+// one line holds, for the stage's 64 rows, one 16-bit column of the stored matrix, two rows to a
+// 32-bit word - so 16 bytes of a line are 8 consecutive rows, paired along k.
+//  * Quantized half (128 channels = 16 word columns, one group): line (W, h) is the 16-bit half h
+//    of word column W, i.e. raw 4-bit codes, an eighth of the fp16 tile.  Lane (fr, fk) reads rows
+//    16 ks + 8 fk .. + 7 of line (fr / 2, fr % 2): four registers whose nibble i (of both halves)
+//    is channel 4 fr + i.  A fragment i is then one mask-and-or per register (no permute), and a
+//    lane's four accumulators for fixed (row, column) are four consecutive channels of dX.
+//    Scales and zero-points vary along k here: they are staged as fp16 vectors per row.
+//  * Weak half (128 fp16 channels): a line is simply one channel; 16 bytes of it are an A fragment
+//    as it stands.  Fragment i of lane fr is channel fr + 32 i.
+// Everything else is the forward kernel's pipeline: 4 waves of 128 x 128, 16 slots of four MFMAs
+// per stage, quantized fragments converted three slots ahead, dY staged through LDS unchanged,
+// one barrier per stage after slot 11.  A tile is 256 channels = two halves, each quantized or
+// weak (Kq is a multiple of 128 here); the two waves that own a half follow its kind.
+// Requires OC % 64 == 0, Kq % 128 == 0 and k % 8 == 0.
+constexpr int DX_LINE = 144;                      // 64 rows x 2 bytes + 16: consecutive lines 4 banks apart
+constexpr int DX_HALF = 128 * DX_LINE;            // lines of one half (a quantized half uses the first 32)
+constexpr int DX_LINES = 2 * DX_HALF;
+constexpr int DX_SZ = 2 * 2 * 64 * 2;             // [half][zero, scale][row] fp16
+constexpr int DX_LINE_BASE = 2 * TILE_BYTES;      // dY0 dY1 | lines0 lines1 | sz0 sz1
+constexpr int DX_SZ_BASE = DX_LINE_BASE + 2 * DX_LINES;
+constexpr int DX_LDS = DX_SZ_BASE + 2 * DX_SZ;
+
+template <int H0, int H1>   // kinds of the tile's two halves: 0 quantized, 1 weak
+__device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict__ dY, int M, int64_t lddy,
+                                        __half* __restrict__ dX, int64_t lddx, int ic0, int m0, unsigned char* lds) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wr = wave >> 1, wc = wave & 1;
+    const int nst = L.oc / BK;
+    const RegConsts cst = make_reg_consts();
+    using lds_u4 = __attribute__((address_space(3))) u4;
+    using lds_u32 = __attribute__((address_space(3))) uint32_t;
+    using lds_u16 = __attribute__((address_space(3))) unsigned short;
+    using lds_h8 = __attribute__((address_space(3))) h8;
+    using gptr = const __attribute__((address_space(1))) char*;
+    using g_u4 = const __attribute__((address_space(1))) u4;
+    using g_u16 = const __attribute__((address_space(1))) unsigned short;
+    constexpr bool ANYQ = H0 == 0 || H1 == 0;
+    constexpr int NW = 2 * (H0 + H1);   // weak items per thread: (row pair, 8 channels) blocks
+    const int fr = lane & 31, fk = lane >> 5;
+    auto sbase = [](const char* p) {
+        asm volatile("" : "+s"(p));
+        return (gptr)p;
+    };
+
+    // ---- producers: global addresses (wave-uniform 64-bit base + 32-bit lane offset) ---------------
+    // dY: chunk u of this thread is tile row xr + 32 u, chunk column xc
+    const int xr = tid >> 3, xc = tid & 7;
+    const char* dyt = reinterpret_cast<const char*>(dY + (size_t)m0 * lddy);
+    uint32_t dyoff[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) dyoff[u] = ((uint32_t)min(xr + 32 * u, M - 1 - m0) * (uint32_t)lddy + 8u * xc) * 2u;
+    // codes: rows 2 rp, 2 rp + 1 of the stage, word columns 4 xc .. 4 xc + 3 of the tile, i.e. of half
+    // xc / 4 (columns past the stored row are clamped; such channels are never stored)
+    const int rp = tid >> 3;
+    const bool code_thread = H0 == 0 && (H1 == 0 || xc < 4);
+    uint32_t coff = ((uint32_t)(2 * rp) * (uint32_t)L.stride + (uint32_t)min((ic0 >> 3) + 4 * xc, L.stride - 4)) * 4u;
+    const char* wt = reinterpret_cast<const char*>(L.qweight);
+    const size_t wstage = (size_t)BK * L.stride * 4, wrow = (size_t)L.stride * 4;
+    // scales / zero-points: thread (row = tid % 64, half = tid / 64 % 2) of waves 0 and 1
+    const bool sz_wave = H0 == 0 && (H1 == 0 ? wave < 2 : wave < 1);
+    uint32_t szoff = ((uint32_t)(tid & 63) * (uint32_t)L.gs + (uint32_t)min((ic0 >> 7) + ((tid >> 6) & 1), L.gs - 1)) * 2u;
+    const char* st_ = reinterpret_cast<const char*>(L.scales);
+    const char* zt = reinterpret_cast<const char*>(L.zeros);
+    const size_t szstage = (size_t)BK * L.gs * 2;
+    // weak: item n of this thread is rows 2 rp, 2 rp + 1 x channels 8 c .. 8 c + 7 of a weak half,
+    // c = xc + 8 (n % 2); the halves in the order they are weak (channel blocks past k are clamped)
+    uint32_t woff[NW > 0 ? NW : 1];
+    const char* wkt = reinterpret_cast<const char*>(L.weak);
+    const size_t wkstage = (size_t)BK * L.k * 2, wkrow = (size_t)L.k * 2;
+#pragma unroll
+    for (int n = 0; n < NW; ++n) {
+        const int half = (H0 == 1) ? n / 2 : 1;
+        const int kc = ic0 + 128 * half - L.kq + 8 * (xc + 8 * (n & 1));
+        woff[n] = ((uint32_t)(2 * rp) * (uint32_t)L.k + (uint32_t)max(min(kc, L.k - 8), 0)) * 2u;
+    }
+
+    // ---- LDS addresses: base register + compile-time offset ---------------------------------------
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    uint32_t xw[2] = {lds0 + (uint32_t)tile_off(xr, xc), lds0 + (uint32_t)tile_off(xr + 32, xc)};
+    uint32_t fb[4];   // dY fragments, indexed by (XOR constant) / 2
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+        fb[x] = lds0 + (uint32_t)(wc * 128 + fr) * 128u + ((((uint32_t)(fk ^ (fr & 7) ^ (fr >> 3))) ^ (2u * x)) << 4);
+    // lines: the 16-byte chunk t of a line (rows 8 t .. 8 t + 7) sits at slot t ^ (line / 8 % 8), so that
+    // the eight threads that write one row pair into eight different line groups spread over the banks
+    const uint32_t lw = (((uint32_t)((rp >> 2) ^ xc)) << 4) + (uint32_t)(rp & 3) * 4u;   // position of row pair rp, line group xc (mod 8)
+    uint32_t cwr = lds0 + DX_LINE_BASE + (uint32_t)(xc >> 2) * DX_HALF + (uint32_t)(8 * (xc & 3)) * DX_LINE + lw;
+    uint32_t wwr[NW > 0 ? NW : 1];
+#pragma unroll
+    for (int n = 0; n < NW; ++n) {
+        const int half = (H0 == 1) ? n / 2 : 1;
+        wwr[n] = lds0 + DX_LINE_BASE + (uint32_t)half * DX_HALF + (uint32_t)(8 * (xc + 8 * (n & 1))) * DX_LINE + lw;
+    }
+    uint32_t szw = lds0 + DX_SZ_BASE + (uint32_t)((tid >> 6) & 1) * 256u + (uint32_t)(tid & 63) * 2u;
+
+    u4 dyv[8];            // dY of the stage after the current one
+    u4 cw0, cw1;          // its code words (two rows)
+    unsigned short sv, zv;
+    u4 ww[NW > 0 ? NW : 1][2];   // its weak blocks (two rows each)
+    auto load_dy = [&](int u, int st) { dyv[u] = *reinterpret_cast<g_u4*>(sbase(dyt + 2 * BK * st) + dyoff[u]); };
+    auto load_codes = [&](int st) {
+        if (code_thread) {
+            cw0 = *reinterpret_cast<g_u4*>(sbase(wt + st * wstage) + coff);
+            cw1 = *reinterpret_cast<g_u4*>(sbase(wt + st * wstage + wrow) + coff);
+        }
+    };
+    auto load_sz = [&](int st) {
+        if (sz_wave) {
+            sv = *reinterpret_cast<g_u16*>(sbase(st_ + st * szstage) + szoff);
+            zv = *reinterpret_cast<g_u16*>(sbase(zt + st * szstage) + szoff);
+        }
+    };
+    auto load_weak = [&](int n, int st) {
+        ww[n][0] = *reinterpret_cast<g_u4*>(sbase(wkt + st * wkstage) + woff[n]);
+        ww[n][1] = *reinterpret_cast<g_u4*>(sbase(wkt + st * wkstage + wkrow) + woff[n]);
+    };
+    auto put_dy = [&](int u, int buf) {
+        *reinterpret_cast<lds_u4*>(xw[u & 1] + (uint32_t)((u >> 1) * 8192 + buf * TILE_BYTES)) = dyv[u];
+    };
+    auto put_codes = [&](int q, int buf) {   // word column 4 xc + q: low halves of both rows, high halves
+        if (code_thread) {
+            *reinterpret_cast<lds_u32*>(cwr + (uint32_t)((2 * q) * DX_LINE + buf * DX_LINES)) =
+                __builtin_amdgcn_perm(cw1[q], cw0[q], 0x05040100u);
+            *reinterpret_cast<lds_u32*>(cwr + (uint32_t)((2 * q + 1) * DX_LINE + buf * DX_LINES)) =
+                __builtin_amdgcn_perm(cw1[q], cw0[q], 0x07060302u);
+        }
+    };
+    auto put_sz = [&](int buf) {
+        if (sz_wave) {
+            *reinterpret_cast<lds_u16*>(szw + (uint32_t)(buf * DX_SZ)) = zv;
+            *reinterpret_cast<lds_u16*>(szw + (uint32_t)(128 + buf * DX_SZ)) = sv;
+        }
+    };
+    auto put_weak = [&](int n, int buf) {    // channel e of the block: rows 2 rp | 2 rp + 1
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            *reinterpret_cast<lds_u32*>(wwr[n] + (uint32_t)(e * DX_LINE + buf * DX_LINES)) =
+                __builtin_amdgcn_perm(ww[n][1][e >> 1], ww[n][0][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
+    };
+
+    f16v acc[4][4];
+    zero_acc(acc);
+
+    // ---- stage 0 into buffer 0, stage 1 into the registers ------------------------------------------
+    {
+        const int s1 = min(1, nst - 1);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) load_dy(u, 0);
+        if (ANYQ) {
+            load_codes(0);
+            load_sz(0);
+        }
+#pragma unroll
+        for (int n = 0; n < NW; ++n) load_weak(n, 0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            put_dy(u, 0);
+            load_dy(u, s1);
+        }
+        if (ANYQ) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) put_codes(q, 0);
+            load_codes(s1);
+            put_sz(0);
+            load_sz(s1);
+        }
+#pragma unroll
+        for (int n = 0; n < NW; ++n) {
+            put_weak(n, 0);
+            load_weak(n, s1);
+        }
+        __syncthreads();
+    }
+
+    // this slot's share of staging stage st+1 into buffer NXT and fetching stage sl
+    auto produce = [&](auto s_c, auto nxt_c, int sl) {
+        constexpr int S = decltype(s_c)::value, NXT = decltype(nxt_c)::value;
+        if (S < 8) {
+            put_dy(S, NXT);
+            load_dy(S, sl);
+        }
+        if (ANYQ) {
+            if (S == 8) {
+                put_codes(0, NXT);
+                put_codes(1, NXT);
+            } else if (S == 9) {
+                put_codes(2, NXT);
+                put_codes(3, NXT);
+                load_codes(sl);
+            } else if (S == 10) {
+                put_sz(NXT);
+                load_sz(sl);
+            }
+        }
+        constexpr int n = S - (12 - NW);   // weak items in the last slots before the barrier
+        if (NW > 0 && n >= 0 && n < NW) {
+            put_weak(n, NXT);
+            load_weak(n, sl);
+        }
+    };
+    auto protect = [&]() {   // keep "base + constant" out of loop-invariant registers: it folds into the offset field
+        asm volatile("" : "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]), "+v"(xw[0]), "+v"(xw[1]), "+v"(cwr), "+v"(szw), "+v"(coff), "+v"(szoff));
+        asm volatile("" : "+v"(dyoff[0]), "+v"(dyoff[1]), "+v"(dyoff[2]), "+v"(dyoff[3]), "+v"(dyoff[4]), "+v"(dyoff[5]), "+v"(dyoff[6]), "+v"(dyoff[7]));
+#pragma unroll
+        for (int n = 0; n < NW; ++n) asm volatile("" : "+v"(woff[n]), "+v"(wwr[n]));
+    };
+    h8 afr[4], bfr[2][4];
+    auto read_b = [&](int set, int j, int buf, int kn) {
+        bfr[set][j] = *reinterpret_cast<const lds_h8*>(fb[kn ^ (2 * (j & 1))] + (uint32_t)(j * 4096 + buf * TILE_BYTES));
+    };
+    const int icw = ic0 + 128 * wr;
+
+    // ---- a wave that owns a quantized half ---------------------------------------------------------------
+    auto run_quant = [&]() {
+        uint32_t crd[4];  // code lines, indexed by k-block
+        {
+            // line fr = (word column fr / 2, half fr % 2) of this wave's half; its line group for the
+            // chunk swizzle is the writer's xc = fr / 8 + 4 wr
+            const int cl = (fr >> 3) + 4 * wr;
+#pragma unroll
+            for (int kn = 0; kn < 4; ++kn)
+                crd[kn] = lds0 + DX_LINE_BASE + (uint32_t)wr * DX_HALF + (uint32_t)fr * DX_LINE + ((uint32_t)((fk ^ cl) ^ (2 * kn)) << 4);
+        }
+        uint32_t szr = lds0 + DX_SZ_BASE + (uint32_t)wr * 256u + 16u * fk;
+        u4 cf[2];         // code fragment of a k-block: register p = rows 2p | 2p+1 (set = block parity)
+        h8 zf[2], sf[2];  // zero-points and scales of its 8 rows
+        auto read_codes = [&](int set, int buf, int kn) {
+            cf[set] = *reinterpret_cast<const lds_u4*>(crd[kn] + (uint32_t)(buf * DX_LINES));
+            zf[set] = *reinterpret_cast<const lds_h8*>(szr + (uint32_t)(32 * kn + buf * DX_SZ));
+            sf[set] = *reinterpret_cast<const lds_h8*>(szr + (uint32_t)(128 + 32 * kn + buf * DX_SZ));
+        };
+        auto convert = [&](int i, int set) {   // A fragment i (channel 4 fr + i) of the block held in `set`
+            const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
+            u4 r;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t w = (i & 2) ? cf[set][p] >> 8 : cf[set][p];
+                const h2 t = (i & 1) ? bits_h2((w & cst.m1) | cst.g1) - b1 : bits_h2((w & cst.m0) | cst.g0) - b0;
+                const h2 z2 = h2{zf[set][2 * p], zf[set][2 * p + 1]}, s2 = h2{sf[set][2 * p], sf[set][2 * p + 1]};
+                r[p] = h2_bits((t - z2) * s2);
+            }
+            afr[i] = __builtin_bit_cast(h8, r);
+        };
+        read_codes(0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) read_b(0, j, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) convert(i, 0);
+
+        auto stage = [&](int st, auto cur_c) {
+            constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+            const int sl = min(st + 2, nst - 1);
+            protect();
+            asm volatile("" : "+v"(crd[0]), "+v"(crd[1]), "+v"(crd[2]), "+v"(crd[3]), "+v"(szr));
+            auto slot = [&](auto s_c) {
+                constexpr int S = decltype(s_c)::value, ks = S >> 2, i = S & 3, kn = (ks + 1) & 3;
+                constexpr int SRC = ks < 3 ? CUR : NXT;   // where the next k-block comes from
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                // dY fragments one block ahead, codes of the next block at its predecessor's first slot,
+                // A fragments three slots ahead of their MFMAs
+                read_b(kn & 1, i, SRC, kn);
+                if (i == 0) {
+                    convert(3, ks & 1);
+                    read_codes(kn & 1, SRC, kn);
+                } else {
+                    convert(i - 1, kn & 1);
+                }
+                produce(s_c, std::integral_constant<int, NXT>{}, sl);
+                if (S == 11) __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            slot(std::integral_constant<int, 0>{});
+            slot(std::integral_constant<int, 1>{});
+            slot(std::integral_constant<int, 2>{});
+            slot(std::integral_constant<int, 3>{});
+            slot(std::integral_constant<int, 4>{});
+            slot(std::integral_constant<int, 5>{});
+            slot(std::integral_constant<int, 6>{});
+            slot(std::integral_constant<int, 7>{});
+            slot(std::integral_constant<int, 8>{});
+            slot(std::integral_constant<int, 9>{});
+            slot(std::integral_constant<int, 10>{});
+            slot(std::integral_constant<int, 11>{});
+            slot(std::integral_constant<int, 12>{});
+            slot(std::integral_constant<int, 13>{});
+            slot(std::integral_constant<int, 14>{});
+            slot(std::integral_constant<int, 15>{});
+        };
+        int st = 0;
+        for (; st + 1 < nst; st += 2) {
+            stage(st, std::integral_constant<int, 0>{});
+            stage(st + 1, std::integral_constant<int, 1>{});
+        }
+        if (nst & 1) stage(st, std::integral_constant<int, 0>{});
+
+        // a lane's accumulators (t_i = 0..3) for fixed row 8 g + 4 fk + e are channels 4 row + t_i
+#pragma unroll
+        for (int tj = 0; tj < 4; ++tj) {
+            const int m = m0 + wc * 128 + tj * 32 + fr;
+            if (m >= M) continue;
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int ic = icw + 4 * (8 * g + 4 * fk + e);
+                    if (ic < L.kq) {
+                        const h2 lo = h2{(_Float16)acc[0][tj][4 * g + e], (_Float16)acc[1][tj][4 * g + e]};
+                        const h2 hi = h2{(_Float16)acc[2][tj][4 * g + e], (_Float16)acc[3][tj][4 * g + e]};
+                        *reinterpret_cast<u2*>(dX + (size_t)m * lddx + ic) = u2{h2_bits(lo), h2_bits(hi)};
+                    }
+                }
+        }
+    };
+
+    // ---- a wave that owns a weak half --------------------------------------------------------------------
+    auto run_weak = [&]() {
+        uint32_t wrd[4];  // weak lines of fragment 0, indexed by (XOR constant) / 2; fragment i is 32 lines on
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+            wrd[x] = lds0 + DX_LINE_BASE + (uint32_t)wr * DX_HALF + (uint32_t)fr * DX_LINE + ((uint32_t)((fk ^ (fr >> 3)) ^ (2 * x)) << 4);
+        auto read_a = [&](int i, int buf, int kn) {
+            afr[i] = *reinterpret_cast<const lds_h8*>(wrd[kn ^ (2 * (i & 1))] + (uint32_t)(i * 32 * DX_LINE + buf * DX_LINES));
+        };
+#pragma unroll
+        for (int j = 0; j < 4; ++j) read_b(0, j, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) read_a(i, 0, 0);
+
+        auto stage = [&](int st, auto cur_c) {
+            constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+            const int sl = min(st + 2, nst - 1);
+            protect();
+            asm volatile("" : "+v"(wrd[0]), "+v"(wrd[1]), "+v"(wrd[2]), "+v"(wrd[3]));
+            auto slot = [&](auto s_c) {
+                constexpr int S = decltype(s_c)::value, ks = S >> 2, i = S & 3, kn = (ks + 1) & 3;
+                constexpr int SRC = ks < 3 ? CUR : NXT;
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                read_b(kn & 1, i, SRC, kn);
+                read_a(i, SRC, kn);   // into the registers the MFMAs above just released
+                produce(s_c, std::integral_constant<int, NXT>{}, sl);
+                if (S == 11) __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            slot(std::integral_constant<int, 0>{});
+            slot(std::integral_constant<int, 1>{});
+            slot(std::integral_constant<int, 2>{});
+            slot(std::integral_constant<int, 3>{});
+            slot(std::integral_constant<int, 4>{});
+            slot(std::integral_constant<int, 5>{});
+            slot(std::integral_constant<int, 6>{});
+            slot(std::integral_constant<int, 7>{});
+            slot(std::integral_constant<int, 8>{});
+            slot(std::integral_constant<int, 9>{});
+            slot(std::integral_constant<int, 10>{});
+            slot(std::integral_constant<int, 11>{});
+            slot(std::integral_constant<int, 12>{});
+            slot(std::integral_constant<int, 13>{});
+            slot(std::integral_constant<int, 14>{});
+            slot(std::integral_constant<int, 15>{});
+        };
+        int st = 0;
+        for (; st + 1 < nst; st += 2) {
+            stage(st, std::integral_constant<int, 0>{});
+            stage(st + 1, std::integral_constant<int, 1>{});
+        }
+        if (nst & 1) stage(st, std::integral_constant<int, 0>{});
+
+        // fragment t_i, row 8 g + 4 fk + e is channel 32 t_i + row: four consecutive e are contiguous
+#pragma unroll
+        for (int tj = 0; tj < 4; ++tj) {
+            const int m = m0 + wc * 128 + tj * 32 + fr;
+            if (m >= M) continue;
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int ic = icw + ti * 32 + 8 * g + 4 * fk;
+                    if (ic < L.ic) {
+                        const h2 lo = h2{(_Float16)acc[ti][tj][4 * g + 0], (_Float16)acc[ti][tj][4 * g + 1]};
+                        const h2 hi = h2{(_Float16)acc[ti][tj][4 * g + 2], (_Float16)acc[ti][tj][4 * g + 3]};
+                        *reinterpret_cast<u2*>(dX + (size_t)m * lddx + ic) = u2{h2_bits(lo), h2_bits(hi)};
+                    }
+                }
+        }
+    };
+
+    if (H0 == H1) {
+        if (H0 == 0) run_quant(); else run_weak();
+    } else {
+        if (wr == 0) run_quant(); else run_weak();
+    }
+}
+
+__global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
+                                                           __half* __restrict__ dX, int64_t lddx, int tiles_ic) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int tile = xcd_tile(tiles_ic * ((M + BT - 1) / BT));
+    if (tile < 0) return;
+    const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
+    const int ic0 = t_ic * BT, m0 = t_m * BT;
+    // a half is weak when it starts at or past Kq (Kq % 128 == 0); without a weak block the surplus
+    // half of the last tile runs as a quantized one on clamped addresses and stores nothing
+    const bool w0 = L.k > 0 && ic0 >= L.kq, w1 = L.k > 0 && ic0 + 128 >= L.kq;
+    if (w0) dx_tile<1, 1>(L, dY, M, lddy, dX, lddx, ic0, m0, lds);
+    else if (w1) dx_tile<0, 1>(L, dY, M, lddy, dX, lddx, ic0, m0, lds);
+    else dx_tile<0, 0>(L, dY, M, lddy, dX, lddx, ic0, m0, lds);
 }
 
 // ======================================================================================= weak gradient
@@ -526,11 +945,22 @@ bool gemm_dx_supported(const Layer& L, int64_t M) {
 }
 
 hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s) {
-    static bool attr = false;
-    hipError_t e = raise_lds_limit((const void*)gemm_dx_kernel, attr);
-    if (e != hipSuccess) return e;
-    const int tiles_ic = ceil_div(L.ic, BT), tiles_m = ceil_div(M, BT);
-    gemm_dx_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, GEMM_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic);
+    const int tiles_m = ceil_div(M, BT), tiles_ic = ceil_div(L.ic, BT);
+    hipError_t e;
+    if (L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0 && !getenv("QEFT_DBG_OLDDX")) {
+        static bool attr = false;
+        if (!attr) {
+            e = hipFuncSetAttribute((const void*)gemm_dx_rega_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, DX_LDS);
+            if (e != hipSuccess) return e;
+            attr = true;
+        }
+        gemm_dx_rega_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic);
+    } else {
+        static bool attr = false;
+        e = raise_lds_limit((const void*)gemm_dx_kernel, attr);
+        if (e != hipSuccess) return e;
+        gemm_dx_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, GEMM_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic, 0);
+    }
     return hipGetLastError();
 }
 

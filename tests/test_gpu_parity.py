@@ -179,6 +179,10 @@ BWD_CASES = [  # oc, ic, k, bits, g, M
     (64, 256, 256, 4, 128, 17),       # k = IC
     (64, 384, 0, 4, 128, 17),         # k = 0
     (384, 512 + 72, 72, 4, 128, 130),
+    (128, 384 + 128, 128, 4, 128, 70),   # a tile whose first half is quantized and second half weak
+    (64, 128 + 256, 256, 4, 128, 290),   # mixed tile, then an all-weak tile with a dead half
+    (192, 256 + 40, 40, 4, 128, 40),     # weak half narrower than 128 channels
+    (320, 896, 0, 4, 128, 257),          # no weak block, last tile half empty, odd stage count
 ]
 
 
