@@ -183,7 +183,7 @@ def main():
         "pct_mfma_peak": round(100 * ft_tflops / MFMA_F16_PEAK_TF, 2),
         "pack_us": round(mean[-1] * 1e3, 1),
         "finetune_kernels": kernels,
-        "roofline": {"kernel": "gemm_dx_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
+        "roofline": {"kernel": "gemm_dx_rega_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
                      "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": None},
         "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_gbs, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),

@@ -145,7 +145,7 @@ __device__ __forceinline__ h8 dequant_word(uint32_t w, uint32_t zs, const RegCon
     return __builtin_bit_cast(h8, r);
 }
 
-constexpr int REGA_LDS = 3 * TILE_BYTES;   // X0 X1, and one tile for the weak block's weights
+constexpr int REGA_LDS = 4 * TILE_BYTES;   // X0 X1 and one tile for the weak block's weights; 32 KB per wave in the epilogue
 
 __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                             __half* __restrict__ Y, int64_t ldy, int tiles_oc) {
@@ -724,22 +724,8 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
         if (nst & 1) stage(st, std::integral_constant<int, 0>{});
 
         // a lane's accumulators (t_i = 0..3) for fixed row 8 g + 4 fk + e are channels 4 row + t_i
-#pragma unroll
-        for (int tj = 0; tj < 4; ++tj) {
-            const int m = m0 + wc * 128 + tj * 32 + fr;
-            if (m >= M) continue;
-#pragma unroll
-            for (int g = 0; g < 4; ++g)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int ic = icw + 4 * (8 * g + 4 * fk + e);
-                    if (ic < L.kq) {
-                        const h2 lo = h2{(_Float16)acc[0][tj][4 * g + e], (_Float16)acc[1][tj][4 * g + e]};
-                        const h2 hi = h2{(_Float16)acc[2][tj][4 * g + e], (_Float16)acc[3][tj][4 * g + e]};
-                        *reinterpret_cast<u2*>(dX + (size_t)m * lddx + ic) = u2{h2_bits(lo), h2_bits(hi)};
-                    }
-                }
-        }
+        __syncthreads();   // every wave is done with the staging buffers
+        store_f16_lds<true>(acc, lds + wave * TILE_BYTES, dX, lddx, icw, L.kq, m0 + 128 * wc, M, lane);
     };
 
     // ---- a wave that owns a weak half --------------------------------------------------------------------
@@ -797,23 +783,9 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
         }
         if (nst & 1) stage(st, std::integral_constant<int, 0>{});
 
-        // fragment t_i, row 8 g + 4 fk + e is channel 32 t_i + row: four consecutive e are contiguous
-#pragma unroll
-        for (int tj = 0; tj < 4; ++tj) {
-            const int m = m0 + wc * 128 + tj * 32 + fr;
-            if (m >= M) continue;
-#pragma unroll
-            for (int ti = 0; ti < 4; ++ti)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int ic = icw + ti * 32 + 8 * g + 4 * fk;
-                    if (ic < L.ic) {
-                        const h2 lo = h2{(_Float16)acc[ti][tj][4 * g + 0], (_Float16)acc[ti][tj][4 * g + 1]};
-                        const h2 hi = h2{(_Float16)acc[ti][tj][4 * g + 2], (_Float16)acc[ti][tj][4 * g + 3]};
-                        *reinterpret_cast<u2*>(dX + (size_t)m * lddx + ic) = u2{h2_bits(lo), h2_bits(hi)};
-                    }
-                }
-        }
+        // fragment t_i, row 8 g + 4 fk + e is channel 32 t_i + row
+        __syncthreads();
+        store_f16_lds<false>(acc, lds + wave * TILE_BYTES, dX, lddx, icw, L.ic, m0 + 128 * wc, M, lane);
     };
 
     if (H0 == H1) {

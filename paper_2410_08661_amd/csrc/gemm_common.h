@@ -279,5 +279,47 @@ __device__ __forceinline__ void store_f32(const f16v (&acc)[4][4], float* out, i
     }
 }
 
+// fp16 epilogue through LDS: the wave's 128 x 128 results are transposed through 32 KB of LDS of
+// its own (rows j of 256 bytes, 16-byte chunks XOR-swizzled with j) so that the global stores are
+// 16 bytes per lane and 256 contiguous bytes per row instead of 8-byte pieces of 32 different
+// rows.  QUADS = false: accumulator tile t_i row 8 g + 4 fk + e is i = 32 t_i + row; QUADS =
+// true: it is i = 4 row + t_i (the input-gradient kernel's quantized halves).  i0 / j0: global
+// index of the wave's first i / j; i0 and ni must be multiples of 8.  The LDS region needs no
+// barrier: only this wave touches it, and a wave's LDS accesses complete in order.
+template <bool QUADS>
+__device__ __forceinline__ void store_f16_lds(const f16v (&acc)[4][4], unsigned char* stage, __half* out, int64_t ld, int i0,
+                                              int ni, int j0, int nj, int lane) {
+    const int fr = lane & 31, fk = lane >> 5;
+    auto pack = [](float a, float b) { return h2_bits(h2{(_Float16)a, (_Float16)b}); };
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+        unsigned char* row = stage + (tj * 32 + fr) * 256;
+        const int sw = fr & 15;
+        if (!QUADS) {
+#pragma unroll
+            for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<u2*>(row + (((4 * ti + g) ^ sw) << 4) + 8 * fk) =
+                        u2{pack(acc[ti][tj][4 * g + 0], acc[ti][tj][4 * g + 1]), pack(acc[ti][tj][4 * g + 2], acc[ti][tj][4 * g + 3])};
+        } else {
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    *reinterpret_cast<u2*>(row + (((4 * g + 2 * fk + (e >> 1)) ^ sw) << 4) + 8 * (e & 1)) =
+                        u2{pack(acc[0][tj][4 * g + e], acc[1][tj][4 * g + e]), pack(acc[2][tj][4 * g + e], acc[3][tj][4 * g + e])};
+        }
+    }
+    const int c = lane & 15, r4 = lane >> 4;
+    const int i = i0 + 8 * c;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+        const int r = 4 * it + r4;
+        const u4 v = *reinterpret_cast<const u4*>(stage + r * 256 + ((c ^ (r & 15)) << 4));
+        if (j0 + r < nj && i < ni) *reinterpret_cast<u4*>(out + (size_t)(j0 + r) * ld + i) = v;
+    }
+}
+
 }  // namespace gemm
 }  // namespace qeft
