@@ -29,6 +29,9 @@
 //
 // Every branch around an MFMA is wave-uniform by construction (the wave index goes through
 // readfirstlane): MFMA executes regardless of the EXEC mask.
+#include <cstdlib>
+#include <type_traits>
+
 #include "qeft_internal.h"
 
 namespace qeft {
@@ -88,12 +91,16 @@ __device__ __forceinline__ float sum8(u4 v) {
     return s;
 }
 
-// sum over each aligned group of 16 lanes
+// sum over each aligned group of 16 lanes, in every lane of the group: butterfly of four
+// data-parallel-primitive moves (lane ^ 1, lane ^ 2, mirrored halves, mirrored row), no LDS round trips
 __device__ __forceinline__ float sum16(float t) {
-    t += __shfl_xor(t, 1, 64);
-    t += __shfl_xor(t, 2, 64);
-    t += __shfl_xor(t, 4, 64);
-    t += __shfl_xor(t, 8, 64);
+    auto dpp = [](float v, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    t += dpp(t, std::integral_constant<int, 0xB1>{});    // quad_perm [1,0,3,2]
+    t += dpp(t, std::integral_constant<int, 0x4E>{});    // quad_perm [2,3,0,1]
+    t += dpp(t, std::integral_constant<int, 0x141>{});   // row_half_mirror
+    t += dpp(t, std::integral_constant<int, 0x140>{});   // row_mirror
     return t;
 }
 
@@ -166,129 +173,143 @@ __device__ __forceinline__ void reduce_store(const Layer& L, f4 (&y)[R], int kw,
 
 // =============================================================================================
 // Small-M kernel: M <= 4.  A workgroup owns TW tiles of 16 rows; its TW*KS waves stage all of X
-// once (one barrier), then wave (t, kw) streams K range kw of tile t.  The K split is in units
-// of 4 steps, so a wave fetches its scales / zero-points as aligned 8-byte loads (16 steps per
-// load instruction: the 4 lanes of a row take 4 steps each) and parks them in its own LDS slice.
-// The wave's share of the weak block is requested first of all and consumed last.
+// once (one barrier), then wave (t, kw) streams K range kw of tile t (K split in units of 4 steps).
+//
+// At these sizes a launch lives for a few microseconds and is bound by memory latency and by the
+// number of cache-line requests queued at its start, not by bandwidth, so the prologue is built
+// around the request stream:
+//   * every request goes out first, in straight-line code - indices are clamped instead of
+//     tested, because a load under a branch makes the compiler wait for all outstanding loads at
+//     the join, and loads return in order;
+//   * X (L2 hits) and the group parameters are requested ahead of the weights, so staging them
+//     never waits for HBM; the weights of up to D steps per lane follow at once;
+//   * the scales / zero-points of a tile are fetched once per tile, not per K-split wave: chunk c
+//     = 32 groups of one array for the tile's 16 rows, one 16-byte load per lane (16 cache lines
+//     per request, each used in full), dealt round-robin to the tile's waves, NSZ per wave;
+//   * the weak block's loads are exactly the WMAX = ceil(steps / KS) the wave consumes.
 // LDS: X [M][ng*256 + 16 B] permuted fragments | Sx float [ng][4] | zero bytes |
-//      (s, 1024+z) float2 [waves][steps per wave][16] | reduction slots
+//      (s, 1024+z) float2 [tiles][groups][16] | reduction slots
 // =============================================================================================
 struct SmallLds {
-    int xrow, sx_off, zero_off, sz_off, sz_wave, red_off, total;
+    int xrow, sx_off, zero_off, sz_off, sz_tile, red_off, total, tw;
 };
 inline SmallLds small_lds(int M, int ng, int tw, int ks) {
     SmallLds l;
-    const int units = (ng + 3) / 4;
-    const int steps_per_wave = ((4 * ((units + ks - 1) / ks) + 15) / 16) * 16;
     l.xrow = ng * 256 + 16;
     l.sx_off = M * l.xrow;
-    l.zero_off = l.sx_off + ng * 16;  // what lanes without an activation row read, 4 steps deep
-    l.sz_off = l.zero_off + 256 * 4;
-    l.sz_wave = steps_per_wave * 128;
-    l.red_off = l.sz_off + tw * ks * l.sz_wave;
+    l.zero_off = l.sx_off + ng * 16;  // what lanes without an activation row read, D steps deep
+    l.sz_off = l.zero_off + 256 * 8;
+    l.sz_tile = ng * 128;
+    l.red_off = l.sz_off + tw * l.sz_tile;
     l.total = l.red_off + (ks - 1) * tw * 4 * 64 * (int)sizeof(float);
+    l.tw = tw;
     return l;
 }
 
+template <int D, int WMAX, int NSZ>
 __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
-                                                             __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS) {
-    constexpr int D = 4;      // weight loads in flight per lane
-    constexpr int WMAX = 4;   // weak steps per wave kept in registers
+                                                             __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS, int ks_magic) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int TW = (blockDim.x >> 6) / KS;
-    const int ti = wave / KS, kw = wave - ti * KS;  // tile within the workgroup, K split index
+    // no integer division here: the launch is short enough for its emulation to show (TW <= 4;
+    // a / KS = a * ks_magic >> 16 with ks_magic = ceil(65536 / KS), exact for a < 4096)
+    const int ti = (wave >= KS) + (wave >= 2 * KS) + (wave >= 3 * KS), kw = wave - ti * KS;  // tile within the workgroup, K split index
+    const int TW = ld.tw;
     const int n = lane & 15, kb = lane >> 4;
     const int row0 = (blockIdx.x * TW + ti) * 16;
     const int nq = L.ng;
     const int units = (nq + 3) >> 2;
-    const int q_beg = 4 * (int)((int64_t)units * kw / KS);
-    const int q_end = min(4 * (int)((int64_t)units * (kw + 1) / KS), nq);
+    const int q_beg = 4 * ((units * kw * ks_magic) >> 16);
+    const int q_end = min(4 * ((units * (kw + 1) * ks_magic) >> 16), nq);
     const int nj = max(q_end - q_beg, 0);
     const int nweak = (L.k + 31) / 32;
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
     const bool has_x = n < M;
 
-    // ---- requests that depend on nothing staged below go out first --------------------------------
+    // ---- requests -------------------------------------------------------------------------------------
     const int orow = min(row0 + n, L.oc - 1);
-    const unsigned char* wp =
-        reinterpret_cast<const unsigned char*>(L.qweight + (size_t)orow * L.stride) + 64 * (size_t)q_beg + 16 * kb;
-    u4 wq[D];
+    const int per_m = nq * 16;
+    const int total = M * per_m;  // X fragments: idx -> (row m, fragment f of 8 columns); multiple of 16
+    u4 xv[4];
+    int xm[4], xf[4];
+    auto load_x = [&](int base) {
 #pragma unroll
-    for (int d = 0; d < D; ++d)
-        if (d < nj) wq[d] = load16(wp + 64 * d);
-    // weak steps of 32 fp16 columns are dealt to the K-split waves from the last one back
-    u4 wk[WMAX], xw[WMAX];
-#pragma unroll
-    for (int i = 0; i < WMAX; ++i) {
-        const int c0 = 32 * (KS - 1 - kw + i * KS) + 8 * kb;
-        wk[i] = (c0 < L.k) ? load16(L.weak + (size_t)orow * L.k + c0) : zero4;
-        xw[i] = (has_x && c0 < L.k) ? load16(X + (size_t)n * ldx + L.kq + c0) : zero4;
-    }
-    // scales / zero-points: lane (n, kb) takes steps 16*b + 4*kb .. +3 of row n
-    const __half* sp = L.scales + (size_t)orow * L.gs + q_beg;
-    const __half* zp = L.zeros + (size_t)orow * L.gs + q_beg;
-    unsigned char* szw = lds + ld.sz_off + (size_t)wave * ld.sz_wave;
-    auto stage_sz = [&](int b0) {   // 64 steps from local step b0
-        u2 sb[4], zb[4];
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int st = b0 + 16 * b + 4 * kb;
-            sb[b] = zb[b] = u2{0u, 0u};
-            if (st < nj) {
-                sb[b] = load8(sp + st);
-                zb[b] = load8(zp + st);
-            }
+        for (int u = 0; u < 4; ++u) {
+            const int idx = base + u * blockDim.x + threadIdx.x;
+            const int cidx = min(idx, total - 1);
+            const int m = (cidx >= per_m) + (cidx >= 2 * per_m) + (cidx >= 3 * per_m);
+            xm[u] = (idx < total) ? m : -1;
+            xf[u] = cidx - m * per_m;
+            // fragments past Kq (the last group's padding) read the row's last quantized fragment and are zeroed below
+            xv[u] = load16(X + (size_t)m * ldx + min(8 * xf[u], L.kq - 8));
         }
+    };
+    auto store_x = [&]() {   // Sx of a group lands with its first fragment
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int st = b0 + 16 * b + 4 * kb;
-            if (st < nj) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float2 v;
-                    v.x = half_at(sb[b], e);
-                    v.y = 1024.f + half_at(zb[b], e);
-                    reinterpret_cast<float2*>(szw)[(st + e) * 16 + n] = v;
-                }
+        for (int u = 0; u < 4; ++u) {
+            if (8 * xf[u] >= L.kq) xv[u] = zero4;
+            const float t = sum16(sum8(xv[u]));
+            if (xm[u] >= 0) {
+                *reinterpret_cast<u4*>(lds + xm[u] * ld.xrow + xf[u] * 16) = permute_x(xv[u]);
+                if ((xf[u] & 15) == 0) reinterpret_cast<float*>(lds + ld.sx_off)[(xf[u] >> 4) * 4 + xm[u]] = t;
             }
         }
     };
-    stage_sz(0);
+    load_x(0);
+    // group parameters of this wave's tile: chunk c = array c % 2 (scales, zero-points), groups
+    // 32 (c / 2) + 8 kb .. + 7 of row n; chunks kw, kw + KS, ... (a chunk past the end repeats the last)
+    const int nchunks = 2 * ((nq + 31) >> 5);
+    u4 pv[NSZ];
+#pragma unroll
+    for (int i = 0; i < NSZ; ++i) {
+        const int c = min(kw + i * KS, nchunks - 1);
+        const int g0 = min(32 * (c >> 1) + 8 * kb, (int)L.gs - 8);
+        pv[i] = load16(((c & 1) ? L.zeros : L.scales) + (size_t)orow * L.gs + g0);
+    }
+    // weights: steps past the wave's range re-read its last step (never consumed)
+    const unsigned char* wp =
+        reinterpret_cast<const unsigned char*>(L.qweight + (size_t)orow * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+    const int j_last = max(min(nj, nq - q_beg) - 1, 0);
+    u4 wq[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) wq[d] = load16(wp + 64 * min(d, j_last));
+    // weak steps of 32 fp16 columns are dealt to the K-split waves from the last one back
+    // (columns past k are clamped here and zeroed where they are used; k >= 8)
+    u4 wk[WMAX], xw[WMAX];
+    const int mrow = min(n, M - 1);
+#pragma unroll
+    for (int i = 0; i < WMAX; ++i) {
+        const int c0 = min(32 * (KS - 1 - kw + i * KS) + 8 * kb, L.k - 8);
+        wk[i] = load16(L.weak + (size_t)orow * L.k + c0);
+        xw[i] = load16(X + (size_t)mrow * ldx + L.kq + c0);
+    }
+    __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
 
-    // ---- stage X: fragment idx -> (row m, fragment f of 8 columns); zero beyond Kq.  Four fragments
-    // per thread and pass, all loads issued before the first use ------------------------------------
+    // ---- stage X (permuted, with Sx) and the group parameters ----------------------------------------
+    store_x();
     {
-        const int per_m = nq * 16;
-        const int total = M * per_m;  // multiple of 16: a 16-lane group is all in or all out
-        for (int base = 0; base < total; base += 4 * blockDim.x) {
-            u4 v[4];
-            int mm[4], ff[4];
+        float* szt = reinterpret_cast<float*>(lds + ld.sz_off + (size_t)ti * ld.sz_tile);
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int idx = base + u * blockDim.x + threadIdx.x;
-                const int m = (idx >= per_m) + (idx >= 2 * per_m) + (idx >= 3 * per_m);
-                mm[u] = (idx < total) ? m : -1;
-                ff[u] = idx - m * per_m;
-                v[u] = zero4;
-                if (idx < total && 8 * ff[u] < L.kq) v[u] = load16(X + (size_t)m * ldx + 8 * ff[u]);
-            }
+        for (int i = 0; i < NSZ; ++i) {
+            const int c = kw + i * KS;
+            const int g0 = 32 * (c >> 1) + 8 * kb;
+            const h8 h = as_h8(pv[i]);
+            if (c < nchunks) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const float t = sum16(sum8(v[u]));
-                if (mm[u] >= 0) {
-                    *reinterpret_cast<u4*>(lds + mm[u] * ld.xrow + ff[u] * 16) = permute_x(v[u]);
-                    if ((ff[u] & 15) == 0) reinterpret_cast<float*>(lds + ld.sx_off)[(ff[u] >> 4) * 4 + mm[u]] = t;
-                }
+                for (int e = 0; e < 8; ++e)
+                    if (g0 + e < nq) szt[((g0 + e) * 16 + n) * 2 + (c & 1)] = (c & 1) ? 1024.f + (float)h[e] : (float)h[e];
             }
         }
-        // rows of Sx beyond M read as zero
-        for (int i = threadIdx.x; i < nq * 4; i += blockDim.x)
-            if ((i & 3) >= M) reinterpret_cast<float*>(lds + ld.sx_off)[i] = 0.f;
-        for (int i = threadIdx.x; i < 64 * 4; i += blockDim.x) reinterpret_cast<float*>(lds + ld.zero_off)[i] = 0.f;
     }
-    for (int b0 = 64; b0 < nj; b0 += 64) stage_sz(b0);
+    for (int base = 4 * blockDim.x; base < total; base += 4 * blockDim.x) {   // only when X exceeds one pass
+        load_x(base);
+        store_x();
+    }
+    // rows of Sx beyond M read as zero
+    for (int i = threadIdx.x; i < nq * 4; i += blockDim.x)
+        if ((i & 3) >= M) reinterpret_cast<float*>(lds + ld.sx_off)[i] = 0.f;
+    for (int i = threadIdx.x; i < 64 * 8; i += blockDim.x) reinterpret_cast<float*>(lds + ld.zero_off)[i] = 0.f;
     __syncthreads();
 
     // ---- stream this wave's steps ---------------------------------------------------------------------
@@ -299,7 +320,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     const bool has_sx = kb == 0;
     int xa_addr = has_x ? n * ld.xrow + kb * 64 + q_beg * 256 : ld.zero_off;
     int sx_addr = has_sx ? ld.sx_off + q_beg * 16 : ld.zero_off;
-    int sz_addr = ld.sz_off + wave * ld.sz_wave + n * 8;
+    int sz_addr = ld.sz_off + ti * ld.sz_tile + q_beg * 128 + n * 8;
     const int xa_inc = has_x ? 256 * D : 0, sx_inc = has_sx ? 16 * D : 0;
 
     auto step = [&](int d) {
@@ -340,14 +361,10 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     // ---- weak block ---------------------------------------------------------------------------------------
 #pragma unroll
     for (int i = 0; i < WMAX; ++i)
-        if (KS - 1 - kw + i * KS < nweak)
-            y[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xw[i]), as_h8(wk[i]), y[0], 0, 0, 0);
-    for (int t = KS - 1 - kw + WMAX * KS; t < nweak; t += KS) {   // very wide weak blocks only
-        const int c0 = 32 * t + 8 * kb;
-        const u4 a = (has_x && c0 < L.k) ? load16(X + (size_t)n * ldx + L.kq + c0) : zero4;
-        const u4 w = (c0 < L.k) ? load16(L.weak + (size_t)orow * L.k + c0) : zero4;
-        y[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(a), as_h8(w), y[0], 0, 0, 0);
-    }
+        if (KS - 1 - kw + i * KS < nweak) {
+            const bool live = has_x && 32 * (KS - 1 - kw + i * KS) + 8 * kb < L.k;
+            y[0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(live ? xw[i] : zero4), as_h8(wk[i]), y[0], 0, 0, 0);
+        }
     reduce_store<1>(L, y, kw, KS, lane, row0, M, Y, ldy, [&](int w) {
         return reinterpret_cast<float*>(lds + ld.red_off) + (size_t)(ti * (KS - 1) + (w - 1)) * 4 * 64;
     });
@@ -500,9 +517,10 @@ bool gemv_supported(const Layer& L, int64_t M, int64_t ldx) {
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int M = (int)M64;
     const int steps = L.ng + (L.k + 31) / 32;
-    if (M <= 4) {
+    if (M <= 4 && L.kq >= 8 && L.k >= 8) {
         const int tiles = ceil_div(L.oc, 16);
         const int units = (L.ng + 3) / 4;
+        const int nweak = (L.k + 31) / 32;
         // ~12 waves per CU over 256 CUs, at most 16 waves per workgroup, K split in units of 4 steps
         int ks = ceil_div(3072, tiles);
         const int ks_max = units < 1 ? 1 : (units > 16 ? 16 : units);
@@ -515,15 +533,23 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
             ks = ks_max;
         }
         const SmallLds ld = small_lds(M, L.ng, tw, ks);
-        if (ld.total <= SMALL_LDS_LIMIT) {
-            static bool attr_set = false;
-            if (!attr_set) {
-                hipError_t e = hipFuncSetAttribute((const void*)gemv_w4_small_kernel,
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
+        const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
+        if (ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3) {
+            using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, SmallLds, int, int);
+            // deep prefetch (8 steps per lane) unless the weak prefetch already takes the registers
+            static const Kern table[3][3] = {
+                {gemv_w4_small_kernel<8, 1, 1>, gemv_w4_small_kernel<8, 1, 2>, gemv_w4_small_kernel<8, 1, 3>},
+                {gemv_w4_small_kernel<8, 2, 1>, gemv_w4_small_kernel<8, 2, 2>, gemv_w4_small_kernel<8, 2, 3>},
+                {gemv_w4_small_kernel<4, 4, 1>, gemv_w4_small_kernel<4, 4, 2>, gemv_w4_small_kernel<4, 4, 3>}};
+            static bool attr_set[3][3] = {};
+            const int wi = wmax <= 1 ? 0 : (wmax <= 2 ? 1 : 2), si = nsz - 1;
+            const Kern kern = table[wi][si];
+            if (!attr_set[wi][si]) {
+                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
                 if (e != hipSuccess) return e;
-                attr_set = true;
+                attr_set[wi][si] = true;
             }
-            gemv_w4_small_kernel<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks);
+            kern<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks, ceil_div(65536, ks));
             return hipGetLastError();
         }
     }
