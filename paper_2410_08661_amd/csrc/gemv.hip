@@ -536,13 +536,17 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
         const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
         if (ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3) {
             using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, SmallLds, int, int);
-            // deep prefetch (8 steps per lane) unless the weak prefetch already takes the registers
-            static const Kern table[3][3] = {
+            // prefetch depth: all of a wave's steps when it has at most 4, else 8 steps per lane unless
+            // the weak prefetch already takes the registers (a request past the range would only repeat
+            // the last one, but it still occupies the CU's address path at launch)
+            static const Kern table[4][3] = {
+                {gemv_w4_small_kernel<4, 1, 1>, gemv_w4_small_kernel<4, 1, 2>, gemv_w4_small_kernel<4, 1, 3>},
                 {gemv_w4_small_kernel<8, 1, 1>, gemv_w4_small_kernel<8, 1, 2>, gemv_w4_small_kernel<8, 1, 3>},
                 {gemv_w4_small_kernel<8, 2, 1>, gemv_w4_small_kernel<8, 2, 2>, gemv_w4_small_kernel<8, 2, 3>},
                 {gemv_w4_small_kernel<4, 4, 1>, gemv_w4_small_kernel<4, 4, 2>, gemv_w4_small_kernel<4, 4, 3>}};
-            static bool attr_set[3][3] = {};
-            const int wi = wmax <= 1 ? 0 : (wmax <= 2 ? 1 : 2), si = nsz - 1;
+            static bool attr_set[4][3] = {};
+            const int nj_max = 4 * ceil_div(units, ks);
+            const int wi = wmax <= 1 ? (nj_max <= 4 ? 0 : 1) : (wmax <= 2 ? 2 : 3), si = nsz - 1;
             const Kern kern = table[wi][si];
             if (!attr_set[wi][si]) {
                 hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
