@@ -505,6 +505,126 @@ hipError_t launch_chunk(const Layer& L, const __half* X, int M, int64_t ldx, __h
     return hipGetLastError();
 }
 
+// =============================================================================================
+// Row-batch kernel: any M <= 16 without staging.  With more than a few activation rows X no
+// longer fits in LDS, and staging it in chunks puts a load latency in front of every chunk.  Here
+// a wave reads the A fragments it needs straight from X (L2-resident: every wave of the launch
+// reads the same few hundred KB), D steps ahead like the weights, and permutes them in registers:
+// lane (n, kb) takes for fragment i the 16 bytes X[n][128 j + 32 kb + 8 i ..] - the columns of word
+// 4 kb + i of the step, which is the word its weight load puts in component i.  R tiles of 16 rows share each fragment, so X adds 4 / R
+// requests per weight request.  The group sums Sx come from the matrix core: one more MFMA per
+// fragment against an all-ones B operand leaves sum_k x[m][k] in the accumulator layout the
+// zero-point correction needs.  Lanes past M read row M - 1: they only feed rows of the 16 x 16
+// result that are never stored.  LDS is used for the final reduction over the K split only.
+// =============================================================================================
+template <int R, int D>
+__global__ __launch_bounds__(512) void gemv_w4_rows_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
+                                                           __half* __restrict__ Y, int64_t ldy, int ks_magic) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int lane = threadIdx.x & 63;
+    const int KS = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, kb = lane >> 4;
+    const int row0 = blockIdx.x * (16 * R);
+    const int nq = L.ng;
+    const int units = (nq + 3) >> 2;
+    const int q_beg = 4 * ((units * wave * ks_magic) >> 16);                 // a / KS = a * ceil(65536 / KS) >> 16
+    const int q_end = min(4 * ((units * (wave + 1) * ks_magic) >> 16), nq);
+    const int nj = max(q_end - q_beg, 0);
+    const int j_last = max(nj - 1, 0);
+    const Consts magic = make_consts();
+    u4 ones = u4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+    asm volatile("" : "+v"(ones.x), "+v"(ones.y), "+v"(ones.z), "+v"(ones.w));
+
+    const unsigned char* wrow[R];
+    const __half *sp[R], *zp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int o = min(row0 + 16 * r + n, L.oc - 1);
+        wrow[r] = reinterpret_cast<const unsigned char*>(L.qweight + (size_t)o * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+        sp[r] = L.scales + (size_t)o * L.gs + q_beg;
+        zp[r] = L.zeros + (size_t)o * L.gs + q_beg;
+    }
+    // fragment i of step j: columns 128 (q_beg + j) + 32 kb + 8 i; the last group may be partial
+    // (a fragment past Kq re-reads the row's last quantized fragment and is zeroed where it is used)
+    const __half* xrow = X + (size_t)min(n, M - 1) * ldx;
+    const int col0 = 128 * q_beg + 32 * kb;
+
+    u4 xq[D][4], wq[D][R];
+    u2 sb[D / 4 > 0 ? D / 4 : 1][R], zb[D / 4 > 0 ? D / 4 : 1][R];
+    static_assert(D % 4 == 0, "scales are fetched four steps at a time");
+    auto load_step = [&](int d, int j) {   // straight-line: the step index is clamped, never tested
+        const int jc = min(j, j_last);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xq[d][i] = load16(xrow + min(col0 + 128 * jc + 8 * i, L.kq - 8));
+#pragma unroll
+        for (int r = 0; r < R; ++r) wq[d][r] = load16(wrow[r] + 64 * (size_t)jc);
+    };
+    auto load_sz = [&](int c, int j) {     // steps j .. j + 3 (j a multiple of 4)
+        const int jc = min(j, j_last & ~3);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            sb[c][r] = load8(sp[r] + jc);
+            zb[c][r] = load8(zp[r] + jc);
+        }
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        if ((d & 3) == 0) load_sz(d >> 2, d);
+        load_step(d, d);
+    }
+
+    f4 y[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) y[r] = f4{0.f, 0.f, 0.f, 0.f};
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+
+    auto step = [&](int d, int j) {
+        u4 xa[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xa[i] = permute_x((col0 + 128 * j + 8 * i < L.kq) ? xq[d][i] : zero4);
+        f4 sx = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[i]), as_h8(ones), sx, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float sf = half_at(sb[d >> 2][r], d & 3), c = 1024.f + half_at(zb[d >> 2][r], d & 3);
+            step_tile(y[r], xa, wq[d][r], sx, sf, c, magic);
+        }
+    };
+
+    int j0 = 0;
+    for (; j0 + 2 * D <= nj; j0 += D) {   // steady state: every load is real, no branches
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            step(d, j0 + d);
+            load_step(d, j0 + d + D);
+            if ((d & 3) == 3) load_sz(d >> 2, j0 + D + d - 3);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    for (; j0 < nj; j0 += D) {            // last < 2 D steps
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            if (j0 + d < nj) step(d, j0 + d);
+            load_step(d, j0 + d + D);
+            if ((d & 3) == 3) load_sz(d >> 2, j0 + D + d - 3);
+        }
+    }
+
+    weak_steps<R>(L, X, M, ldx, row0, wave, KS, n, kb, y);
+    reduce_store<R>(L, y, wave, KS, lane, row0, M, Y, ldy,
+                    [&](int w) { return reinterpret_cast<float*>(lds) + (size_t)(w - 1) * R * 4 * 64; });
+}
+
+template <int R, int D>
+hipError_t launch_rows(const Layer& L, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy, int ks, hipStream_t s) {
+    const int grid = ceil_div(L.oc, 16 * R);
+    const size_t lds_bytes = (size_t)(ks > 1 ? ks - 1 : 1) * R * 4 * 64 * sizeof(float);
+    gemv_w4_rows_kernel<R, D><<<grid, 64 * ks, lds_bytes, s>>>(L, X, M, ldx, Y, ldy, ceil_div(65536, ks));
+    return hipGetLastError();
+}
+
 constexpr int SMALL_LDS_LIMIT = 144 * 1024;   // of the 160 KB a CU has
 
 }  // namespace
@@ -556,6 +676,19 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
             kern<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks, ceil_div(65536, ks));
             return hipGetLastError();
         }
+    }
+    if (L.kq >= 8 && !getenv("QEFT_DBG_CHUNK")) {
+        // unstaged kernel: R tiles per wave share the activation fragments (more rows, more sharing),
+        // and enough K-split waves for ~8-12 per CU
+        const int units = (L.ng + 3) / 4;
+        const int R = (M > 8 && ceil_div(L.oc, 64) * (units < 8 ? units : 8) >= 1536) ? 4 : 2;
+        const int tiles = ceil_div(L.oc, 16 * R);
+        int ks = ceil_div(R == 4 ? 2048 : 3072, tiles);
+        ks = ks > 8 ? 8 : ks;
+        ks = ks > units ? units : ks;
+        ks = ks < 1 ? 1 : ks;
+        if (R == 4) return launch_rows<4, 4>(L, X, M, ldx, Y, ldy, ks, s);
+        return launch_rows<2, 4>(L, X, M, ldx, Y, ldy, ks, s);
     }
     const int R = (M <= 4) ? 1 : (M <= 8 ? 2 : 4);
     const int tiles = ceil_div(L.oc, 16 * R);
