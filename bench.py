@@ -4,10 +4,10 @@
 One step = one pass of the whole hot path over synthetic inputs with the Llama-2 7B layer
 shapes (4-bit, group 128, k = 128 weak columns):
 
-  decode     one decoder block at M = 1: 7 matrix-vector launches (q, k, v, o, gate, up, down),
-             each step on a different packed copy of the block (> 1 GB in rotation, so the
-             weights come from HBM, not from the 256 MB last-level cache); the 7 launches are
-             replayed from a HIP graph so that the GPU, not Python, sets the pace
+  decode     decoder blocks at M = 1: 7 matrix-vector launches each (q, k, v, o, gate, up, down),
+             over 10 distinct packed copies of the block in a row (> 1 GB, so the weights come
+             from HBM, not from the 256 MB last-level cache); the 70 launches are replayed from
+             one HIP graph so that the GPU, not Python, sets the pace
   fine-tune  M = 4096 tokens on the three layer shapes: forward, dX through the full mixed
              weight, dW of the weak columns
   pack       min-max round-to-nearest quantization + packing of one 4096 x 4096 layer
@@ -86,13 +86,12 @@ def main():
 
     decode_block(blocks[0])                        # first launch sets kernel attributes: outside capture
     torch.cuda.synchronize()
-    graphs = []
+    # one graph = one pass over all the rotating blocks (a decode token runs 32 such blocks in a row)
     cap_stream = torch.cuda.Stream()
-    for layers in blocks:
-        gr = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gr, stream=cap_stream):
+    decode_graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(decode_graph, stream=cap_stream):
+        for layers in blocks:
             decode_block(layers)
-        graphs.append(gr)
 
     # ---- fine-tune operands -----------------------------------------------------------------------
     ft = []
@@ -116,7 +115,7 @@ def main():
     def one_step(i, timed):
         marks = [ev()]
         marks[0].record()
-        graphs[i % n_blocks].replay()
+        decode_graph.replay()
         marks.append(ev()); marks[-1].record()
         for f in ft:
             B.qeft_linear_fwd(f["desc"], f["w"], f["x"], f["y"])
@@ -139,9 +138,45 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
 
+    # ---- the decode kernel by layer shape: one graph per shape holding the launches of that layer of
+    # every rotating block, so that the launch period of one shape can be told apart (host launch
+    # overhead would dominate eager launches this short)
+    decode_kernels = []
+    gemv_bytes, gemv_ms = 0.0, 0.0
+    for s in ft_shapes:
+        li = block_shapes.index(s)
+        gs = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gs, stream=cap_stream):
+            for b in range(n_blocks):
+                B.qeft_linear_fwd(descs[s], blocks[b][li], x1[s[1]], y1[s[0]])
+        gs.replay()
+        torch.cuda.synchronize()
+        n_rep = max(args.steps, 5)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for r in range(n_rep):
+            gs.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (n_rep * n_blocks)
+        nb = blocks[0][li].nbytes()
+        count = sum(1 for t in block_shapes if t == s)
+        gemv_bytes += count * nb
+        gemv_ms += count * us * 1e-3
+        decode_kernels.append(dict(shape=f"{s[0]}x{s[1]}", launches_per_block=count, bytes=nb, us=round(us, 2),
+                                   gbs=round(nb / us / 1e3, 1)))
+    gemv_kernel_gbs = gemv_bytes / (gemv_ms * 1e-3) / 1e9
+
+    # a plain device copy of known size: the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
+    cal = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
+    cal2 = torch.empty_like(cal)
+    cal2.copy_(cal)
+    torch.cuda.synchronize()
+    del cal, cal2
+
     seg = np.array([[m[j].elapsed_time(m[j + 1]) for j in range(len(m) - 1)] for m in records])   # ms
     mean = seg.mean(axis=0)
-    decode_ms = mean[0]
+    decode_ms = mean[0] / n_blocks
     gemv_gbs = block_bytes / (decode_ms * 1e-3) / 1e9
     kernels = []
     flops_tot, ms_tot = 0.0, 0.0
@@ -174,8 +209,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f16",
         "data": "synthetic",
-        "config": {"workload": "Llama-2-7B layer shapes, w4 g128 k=128: decode block M=1 (7 launches, "
-                               f"{n_blocks} distinct packed blocks in rotation) + fine-tune M=4096 fwd+dX+dW_weak + pack",
+        "config": {"workload": "Llama-2-7B layer shapes, w4 g128 k=128: decode M=1 over "
+                               f"{n_blocks} distinct packed blocks (7 launches each, one graph) + fine-tune M=4096 fwd+dX+dW_weak + pack",
                    "block_bytes": block_bytes, "M_decode": 1, "M_finetune": M_ft},
         "pct_hbm_peak": round(100 * gemv_gbs / HBM_PEAK_GBS, 2),
         "decode_us_per_block": round(decode_ms * 1e3, 2),
@@ -185,9 +220,13 @@ def main():
         "finetune_kernels": kernels,
         "roofline": {"kernel": "gemm_dx_rega_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
                      "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": None},
-        "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_gbs, 1),
-                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_gbs / HBM_PEAK_GBS, 4),
-                          "traffic": None, "note": "per-block average over 7 graph-replayed launches, launch gaps included"},
+        "decode_kernels": decode_kernels,
+        "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
+                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_kernel_gbs / HBM_PEAK_GBS, 4),
+                          "traffic": None,
+                          "note": "stored bytes of the block's 7 layers / sum of their launch periods, each shape "
+                                  "replayed from a graph of its own (HIP events; gaps between launches included, "
+                                  "host overhead not)"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(np, synth, k, bits, g)
