@@ -582,7 +582,7 @@ __global__ __launch_bounds__(512) void gemv_w4_rows_kernel(Layer L, const __half
     auto step = [&](int d, int j) {
         u4 xa[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) xa[i] = permute_x((col0 + 128 * j + 8 * i < L.kq) ? xq[d][i] : zero4);
+        for (int i = 0; i < 4; ++i) xa[i] = permute_x((col0 + 128 * j + 8 * i < L.kq && j < nj) ? xq[d][i] : zero4);
         f4 sx = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < 4; ++i) sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[i]), as_h8(ones), sx, 0, 0, 0);
@@ -593,22 +593,14 @@ __global__ __launch_bounds__(512) void gemv_w4_rows_kernel(Layer L, const __half
         }
     };
 
-    int j0 = 0;
-    for (; j0 + 2 * D <= nj; j0 += D) {   // steady state: every load is real, no branches
+    // no branches inside: steps past the wave's range run on clamped loads and zeroed activations
+    for (int j0 = 0; j0 < nj; j0 += D) {
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             step(d, j0 + d);
             load_step(d, j0 + d + D);
             if ((d & 3) == 3) load_sz(d >> 2, j0 + D + d - 3);
             __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-    for (; j0 < nj; j0 += D) {            // last < 2 D steps
-#pragma unroll
-        for (int d = 0; d < D; ++d) {
-            if (j0 + d < nj) step(d, j0 + d);
-            load_step(d, j0 + d + D);
-            if ((d & 3) == 3) load_sz(d >> 2, j0 + D + d - 3);
         }
     }
 
@@ -625,17 +617,208 @@ hipError_t launch_rows(const Layer& L, const __half* X, int M, int64_t ldx, __ha
     return hipGetLastError();
 }
 
+// =============================================================================================
+// 3-bit kernel: any M <= 16.  Ten codes fill a 32-bit word, so a lane's 128-bit load holds 40
+// consecutive codes of its row and a step of the four k-slot lanes covers 160 columns - groups
+// of 128 columns do not line up with anything the matrix core sums over.  Dequantization is
+// therefore done on the weight side: the 40 codes become five B fragments of 8 fp16 weights
+// (q - z) s each, and five 16x16x32 MFMAs per step accumulate straight into the result.
+//   * a word holds exactly five pairs of codes, so a pair never straddles words: its two codes are
+//     spread to bits 0..2 and 16..18 by one 6-bit field extract and one multiplication by
+//     2^13 + 1, then masked and or-ed with the exponent bits (3 instructions per 2 codes);
+//   * fragment s of lane (n, kb) covers columns 160 j + 40 kb + 8 s .. + 7: one group, since
+//     every such octet starts on a multiple of 8; its (zero-point, scale) pair comes from a table
+//     of the tile's rows in LDS, filled once per workgroup with the same 16-byte-per-lane loads
+//     of 8 groups as in the 4-bit kernel;
+//   * activations are read from X as they are (natural column order), D steps ahead like the
+//     weights, and shared by the R tiles of a wave; octets past Kq are zeroed.
+// LDS: (z, s) fp16 pairs [groups][16 R rows] | reduction slots
+// =============================================================================================
+template <int R, int D, int NSZ>
+__global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
+                                                      __half* __restrict__ Y, int64_t ldy, int ks_magic, int nsteps) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int lane = threadIdx.x & 63;
+    const int KS = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, kb = lane >> 4;
+    const int row0 = blockIdx.x * (16 * R);
+    const int q_beg = (nsteps * wave * ks_magic) >> 16;                 // a / KS = a * ceil(65536 / KS) >> 16
+    const int q_end = (nsteps * (wave + 1) * ks_magic) >> 16;
+    const int nj = max(q_end - q_beg, 0);
+    const int j_last = max(nj - 1, 0);
+    const int nq = L.ng;
+
+    // ---- requests: group parameters of the workgroup's rows first, then D steps of X and weights ----
+    // chunk c = (tile c / (2 nch), array c % 2, groups 32 (c / 2 % nch) ..): 8 groups per lane
+    const int nch = (nq + 31) >> 5, nchunks = 2 * nch * R;
+    u4 pv[NSZ];
+#pragma unroll
+    for (int i = 0; i < NSZ; ++i) {
+        const int c = min(wave + i * KS, nchunks - 1);
+        const int r = c / (2 * nch), cc = c - r * 2 * nch;
+        const int o = min(row0 + 16 * r + n, L.oc - 1);
+        const int g0 = min(32 * (cc >> 1) + 8 * kb, (int)L.gs - 8);
+        pv[i] = load16(((cc & 1) ? L.zeros : L.scales) + (size_t)o * L.gs + g0);
+    }
+    const unsigned char* wrow[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int o = min(row0 + 16 * r + n, L.oc - 1);
+        wrow[r] = reinterpret_cast<const unsigned char*>(L.qweight + (size_t)o * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+    }
+    const __half* xrow = X + (size_t)min(n, M - 1) * ldx;
+    const int col0 = 160 * q_beg + 40 * kb;
+    u4 xq[D][5], wq[D][R];
+    auto load_step = [&](int d, int j) {   // straight-line: the step index is clamped, never tested
+        const int jc = min(j, j_last);
+#pragma unroll
+        for (int s = 0; s < 5; ++s) xq[d][s] = load16(xrow + min(col0 + 160 * jc + 8 * s, L.kq - 8));
+#pragma unroll
+        for (int r = 0; r < R; ++r) wq[d][r] = load16(wrow[r] + 64 * (size_t)jc);
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) load_step(d, d);
+    __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
+
+    // ---- the (zero-point, scale) table ---------------------------------------------------------------
+    unsigned short* szt = reinterpret_cast<unsigned short*>(lds);   // [group][16 R rows][z, s]
+#pragma unroll
+    for (int i = 0; i < NSZ; ++i) {
+        const int c = wave + i * KS;
+        const int r = c / (2 * nch), cc = c - r * 2 * nch;
+        const int g0 = 32 * (cc >> 1) + 8 * kb;
+        if (c < nchunks) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (g0 + e < nq) szt[((g0 + e) * (16 * R) + 16 * r + n) * 2 + ((cc & 1) ? 0 : 1)] = (unsigned short)(pv[i][e >> 1] >> (16 * (e & 1)));
+        }
+    }
+    __syncthreads();
+
+    f4 y[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) y[r] = f4{0.f, 0.f, 0.f, 0.f};
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    uint32_t cmask = 0x00070007u, cmagic = 0x64006400u;
+    asm volatile("" : "+v"(cmask), "+v"(cmagic));
+    const h2 k1024 = h2{(_Float16)1024.f, (_Float16)1024.f};
+    const uint32_t* sz32 = reinterpret_cast<const uint32_t*>(lds);
+
+    // a lane's 40 columns of a step touch at most two groups: both (zero-point, scale) pairs are read
+    // one step ahead, and each fragment picks its own by comparing its first column with the boundary
+    uint32_t zs_lo[R], zs_hi[R];
+    const uint32_t* szl = sz32 + n;
+    auto read_zs = [&](int j) {
+        const int g = min((col0 + 160 * j) >> 7, nq - 1), gh = min(g + 1, nq - 1);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            zs_lo[r] = szl[g * (16 * R) + 16 * r];
+            zs_hi[r] = szl[gh * (16 * R) + 16 * r];
+        }
+    };
+    read_zs(0);
+    auto step = [&](int d, int j) {
+        const int col = col0 + 160 * j;
+        const int split = ((col >> 7) + 1) << 7;   // first column of the next group
+        h2 zsl[R], zsh[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            zsl[r] = __builtin_bit_cast(h2, zs_lo[r]);
+            zsh[r] = __builtin_bit_cast(h2, zs_hi[r]);
+        }
+        read_zs(j + 1);
+        f4 ya[R], yb[R];   // two accumulation chains per tile: consecutive MFMAs do not wait for each other
+#pragma unroll
+        for (int r = 0; r < R; ++r) ya[r] = yb[r] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 5; ++s) {
+            const u4 xa = (col + 8 * s < L.kq && j < nj) ? xq[d][s] : zero4;
+            const bool hi = col + 8 * s >= split;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const h2 zs = hi ? zsh[r] : zsl[r];
+                const h2 z2 = h2{zs.x, zs.x}, s2 = h2{zs.y, zs.y};
+                u4 b;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int P = 4 * s + p;   // pair P of the lane's 20: word P / 5, codes 2 (P % 5) and the next
+                    const uint32_t six = __builtin_amdgcn_ubfe(wq[d][r][P / 5], 6 * (P % 5), 6);
+                    const uint32_t codes = ((six * 0x2001u) & cmask) | cmagic;   // fp16 pair (1024 + q0, 1024 + q1)
+                    b[p] = __builtin_bit_cast(uint32_t, ((__builtin_bit_cast(h2, codes) - k1024) - z2) * s2);
+                }
+                if (s & 1) yb[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa), as_h8(b), yb[r], 0, 0, 0);
+                else ya[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa), as_h8(b), ya[r], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[r][e] += ya[r][e] + yb[r][e];
+    };
+
+    // no branches inside: steps past the wave's range run on clamped loads and zeroed activations
+    for (int j0 = 0; j0 < nj; j0 += D) {
+#pragma unroll
+        for (int d = 0; d < D; ++d) {
+            step(d, j0 + d);
+            load_step(d, j0 + d + D);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    weak_steps<R>(L, X, M, ldx, row0, wave, KS, n, kb, y);
+    __syncthreads();   // the table is dead: its memory becomes the reduction slots
+    reduce_store<R>(L, y, wave, KS, lane, row0, M, Y, ldy,
+                    [&](int w) { return reinterpret_cast<float*>(lds) + (size_t)(w - 1) * R * 4 * 64; });
+}
+
+template <int R>
+hipError_t launch_w3(const Layer& L, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
+    const int tiles = ceil_div(L.oc, 16 * R);
+    const int nsteps = ceil_div(L.words, 16);
+    int ks = ceil_div(3072, tiles);
+    ks = ks > 8 ? 8 : ks;
+    ks = ks > nsteps ? nsteps : ks;
+    ks = ks < 1 ? 1 : ks;
+    const int nchunks = 2 * ceil_div(L.ng, 32) * R;
+    const int nsz = ceil_div(nchunks, ks);
+    const size_t table = (size_t)L.ng * 16 * R * 4, red = (size_t)(ks > 1 ? ks - 1 : 1) * R * 4 * 64 * sizeof(float);
+    const size_t lds_bytes = table > red ? table : red;
+    using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, int, int);
+    static const Kern table_k[4] = {gemv_w3_kernel<R, 4, 1>, gemv_w3_kernel<R, 4, 2>, gemv_w3_kernel<R, 4, 3>, gemv_w3_kernel<R, 4, 4>};
+    if (nsz > 4 || lds_bytes > 64 * 1024) return hipErrorInvalidValue;   // not reached for the shapes gemv_supported admits
+    table_k[nsz - 1]<<<tiles, 64 * ks, lds_bytes, s>>>(L, X, M, ldx, Y, ldy, ceil_div(65536, ks), nsteps);
+    return hipGetLastError();
+}
+
 constexpr int SMALL_LDS_LIMIT = 144 * 1024;   // of the 160 KB a CU has
 
 }  // namespace
 
+// the 3-bit kernel: its (zero-point, scale) table must fit in LDS and be loadable in 4 requests per wave
+static bool w3_fits(const Layer& L) {
+    for (int R = 1; R <= 2; ++R) {
+        const int tiles = ceil_div(L.oc, 16 * R), nsteps = ceil_div(L.words, 16);
+        int ks = ceil_div(3072, tiles);
+        ks = ks > 8 ? 8 : ks;
+        ks = ks > nsteps ? nsteps : ks;
+        ks = ks < 1 ? 1 : ks;
+        if (ceil_div(2 * ceil_div(L.ng, 32) * R, ks) > 4 || (size_t)L.ng * 16 * R * 4 > 64 * 1024) return false;
+    }
+    return true;
+}
+
 bool gemv_supported(const Layer& L, int64_t M, int64_t ldx) {
     (void)ldx;
-    return M >= 1 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0;
+    if (M < 1 || L.g != 128 || (L.kq % 8) != 0 || (L.k % 8) != 0) return false;
+    if (L.bits == 3) return L.kq >= 8 && w3_fits(L);
+    return L.bits == 4;
 }
 
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int M = (int)M64;
+    if (L.bits == 3) return M > 4 ? launch_w3<2>(L, X, M, ldx, Y, ldy, s) : launch_w3<1>(L, X, M, ldx, Y, ldy, s);
     const int steps = L.ng + (L.k + 31) / 32;
     if (M <= 4 && L.kq >= 8 && L.k >= 8) {
         const int tiles = ceil_div(L.oc, 16);
