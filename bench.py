@@ -29,6 +29,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
+# same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
+# the launches of the kernel in one step
+TRAFFIC_DX_BYTES = (2 * (232.3e6 + 37.2e6) + (488.6e6 + 99.1e6)) / 3      # three dX launches
+TRAFFIC_GEMV_BYTES = (4 * 9.92e6 + 2 * 26.30e6 + 25.13e6) / 7            # seven decode launches of a block
 
 
 def main():
@@ -219,11 +224,11 @@ def main():
         "pack_us": round(mean[-1] * 1e3, 1),
         "finetune_kernels": kernels,
         "roofline": {"kernel": "gemm_dx_rega_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
-                     "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": round(TRAFFIC_DX_BYTES)},
         "decode_kernels": decode_kernels,
         "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_kernel_gbs / HBM_PEAK_GBS, 4),
-                          "traffic": None,
+                          "traffic": round(TRAFFIC_GEMV_BYTES),
                           "note": "stored bytes of the block's 7 layers / sum of their launch periods, each shape "
                                   "replayed from a graph of its own (HIP events; gaps between launches included, "
                                   "host overhead not)"},
