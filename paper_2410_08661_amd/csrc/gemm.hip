@@ -5,17 +5,20 @@
 //   backward   dX[M][IC]  = dY . W              contraction over OC, through the full mixed weight
 //   weak grad  dW[OC][k]  = dY^T . X[:, weak]   contraction over the M tokens (Eq. 5, weak block only)
 //
-// The next stage's global loads are issued before the current stage's MFMAs and converted on
-// their way into LDS afterwards: the 4-bit codes are dequantized in registers, so the MFMA loop
-// only ever sees plain fp16 tiles.
+// Two generations of kernels live here.
+//   * gemm_fwd_rega_kernel / gemm_dx_rega_kernel: the 4-bit codes are dequantized straight into the
+//     MFMA operand registers of the wave that multiplies them; LDS carries only the fp16 activation
+//     tile (and, for dX, the raw codes transposed at 16-bit granularity).  Software-pipelined in
+//     slots of four MFMAs with static LDS / global addressing.  Described at each kernel.
+//   * gemm_fwd_kernel / gemm_dx_kernel: producer threads dequantize into an fp16 weight tile in
+//     LDS.  Simpler, LDS-bound, kept for the shapes the register kernels do not take.
 //
-// Dequantization: codes become the exact fp16 numbers 1024 + q by or-ing exponent bits onto
-// the masked nibbles (two codes per instruction), then ((1024+q) - 1024 - z) * s in packed fp16.
-// Forward: a thread converts whole words of one weight row; the nibbles of a word come out in
-// the order (0,4)(1,5)(2,6)(3,7) and the activations of quantized stages are permuted to match.
-// Backward: the contraction runs across weight rows, so a thread takes the same word column of
-// 8 consecutive rows and pairs the rows with a byte permute before the conversion; the result is
-// already transposed, in natural order.
+// Dequantization: codes become exact fp16 numbers by or-ing exponent bits onto masked nibbles
+// (two codes per instruction): 1024 + q for a nibble at bits 0..3 of a half, 64 + q for one at
+// bits 4..7 (mantissa bit 4 then weighs 1); then ((h - base) - z) * s in packed fp16: the first
+// subtraction is exact, the second rounds once (exact for integer zero-points), the product once.
+// The nibbles of a word come out in the order (0,4)(1,5)(2,6)(3,7); in the forward kernels the
+// activations of quantized stages are permuted to match.
 #include <cstdlib>
 #include <type_traits>
 

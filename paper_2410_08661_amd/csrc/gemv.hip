@@ -20,12 +20,14 @@
 //
 // Work split.  A workgroup owns whole tiles of 16 output channels; KS waves per tile split
 // the K steps into contiguous ranges and are reduced through LDS in a fixed order (no
-// atomics: run-to-run deterministic).  The inner loop issues weight loads 4 steps ahead and
-// is counted exactly by the hardware load counter (no branches, no bounds tests: rows are
-// padded to whole steps and rows past OC are clamped, never stored).
+// atomics: run-to-run deterministic).  Weight loads run several steps ahead in loops without
+// branches (rows are padded to whole steps and rows past OC are clamped, never stored).
 //   * small-M kernel (M <= 4 and X fits in LDS): the workgroup stages X once (permuted, with
-//     Sx), one barrier; scales / zero-points come straight from memory, 4 steps per 8-byte load;
-//   * chunked kernel (any M <= 16): each wave stages its own slice, CH steps at a time.
+//     Sx), one barrier; a launch-latency-shaped prologue (see the kernel);
+//   * row-batch kernel (any M <= 16): nothing staged, A fragments straight from X, Sx from the
+//     matrix core;
+//   * 3-bit kernel (any M <= 16): weight-side dequantization, ten codes per word;
+//   * chunked kernel: each wave stages its own slice, CH steps at a time (fallback only).
 //
 // Every branch around an MFMA is wave-uniform by construction (the wave index goes through
 // readfirstlane): MFMA executes regardless of the EXEC mask.
