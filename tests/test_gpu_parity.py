@@ -94,6 +94,10 @@ FWD_CASES = [  # oc, ic, k, bits, g, Ms
     (48, 384, 0, 4, 128, [1, 9]),                    # k = 0: pure group quantization
     (256, 1024 + 128, 128, 4, 128, [64, 300]),       # larger M: GEMM path, ragged M
     (384, 512 + 72, 72, 4, 128, [130]),              # k not a multiple of 32
+    (272, 320 + 128, 128, 4, 128, [64, 257]),        # GEMM path, odd number of 64-column stages, ragged OC
+    (256, 2560 + 256, 256, 4, 128, [33]),            # GEMM path, 20 groups (three reloads of the group parameters)
+    (2064, 2176 + 64, 64, 4, 128, [5, 16]),          # unstaged decode kernel with a K split, 17 groups
+    (2064, 2000 + 64, 64, 3, 128, [1, 6, 16]),       # 3-bit decode kernel with a K split, ragged OC
 ]
 
 
@@ -149,6 +153,21 @@ def test_forward_non_integer_zero_points():
     y = B.qeft_linear_fwd(h.desc, h.to_device(), torch.from_numpy(x).cuda())
     torch.cuda.synchronize()
     assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), "float zero-points")
+
+
+@pytest.mark.parametrize("m", [40, 300])
+def test_gemm_paths_with_non_integer_zero_points(m):
+    """The tiled kernels may not assume integer zero-points either (forward and input gradient)."""
+    h = HostLayer(256, 512 + 128, 128, 4, 128, seed=11)
+    h.zeros = np.random.default_rng(4).uniform(0, 15, size=h.zeros.shape).astype(np.float16)
+    w = h.to_device()
+    x = synth.make_activations(m, h.ic, h.k, 6)
+    dy = synth.make_grad_output(m, h.oc, 7)
+    y = B.qeft_linear_fwd(h.desc, w, torch.from_numpy(x).cuda())
+    dx = B.qeft_linear_bwd_dx(h.desc, w, torch.from_numpy(dy).cuda())
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), "fwd, float zero-points")
+    assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), "dX, float zero-points")
 
 
 def test_forward_respects_leading_dimensions_and_is_deterministic():
