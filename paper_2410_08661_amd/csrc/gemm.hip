@@ -110,17 +110,21 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
 // ------------------------------------------------------------------------- forward, weights in registers
 // One packed word is 8 consecutive columns of one output channel - exactly the 8 k-values one
 // lane feeds into a 32x32x16 MFMA as its A operand.  So the quantized weights never touch LDS:
-// lane (fr, fk) of a wave fetches, for each of its four 32-row blocks, the 16 bytes holding words
+// lane (fr, fk) of a wave fetches, for each of its 32-row blocks, the 16 bytes holding words
 // 4 fk .. 4 fk + 3 of its row for the stage, and dequantizes word ks straight into the A fragment
 // of k-block ks (the k-blocks of a stage are numbered so that this works: block ks covers the
 // columns of words ks and 4 + ks; the X fragments are read from LDS chunk 4 fk + ks to match).
-// LDS holds only the activations (two 32 KB buffers), which halves the LDS traffic per MFMA of
-// the LDS-staged kernels; the price is that the two waves sharing a row block both convert it.
-//  * 4 waves (2 x 2), each 128 x 128; a stage is 16 slots of four MFMAs (one row block against
-//    the four X fragments); every slot also converts one word for the next k-block, reads one X
-//    fragment for it, and carries a share of the X staging (global -> registers -> nibble order
-//    -> LDS) and of the fetches; a scheduling barrier after each slot keeps that interleaving.
-//  * one workgroup barrier per stage, after slot 11; the last four slots read the next stage's
+// LDS holds only the activations (two 32 KB buffers).
+//  * 4 waves stacked along the output channels, each 64 channels x 256 tokens (2 x 8 MFMA tiles):
+//    every word is converted by exactly one wave, and each wave reads all eight X fragments of a
+//    k-block - per MFMA the same LDS traffic as a kernel that reads both operands from LDS.
+//    Conversion is what limits the kernel: measured on gfx950, a wave hides about four vector
+//    instructions behind each 32x32x16 MFMA and pays in full for any more.
+//  * a stage is 64 steps of one MFMA; a scheduling barrier after every step pins its share of
+//    the other work: even steps read one X fragment of the next k-block and (first half of the
+//    stage) permute and store half an X chunk of the next stage; odd steps convert one pair of
+//    codes of the next k-block.
+//  * one workgroup barrier per stage, after step 47; the last k-block reads the next stage's
 //    first X fragments behind it.
 //  * scales / zero-points: 8 bytes (four groups) per row and array every 8 stages, latched into a
 //    packed register per row when the group changes.
@@ -132,30 +136,60 @@ __device__ __forceinline__ RegConsts make_reg_consts() {
     asm volatile("" : "+v"(c.m0), "+v"(c.m1), "+v"(c.g0), "+v"(c.g1));
     return c;
 }
-// word -> 8 weights in the order (c0,c4)(c1,c5)(c2,c6)(c3,c7).  Codes at bits 0..3 of a half
-// become 1024 + q, codes at bits 4..7 become 64 + q (exponent chosen so that mantissa bit 4
-// weighs 1); (h - base) is exact, then - z and * s as everywhere else.
+// Pair P of a word (P = 0..3 -> codes (c0,c4) (c1,c5) (c2,c6) (c3,c7)); w8 = w >> 8.  Codes at bits
+// 0..3 of a half become 1024 + q, codes at bits 4..7 become 64 + q (exponent chosen so that
+// mantissa bit 4 weighs 1); (h - base) is exact, then - z and * s as everywhere else.
+template <int P>
+__device__ __forceinline__ uint32_t dequant_pair_of(uint32_t w, uint32_t w8, h2 z2, h2 s2, const RegConsts& c) {
+    const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
+    const uint32_t src = P < 2 ? w : w8;
+    const uint32_t h = (P & 1) ? ((src & c.m1) | c.g1) : ((src & c.m0) | c.g0);
+    return h2_bits(((bits_h2(h) - ((P & 1) ? b1 : b0)) - z2) * s2);
+}
 __device__ __forceinline__ h8 dequant_word(uint32_t w, uint32_t zs, const RegConsts& c) {
     const h2 v = bits_h2(zs);
     const h2 z2 = h2{v.x, v.x}, s2 = h2{v.y, v.y};
-    const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
     const uint32_t w8 = w >> 8;
-    u4 r;
-    r.x = h2_bits(((bits_h2((w & c.m0) | c.g0) - b0) - z2) * s2);
-    r.y = h2_bits(((bits_h2((w & c.m1) | c.g1) - b1) - z2) * s2);
-    r.z = h2_bits(((bits_h2((w8 & c.m0) | c.g0) - b0) - z2) * s2);
-    r.w = h2_bits(((bits_h2((w8 & c.m1) | c.g1) - b1) - z2) * s2);
+    const u4 r = u4{dequant_pair_of<0>(w, w8, z2, s2, c), dequant_pair_of<1>(w, w8, z2, s2, c),
+                    dequant_pair_of<2>(w, w8, z2, s2, c), dequant_pair_of<3>(w, w8, z2, s2, c)};
     return __builtin_bit_cast(h8, r);
 }
 
 constexpr int REGA_LDS = 4 * TILE_BYTES;   // X0 X1 and one tile for the weak block's weights; 32 KB per wave in the epilogue
 
+// fp16 epilogue of a 64 (i) x 256 (j) wave tile through 32 KB of LDS of the wave's own: rows j of
+// 128 bytes, 16-byte chunks XOR-swizzled with j, then 16-byte global stores (128 contiguous bytes
+// per row).  i0 and ni multiples of 8, out rows 16-byte aligned.  No barrier: one wave, in-order LDS.
+__device__ __forceinline__ void store_f16_lds_64x256(const f16v (&acc)[2][8], unsigned char* stage, __half* out, int64_t ld,
+                                                     int i0, int ni, int j0, int nj, int lane) {
+    const int fr = lane & 31, fk = lane >> 5;
+    auto pack = [](float a, float b) { return h2_bits(h2{(_Float16)a, (_Float16)b}); };
+#pragma unroll
+    for (int tj = 0; tj < 8; ++tj) {
+        unsigned char* row = stage + (tj * 32 + fr) * 128;
+        const int sw = fr & 7;
+#pragma unroll
+        for (int ti = 0; ti < 2; ++ti)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<u2*>(row + (((4 * ti + g) ^ sw) << 4) + 8 * fk) =
+                    u2{pack(acc[ti][tj][4 * g + 0], acc[ti][tj][4 * g + 1]), pack(acc[ti][tj][4 * g + 2], acc[ti][tj][4 * g + 3])};
+    }
+    const int c = lane & 7, r8 = lane >> 3;
+    const int i = i0 + 8 * c;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+        const int r = 8 * it + r8;
+        const u4 v = *reinterpret_cast<const u4*>(stage + r * 128 + ((c ^ (r & 7)) << 4));
+        if (j0 + r < nj && i < ni) *reinterpret_cast<u4*>(out + (size_t)(j0 + r) * ld + i) = v;
+    }
+}
+
 __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
-                                                            __half* __restrict__ Y, int64_t ldy, int tiles_oc) {
+                                                            __half* __restrict__ Y, int64_t ldy, int tiles_oc, int wide_stores) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
     const int tile = xcd_tile(tiles_oc * ((M + BT - 1) / BT));
     if (tile < 0) return;
     const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
@@ -174,10 +208,10 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const char* st_ = reinterpret_cast<const char*>(L.scales + (size_t)oc0 * L.gs);
     const char* zt = reinterpret_cast<const char*>(L.zeros + (size_t)oc0 * L.gs);
     const char* xt = reinterpret_cast<const char*>(X + (size_t)m0 * ldx);
-    uint32_t aoff[4], szoff[4], xoff[8];
+    uint32_t aoff[2], szoff[2], xoff[8];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const uint32_t row = (uint32_t)min(wr * 128 + 32 * i + fr, L.oc - 1 - oc0);
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t row = (uint32_t)min(wave * 64 + 32 * i + fr, L.oc - 1 - oc0);
         aoff[i] = (row * (uint32_t)L.stride + 4u * fk) * 4u;
         szoff[i] = row * (uint32_t)L.gs * 2u;
     }
@@ -198,19 +232,23 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     {
         const uint32_t base = (uint32_t)((4 * fk) ^ (fr & 7) ^ (fr >> 3));
 #pragma unroll
-        for (int x = 0; x < 8; ++x) fb[x] = lds0 + (uint32_t)(wc * 128 + fr) * 128u + ((base ^ (uint32_t)x) << 4);
+        for (int x = 0; x < 8; ++x) fb[x] = lds0 + (uint32_t)fr * 128u + ((base ^ (uint32_t)x) << 4);
     }
 
-    u4 araw[2][4];      // codes: set = stage parity, row block i; word ks of the stage in component ks
+    u4 araw[2][2];      // codes: set = stage parity, row block i; word ks of the stage in component ks
     u4 xv[8];           // X of the stage after the current one
-    u2 szs[4], szz[4];  // scales / zero-points of four consecutive groups, per row block
-    uint32_t lsz[4];    // latched group: zero-point in the low half, scale in the high half
-    h8 afr[2][4], bfr[2][4];
+    u2 szs[2], szz[2];  // scales / zero-points of four consecutive groups, per row block
+    uint32_t lsz[2];    // latched group: zero-point in the low half, scale in the high half
+    u4 afr[2][2];       // A fragments as packed halfs, written one pair at a time
+    h8 bfr[2][8];
+    uint32_t cq[8];     // the conversion pipeline: one register per pair of the k-block being converted
+    uint32_t w8[2];     // word >> 8 per row block
+    u4 px;              // the X chunk being permuted
     auto load_a = [&](int set, int i, int st) { araw[set][i] = *reinterpret_cast<g_u4*>(sbase(wt + 32 * st) + aoff[i]); };
     auto load_x = [&](int u, int st) { xv[u] = *reinterpret_cast<g_u4*>(sbase(xt + 2 * BK * st) + xoff[u]); };
     auto load_sz = [&](int g4) {   // groups g4 .. g4 + 3 (g4 a multiple of 4; the arrays are padded to a multiple of 8 groups)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             szs[i] = *reinterpret_cast<g_u2*>(sbase(st_ + 2 * g4) + szoff[i]);
             szz[i] = *reinterpret_cast<g_u2*>(sbase(zt + 2 * g4) + szoff[i]);
         }
@@ -218,7 +256,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     auto latch = [&](int g) {
         const int sh = 16 * (g & 3);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             const uint64_t s64 = ((uint64_t)szs[i].y << 32) | szs[i].x, z64 = ((uint64_t)szz[i].y << 32) | szz[i].x;
             lsz[i] = ((uint32_t)(z64 >> sh) & 0xffffu) | ((uint32_t)(s64 >> sh) << 16);
         }
@@ -230,18 +268,23 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
         bfr[set][j] = *reinterpret_cast<const lds_h8*>(fb[kn ^ (4 * (j & 1))] + (uint32_t)(j * 4096 + buf * TILE_BYTES));
     };
 
-    f16v acc[4][4];
-    zero_acc(acc);
+    f16v acc[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     if (nq > 0) {
         const int s1 = min(1, nq - 1);
 #pragma unroll
         for (int u = 0; u < 8; ++u) load_x(u, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_a(0, i, 0);
+        for (int i = 0; i < 2; ++i) load_a(0, i, 0);
         load_sz(0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_a(1, i, s1);
+        for (int i = 0; i < 2; ++i) load_a(1, i, s1);
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             put_x(u, 0);
@@ -249,10 +292,17 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
         }
         latch(0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) afr[0][i] = dequant_word(araw[0][i].x, lsz[i], cst);
+        for (int i = 0; i < 2; ++i) afr[0][i] = __builtin_bit_cast(u4, dequant_word(araw[0][i].x, lsz[i], cst));
+        // the pipeline finishes "the previous k-block's last pair" in its first two steps: hand it
+        // that pair of the first k-block in the state it expects (masked and rebased)
+        cq[7] = h2_bits(bits_h2(((araw[0][1].x >> 8) & cst.m1) | cst.g1) - h2{(_Float16)64.f, (_Float16)64.f});
+#pragma unroll
+        for (int e = 0; e < 7; ++e) cq[e] = 0u;
+        w8[0] = w8[1] = 0u;
+        px = u4{0u, 0u, 0u, 0u};
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) read_b(0, j, 0, 0);
+        for (int j = 0; j < 8; ++j) read_b(0, j, 0, 0);
 
         // stage st: X in buffer CUR, codes in set CUR
         auto stage = [&](int st, auto cur_c) {
@@ -261,47 +311,78 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
             // keep "base + constant" from being hoisted out of the loop into a register per constant:
             // inside the stage it folds into the instruction's offset field
             asm volatile("" : "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]), "+v"(fb[4]), "+v"(fb[5]), "+v"(fb[6]), "+v"(fb[7]));
-            asm volatile("" : "+v"(xw[0]), "+v"(xw[1]), "+v"(aoff[0]), "+v"(aoff[1]), "+v"(aoff[2]), "+v"(aoff[3]));
+            asm volatile("" : "+v"(xw[0]), "+v"(xw[1]), "+v"(aoff[0]), "+v"(aoff[1]));
             asm volatile("" : "+v"(xoff[0]), "+v"(xoff[1]), "+v"(xoff[2]), "+v"(xoff[3]), "+v"(xoff[4]), "+v"(xoff[5]), "+v"(xoff[6]), "+v"(xoff[7]));
-            auto slot = [&](auto s_c) {
-                constexpr int S = decltype(s_c)::value, ks = S >> 2, i = S & 3, kn = (ks + 1) & 3;
+            auto step = [&](auto t_c) {
+                constexpr int T = decltype(t_c)::value, ks = T >> 4, t = T & 15, i = t >> 3, j = t & 7, kn = (ks + 1) & 3;
                 constexpr int SRC = ks < 3 ? CUR : NXT;   // where the next k-block comes from
-                if (S == 12 && CUR == 1) {
-                    // the next stage opens a new group: latch it, and when it was the last of the four
-                    // held in registers fetch the following four (needed two stages from now)
+                if (T == 50 && CUR == 1) {
+                    // the pairs converted from here on belong to the next stage, which opens a new group:
+                    // latch it, and when it was the last of the four held in registers fetch the
+                    // following four (needed two stages from now)
                     const int g = min(st + 1, nq - 1) >> 1;
                     latch(g);
                     if ((g & 3) == 3 && 2 * (g + 1) < nq) load_sz(g + 1);
                 }
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[ks & 1][i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-                read_b(kn & 1, i, SRC, kn);
-                afr[kn & 1][i] = dequant_word(araw[SRC][i][kn], lsz[i], cst);
-                if (S < 8) {
-                    put_x(S, NXT);
-                    load_x(S, sl);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, afr[ks & 1][i]), bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                // Conversion of the next k-block's two words, software-pipelined so that no step holds
+                // two dependent instructions: pair a = t / 2 is masked at step 2a, rebased at 2a + 1,
+                // has its zero-point subtracted at 2a + 2 and is scaled at 2a + 3 (the last pair
+                // finishes in the first two steps of the following k-block, before its row block is used).
+                constexpr int a = t >> 1, ap = (a + 7) & 7;   // this step's young pair, and the one two steps older
+                constexpr int aci = a >> 2, apci = ap >> 2;
+                const h2 zs_old = bits_h2(lsz[apci]);
+                if ((t & 1) == 0) {
+                    const uint32_t w = araw[SRC][aci][kn];
+                    if ((a & 3) == 1) w8[aci] = w >> 8;
+                    const uint32_t src = (a & 3) < 2 ? w : w8[aci];
+                    cq[a] = (a & 1) ? ((src & cst.m1) | cst.g1) : ((src & cst.m0) | cst.g0);
+                    cq[ap] = h2_bits(bits_h2(cq[ap]) - h2{zs_old.x, zs_old.x});
+                    read_b(kn & 1, t >> 1, SRC, kn);
+                    if (T >= 4 && T <= 32 && (T & 3) == 0) {   // the chunk permuted in the two odd steps before
+                        constexpr int u = (T >> 2) - 1;
+                        *reinterpret_cast<lds_u4*>(xw[u & 1] + (uint32_t)((u >> 1) * 8192 + NXT * TILE_BYTES)) = px;
+                    }
+                } else {
+                    const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
+                    cq[a] = h2_bits(bits_h2(cq[a]) - ((a & 1) ? b1 : b0));
+                    // pair 7 of the previous conversion belongs to the k-block now being multiplied
+                    afr[a == 0 ? (ks & 1) : (kn & 1)][apci][ap & 3] = h2_bits(bits_h2(cq[ap]) * h2{zs_old.y, zs_old.y});
+                    if (T < 32) {   // X chunk u of the next stage: half of the permutation per odd step
+                        constexpr int u = T >> 2;
+                        if ((T & 2) == 0) {
+                            px.x = __builtin_amdgcn_perm(xv[u].z, xv[u].x, 0x05040100u);
+                            px.y = __builtin_amdgcn_perm(xv[u].z, xv[u].x, 0x07060302u);
+                        } else {
+                            px.z = __builtin_amdgcn_perm(xv[u].w, xv[u].y, 0x05040100u);
+                            px.w = __builtin_amdgcn_perm(xv[u].w, xv[u].y, 0x07060302u);
+                            load_x(u, sl);
+                        }
+                    }
+                    if (ks == 3 && j == 7) load_a(CUR, i, sl);
                 }
-                if (S >= 12) load_a(CUR, i, sl);
-                if (S == 11) __syncthreads();
+                if (T == 47) __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             };
-            slot(std::integral_constant<int, 0>{});
-            slot(std::integral_constant<int, 1>{});
-            slot(std::integral_constant<int, 2>{});
-            slot(std::integral_constant<int, 3>{});
-            slot(std::integral_constant<int, 4>{});
-            slot(std::integral_constant<int, 5>{});
-            slot(std::integral_constant<int, 6>{});
-            slot(std::integral_constant<int, 7>{});
-            slot(std::integral_constant<int, 8>{});
-            slot(std::integral_constant<int, 9>{});
-            slot(std::integral_constant<int, 10>{});
-            slot(std::integral_constant<int, 11>{});
-            slot(std::integral_constant<int, 12>{});
-            slot(std::integral_constant<int, 13>{});
-            slot(std::integral_constant<int, 14>{});
-            slot(std::integral_constant<int, 15>{});
+            auto steps8 = [&](auto b_c) {
+                constexpr int B = decltype(b_c)::value;
+                step(std::integral_constant<int, B + 0>{});
+                step(std::integral_constant<int, B + 1>{});
+                step(std::integral_constant<int, B + 2>{});
+                step(std::integral_constant<int, B + 3>{});
+                step(std::integral_constant<int, B + 4>{});
+                step(std::integral_constant<int, B + 5>{});
+                step(std::integral_constant<int, B + 6>{});
+                step(std::integral_constant<int, B + 7>{});
+            };
+            steps8(std::integral_constant<int, 0>{});
+            steps8(std::integral_constant<int, 8>{});
+            steps8(std::integral_constant<int, 16>{});
+            steps8(std::integral_constant<int, 24>{});
+            steps8(std::integral_constant<int, 32>{});
+            steps8(std::integral_constant<int, 40>{});
+            steps8(std::integral_constant<int, 48>{});
+            steps8(std::integral_constant<int, 56>{});
         };
         int st = 0;
         for (; st + 1 < nq; st += 2) {
@@ -312,33 +393,43 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
         __syncthreads();
     }
 
-    // ---- weak block: plain fp16 stages with both operands through LDS, one at a time ----------------
+    // ---- weak block: plain fp16 stages with both operands through LDS -------------------------------
+    // Stage w sits in tiles (w & 1) [X] and 2 + (w & 1) [weights]; the fetch of stage w + 1 is in
+    // flight while stage w is multiplied, and alternating tiles need one barrier per stage only.
     const int nw = (L.k + BK - 1) / BK;
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
-    unsigned char* sA = lds + 2 * TILE_BYTES;
-    for (int w = 0; w < nw; ++w) {
-        u4 wa[8], wb[8];
+    u4 wa[8], wb[8];
+    auto load_weak = [&](int w) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const int r = xr + 32 * u, col = BK * w + 8 * xc;
             wa[u] = (col < L.k) ? ld16(L.weak + (size_t)min(oc0 + r, L.oc - 1) * L.k + col) : zero4;
             wb[u] = (col < L.k) ? ld16(X + (size_t)min(m0 + r, M - 1) * ldx + L.kq + col) : zero4;
         }
+    };
+    if (nw > 0) load_weak(0);
+    for (int w = 0; w < nw; ++w) {
+        unsigned char* sB = lds + (w & 1) * TILE_BYTES;
+        unsigned char* sA = lds + (2 + (w & 1)) * TILE_BYTES;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             *reinterpret_cast<u4*>(sA + tile_off(xr + 32 * u, xc)) = wa[u];
-            *reinterpret_cast<u4*>(lds + tile_off(xr + 32 * u, xc)) = wb[u];
+            *reinterpret_cast<u4*>(sB + tile_off(xr + 32 * u, xc)) = wb[u];
         }
+        if (w + 1 < nw) load_weak(w + 1);
         __syncthreads();
-        Frags f;
+        FragsT<2, 8> f;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            load_frags(f, sA, lds, wr, wc, lane, ks);
-            mfma_block(f, acc);
+            load_frags_t<2, 8>(f, sA, sB, wave * 64, 0, lane, ks);
+            mfma_block_t<2, 8>(f, acc);
         }
-        __syncthreads();
     }
-    store_f16(acc, Y, ldy, oc0, L.oc, m0, M, wr, wc, lane);
+    if (wide_stores) __syncthreads();   // the epilogue reuses the tiles
+    if (wide_stores)
+        store_f16_lds_64x256(acc, lds + wave * TILE_BYTES, Y, ldy, oc0 + wave * 64, L.oc, m0, M, lane);
+    else
+        store_f16_t<2, 8>(acc, Y, ldy, oc0 + wave * 64, L.oc, m0, M, lane);
 }
 
 // ======================================================================================= backward dX
@@ -904,7 +995,8 @@ hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __h
             if (e != hipSuccess) return e;
             attr = true;
         }
-        gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc);
+        const int wide = (ldy % 8 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+        gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide);
     } else {
         static bool attr = false;
         e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);
