@@ -946,6 +946,150 @@ __global__ __launch_bounds__(256) void weak_grad_kernel(int oc_total, int k, con
     store_f32(acc, part + (size_t)split * oc_total * k, k, 0, k, oc0, oc_total, wm, wn, lane);
 }
 
+// The same for k <= 128 (the paper's settings), sized for what bounds it - reading dY once from
+// HBM: a workgroup owns 64 output channels x all k weak columns over a range of tokens, so the
+// MFMA tiles hold no padding and a dY row contributes 128 contiguous bytes.  Both operands have
+// the contraction index (the token) as their row index; instead of transposing 8 x 8 blocks in
+// registers, the tiles go to LDS as they are ([token][column], rows padded by 32 bytes) and the
+// fragments are read with the transposing LDS load of gfx950 (ds_read_b64_tr_b16: the 16 lanes
+// of a group each name 4 consecutive halfs; output lane l receives element l % 4 of source
+// lanes l / 4, l / 4 + 4, l / 4 + 8, l / 4 + 12).  With source lane s pointing at row k0 + s / 4,
+// columns c0 + 4 (s % 4) .., a group receives columns c0 .. c0 + 15 of rows k0 .. k0 + 3 - four
+// consecutive contraction steps for 16 MFMA rows; two such loads make one fragment.
+// Wave w multiplies weak columns 32 w .. 32 w + 31 against the 64 channels.  With one split
+// the result goes straight to dW, otherwise into fp32 slabs as above.
+constexpr int WG_OC = 64;                             // output channels per workgroup
+constexpr int WG_A_PITCH = 128 * 2 + 32;              // bytes per token row of the Xw tile
+constexpr int WG_B_PITCH = WG_OC * 2 + 32;            // ... of the dY tile
+constexpr int WG_A_BYTES = BK * WG_A_PITCH, WG_B_BYTES = BK * WG_B_PITCH;
+constexpr int WG_LDS = 2 * (WG_A_BYTES + WG_B_BYTES); // A0 A1 B0 B1
+
+__global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int k, const __half* __restrict__ dY, int M,
+                                                              int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
+                                                              float* __restrict__ part, int splits, int chunk, void* dW,
+                                                              int out_f32, int accumulate) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    typedef short s4 __attribute__((ext_vector_type(4)));
+    typedef short s8 __attribute__((ext_vector_type(8)));
+    using lds_s4 = __attribute__((address_space(3))) s4;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int split = blockIdx.x % splits, t_oc = blockIdx.x / splits;
+    const int oc0 = t_oc * WG_OC;
+    const int mb = split * chunk, me = min(mb + chunk, M);
+    const int nst = (me - mb + BK - 1) / BK;
+    const int fr = lane & 31, fk = lane >> 5;
+
+    // producers: 16-byte chunks, copied as they are.  Xw tile: 64 tokens x 16 chunks, four per
+    // thread (token ar + 16 u, chunk ac); dY tile: 64 tokens x 8 chunks, two per thread (token
+    // br + 32 u, chunk bc).  Chunks past k or past the last channel read column 0 and are zeroed.
+    const int ar = tid >> 4, ac = tid & 15, br = tid >> 3, bc = tid & 7;
+    const bool a_ok = 8 * ac < k, b_ok = oc0 + 8 * bc < oc_total;
+    const __half* a_src = Xw + (a_ok ? 8 * ac : 0);
+    const __half* b_src = dY + (b_ok ? oc0 + 8 * bc : 0);
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    // three stages of fetches in flight per thread (registers), a fourth in LDS being multiplied
+    u4 va[3][4], vb[3][2];
+    auto fetch = [&](auto set_c, int st) {
+        constexpr int SET = decltype(set_c)::value;
+        // branch-free (a fetch under a condition would be waited for at once): tokens past the range
+        // read a valid row; put() zeroes them when it consumes the registers (a select here would
+        // make every turn of the loop wait for its fetches)
+        const int m0 = mb + BK * st;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) va[SET][u] = ld16(a_src + (size_t)min(m0 + ar + 16 * u, M - 1) * ldxw);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) vb[SET][u] = ld16(b_src + (size_t)min(m0 + br + 32 * u, M - 1) * lddy);
+    };
+    auto put = [&](auto set_c, int st, int buf) {   // stage st, held by register set SET, into LDS buffer buf
+        constexpr int SET = decltype(set_c)::value;
+        const int m0 = mb + BK * st;
+        unsigned char* sA = lds + buf * WG_A_BYTES;
+        unsigned char* sB = lds + 2 * WG_A_BYTES + buf * WG_B_BYTES;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            *reinterpret_cast<u4*>(sA + (ar + 16 * u) * WG_A_PITCH + 16 * ac) = (a_ok && m0 + ar + 16 * u < me) ? va[SET][u] : zero4;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+            *reinterpret_cast<u4*>(sB + (br + 32 * u) * WG_B_PITCH + 16 * bc) = (b_ok && m0 + br + 32 * u < me) ? vb[SET][u] : zero4;
+    };
+
+    f16v acc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.f;
+
+    // fragment addressing: lane = 16 g + s; rows (tokens) 8 (g / 2) + s / 4 (+ 4 for the second
+    // load, + 16 per k-block), columns 16 (g % 2) + 4 (s % 4) of the wave's 32
+    const int g = lane >> 4, s = lane & 15;
+    const int frow = 8 * (g >> 1) + (s >> 2), fcol = 16 * (g & 1) + 4 * (s & 3);
+    const uint32_t lds0 = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)lds;
+    const uint32_t fa = lds0 + frow * WG_A_PITCH + 2 * (32 * wave + fcol);
+    const uint32_t fb = lds0 + 2 * WG_A_BYTES + frow * WG_B_PITCH + 2 * fcol;
+    auto frag = [&](uint32_t addr, int pitch) {   // 8 contraction steps: rows +0..3 and +4..7
+        const s4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(size_t)(addr));
+        const s4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4*)(size_t)(addr + 4 * pitch));
+        return __builtin_bit_cast(h8, s8{lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w});
+    };
+
+    // stage st (already in LDS buffer st & 1, fetched through register set SET): refill the set
+    // with stage st + 3, multiply, move stage st + 1 from the next set into the other buffer
+    auto stage = [&](auto set_c, int st) {
+        constexpr int SET = decltype(set_c)::value;
+        const int cur = st & 1;
+        fetch(set_c, st + 3);
+        __builtin_amdgcn_sched_barrier(0);   // issue the fetches first: they are what the stage waits for
+        const uint32_t a0 = fa + cur * WG_A_BYTES, b0 = fb + cur * WG_B_BYTES;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const h8 a = frag(a0 + 16 * ks * WG_A_PITCH, WG_A_PITCH);
+            const h8 bl = frag(b0 + 16 * ks * WG_B_PITCH, WG_B_PITCH);
+            const h8 bh = frag(b0 + 16 * ks * WG_B_PITCH + 64, WG_B_PITCH);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bl, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bh, acc[1], 0, 0, 0);
+        }
+        put(std::integral_constant<int, (SET + 1) % 3>{}, st + 1, cur ^ 1);
+        __syncthreads();
+    };
+    fetch(std::integral_constant<int, 0>{}, 0);
+    fetch(std::integral_constant<int, 1>{}, 1);
+    fetch(std::integral_constant<int, 2>{}, 2);
+    put(std::integral_constant<int, 0>{}, 0, 0);
+    __syncthreads();
+    // always three stages per turn, with no branch between them (the compiler's wait counting then
+    // lets two stages of fetches stay in flight); stages past the range multiply zeros
+    for (int st = 0; st < nst; st += 3) {
+        stage(std::integral_constant<int, 0>{}, st);
+        stage(std::integral_constant<int, 1>{}, st + 1);
+        stage(std::integral_constant<int, 2>{}, st + 2);
+    }
+    if (32 * wave >= k) return;   // this wave's weak columns do not exist
+    // lane (fr, fk) holds, for channel oc0 + 32 t + fr, weak columns 32 wave + 8 g + 4 fk .. + 3
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        const int j = oc0 + 32 * t + fr;
+        if (j >= oc_total) continue;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = 32 * wave + 8 * q + 4 * fk;
+            if (i >= k) continue;
+            f4 r = f4{acc[t][4 * q + 0], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
+            const size_t at = (size_t)j * k + i;
+            if (splits > 1) {
+                *reinterpret_cast<f4*>(part + (size_t)split * oc_total * k + at) = r;
+            } else if (out_f32) {
+                f4* o = reinterpret_cast<f4*>((float*)dW + at);
+                *o = accumulate ? *o + r : r;
+            } else {
+                __half* o = (__half*)dW + at;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o[e] = __float2half_rn(accumulate ? __half2float(o[e]) + r[e] : r[e]);
+            }
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void weak_grad_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
                                                                void* dW, int out_f32, int accumulate) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1035,22 +1179,48 @@ bool weak_grad_mfma_supported(int oc, int k, int64_t M) {
     return M >= 64 && k >= 8 && k <= BT && (k % 8) == 0 && (oc % 8) == 0;
 }
 
+namespace {
+// split of the tokens for the strip kernel: about one workgroup per CU (more splits would add
+// slab traffic comparable to dY itself), every split a whole number of stages
+void weak_grad_strip_split(int oc, int64_t M, int& splits, int& chunk) {
+    const int tiles = ceil_div(oc, WG_OC);
+    const int stages = ceil_div(M, BK);
+    int want = ceil_div(256, tiles);
+    if (want > stages) want = stages;
+    if (want < 1) want = 1;
+    chunk = ceil_div(stages, want) * BK;
+    splits = ceil_div(M, chunk);
+}
+}  // namespace
+
 size_t weak_grad_mfma_workspace(int oc, int k, int64_t M) {
     int splits, chunk;
+    if (k <= 128) {
+        weak_grad_strip_split(oc, M, splits, chunk);
+        return splits > 1 ? (size_t)splits * oc * k * sizeof(float) : 0;
+    }
     weak_grad_split(oc, M, splits, chunk);
     return (size_t)splits * oc * k * sizeof(float);
 }
 
 hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
                           void* dW, int out_f32, int accumulate, void* ws, hipStream_t s) {
+    int splits, chunk;
+    const int64_t n = (int64_t)oc * k;
+    if (k <= 128) {
+        weak_grad_strip_split(oc, M, splits, chunk);
+        weak_grad_strip_kernel<<<ceil_div(oc, WG_OC) * splits, 256, WG_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws,
+                                                                                splits, chunk, dW, out_f32, accumulate);
+        if (splits > 1)
+            weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
+        return hipGetLastError();
+    }
     static bool attr = false;
     hipError_t e = raise_lds_limit((const void*)weak_grad_kernel, attr);
     if (e != hipSuccess) return e;
-    int splits, chunk;
     weak_grad_split(oc, M, splits, chunk);
     weak_grad_kernel<<<ceil_div(oc, BT) * splits, 256, GEMM_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws,
                                                                      splits, chunk);
-    const int64_t n = (int64_t)oc * k;
     weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
     return hipGetLastError();
 }
