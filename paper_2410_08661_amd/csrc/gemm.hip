@@ -159,7 +159,10 @@ constexpr int REGA_LDS = 4 * TILE_BYTES;   // X0 X1 and one tile for the weak bl
 
 // fp16 epilogue of a 64 (i) x 256 (j) wave tile through 32 KB of LDS of the wave's own: rows j of
 // 128 bytes, 16-byte chunks XOR-swizzled with j, then 16-byte global stores (128 contiguous bytes
-// per row).  i0 and ni multiples of 8, out rows 16-byte aligned.  No barrier: one wave, in-order LDS.
+// per row).  QUADS = false: accumulator tile t_i row 8 g + 4 fk + e is i = 32 t_i + row; QUADS =
+// true (the input-gradient kernel's quantized halves): it is i = 4 (row % 16) + t_i + 2 (row / 16).
+// i0 and ni multiples of 8, out rows 16-byte aligned.  No barrier: one wave, in-order LDS.
+template <bool QUADS>
 __device__ __forceinline__ void store_f16_lds_64x256(const f16v (&acc)[2][8], unsigned char* stage, __half* out, int64_t ld,
                                                      int i0, int ni, int j0, int nj, int lane) {
     const int fr = lane & 31, fk = lane >> 5;
@@ -168,12 +171,22 @@ __device__ __forceinline__ void store_f16_lds_64x256(const f16v (&acc)[2][8], un
     for (int tj = 0; tj < 8; ++tj) {
         unsigned char* row = stage + (tj * 32 + fr) * 128;
         const int sw = fr & 7;
+        if (!QUADS) {
 #pragma unroll
-        for (int ti = 0; ti < 2; ++ti)
+            for (int ti = 0; ti < 2; ++ti)
 #pragma unroll
-            for (int g = 0; g < 4; ++g)
-                *reinterpret_cast<u2*>(row + (((4 * ti + g) ^ sw) << 4) + 8 * fk) =
-                    u2{pack(acc[ti][tj][4 * g + 0], acc[ti][tj][4 * g + 1]), pack(acc[ti][tj][4 * g + 2], acc[ti][tj][4 * g + 3])};
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<u2*>(row + (((4 * ti + g) ^ sw) << 4) + 8 * fk) =
+                        u2{pack(acc[ti][tj][4 * g + 0], acc[ti][tj][4 * g + 1]), pack(acc[ti][tj][4 * g + 2], acc[ti][tj][4 * g + 3])};
+        } else {
+            // channels 4 c .. 4 c + 3, c = 8 g0 + 4 fk + e: (t_i, g) = (0, g0) (1, g0) (0, g0 + 2) (1, g0 + 2)
+#pragma unroll
+            for (int g0 = 0; g0 < 2; ++g0)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    *reinterpret_cast<u2*>(row + (((4 * g0 + 2 * fk + (e >> 1)) ^ sw) << 4) + 8 * (e & 1)) =
+                        u2{pack(acc[0][tj][4 * g0 + e], acc[1][tj][4 * g0 + e]), pack(acc[0][tj][4 * (g0 + 2) + e], acc[1][tj][4 * (g0 + 2) + e])};
+        }
     }
     const int c = lane & 7, r8 = lane >> 3;
     const int i = i0 + 8 * c;
@@ -427,7 +440,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     }
     if (wide_stores) __syncthreads();   // the epilogue reuses the tiles
     if (wide_stores)
-        store_f16_lds_64x256(acc, lds + wave * TILE_BYTES, Y, ldy, oc0 + wave * 64, L.oc, m0, M, lane);
+        store_f16_lds_64x256<false>(acc, lds + wave * TILE_BYTES, Y, ldy, oc0 + wave * 64, L.oc, m0, M, lane);
     else
         store_f16_t<2, 8>(acc, Y, ldy, oc0 + wave * 64, L.oc, m0, M, lane);
 }
@@ -546,7 +559,7 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
                                         __half* __restrict__ dX, int64_t lddx, int ic0, int m0, unsigned char* lds) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wr = wave >> 1, wc = wave & 1;
+    const int half = wave >> 1, lb = wave & 1;   // the tile half this wave works in, and which 64 channels of it
     const int nst = L.oc / BK;
     const RegConsts cst = make_reg_consts();
     using lds_u4 = __attribute__((address_space(3))) u4;
@@ -602,7 +615,7 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
     uint32_t fb[4];   // dY fragments, indexed by (XOR constant) / 2
 #pragma unroll
     for (int x = 0; x < 4; ++x)
-        fb[x] = lds0 + (uint32_t)(wc * 128 + fr) * 128u + ((((uint32_t)(fk ^ (fr & 7) ^ (fr >> 3))) ^ (2u * x)) << 4);
+        fb[x] = lds0 + (uint32_t)fr * 128u + ((((uint32_t)(fk ^ (fr & 7) ^ (fr >> 3))) ^ (2u * x)) << 4);
     // lines: the 16-byte chunk t of a line (rows 8 t .. 8 t + 7) sits at slot t ^ (line / 8 % 8), so that
     // the eight threads that write one row pair into eight different line groups spread over the banks
     const uint32_t lw = (((uint32_t)((rp >> 2) ^ xc)) << 4) + (uint32_t)(rp & 3) * 4u;   // position of row pair rp, line group xc (mod 8)
@@ -660,8 +673,13 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
                 __builtin_amdgcn_perm(ww[n][1][e >> 1], ww[n][0][e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
     };
 
-    f16v acc[4][4];
-    zero_acc(acc);
+    f16v acc[2][8];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
     // ---- stage 0 into buffer 0, stage 1 into the registers ------------------------------------------
     {
@@ -726,166 +744,180 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
 #pragma unroll
         for (int n = 0; n < NW; ++n) asm volatile("" : "+v"(woff[n]), "+v"(wwr[n]));
     };
-    h8 afr[4], bfr[2][4];
+    // ---- consumers: wave w owns 64 channels (block lb = w % 2 of half w / 2) x all 256 tokens --------
+    // A stage is 64 steps of one MFMA (k-block T / 16, channel fragment T / 8 % 2, token fragment
+    // T % 8) with a scheduling barrier after each: even steps read one dY fragment of the next
+    // k-block, odd steps 4 S + 1 carry the producers' slot S, and the conversion of the next
+    // k-block's codes is spread so that no step holds two dependent instructions.
+    h8 bfr[2][8];
+    u4 afr[2][2];   // A fragments of a k-block (set = block parity), as packed halfs
     auto read_b = [&](int set, int j, int buf, int kn) {
         bfr[set][j] = *reinterpret_cast<const lds_h8*>(fb[kn ^ (2 * (j & 1))] + (uint32_t)(j * 4096 + buf * TILE_BYTES));
     };
-    const int icw = ic0 + 128 * wr;
+    const int icw = ic0 + 128 * half + 64 * lb;
+    auto mfma_step = [&](auto t_c) {
+        constexpr int T = decltype(t_c)::value, ks = T >> 4, i = (T >> 3) & 1, j = T & 7;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, afr[ks & 1][i]), bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+    };
+    auto produce_step = [&](auto t_c, auto nxt_c, int sl) {
+        constexpr int T = decltype(t_c)::value;
+        if ((T & 3) == 1 && T < 48) produce(std::integral_constant<int, (T >> 2)>{}, nxt_c, sl);
+    };
+    auto run_stages = [&](auto&& stage) {
+        int st = 0;
+        for (; st + 1 < nst; st += 2) {
+            stage(st, std::integral_constant<int, 0>{});
+            stage(st + 1, std::integral_constant<int, 1>{});
+        }
+        if (nst & 1) stage(st, std::integral_constant<int, 0>{});
+        __syncthreads();   // every wave is done with the staging buffers
+    };
+#define QEFT_STEPS8(F, B)                                                                                        \
+    F(std::integral_constant<int, (B) + 0>{}); F(std::integral_constant<int, (B) + 1>{});                       \
+    F(std::integral_constant<int, (B) + 2>{}); F(std::integral_constant<int, (B) + 3>{});                       \
+    F(std::integral_constant<int, (B) + 4>{}); F(std::integral_constant<int, (B) + 5>{});                       \
+    F(std::integral_constant<int, (B) + 6>{}); F(std::integral_constant<int, (B) + 7>{});
+#define QEFT_STEPS64(F)                                                                                          \
+    QEFT_STEPS8(F, 0) QEFT_STEPS8(F, 8) QEFT_STEPS8(F, 16) QEFT_STEPS8(F, 24) QEFT_STEPS8(F, 32) QEFT_STEPS8(F, 40) \
+    QEFT_STEPS8(F, 48) QEFT_STEPS8(F, 56)
 
-    // ---- a wave that owns a quantized half ---------------------------------------------------------------
+    // ---- a wave in a quantized half ---------------------------------------------------------------------
+    // Lane fr reads line 16 lb + fr % 16 (both lanes fr and fr + 16 the same one) and takes nibble
+    // t + 2 (fr / 16) of its 16-bit words for fragment t: after a per-lane shift by 0 or 8 bits,
+    // fragment 0 is the nibble at bits 0..3 (as 1024 + q) and fragment 1 the one at bits 4..7 (as
+    // 64 + q), the two positions that lie inside the fp16 mantissa.  Row fr of fragment t is channel
+    // 4 (fr % 16) + t + 2 (fr / 16) of the wave's 64, so a lane's accumulators (0, g, e) (1, g, e)
+    // (0, g + 2, e) (1, g + 2, e) are four consecutive channels.
     auto run_quant = [&]() {
         uint32_t crd[4];  // code lines, indexed by k-block
         {
-            // line fr = (word column fr / 2, half fr % 2) of this wave's half; its line group for the
-            // chunk swizzle is the writer's xc = fr / 8 + 4 wr
-            const int cl = (fr >> 3) + 4 * wr;
+            const int ln = 16 * lb + (fr & 15);
+            const int cl = (ln >> 3) + 4 * half;   // the line's group in the chunk swizzle: its writer's xc
 #pragma unroll
             for (int kn = 0; kn < 4; ++kn)
-                crd[kn] = lds0 + DX_LINE_BASE + (uint32_t)wr * DX_HALF + (uint32_t)fr * DX_LINE + ((uint32_t)((fk ^ cl) ^ (2 * kn)) << 4);
+                crd[kn] = lds0 + DX_LINE_BASE + (uint32_t)half * DX_HALF + (uint32_t)ln * DX_LINE + ((uint32_t)((fk ^ cl) ^ (2 * kn)) << 4);
         }
-        uint32_t szr = lds0 + DX_SZ_BASE + (uint32_t)wr * 256u + 16u * fk;
-        u4 cf[2];         // code fragment of a k-block: register p = rows 2p | 2p+1 (set = block parity)
-        h8 zf[2], sf[2];  // zero-points and scales of its 8 rows
-        auto read_codes = [&](int set, int buf, int kn) {
-            cf[set] = *reinterpret_cast<const lds_u4*>(crd[kn] + (uint32_t)(buf * DX_LINES));
-            zf[set] = *reinterpret_cast<const lds_h8*>(szr + (uint32_t)(32 * kn + buf * DX_SZ));
-            sf[set] = *reinterpret_cast<const lds_h8*>(szr + (uint32_t)(128 + 32 * kn + buf * DX_SZ));
+        uint32_t szr = lds0 + DX_SZ_BASE + (uint32_t)half * 256u + 16u * fk;
+        uint32_t nsh = 8u * (uint32_t)(fr >> 4);
+        u4 cf;            // code words of the k-block being converted: register p = rows 2p | 2p+1
+        u4 cfs;           // ... shifted to this lane's nibbles
+        h8 zf, sf;        // zero-points and scales of its 8 rows
+        uint32_t cq[8];   // the conversion pipeline, one register per pair
+        auto read_codes = [&](int buf, int kn) {
+            cf = *reinterpret_cast<const lds_u4*>(crd[kn] + (uint32_t)(buf * DX_LINES));
+            zf = *reinterpret_cast<const lds_h8*>(szr + (uint32_t)(32 * kn + buf * DX_SZ));
+            sf = *reinterpret_cast<const lds_h8*>(szr + (uint32_t)(128 + 32 * kn + buf * DX_SZ));
         };
-        auto convert = [&](int i, int set) {   // A fragment i (channel 4 fr + i) of the block held in `set`
-            const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
-            u4 r;
+        const h2 b0 = h2{(_Float16)1024.f, (_Float16)1024.f}, b1 = h2{(_Float16)64.f, (_Float16)64.f};
+        // pair a = 4 t + p (fragment t, register p) goes through: mask, rebase, zero-point, scale
+        auto cv_mask = [&](auto a_c) {
+            constexpr int a = decltype(a_c)::value;
+            cq[a] = (a < 4) ? ((cfs[a & 3] & cst.m0) | cst.g0) : ((cfs[a & 3] & cst.m1) | cst.g1);
+        };
+        auto cv_base = [&](auto a_c) {
+            constexpr int a = decltype(a_c)::value;
+            cq[a] = h2_bits(bits_h2(cq[a]) - (a < 4 ? b0 : b1));
+        };
+        auto cv_zero = [&](auto a_c) {
+            constexpr int a = decltype(a_c)::value, p = a & 3;
+            cq[a] = h2_bits(bits_h2(cq[a]) - h2{zf[2 * p], zf[2 * p + 1]});
+        };
+        auto cv_scale = [&](auto a_c, int set) {
+            constexpr int a = decltype(a_c)::value, p = a & 3;
+            afr[set][a >> 2][p] = h2_bits(bits_h2(cq[a]) * h2{sf[2 * p], sf[2 * p + 1]});
+        };
+        // pair a enters the pipeline at step 4 + a of the k-block (the lines are read at step 0, shifted
+        // at step 3) and leaves it at step 7 + a <= 14
+        auto convert_step = [&](auto t_c, int buf_src) {
+            constexpr int T = decltype(t_c)::value, ks = T >> 4, t = T & 15, kn = (ks + 1) & 3;
+            if (t == 0) read_codes(buf_src, kn);
+            if (t == 3) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const uint32_t w = (i & 2) ? cf[set][p] >> 8 : cf[set][p];
-                const h2 t = (i & 1) ? bits_h2((w & cst.m1) | cst.g1) - b1 : bits_h2((w & cst.m0) | cst.g0) - b0;
-                const h2 z2 = h2{zf[set][2 * p], zf[set][2 * p + 1]}, s2 = h2{sf[set][2 * p], sf[set][2 * p + 1]};
-                r[p] = h2_bits((t - z2) * s2);
+                for (int p = 0; p < 4; ++p) cfs[p] = cf[p] >> nsh;
             }
-            afr[i] = __builtin_bit_cast(h8, r);
+            if (t >= 4 && t <= 11) cv_mask(std::integral_constant<int, (t - 4) & 7>{});
+            if (t >= 5 && t <= 12) cv_base(std::integral_constant<int, (t - 5) & 7>{});
+            if (t >= 6 && t <= 13) cv_zero(std::integral_constant<int, (t - 6) & 7>{});
+            if (t >= 7 && t <= 14) cv_scale(std::integral_constant<int, (t - 7) & 7>{}, kn & 1);
         };
-        read_codes(0, 0, 0);
+        // k-block 0 of stage 0, unpipelined
+        read_codes(0, 0);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) read_b(0, j, 0, 0);
+        for (int j = 0; j < 8; ++j) read_b(0, j, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 3; ++i) convert(i, 0);
+        for (int p = 0; p < 4; ++p) cfs[p] = cf[p] >> nsh;
+        QEFT_STEPS8(cv_mask, 0)
+        QEFT_STEPS8(cv_base, 0)
+        QEFT_STEPS8(cv_zero, 0)
+        {
+            auto sc0 = [&](auto a_c) { cv_scale(a_c, 0); };
+            QEFT_STEPS8(sc0, 0)
+        }
 
         auto stage = [&](int st, auto cur_c) {
             constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
             const int sl = min(st + 2, nst - 1);
             protect();
             asm volatile("" : "+v"(crd[0]), "+v"(crd[1]), "+v"(crd[2]), "+v"(crd[3]), "+v"(szr));
-            auto slot = [&](auto s_c) {
-                constexpr int S = decltype(s_c)::value, ks = S >> 2, i = S & 3, kn = (ks + 1) & 3;
+            auto step = [&](auto t_c) {
+                constexpr int T = decltype(t_c)::value, ks = T >> 4, t = T & 15, kn = (ks + 1) & 3;
                 constexpr int SRC = ks < 3 ? CUR : NXT;   // where the next k-block comes from
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-                // dY fragments one block ahead, codes of the next block at its predecessor's first slot,
-                // A fragments three slots ahead of their MFMAs
-                read_b(kn & 1, i, SRC, kn);
-                if (i == 0) {
-                    convert(3, ks & 1);
-                    read_codes(kn & 1, SRC, kn);
-                } else {
-                    convert(i - 1, kn & 1);
-                }
-                produce(s_c, std::integral_constant<int, NXT>{}, sl);
-                if (S == 11) __syncthreads();
+                mfma_step(t_c);
+                if ((t & 1) == 0) read_b(kn & 1, t >> 1, SRC, kn);
+                convert_step(t_c, SRC);
+                produce_step(t_c, std::integral_constant<int, NXT>{}, sl);
+                if (T == 47) __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             };
-            slot(std::integral_constant<int, 0>{});
-            slot(std::integral_constant<int, 1>{});
-            slot(std::integral_constant<int, 2>{});
-            slot(std::integral_constant<int, 3>{});
-            slot(std::integral_constant<int, 4>{});
-            slot(std::integral_constant<int, 5>{});
-            slot(std::integral_constant<int, 6>{});
-            slot(std::integral_constant<int, 7>{});
-            slot(std::integral_constant<int, 8>{});
-            slot(std::integral_constant<int, 9>{});
-            slot(std::integral_constant<int, 10>{});
-            slot(std::integral_constant<int, 11>{});
-            slot(std::integral_constant<int, 12>{});
-            slot(std::integral_constant<int, 13>{});
-            slot(std::integral_constant<int, 14>{});
-            slot(std::integral_constant<int, 15>{});
+            QEFT_STEPS64(step)
         };
-        int st = 0;
-        for (; st + 1 < nst; st += 2) {
-            stage(st, std::integral_constant<int, 0>{});
-            stage(st + 1, std::integral_constant<int, 1>{});
-        }
-        if (nst & 1) stage(st, std::integral_constant<int, 0>{});
-
-        // a lane's accumulators (t_i = 0..3) for fixed row 8 g + 4 fk + e are channels 4 row + t_i
-        __syncthreads();   // every wave is done with the staging buffers
-        store_f16_lds<true>(acc, lds + wave * TILE_BYTES, dX, lddx, icw, L.kq, m0 + 128 * wc, M, lane);
+        run_stages(stage);
+        store_f16_lds_64x256<true>(acc, lds + wave * TILE_BYTES, dX, lddx, icw, L.kq, m0, M, lane);
     };
 
-    // ---- a wave that owns a weak half --------------------------------------------------------------------
+    // ---- a wave in a weak half --------------------------------------------------------------------------
+    // Fragment t of lane fr is line (channel) 64 lb + 32 t + fr of the half, 16 bytes of it as they are.
     auto run_weak = [&]() {
-        uint32_t wrd[4];  // weak lines of fragment 0, indexed by (XOR constant) / 2; fragment i is 32 lines on
+        uint32_t wrd[4];  // weak lines of fragment 0, indexed by (XOR constant) / 2
 #pragma unroll
         for (int x = 0; x < 4; ++x)
-            wrd[x] = lds0 + DX_LINE_BASE + (uint32_t)wr * DX_HALF + (uint32_t)fr * DX_LINE + ((uint32_t)((fk ^ (fr >> 3)) ^ (2 * x)) << 4);
-        auto read_a = [&](int i, int buf, int kn) {
-            afr[i] = *reinterpret_cast<const lds_h8*>(wrd[kn ^ (2 * (i & 1))] + (uint32_t)(i * 32 * DX_LINE + buf * DX_LINES));
+            wrd[x] = lds0 + DX_LINE_BASE + (uint32_t)half * DX_HALF + (uint32_t)(64 * lb + fr) * DX_LINE +
+                     ((uint32_t)((fk ^ (fr >> 3)) ^ (2 * x)) << 4);
+        auto read_a = [&](int set, int i, int buf, int kn) {
+            afr[set][i] = *reinterpret_cast<const lds_u4*>(wrd[kn ^ (2 * (i & 1))] + (uint32_t)(i * 32 * DX_LINE + buf * DX_LINES));
         };
 #pragma unroll
-        for (int j = 0; j < 4; ++j) read_b(0, j, 0, 0);
+        for (int j = 0; j < 8; ++j) read_b(0, j, 0, 0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) read_a(i, 0, 0);
+        for (int i = 0; i < 2; ++i) read_a(0, i, 0, 0);
 
         auto stage = [&](int st, auto cur_c) {
             constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
             const int sl = min(st + 2, nst - 1);
             protect();
             asm volatile("" : "+v"(wrd[0]), "+v"(wrd[1]), "+v"(wrd[2]), "+v"(wrd[3]));
-            auto slot = [&](auto s_c) {
-                constexpr int S = decltype(s_c)::value, ks = S >> 2, i = S & 3, kn = (ks + 1) & 3;
+            auto step = [&](auto t_c) {
+                constexpr int T = decltype(t_c)::value, ks = T >> 4, t = T & 15, kn = (ks + 1) & 3;
                 constexpr int SRC = ks < 3 ? CUR : NXT;
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(afr[i], bfr[ks & 1][j], acc[i][j], 0, 0, 0);
-                read_b(kn & 1, i, SRC, kn);
-                read_a(i, SRC, kn);   // into the registers the MFMAs above just released
-                produce(s_c, std::integral_constant<int, NXT>{}, sl);
-                if (S == 11) __syncthreads();
+                mfma_step(t_c);
+                if ((t & 1) == 0) read_b(kn & 1, t >> 1, SRC, kn);
+                if (t == 3 || t == 7) read_a(kn & 1, t >> 2, SRC, kn);
+                produce_step(t_c, std::integral_constant<int, NXT>{}, sl);
+                if (T == 47) __syncthreads();
                 __builtin_amdgcn_sched_barrier(0);
             };
-            slot(std::integral_constant<int, 0>{});
-            slot(std::integral_constant<int, 1>{});
-            slot(std::integral_constant<int, 2>{});
-            slot(std::integral_constant<int, 3>{});
-            slot(std::integral_constant<int, 4>{});
-            slot(std::integral_constant<int, 5>{});
-            slot(std::integral_constant<int, 6>{});
-            slot(std::integral_constant<int, 7>{});
-            slot(std::integral_constant<int, 8>{});
-            slot(std::integral_constant<int, 9>{});
-            slot(std::integral_constant<int, 10>{});
-            slot(std::integral_constant<int, 11>{});
-            slot(std::integral_constant<int, 12>{});
-            slot(std::integral_constant<int, 13>{});
-            slot(std::integral_constant<int, 14>{});
-            slot(std::integral_constant<int, 15>{});
+            QEFT_STEPS64(step)
         };
-        int st = 0;
-        for (; st + 1 < nst; st += 2) {
-            stage(st, std::integral_constant<int, 0>{});
-            stage(st + 1, std::integral_constant<int, 1>{});
-        }
-        if (nst & 1) stage(st, std::integral_constant<int, 0>{});
-
-        // fragment t_i, row 8 g + 4 fk + e is channel 32 t_i + row
-        __syncthreads();
-        store_f16_lds<false>(acc, lds + wave * TILE_BYTES, dX, lddx, icw, L.ic, m0 + 128 * wc, M, lane);
+        run_stages(stage);
+        store_f16_lds_64x256<false>(acc, lds + wave * TILE_BYTES, dX, lddx, icw, L.ic, m0, M, lane);
     };
+#undef QEFT_STEPS64
+#undef QEFT_STEPS8
 
     if (H0 == H1) {
         if (H0 == 0) run_quant(); else run_weak();
     } else {
-        if (wr == 0) run_quant(); else run_weak();
+        if (half == 0) run_quant(); else run_weak();
     }
 }
 
