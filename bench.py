@@ -4,10 +4,12 @@
 One step = one pass of the whole hot path over synthetic inputs with the Llama-2 7B layer
 shapes (4-bit, group 128, k = 128 weak columns):
 
-  decode     decoder blocks at M = 1: 7 matrix-vector launches each (q, k, v, o, gate, up, down),
-             over 10 distinct packed copies of the block in a row (> 1 GB, so the weights come
-             from HBM, not from the 256 MB last-level cache); the 70 launches are replayed from
-             one HIP graph so that the GPU, not Python, sets the pace
+  decode     decoder blocks at M = 1: the seven layers of a block (q, k, v, o, gate, up, down), each
+             stored and packed on its own, in the four launches the block's dataflow allows -
+             q / k / v read the same input and go out together (qeft_linear_fwd_group), so do gate
+             and up; over 10 distinct packed copies of the block in a row (> 1 GB, so the weights
+             come from HBM, not from the 256 MB last-level cache); the 40 launches are replayed
+             from one HIP graph so that the GPU, not Python, sets the pace
   fine-tune  M = 4096 tokens on the three layer shapes: forward, dX through the full mixed
              weight, dW of the weak columns
   pack       min-max round-to-nearest quantization + packing of one 4096 x 4096 layer
@@ -33,7 +35,7 @@ MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
 # the launches of the kernel in one step
 TRAFFIC_DX_BYTES = (2 * (232.3e6 + 37.2e6) + (488.6e6 + 99.1e6)) / 3      # three dX launches
-TRAFFIC_GEMV_BYTES = (4 * 9.92e6 + 2 * 26.30e6 + 25.13e6) / 7            # seven decode launches of a block
+TRAFFIC_GEMV_BYTES = (4 * 9.92e6 + 2 * 26.30e6 + 25.13e6) / 4            # the four decode launches of a block
 
 
 def main():
@@ -83,20 +85,33 @@ def main():
         blocks.append(layers)
     block_bytes = sum(l.nbytes() for l in blocks[0])
     x1 = {ic: synth_x(1, ic) for ic in {s[1] for s in block_shapes}}
-    y1 = {oc: torch.empty((1, oc), dtype=torch.float16, device=dev) for oc in {s[0] for s in block_shapes}}
+    y1 = [torch.empty((1, s[0]), dtype=torch.float16, device=dev) for s in block_shapes]   # one output per layer
+    # the launches of a block, as lists of layer indices: q/k/v share their input, and so do gate/up
+    assert block_shapes == [(4096, 4096)] * 4 + [(11008, 4096)] * 2 + [(4096, 11008)]
+    launches = [("q/k/v", [0, 1, 2]), ("o", [3]), ("gate/up", [4, 5]), ("down", [6])]
+    groups = [[B.Group([descs[block_shapes[i]] for i in idx], [layers[i] for i in idx], [y1[i] for i in idx])
+               for _, idx in launches] for layers in blocks]
 
-    def decode_block(layers):
-        for s, l in zip(block_shapes, layers):
-            B.qeft_linear_fwd(descs[s], l, x1[s[1]], y1[s[0]])
+    def decode_launch(b, li):
+        idx = launches[li][1]
+        x = x1[block_shapes[idx[0]][1]]
+        if len(idx) == 1:
+            B.qeft_linear_fwd(descs[block_shapes[idx[0]]], blocks[b][idx[0]], x, y1[idx[0]])
+        else:
+            B.qeft_linear_fwd_group(None, None, x, group=groups[b][li])
 
-    decode_block(blocks[0])                        # first launch sets kernel attributes: outside capture
+    def decode_block(b):
+        for li in range(len(launches)):
+            decode_launch(b, li)
+
+    decode_block(0)                                # first launch sets kernel attributes: outside capture
     torch.cuda.synchronize()
     # one graph = one pass over all the rotating blocks (a decode token runs 32 such blocks in a row)
     cap_stream = torch.cuda.Stream()
     decode_graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(decode_graph, stream=cap_stream):
-        for layers in blocks:
-            decode_block(layers)
+        for b in range(n_blocks):
+            decode_block(b)
 
     # ---- fine-tune operands -----------------------------------------------------------------------
     ft = []
@@ -143,17 +158,16 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
 
-    # ---- the decode kernel by layer shape: one graph per shape holding the launches of that layer of
-    # every rotating block, so that the launch period of one shape can be told apart (host launch
-    # overhead would dominate eager launches this short)
+    # ---- the decode kernel by launch: one graph per launch of the block holding that launch of every
+    # rotating block, so that the launch periods can be told apart (host launch overhead would
+    # dominate eager launches this short)
     decode_kernels = []
     gemv_bytes, gemv_ms = 0.0, 0.0
-    for s in ft_shapes:
-        li = block_shapes.index(s)
+    for li, (name, idx) in enumerate(launches):
         gs = torch.cuda.CUDAGraph()
         with torch.cuda.graph(gs, stream=cap_stream):
             for b in range(n_blocks):
-                B.qeft_linear_fwd(descs[s], blocks[b][li], x1[s[1]], y1[s[0]])
+                decode_launch(b, li)
         gs.replay()
         torch.cuda.synchronize()
         n_rep = max(args.steps, 5)
@@ -164,11 +178,11 @@ def main():
         e1.record()
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / (n_rep * n_blocks)
-        nb = blocks[0][li].nbytes()
-        count = sum(1 for t in block_shapes if t == s)
-        gemv_bytes += count * nb
-        gemv_ms += count * us * 1e-3
-        decode_kernels.append(dict(shape=f"{s[0]}x{s[1]}", launches_per_block=count, bytes=nb, us=round(us, 2),
+        nb = sum(blocks[0][i].nbytes() for i in idx)
+        s0 = block_shapes[idx[0]]
+        gemv_bytes += nb
+        gemv_ms += us * 1e-3
+        decode_kernels.append(dict(launch=name, layers=f"{len(idx)} x {s0[0]}x{s0[1]}", bytes=nb, us=round(us, 2),
                                    gbs=round(nb / us / 1e3, 1)))
     gemv_kernel_gbs = gemv_bytes / (gemv_ms * 1e-3) / 1e9
 
@@ -215,7 +229,7 @@ def main():
         "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": "Llama-2-7B layer shapes, w4 g128 k=128: decode M=1 over "
-                               f"{n_blocks} distinct packed blocks (7 launches each, one graph) + fine-tune M=4096 fwd+dX+dW_weak + pack",
+                               f"{n_blocks} distinct packed blocks (7 layers in 4 launches each: q/k/v, o, gate/up, down; one graph) + fine-tune M=4096 fwd+dX+dW_weak + pack",
                    "block_bytes": block_bytes, "M_decode": 1, "M_finetune": M_ft},
         "pct_hbm_peak": round(100 * gemv_gbs / HBM_PEAK_GBS, 2),
         "decode_us_per_block": round(decode_ms * 1e3, 2),
@@ -229,7 +243,7 @@ def main():
         "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_kernel_gbs / HBM_PEAK_GBS, 4),
                           "traffic": round(TRAFFIC_GEMV_BYTES),
-                          "note": "stored bytes of the block's 7 layers / sum of their launch periods, each shape "
+                          "note": "stored bytes of the block's 7 layers / sum of its 4 launch periods, each launch "
                                   "replayed from a graph of its own (HIP events; gaps between launches included, "
                                   "host overhead not)"},
     }

@@ -121,6 +121,17 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
 int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* X, int64_t M,
                     int64_t ldx, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream);
 
+/* Forward of n (1 .. QEFT_MAX_GROUP) layers that read the same input, Y_i = X . W_i^T for each:
+ * the query / key / value projections, or gate and up (Sec. 3.2.1; the weak columns are chosen
+ * from the statistics of the layer's input, Sec. 3.1, so layers that share an input share
+ * them).  The layers must agree in in_features, n_weak, bits and group_size; out_features may
+ * differ.  descs, w, Y and ldy are host arrays of n entries (w[i]'s device pointers and the
+ * device buffer Y[i] fp16 [M][ldy[i]] are borrowed for the call).  Results equal those of n
+ * qeft_linear_fwd calls up to summation order; decode-sized M runs them as one launch. */
+#define QEFT_MAX_GROUP 4
+int qeft_linear_fwd_group(int n, const qeft_desc_t* descs, const qeft_weight_t* w, const void* X,
+                          int64_t M, int64_t ldx, void* const* Y, const int64_t* ldy, void* stream);
+
 /* Input gradient through the full mixed weight (Sec. 3.3): dX = dY . W, i.e.
  * dX[:, :Kq] = dY . dq(Q) and dX[:, Kq:] = dY . weak (the weak block's current values).
  * dY fp16 [M][lddy] (lddy >= OC), dX fp16 [M][lddx] (lddx >= IC). */

@@ -48,6 +48,8 @@ EXPORTS = {
     "qeft_workspace_bytes": (C.c_size_t, [C.POINTER(qeft_desc_t), C.c_int, C.c_int64]),
     "qeft_linear_fwd": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64, C.c_int64,
                                   C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_linear_fwd_group": (C.c_int, [C.c_int, C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64,
+                                        C.c_int64, C.POINTER(C.c_void_p), C.POINTER(C.c_int64), C.c_void_p]),
     "qeft_linear_bwd_dx": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64,
                                      C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
@@ -172,6 +174,35 @@ def qeft_linear_fwd(desc, w: Weight, X: torch.Tensor, Y: torch.Tensor | None = N
                                _ptr(Y), Y.stride(0) if M else desc.out_features, _ptr(ws),
                                ws.numel() if ws is not None else 0, _stream()), "qeft_linear_fwd")
     return Y
+
+
+class Group:
+    """The host-side argument arrays of qeft_linear_fwd_group for a fixed set of layers and outputs
+    (built once; a decode loop then only passes X)."""
+
+    def __init__(self, descs, ws, Ys):
+        n = len(descs)
+        assert n == len(ws) == len(Ys) and n >= 1
+        self.n = n
+        self.descs = (qeft_desc_t * n)(*descs)
+        self.wst = (qeft_weight_t * n)(*[w.c_struct() for w in ws])
+        self.ys = (C.c_void_p * n)(*[_ptr(y) for y in Ys])
+        self.ldy = (C.c_int64 * n)(*[y.stride(0) for y in Ys])
+        self.keep = (list(ws), list(Ys))   # the device buffers the arrays point into
+        self.Ys = list(Ys)
+
+
+def qeft_linear_fwd_group(descs, ws, X: torch.Tensor, Ys=None, group: Group | None = None):
+    """Forward of several layers that share the input X; returns the list of outputs."""
+    M = X.shape[0]
+    if group is None:
+        if Ys is None:
+            Ys = [_empty_rows(M, d.out_features, torch.float16, X.device) for d in descs]
+        group = Group(descs, ws, Ys)
+    _check(raw.qeft_linear_fwd_group(group.n, group.descs, group.wst, _ptr(X), M,
+                                     X.stride(0) if M else group.descs[0].in_features, group.ys, group.ldy, _stream()),
+           "qeft_linear_fwd_group")
+    return group.Ys
 
 
 def qeft_linear_bwd_dx(desc, w: Weight, dY: torch.Tensor, dX: torch.Tensor | None = None, ws=None) -> torch.Tensor:

@@ -147,6 +147,37 @@ int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
     return hip_status(fwd_generic(L, x, M, ldx, y, ldy, s));
 }
 
+int qeft_linear_fwd_group(int n, const qeft_desc_t* descs, const qeft_weight_t* w, const void* X, int64_t M,
+                          int64_t ldx, void* const* Y, const int64_t* ldy, void* stream) {
+    if (n < 1 || n > QEFT_MAX_GROUP) return QEFT_ERR_SHAPE;
+    if (!descs || !w || !Y || !ldy) return QEFT_ERR_NULL;
+    Layer Ls[QEFT_MAX_GROUP];
+    for (int i = 0; i < n; ++i) {
+        int st = make_layer(&descs[i], &w[i], &Ls[i]);
+        if (st != QEFT_OK) return st;
+        if (Ls[i].ic != Ls[0].ic || Ls[i].k != Ls[0].k || Ls[i].bits != Ls[0].bits || Ls[i].g != Ls[0].g) return QEFT_ERR_SHAPE;
+        st = check_matrix(Y[i], M, ldy[i], Ls[i].oc);
+        if (st != QEFT_OK) return st;
+    }
+    int st = check_matrix(X, M, ldx, Ls[0].ic);
+    if (st != QEFT_OK) return st;
+    if (M == 0) return QEFT_OK;
+    hipStream_t s = (hipStream_t)stream;
+    if (n > 1 && M <= 4 && gemv_supported(Ls[0], M, ldx)) {
+        __half* ys[QEFT_MAX_GROUP];
+        for (int i = 0; i < n; ++i) ys[i] = (__half*)Y[i];
+        bool handled = false;
+        hipError_t e = gemv_fwd_group(Ls, n, (const __half*)X, M, ldx, ys, ldy, s, &handled);
+        if (e != hipSuccess) return QEFT_ERR_HIP;
+        if (handled) return QEFT_OK;
+    }
+    for (int i = 0; i < n; ++i) {
+        st = qeft_linear_fwd(&descs[i], &w[i], X, M, ldx, Y[i], ldy[i], nullptr, 0, stream);
+        if (st != QEFT_OK) return st;
+    }
+    return QEFT_OK;
+}
+
 int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M, int64_t lddy,
                        void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* stream) {
     (void)ws;

@@ -34,6 +34,7 @@
 #include <cstdlib>
 #include <type_traits>
 
+#include <climits>
 #include "qeft_internal.h"
 
 namespace qeft {
@@ -210,7 +211,8 @@ inline SmallLds small_lds(int M, int ng, int tw, int ks) {
 
 template <int D, int WMAX, int NSZ>
 __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
-                                                             __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS, int ks_magic) {
+                                                             __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS, int ks_magic,
+                                                             GroupTail G) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -219,7 +221,20 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     const int ti = (wave >= KS) + (wave >= 2 * KS) + (wave >= 3 * KS), kw = wave - ti * KS;  // tile within the workgroup, K split index
     const int TW = ld.tw;
     const int n = lane & 15, kb = lane >> 4;
-    const int row0 = (blockIdx.x * TW + ti) * 16;
+    // which layer of the group this wave's tile belongs to (a workgroup may straddle two)
+    int tile = blockIdx.x * TW + ti;
+    const int li = (tile >= G.tile_begin[0]) + (tile >= G.tile_begin[1]) + (tile >= G.tile_begin[2]);
+    if (li > 0) {
+        L.qweight = G.qweight[li - 1];
+        L.scales = G.scales[li - 1];
+        L.zeros = G.zeros[li - 1];
+        L.weak = G.weak[li - 1];
+        L.oc = G.oc[li - 1];
+        Y = G.Y[li - 1];
+        ldy = G.ldy[li - 1];
+        tile -= G.tile_begin[li - 1];
+    }
+    const int row0 = tile * 16;
     const int nq = L.ng;
     const int units = (nq + 3) >> 2;
     const int q_beg = 4 * ((units * kw * ks_magic) >> 16);
@@ -818,49 +833,88 @@ bool gemv_supported(const Layer& L, int64_t M, int64_t ldx) {
     return L.bits == 4;
 }
 
+namespace {
+// The small-M kernel over `tiles` 16-row tiles (of one layer, or of a group's layers back to
+// back).  Returns false when the configuration does not fit it; nothing is launched then.
+bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy,
+                  hipStream_t s, hipError_t* err) {
+    const int units = (L.ng + 3) / 4;
+    const int nweak = (L.k + 31) / 32;
+    // ~12 waves per CU over 256 CUs, at most 16 waves per workgroup, K split in units of 4 steps
+    int ks = ceil_div(3072, tiles);
+    const int ks_max = units < 1 ? 1 : (units > 16 ? 16 : units);
+    ks = ks < 1 ? 1 : (ks > ks_max ? ks_max : ks);
+    while (ks > 1 && ceil_div(units, ks - 1) == ceil_div(units, ks)) --ks;   // no wave with less than the longest share
+    int tw = 16 / ks;
+    tw = tw < 1 ? 1 : (tw > 4 ? 4 : tw);
+    while (tw > 1 && ceil_div(tiles, tw) < 512) tw >>= 1;  // keep every CU busy
+    if (small_lds(M, L.ng, tw, ks).total > 64 * 1024) {     // one workgroup per CU: make it a full one
+        tw = 1;
+        ks = ks_max;
+    }
+    const SmallLds ld = small_lds(M, L.ng, tw, ks);
+    const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
+    if (!(ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3)) return false;
+    using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, SmallLds, int, int, GroupTail);
+    // prefetch depth: all of a wave's steps when it has at most 4, else 8 steps per lane unless
+    // the weak prefetch already takes the registers (a request past the range would only repeat
+    // the last one, but it still occupies the CU's address path at launch)
+    static const Kern table[4][3] = {
+        {gemv_w4_small_kernel<4, 1, 1>, gemv_w4_small_kernel<4, 1, 2>, gemv_w4_small_kernel<4, 1, 3>},
+        {gemv_w4_small_kernel<8, 1, 1>, gemv_w4_small_kernel<8, 1, 2>, gemv_w4_small_kernel<8, 1, 3>},
+        {gemv_w4_small_kernel<8, 2, 1>, gemv_w4_small_kernel<8, 2, 2>, gemv_w4_small_kernel<8, 2, 3>},
+        {gemv_w4_small_kernel<4, 4, 1>, gemv_w4_small_kernel<4, 4, 2>, gemv_w4_small_kernel<4, 4, 3>}};
+    static bool attr_set[4][3] = {};
+    const int nj_max = 4 * ceil_div(units, ks);
+    const int wi = wmax <= 1 ? (nj_max <= 4 ? 0 : 1) : (wmax <= 2 ? 2 : 3), si = nsz - 1;
+    const Kern kern = table[wi][si];
+    if (!attr_set[wi][si]) {
+        *err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
+        if (*err != hipSuccess) return true;
+        attr_set[wi][si] = true;
+    }
+    kern<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks, ceil_div(65536, ks), tail);
+    *err = hipGetLastError();
+    return true;
+}
+
+GroupTail no_tail() {
+    GroupTail t = {};
+    for (int i = 0; i < MAX_GROUP - 1; ++i) t.tile_begin[i] = INT_MAX;
+    return t;
+}
+}  // namespace
+
+hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, int64_t ldx, __half* const* Y,
+                          const int64_t* ldy, hipStream_t s, bool* handled) {
+    *handled = false;
+    const Layer& L = Ls[0];
+    if (n < 1 || n > MAX_GROUP || M64 > 4 || L.bits != 4 || L.kq < 8 || L.k < 8) return hipSuccess;
+    GroupTail tail = no_tail();
+    int tiles = ceil_div(L.oc, 16);
+    for (int i = 1; i < n; ++i) {
+        tail.qweight[i - 1] = Ls[i].qweight;
+        tail.scales[i - 1] = Ls[i].scales;
+        tail.zeros[i - 1] = Ls[i].zeros;
+        tail.weak[i - 1] = Ls[i].weak;
+        tail.Y[i - 1] = Y[i];
+        tail.ldy[i - 1] = ldy[i];
+        tail.oc[i - 1] = Ls[i].oc;
+        tail.tile_begin[i - 1] = tiles;
+        tiles += ceil_div(Ls[i].oc, 16);
+    }
+    hipError_t err = hipSuccess;
+    *handled = launch_small(L, tiles, tail, X, (int)M64, ldx, Y[0], ldy[0], s, &err);
+    return err;
+}
+
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int M = (int)M64;
     if (L.bits == 3) return M > 4 ? launch_w3<2>(L, X, M, ldx, Y, ldy, s) : launch_w3<1>(L, X, M, ldx, Y, ldy, s);
     const int steps = L.ng + (L.k + 31) / 32;
     if (M <= 4 && L.kq >= 8 && L.k >= 8) {
-        const int tiles = ceil_div(L.oc, 16);
-        const int units = (L.ng + 3) / 4;
-        const int nweak = (L.k + 31) / 32;
-        // ~12 waves per CU over 256 CUs, at most 16 waves per workgroup, K split in units of 4 steps
-        int ks = ceil_div(3072, tiles);
-        const int ks_max = units < 1 ? 1 : (units > 16 ? 16 : units);
-        ks = ks < 1 ? 1 : (ks > ks_max ? ks_max : ks);
-        int tw = 16 / ks;
-        tw = tw < 1 ? 1 : (tw > 4 ? 4 : tw);
-        while (tw > 1 && ceil_div(tiles, tw) < 512) tw >>= 1;  // keep every CU busy
-        if (small_lds(M, L.ng, tw, ks).total > 64 * 1024) {     // one workgroup per CU: make it a full one
-            tw = 1;
-            ks = ks_max;
-        }
-        const SmallLds ld = small_lds(M, L.ng, tw, ks);
-        const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
-        if (ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3) {
-            using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, SmallLds, int, int);
-            // prefetch depth: all of a wave's steps when it has at most 4, else 8 steps per lane unless
-            // the weak prefetch already takes the registers (a request past the range would only repeat
-            // the last one, but it still occupies the CU's address path at launch)
-            static const Kern table[4][3] = {
-                {gemv_w4_small_kernel<4, 1, 1>, gemv_w4_small_kernel<4, 1, 2>, gemv_w4_small_kernel<4, 1, 3>},
-                {gemv_w4_small_kernel<8, 1, 1>, gemv_w4_small_kernel<8, 1, 2>, gemv_w4_small_kernel<8, 1, 3>},
-                {gemv_w4_small_kernel<8, 2, 1>, gemv_w4_small_kernel<8, 2, 2>, gemv_w4_small_kernel<8, 2, 3>},
-                {gemv_w4_small_kernel<4, 4, 1>, gemv_w4_small_kernel<4, 4, 2>, gemv_w4_small_kernel<4, 4, 3>}};
-            static bool attr_set[4][3] = {};
-            const int nj_max = 4 * ceil_div(units, ks);
-            const int wi = wmax <= 1 ? (nj_max <= 4 ? 0 : 1) : (wmax <= 2 ? 2 : 3), si = nsz - 1;
-            const Kern kern = table[wi][si];
-            if (!attr_set[wi][si]) {
-                hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
-                if (e != hipSuccess) return e;
-                attr_set[wi][si] = true;
-            }
-            kern<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks, ceil_div(65536, ks));
-            return hipGetLastError();
-        }
+        hipError_t err = hipSuccess;
+        if (launch_small(L, ceil_div(L.oc, 16), no_tail(), X, M, ldx, Y, ldy, s, &err)) return err;
     }
     if (L.kq >= 8 && !getenv("QEFT_DBG_CHUNK")) {
         // unstaged kernel: R tiles per wave share the activation fragments (more rows, more sharing),

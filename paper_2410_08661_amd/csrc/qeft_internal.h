@@ -41,6 +41,22 @@ hipError_t unpack(const Layer& L, uint8_t* codes, __half* scales, __half* zeros,
 // ---- decode path: fused dequant matrix-vector product for M <= 16 (gemv.hip) -------------
 bool gemv_supported(const Layer& L, int64_t M, int64_t ldx);
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s);
+// Several layers that share the input (same IC, k, bits and group size; any OC each) in one
+// launch of the small-M kernel: its row tiles are those of layer 0, then layer 1, ...
+constexpr int MAX_GROUP = 4;
+struct GroupTail {            // layers 1 .. 3 of a group (layer 0 travels as the kernel's Layer)
+    const uint32_t* qweight[MAX_GROUP - 1];
+    const __half* scales[MAX_GROUP - 1];
+    const __half* zeros[MAX_GROUP - 1];
+    const __half* weak[MAX_GROUP - 1];
+    __half* Y[MAX_GROUP - 1];
+    int64_t ldy[MAX_GROUP - 1];
+    int oc[MAX_GROUP - 1];
+    int tile_begin[MAX_GROUP - 1];   // first 16-row tile of the layer; INT_MAX when absent
+};
+// *handled = false (and nothing launched) when the shapes do not fit the one-launch kernel
+hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M, int64_t ldx, __half* const* Y,
+                          const int64_t* ldy, hipStream_t s, bool* handled);
 
 // ---- prefill / fine-tune path: MFMA GEMMs (gemm.hip) ---------------------------------------
 bool gemm_fwd_supported(const Layer& L, int64_t M);

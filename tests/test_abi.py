@@ -88,6 +88,28 @@ def test_forward_and_backward_validation():
     assert fwd(C.byref(d3), C.byref(_w(k=None)), X, 0, 128, Y, 64, None, 0, None) == B.QEFT_OK
 
 
+def test_forward_group_validation():
+    grp = B.raw.qeft_linear_fwd_group
+    X = 0x10000
+    d = B.make_desc(64, 256, 128, 4)
+    descs = (B.qeft_desc_t * 2)(d, B.make_desc(32, 256, 128, 4))
+    ws = (B.qeft_weight_t * 2)(_w(), _w())
+    ys = (C.c_void_p * 2)(0x20000, 0x30000)
+    ldy = (C.c_int64 * 2)(64, 32)
+    assert grp(2, descs, ws, X, 0, 256, ys, ldy, None) == B.QEFT_OK                 # M = 0: no-op
+    assert grp(0, descs, ws, X, 0, 256, ys, ldy, None) == B.QEFT_ERR_SHAPE
+    assert grp(5, descs, ws, X, 0, 256, ys, ldy, None) == B.QEFT_ERR_SHAPE
+    assert grp(2, None, ws, X, 0, 256, ys, ldy, None) == B.QEFT_ERR_NULL
+    assert grp(2, descs, ws, X, 0, 256, None, ldy, None) == B.QEFT_ERR_NULL
+    assert grp(2, descs, ws, X, 1, 248, ys, ldy, None) == B.QEFT_ERR_SHAPE          # ldx < IC
+    assert grp(2, descs, ws, X, 1, 256, ys, (C.c_int64 * 2)(64, 24), None) == B.QEFT_ERR_SHAPE   # ldy[1] < OC
+    # the layers of a group share the input: in_features, n_weak, bits and group size must agree
+    for other in (B.make_desc(32, 512, 128, 4), B.make_desc(32, 256, 64, 4), B.make_desc(32, 256, 128, 3),
+                  B.make_desc(32, 256, 128, 4, 64)):
+        bad = (B.qeft_desc_t * 2)(d, other)
+        assert grp(2, bad, ws, X, 0, 256, ys, ldy, None) == B.QEFT_ERR_SHAPE
+
+
 def test_pack_and_weak_grad_validation():
     d = B.make_desc(64, 256, 128, 4)
     w = _w()

@@ -170,6 +170,49 @@ def test_gemm_paths_with_non_integer_zero_points(m):
     assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), "dX, float zero-points")
 
 
+GROUP_CASES = [  # ic, k, bits, [oc per layer], Ms
+    (1024 + 128, 128, 4, [256, 64, 64], [1, 3]),        # query / key / value of different widths
+    (512 + 64, 64, 4, [176, 176], [1, 4]),              # gate / up; a workgroup straddles the two layers
+    (2048 + 128, 128, 4, [40, 24, 520, 8], [2]),        # four layers, ragged tiles
+    (1024 + 128, 128, 4, [256, 64], [9, 40]),           # more rows than the one-launch kernel takes: per-layer calls
+    (640 + 40, 40, 3, [96, 32], [1]),                   # 3-bit: per-layer calls
+]
+
+
+@pytest.mark.parametrize("ic,k,bits,ocs,Ms", GROUP_CASES)
+def test_forward_group_parity(ic, k, bits, ocs, Ms):
+    """Layers that share an input, through qeft_linear_fwd_group: each output equals the oracle's."""
+    hs = [HostLayer(oc, ic, k, bits, 128, seed=20 + i + oc) for i, oc in enumerate(ocs)]
+    ws = [h.to_device() for h in hs]
+    for m in Ms:
+        x = synth.make_activations(m, ic, k, 31 + m)
+        ys = B.qeft_linear_fwd_group([h.desc for h in hs], ws, torch.from_numpy(x).cuda())
+        torch.cuda.synchronize()
+        for i, (h, y) in enumerate(zip(hs, ys)):
+            assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), f"group layer {i} (OC {h.oc}) M={m}")
+
+
+def test_forward_group_writes_only_its_outputs_and_repeats_bitwise():
+    ic, k = 1024 + 128, 128
+    hs = [HostLayer(oc, ic, k, 4, 128, seed=40 + oc) for oc in (200, 72)]
+    ws = [h.to_device() for h in hs]
+    x = torch.from_numpy(synth.make_activations(1, ic, k, 5)).cuda()
+    bufs = [torch.full((1, h.oc + 16), -3.0, dtype=torch.float16, device="cuda") for h in hs]
+    grp = B.Group([h.desc for h in hs], ws, [b[:, :h.oc] for b, h in zip(bufs, hs)])
+    B.qeft_linear_fwd_group(None, None, x, group=grp)
+    torch.cuda.synchronize()
+    first = [b.clone() for b in bufs]
+    for b, h in zip(bufs, hs):
+        assert torch.all(b[:, h.oc:] == -3.0)              # nothing written past a layer's OC
+        assert_close(b[:, :h.oc].cpu().numpy(), qo.linear_fwd(h.w64, x.cpu().numpy()), "group output")
+    for _ in range(3):
+        for b in bufs:
+            b.fill_(-3.0)
+        B.qeft_linear_fwd_group(None, None, x, group=grp)
+        for b, f in zip(bufs, first):
+            assert torch.equal(b, f)
+
+
 def test_forward_respects_leading_dimensions_and_is_deterministic():
     h = HostLayer(320, 640 + 128, 128, 4, 128, seed=9)
     w = h.to_device()
