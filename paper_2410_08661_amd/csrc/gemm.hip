@@ -289,6 +289,21 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
+    // weak block operands: chunk u of this thread is tile row xr + 32 u, 16-byte column xc of the stage
+    // (branch-free fetches: columns past k read the row's last 8 and are zeroed when stored)
+    const int nw = (L.k + BK - 1) / BK;
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    u4 wa[8], wb[8];
+    auto load_weak = [&](int w) {
+        const int col = min(BK * w + 8 * xc, L.k - 8);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int r = xr + 32 * u;
+            wa[u] = ld16(L.weak + (size_t)min(oc0 + r, L.oc - 1) * L.k + col);
+            wb[u] = ld16(X + (size_t)min(m0 + r, M - 1) * ldx + L.kq + col);
+        }
+    };
+
     if (nq > 0) {
         const int s1 = min(1, nq - 1);
 #pragma unroll
@@ -405,38 +420,42 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
         if (nq & 1) stage(st, std::integral_constant<int, 0>{});
         __syncthreads();
     }
+    if (nw > 0) load_weak(0);
 
     // ---- weak block: plain fp16 stages with both operands through LDS -------------------------------
-    // Stage w sits in tiles (w & 1) [X] and 2 + (w & 1) [weights]; the fetch of stage w + 1 is in
-    // flight while stage w is multiplied, and alternating tiles need one barrier per stage only.
-    const int nw = (L.k + BK - 1) / BK;
-    const u4 zero4 = u4{0u, 0u, 0u, 0u};
-    u4 wa[8], wb[8];
-    auto load_weak = [&](int w) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int r = xr + 32 * u, col = BK * w + 8 * xc;
-            wa[u] = (col < L.k) ? ld16(L.weak + (size_t)min(oc0 + r, L.oc - 1) * L.k + col) : zero4;
-            wb[u] = (col < L.k) ? ld16(X + (size_t)min(m0 + r, M - 1) * ldx + L.kq + col) : zero4;
-        }
-    };
-    if (nw > 0) load_weak(0);
-    for (int w = 0; w < nw; ++w) {
+    // Stage w sits in tiles (w & 1) [X] and 2 + (w & 1) [weights].  While its four k-blocks are
+    // multiplied (fragments read one block ahead), stage w + 1 moves from the registers into the
+    // other pair of tiles, a quarter per k-block, and stage w + 2 is fetched.
+    auto store_weak = [&](int w, int q) {   // chunks 2 q, 2 q + 1 of this thread, of stage w
         unsigned char* sB = lds + (w & 1) * TILE_BYTES;
         unsigned char* sA = lds + (2 + (w & 1)) * TILE_BYTES;
+        const bool ok = BK * w + 8 * xc < L.k;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            *reinterpret_cast<u4*>(sA + tile_off(xr + 32 * u, xc)) = wa[u];
-            *reinterpret_cast<u4*>(sB + tile_off(xr + 32 * u, xc)) = wb[u];
+        for (int u = 2 * q; u < 2 * q + 2; ++u) {
+            *reinterpret_cast<u4*>(sA + tile_off(xr + 32 * u, xc)) = ok ? wa[u] : zero4;
+            *reinterpret_cast<u4*>(sB + tile_off(xr + 32 * u, xc)) = ok ? wb[u] : zero4;
         }
-        if (w + 1 < nw) load_weak(w + 1);
+    };
+    if (nw > 0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) store_weak(0, q);
+        if (nw > 1) load_weak(1);
         __syncthreads();
-        FragsT<2, 8> f;
+    }
+    for (int w = 0; w < nw; ++w) {
+        const unsigned char* sB = lds + (w & 1) * TILE_BYTES;
+        const unsigned char* sA = lds + (2 + (w & 1)) * TILE_BYTES;
+        FragsT<2, 8> f[2];
+        load_frags_t<2, 8>(f[0], sA, sB, wave * 64, 0, lane, 0);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            load_frags_t<2, 8>(f, sA, sB, wave * 64, 0, lane, ks);
-            mfma_block_t<2, 8>(f, acc);
+            if (ks < 3) load_frags_t<2, 8>(f[(ks + 1) & 1], sA, sB, wave * 64, 0, lane, ks + 1);
+            mfma_block_t<2, 8>(f[ks & 1], acc);
+            if (w + 1 < nw) store_weak(w + 1, ks);
+            __builtin_amdgcn_sched_barrier(0);
         }
+        if (w + 2 < nw) load_weak(w + 2);
+        if (w + 1 < nw) __syncthreads();
     }
     if (wide_stores) __syncthreads();   // the epilogue reuses the tiles
     if (wide_stores)
