@@ -1,7 +1,8 @@
 // Shared pieces of the tiled MFMA GEMM kernels (forward, input gradient, weak-column gradient).
 //
-// A workgroup of 4 waves (2 x 2) owns a 256 x 256 output tile C[i][j] = sum_k A[i][k] * B[j][k],
-// each wave 128 x 128 (4 x 4 MFMA 32x32x16 tiles, 256 fp32 accumulators per lane).  K advances
+// A workgroup of 4 waves owns a 256 x 256 output tile C[i][j] = sum_k A[i][k] * B[j][k]; each
+// wave 128 x 128 (4 x 4 MFMA 32x32x16 tiles) in the LDS-staged kernels, 64 x 256 (2 x 8) in the
+// register-operand kernels - 256 fp32 accumulators per lane either way.  K advances
 // in stages of 64: both operand tiles are 256 rows x 64 halfs in LDS, rows of 128 bytes whose
 // 16-byte chunks are XOR-swizzled with the row number so that fragment reads and the producers'
 // writes are free of bank conflicts; two buffers per operand (128 KB of the CU's 160 KB).

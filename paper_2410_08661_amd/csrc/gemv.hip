@@ -23,7 +23,9 @@
 // atomics: run-to-run deterministic).  Weight loads run several steps ahead in loops without
 // branches (rows are padded to whole steps and rows past OC are clamped, never stored).
 //   * small-M kernel (M <= 4 and X fits in LDS): the workgroup stages X once (permuted, with
-//     Sx), one barrier; a launch-latency-shaped prologue (see the kernel);
+//     Sx), one barrier; a launch-latency-shaped prologue (see the kernel).  It also takes a
+//     group of layers that share X (query / key / value, gate / up) as one launch: its tiles
+//     are those of layer 0, then layer 1, ..., each wave picking its layer's pointers;
 //   * row-batch kernel (any M <= 16): nothing staged, A fragments straight from X, Sx from the
 //     matrix core;
 //   * 3-bit kernel (any M <= 16): weight-side dequantization, ten codes per word;
