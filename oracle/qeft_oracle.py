@@ -38,6 +38,7 @@ import numpy as np
 
 __all__ = [
     "layout", "pack_codes", "unpack_codes", "quantize_rtn", "dequantize",
+    "stored_order", "linear_fwd_irregular", "linear_bwd_dx_irregular",
     "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
     "fwd_samples", "bwd_dx_samples", "weak_grad_samples",
 ]
@@ -189,6 +190,39 @@ def linear_bwd_dx(w: np.ndarray, dy: np.ndarray) -> np.ndarray:
 def weak_grad(dy: np.ndarray, x_weak: np.ndarray) -> np.ndarray:
     """dW_weak = dY^T . X[:, weak]  [Sec. 3.3, Eq. 5].  -> float64 [OC][k]."""
     return np.asarray(dy).astype(np.float64).T @ np.asarray(x_weak).astype(np.float64)
+
+
+# --------------------------------------------------------------------------- weak columns at arbitrary indices
+# The attention output projection cannot be reordered offline [Sec. 3.2, last paragraph;
+# Limitations]: its weak columns stay where the sensitivity analysis found them, and the
+# mixed-precision format is used "without reordering": the stored layer holds the non-weak
+# columns in ascending order (quantized, grouped over that compacted order) followed by the
+# weak block, and the activations are brought into that order on the fly.
+def stored_order(in_features: int, weak_idx) -> np.ndarray:
+    """perm[j] = original input channel held at stored position j: the non-weak channels in
+    ascending order, then the weak channels in the order given.  weak_idx: k distinct indices."""
+    weak_idx = np.asarray(weak_idx, dtype=np.int64)
+    assert weak_idx.ndim == 1 and len(set(weak_idx.tolist())) == len(weak_idx)
+    assert len(weak_idx) == 0 or (weak_idx.min() >= 0 and weak_idx.max() < in_features)
+    is_weak = np.zeros(in_features, dtype=bool)
+    is_weak[weak_idx] = True
+    return np.concatenate([np.nonzero(~is_weak)[0], weak_idx]).astype(np.int32)
+
+
+def linear_fwd_irregular(w_stored: np.ndarray, perm: np.ndarray, x: np.ndarray) -> np.ndarray:
+    """Forward with the weak columns at arbitrary indices: w_stored float64 [OC][IC] is the
+    dequantized stored layer (columns in stored order), x [M][IC] is in ORIGINAL channel
+    order.  Y[m][o] = sum_j x[m][perm[j]] * w_stored[o][j]."""
+    x = np.asarray(x).astype(np.float64)
+    return x[:, np.asarray(perm, dtype=np.int64)] @ w_stored.T
+
+
+def linear_bwd_dx_irregular(w_stored: np.ndarray, perm: np.ndarray, dy: np.ndarray) -> np.ndarray:
+    """dX in ORIGINAL channel order: dX[m][perm[j]] = sum_o dy[m][o] * w_stored[o][j]."""
+    d = np.asarray(dy).astype(np.float64) @ w_stored
+    out = np.empty_like(d)
+    out[:, np.asarray(perm, dtype=np.int64)] = d
+    return out
 
 
 def round_fp16(a: np.ndarray) -> np.ndarray:
