@@ -84,7 +84,7 @@ typedef struct {
     void* weak;
 } qeft_weight_t;
 
-enum { QEFT_OP_FWD = 0, QEFT_OP_BWD_DX = 1, QEFT_OP_WEAK_GRAD = 2 };
+enum { QEFT_OP_FWD = 0, QEFT_OP_BWD_DX = 1, QEFT_OP_WEAK_GRAD = 2, QEFT_OP_FWD_IRREGULAR = 3, QEFT_OP_BWD_DX_IRREGULAR = 4 };
 enum { QEFT_DTYPE_F16 = 0, QEFT_DTYPE_F32 = 1 };
 
 /* Component sizes of the stored form (Sec. 3.1).  Host only, pure. */
@@ -137,6 +137,26 @@ int qeft_linear_fwd_group(int n, const qeft_desc_t* descs, const qeft_weight_t* 
  * dY fp16 [M][lddy] (lddy >= OC), dX fp16 [M][lddx] (lddx >= IC). */
 int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M,
                        int64_t lddy, void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* stream);
+
+/* The layer whose weak columns stay at arbitrary input channels: the attention output
+ * projection, which the offline reordering cannot reach, uses the mixed-precision format
+ * without reordering and brings its activations into order on the fly (Sec. 3.2, last
+ * paragraph; Limitations).  The stored form is the same as everywhere else - the non-weak
+ * channels in ascending order, then the k weak ones - and perm (int32 [IC], device) names the
+ * original input channel of every stored column.  X and dX are in ORIGINAL channel order:
+ *     Y[m][o] = sum_j X[m][perm[j]] * W[o][j]        dX[m][perm[j]] = sum_o dY[m][o] * W[o][j]
+ * perm must be a permutation of 0 .. IC-1 (entries are clamped to that range; a table that is
+ * not a permutation gives unspecified values, never an access outside X / dX).  Both calls
+ * need qeft_workspace_bytes(desc, QEFT_OP_FWD_IRREGULAR / QEFT_OP_BWD_DX_IRREGULAR, M) bytes of
+ * device workspace, 16-byte aligned, for the gathered activations / the un-scattered gradient.
+ * For the weak block's gradient, call qeft_weak_grad on the weak activations gathered by the
+ * caller (X[:, perm[Kq:]], compact [M][k]). */
+int qeft_linear_fwd_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, const int32_t* perm,
+                              const void* X, int64_t M, int64_t ldx, void* Y, int64_t ldy,
+                              void* ws, size_t ws_bytes, void* stream);
+int qeft_linear_bwd_dx_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, const int32_t* perm,
+                                 const void* dY, int64_t M, int64_t lddy, void* dX, int64_t lddx,
+                                 void* ws, size_t ws_bytes, void* stream);
 
 /* Weight gradient of the weak block only (Sec. 3.3, Eq. 5): dW[o][c] = sum_m dY[m][o] * Xw[m][c].
  * Xw fp16 [M][ldxw] holds the k weak activations of each token: either a view into X

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libqeft.so")
 QEFT_OK = 0
 QEFT_ERR_NULL, QEFT_ERR_SHAPE, QEFT_ERR_BITS, QEFT_ERR_ALIGN = -1, -2, -3, -4
 QEFT_ERR_WORKSPACE, QEFT_ERR_UNSUPPORTED, QEFT_ERR_HIP = -5, -6, -7
-QEFT_OP_FWD, QEFT_OP_BWD_DX, QEFT_OP_WEAK_GRAD = 0, 1, 2
+QEFT_OP_FWD, QEFT_OP_BWD_DX, QEFT_OP_WEAK_GRAD, QEFT_OP_FWD_IRREGULAR, QEFT_OP_BWD_DX_IRREGULAR = 0, 1, 2, 3, 4
 QEFT_DTYPE_F16, QEFT_DTYPE_F32 = 0, 1
 
 
@@ -52,6 +52,10 @@ EXPORTS = {
                                         C.c_int64, C.POINTER(C.c_void_p), C.POINTER(C.c_int64), C.c_void_p]),
     "qeft_linear_bwd_dx": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64,
                                      C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_linear_fwd_irregular": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_void_p,
+                                            C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_linear_bwd_dx_irregular": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_void_p,
+                                               C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_status_string": (C.c_char_p, [C.c_int]),
@@ -213,6 +217,38 @@ def qeft_linear_bwd_dx(desc, w: Weight, dY: torch.Tensor, dX: torch.Tensor | Non
     _check(raw.qeft_linear_bwd_dx(C.byref(desc), C.byref(wst), _ptr(dY), M, dY.stride(0) if M else desc.out_features,
                                   _ptr(dX), dX.stride(0) if M else desc.in_features, _ptr(ws),
                                   ws.numel() if ws is not None else 0, _stream()), "qeft_linear_bwd_dx")
+    return dX
+
+
+def qeft_linear_fwd_irregular(desc, w: Weight, perm: torch.Tensor, X: torch.Tensor, Y: torch.Tensor | None = None,
+                              ws=None) -> torch.Tensor:
+    """Forward of a layer whose weak columns stay at arbitrary channels; perm int32 [IC] on the device."""
+    M = X.shape[0]
+    if Y is None:
+        Y = _empty_rows(M, desc.out_features, torch.float16, X.device)
+    if ws is None:
+        ws, _ = _workspace(desc, QEFT_OP_FWD_IRREGULAR, M, X.device)
+    wst = w.c_struct()
+    _check(raw.qeft_linear_fwd_irregular(C.byref(desc), C.byref(wst), _ptr(perm), _ptr(X), M,
+                                         X.stride(0) if M else desc.in_features, _ptr(Y),
+                                         Y.stride(0) if M else desc.out_features, _ptr(ws),
+                                         ws.numel() if ws is not None else 0, _stream()), "qeft_linear_fwd_irregular")
+    return Y
+
+
+def qeft_linear_bwd_dx_irregular(desc, w: Weight, perm: torch.Tensor, dY: torch.Tensor, dX: torch.Tensor | None = None,
+                                 ws=None) -> torch.Tensor:
+    M = dY.shape[0]
+    if dX is None:
+        dX = _empty_rows(M, desc.in_features, torch.float16, dY.device)
+    if ws is None:
+        ws, _ = _workspace(desc, QEFT_OP_BWD_DX_IRREGULAR, M, dY.device)
+    wst = w.c_struct()
+    _check(raw.qeft_linear_bwd_dx_irregular(C.byref(desc), C.byref(wst), _ptr(perm), _ptr(dY), M,
+                                            dY.stride(0) if M else desc.out_features, _ptr(dX),
+                                            dX.stride(0) if M else desc.in_features, _ptr(ws),
+                                            ws.numel() if ws is not None else 0, _stream()),
+           "qeft_linear_bwd_dx_irregular")
     return dX
 
 

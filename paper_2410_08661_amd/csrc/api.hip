@@ -116,6 +116,7 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
     if (check_desc(desc) != QEFT_OK || M <= 0) return 0;
     if (op == QEFT_OP_WEAK_GRAD && weak_grad_mfma_supported(desc->out_features, desc->n_weak, M))
         return weak_grad_mfma_workspace(desc->out_features, desc->n_weak, M);
+    if (op == QEFT_OP_FWD_IRREGULAR || op == QEFT_OP_BWD_DX_IRREGULAR) return irregular_workspace(desc->in_features, M);
     return 0;
 }
 
@@ -193,6 +194,43 @@ int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const vo
     hipStream_t s = (hipStream_t)stream;
     if (gemm_dx_supported(L, M)) return hip_status(gemm_dx(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
     return hip_status(bwd_dx_generic(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+}
+
+int qeft_linear_fwd_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, const int32_t* perm, const void* X,
+                              int64_t M, int64_t ldx, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream) {
+    int st = check_desc(desc);
+    if (st != QEFT_OK) return st;
+    const int ic = desc->in_features;
+    st = check_matrix(X, M, ldx, ic);
+    if (st != QEFT_OK) return st;
+    if (M == 0) return qeft_linear_fwd(desc, w, X, M, ldx, Y, ldy, nullptr, 0, stream);
+    if (!perm) return QEFT_ERR_NULL;
+    const size_t need = irregular_workspace(ic, M);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return QEFT_ERR_WORKSPACE;
+    // validate the product's arguments before the gather is launched (M = 0 launches nothing)
+    st = qeft_linear_fwd(desc, w, ws, 0, (ic + 7) / 8 * 8, Y, ldy, nullptr, 0, stream);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(Y, M, ldy, desc->out_features);
+    if (st != QEFT_OK) return st;
+    if (gather_cols((const __half*)X, M, ldx, perm, ic, (__half*)ws, (hipStream_t)stream) != hipSuccess) return QEFT_ERR_HIP;
+    return qeft_linear_fwd(desc, w, ws, M, (ic + 7) / 8 * 8, Y, ldy, nullptr, 0, stream);
+}
+
+int qeft_linear_bwd_dx_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, const int32_t* perm, const void* dY,
+                                 int64_t M, int64_t lddy, void* dX, int64_t lddx, void* ws, size_t ws_bytes,
+                                 void* stream) {
+    int st = check_desc(desc);
+    if (st != QEFT_OK) return st;
+    const int ic = desc->in_features;
+    st = check_matrix(dX, M, lddx, ic);
+    if (st != QEFT_OK) return st;
+    if (M == 0) return qeft_linear_bwd_dx(desc, w, dY, M, lddy, dX, lddx, nullptr, 0, stream);
+    if (!perm) return QEFT_ERR_NULL;
+    const size_t need = irregular_workspace(ic, M);
+    if (!ws || ws_bytes < need || !aligned16(ws)) return QEFT_ERR_WORKSPACE;
+    st = qeft_linear_bwd_dx(desc, w, dY, M, lddy, ws, (ic + 7) / 8 * 8, nullptr, 0, stream);
+    if (st != QEFT_OK) return st;
+    return hip_status(scatter_cols((const __half*)ws, M, perm, ic, (__half*)dX, lddx, (hipStream_t)stream));
 }
 
 int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy, const void* Xw, int64_t ldxw,

@@ -31,6 +31,11 @@ hipError_t bwd_dx_generic(const Layer& L, const __half* dY, int64_t M, int64_t l
 hipError_t weak_grad_generic(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
                              void* dW, int out_f32, int accumulate, hipStream_t s);
 
+// ---- weak columns at arbitrary channels: gather / scatter through a workspace (irregular.hip) ----
+size_t irregular_workspace(int ic, int64_t M);   // [M][IC rounded up to 8] fp16
+hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, hipStream_t s);
+hipError_t scatter_cols(const __half* Ds, int64_t M, const int* perm, int ic, __half* dX, int64_t lddx, hipStream_t s);
+
 // ---- format conversion (pack.hip) ----------------------------------------------------
 hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,
                     __half* weak, hipStream_t s);

@@ -232,6 +232,56 @@ def test_forward_respects_leading_dimensions_and_is_deterministic():
         assert torch.equal(ybuf, first)                   # run-to-run bitwise equal (no atomics)
 
 
+# ------------------------------------------------------------------------------ weak columns in place
+IRREGULAR_CASES = [  # oc, ic, k, bits, Ms
+    (256, 1024 + 128, 128, 4, [1, 3, 40]),     # decode kernels and the tiled GEMM behind the gather
+    (272, 640 + 64, 64, 4, [300]),
+    (96, 640 + 40, 40, 3, [1, 33]),            # 3-bit
+    (64, 333, 21, 4, [5]),                     # odd sizes: generic kernels, ragged last chunk of the table
+    (64, 384, 0, 4, [2]),                      # no weak column: the table is the identity
+]
+
+
+@pytest.mark.parametrize("oc,ic,k,bits,Ms", IRREGULAR_CASES)
+def test_irregular_indices_parity(oc, ic, k, bits, Ms):
+    """Weak columns at arbitrary channels (the un-reordered attention output projection): forward and
+    input gradient against the oracle's gather / scatter definition."""
+    h = HostLayer(oc, ic, k, bits, 128, seed=60 + oc)
+    w = h.to_device()
+    r = np.random.default_rng(ic)
+    weak_idx = r.permutation(ic)[:k]           # arbitrary places, arbitrary order
+    perm = qo.stored_order(ic, weak_idx)
+    perm_d = torch.from_numpy(perm).cuda()
+    for m in Ms:
+        x = synth.make_activations(m, ic, 0, 70 + m)
+        x[:, weak_idx] *= 20.0                 # the outlier channels sit where the weak columns are
+        dy = synth.make_grad_output(m, oc, 71 + m)
+        _, xbuf = pad_cols(x)                  # leading dimension a multiple of 8
+        y = B.qeft_linear_fwd_irregular(h.desc, w, perm_d, xbuf[:, :ic])
+        dx = B.qeft_linear_bwd_dx_irregular(h.desc, w, perm_d, torch.from_numpy(dy).cuda())
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy(), qo.linear_fwd_irregular(h.w64, perm, x), f"irregular fwd M={m}")
+        assert_close(dx.cpu().numpy(), qo.linear_bwd_dx_irregular(h.w64, perm, dy), f"irregular dX M={m}")
+
+
+def test_irregular_malformed_table_stays_in_bounds():
+    """Entries outside 0 .. IC-1 are clamped: wrong numbers, but nothing outside X / dX is touched."""
+    h = HostLayer(64, 256 + 128, 128, 4, 128, seed=3)
+    w = h.to_device()
+    ic, m = h.ic, 4
+    perm = torch.full((ic,), 10 ** 6, dtype=torch.int32, device="cuda")
+    perm[::2] = -7
+    xbuf = torch.zeros((m + 2, ic), dtype=torch.float16, device="cuda")
+    xbuf[0].fill_(float("nan")); xbuf[-1].fill_(float("nan"))      # guard rows around X
+    xbuf[1:-1] = 1.0
+    y = B.qeft_linear_fwd_irregular(h.desc, w, perm, xbuf[1:-1])
+    dbuf = torch.full((m + 2, ic), 5.0, dtype=torch.float16, device="cuda")
+    B.qeft_linear_bwd_dx_irregular(h.desc, w, perm, torch.ones((m, h.oc), dtype=torch.float16, device="cuda"), dbuf[1:-1])
+    torch.cuda.synchronize()
+    assert torch.all(torch.isfinite(y))                             # no guard row was read
+    assert torch.all(dbuf[0] == 5.0) and torch.all(dbuf[-1] == 5.0)  # no guard row was written
+
+
 # ------------------------------------------------------------------------------ backward
 BWD_CASES = [  # oc, ic, k, bits, g, M
     (256, 512 + 128, 128, 4, 128, 300),
