@@ -274,7 +274,7 @@ def main():
         "roofline": {"kernel": "gemm_dx_rega_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
                      "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": round(TRAFFIC_DX_BYTES)},
         "decode_kernels": decode_kernels,
-        "irregular_out_proj": {"layer": "4096x4096, weak columns at arbitrary channels (gather of X + the same kernels)",
+        "irregular_out_proj": {"layer": "4096x4096, weak columns at arbitrary channels (decode: gather inside the matrix-vector kernel; M=4096: a gather pass, then the same GEMM)",
                                "decode_us": round(irr_decode_us, 2),
                                "decode_us_reordered": next(dk["us"] for dk in decode_kernels if dk["launch"] == "o"),
                                "fwd_M4096_us": round(irr_ft_us, 1), "fwd_M4096_us_reordered": kernels[0]["fwd_us"]},

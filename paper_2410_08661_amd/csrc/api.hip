@@ -205,6 +205,20 @@ int qeft_linear_fwd_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, c
     if (st != QEFT_OK) return st;
     if (M == 0) return qeft_linear_fwd(desc, w, X, M, ldx, Y, ldy, nullptr, 0, stream);
     if (!perm) return QEFT_ERR_NULL;
+    if (!aligned16(perm)) return QEFT_ERR_ALIGN;
+    if (M <= 4) {   // decode: the gather happens inside the matrix-vector kernel, no workspace
+        Layer L;
+        st = make_layer(desc, w, &L);
+        if (st != QEFT_OK) return st;
+        st = check_matrix(Y, M, ldy, L.oc);
+        if (st != QEFT_OK) return st;
+        if (gemv_supported(L, M, ldx)) {
+            bool handled = false;
+            if (gemv_fwd_perm(L, perm, (const __half*)X, M, ldx, (__half*)Y, ldy, (hipStream_t)stream, &handled) != hipSuccess)
+                return QEFT_ERR_HIP;
+            if (handled) return QEFT_OK;
+        }
+    }
     const size_t need = irregular_workspace(ic, M);
     if (!ws || ws_bytes < need || !aligned16(ws)) return QEFT_ERR_WORKSPACE;
     // validate the product's arguments before the gather is launched (M = 0 launches nothing)
@@ -226,6 +240,7 @@ int qeft_linear_bwd_dx_irregular(const qeft_desc_t* desc, const qeft_weight_t* w
     if (st != QEFT_OK) return st;
     if (M == 0) return qeft_linear_bwd_dx(desc, w, dY, M, lddy, dX, lddx, nullptr, 0, stream);
     if (!perm) return QEFT_ERR_NULL;
+    if (!aligned16(perm)) return QEFT_ERR_ALIGN;
     const size_t need = irregular_workspace(ic, M);
     if (!ws || ws_bytes < need || !aligned16(ws)) return QEFT_ERR_WORKSPACE;
     st = qeft_linear_bwd_dx(desc, w, dY, M, lddy, ws, (ic + 7) / 8 * 8, nullptr, 0, stream);

@@ -211,10 +211,13 @@ inline SmallLds small_lds(int M, int ng, int tw, int ks) {
     return l;
 }
 
-template <int D, int WMAX, int NSZ>
+// PERM: the activations are in the layer's ORIGINAL channel order and stored column j reads
+// X[perm[j]] (weak columns left at arbitrary channels): the 16-byte fragment loads become eight
+// 2-byte gathers through the table, whose own requests head the stream.
+template <int D, int WMAX, int NSZ, bool PERM>
 __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                              __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS, int ks_magic,
-                                                             GroupTail G) {
+                                                             GroupTail G, const int* __restrict__ perm) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -252,16 +255,38 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     const int total = M * per_m;  // X fragments: idx -> (row m, fragment f of 8 columns); multiple of 16
     u4 xv[4];
     int xm[4], xf[4];
-    auto load_x = [&](int base) {
+    // 8 activations of row m at stored columns c0 .. c0 + 7 (c0 a multiple of 8)
+    auto table8 = [&](int c0, u4& lo, u4& hi) {
+        lo = load16(perm + c0);
+        hi = load16(perm + c0 + 4);
+    };
+    auto gather8 = [&](int m, u4 lo, u4 hi) {
+        const unsigned short* row = reinterpret_cast<const unsigned short*>(X) + (size_t)m * ldx;
+        uint32_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = row[min(max((int)(e < 4 ? lo[e] : hi[e - 4]), 0), L.ic - 1)];
+        return u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    };
+    u4 tlo[4], thi[4];
+    int xrow[4];
+    auto load_x = [&](int base) {   // with a table: its entries only; gather_x() then fetches the activations
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int idx = base + u * blockDim.x + threadIdx.x;
             const int cidx = min(idx, total - 1);
             const int m = (cidx >= per_m) + (cidx >= 2 * per_m) + (cidx >= 3 * per_m);
             xm[u] = (idx < total) ? m : -1;
+            xrow[u] = m;
             xf[u] = cidx - m * per_m;
             // fragments past Kq (the last group's padding) read the row's last quantized fragment and are zeroed below
-            xv[u] = load16(X + (size_t)m * ldx + min(8 * xf[u], L.kq - 8));
+            if (PERM) table8(min(8 * xf[u], L.kq - 8), tlo[u], thi[u]);
+            else xv[u] = load16(X + (size_t)m * ldx + min(8 * xf[u], L.kq - 8));
+        }
+    };
+    auto gather_x = [&]() {
+        if (PERM) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xv[u] = gather8(xrow[u], tlo[u], thi[u]);
         }
     };
     auto store_x = [&]() {   // Sx of a group lands with its first fragment
@@ -295,15 +320,22 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     for (int d = 0; d < D; ++d) wq[d] = load16(wp + 64 * min(d, j_last));
     // weak steps of 32 fp16 columns are dealt to the K-split waves from the last one back
     // (columns past k are clamped here and zeroed where they are used; k >= 8)
-    u4 wk[WMAX], xw[WMAX];
+    u4 wk[WMAX], xw[WMAX], wlo[WMAX], whi[WMAX];
     const int mrow = min(n, M - 1);
 #pragma unroll
     for (int i = 0; i < WMAX; ++i) {
         const int c0 = min(32 * (KS - 1 - kw + i * KS) + 8 * kb, L.k - 8);
         wk[i] = load16(L.weak + (size_t)orow * L.k + c0);
-        xw[i] = load16(X + (size_t)mrow * ldx + L.kq + c0);
+        if (PERM) table8(L.kq + c0, wlo[i], whi[i]);
+        else xw[i] = load16(X + (size_t)mrow * ldx + L.kq + c0);
     }
     __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
+    if (PERM) {   // the table entries were requested first and arrive first: now the activations themselves
+        gather_x();
+#pragma unroll
+        for (int i = 0; i < WMAX; ++i) xw[i] = gather8(mrow, wlo[i], whi[i]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 
     // ---- stage X (permuted, with Sx) and the group parameters ----------------------------------------
     store_x();
@@ -323,6 +355,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     }
     for (int base = 4 * blockDim.x; base < total; base += 4 * blockDim.x) {   // only when X exceeds one pass
         load_x(base);
+        gather_x();
         store_x();
     }
     // rows of Sx beyond M read as zero
@@ -838,8 +871,8 @@ bool gemv_supported(const Layer& L, int64_t M, int64_t ldx) {
 namespace {
 // The small-M kernel over `tiles` 16-row tiles (of one layer, or of a group's layers back to
 // back).  Returns false when the configuration does not fit it; nothing is launched then.
-bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy,
-                  hipStream_t s, hipError_t* err) {
+bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* perm, const __half* X, int M, int64_t ldx, __half* Y,
+                  int64_t ldy, hipStream_t s, hipError_t* err) {
     const int units = (L.ng + 3) / 4;
     const int nweak = (L.k + 31) / 32;
     // ~12 waves per CU over 256 CUs, at most 16 waves per workgroup, K split in units of 4 steps
@@ -857,25 +890,26 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const __half
     const SmallLds ld = small_lds(M, L.ng, tw, ks);
     const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
     if (!(ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3)) return false;
-    using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, SmallLds, int, int, GroupTail);
+    using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, SmallLds, int, int, GroupTail, const int*);
     // prefetch depth: all of a wave's steps when it has at most 4, else 8 steps per lane unless
     // the weak prefetch already takes the registers (a request past the range would only repeat
     // the last one, but it still occupies the CU's address path at launch)
-    static const Kern table[4][3] = {
-        {gemv_w4_small_kernel<4, 1, 1>, gemv_w4_small_kernel<4, 1, 2>, gemv_w4_small_kernel<4, 1, 3>},
-        {gemv_w4_small_kernel<8, 1, 1>, gemv_w4_small_kernel<8, 1, 2>, gemv_w4_small_kernel<8, 1, 3>},
-        {gemv_w4_small_kernel<8, 2, 1>, gemv_w4_small_kernel<8, 2, 2>, gemv_w4_small_kernel<8, 2, 3>},
-        {gemv_w4_small_kernel<4, 4, 1>, gemv_w4_small_kernel<4, 4, 2>, gemv_w4_small_kernel<4, 4, 3>}};
-    static bool attr_set[4][3] = {};
+#define QEFT_SMALL_ROW(P, D, W) {gemv_w4_small_kernel<D, W, 1, P>, gemv_w4_small_kernel<D, W, 2, P>, gemv_w4_small_kernel<D, W, 3, P>}
+    static const Kern table[2][4][3] = {
+        {QEFT_SMALL_ROW(false, 4, 1), QEFT_SMALL_ROW(false, 8, 1), QEFT_SMALL_ROW(false, 8, 2), QEFT_SMALL_ROW(false, 4, 4)},
+        {QEFT_SMALL_ROW(true, 4, 1), QEFT_SMALL_ROW(true, 8, 1), QEFT_SMALL_ROW(true, 8, 2), QEFT_SMALL_ROW(true, 4, 4)}};
+#undef QEFT_SMALL_ROW
+    static bool attr_set[2][4][3] = {};
     const int nj_max = 4 * ceil_div(units, ks);
     const int wi = wmax <= 1 ? (nj_max <= 4 ? 0 : 1) : (wmax <= 2 ? 2 : 3), si = nsz - 1;
-    const Kern kern = table[wi][si];
-    if (!attr_set[wi][si]) {
+    const int pi = perm ? 1 : 0;
+    const Kern kern = table[pi][wi][si];
+    if (!attr_set[pi][wi][si]) {
         *err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
         if (*err != hipSuccess) return true;
-        attr_set[wi][si] = true;
+        attr_set[pi][wi][si] = true;
     }
-    kern<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks, ceil_div(65536, ks), tail);
+    kern<<<ceil_div(tiles, tw), 64 * ks * tw, ld.total, s>>>(L, X, M, ldx, Y, ldy, ld, ks, ceil_div(65536, ks), tail, perm);
     *err = hipGetLastError();
     return true;
 }
@@ -906,7 +940,16 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, 
         tiles += ceil_div(Ls[i].oc, 16);
     }
     hipError_t err = hipSuccess;
-    *handled = launch_small(L, tiles, tail, X, (int)M64, ldx, Y[0], ldy[0], s, &err);
+    *handled = launch_small(L, tiles, tail, nullptr, X, (int)M64, ldx, Y[0], ldy[0], s, &err);
+    return err;
+}
+
+hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy,
+                         hipStream_t s, bool* handled) {
+    *handled = false;
+    if (M64 > 4 || L.bits != 4 || L.kq < 8 || L.k < 8) return hipSuccess;
+    hipError_t err = hipSuccess;
+    *handled = launch_small(L, ceil_div(L.oc, 16), no_tail(), perm, X, (int)M64, ldx, Y, ldy, s, &err);
     return err;
 }
 
@@ -916,7 +959,7 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
     const int steps = L.ng + (L.k + 31) / 32;
     if (M <= 4 && L.kq >= 8 && L.k >= 8) {
         hipError_t err = hipSuccess;
-        if (launch_small(L, ceil_div(L.oc, 16), no_tail(), X, M, ldx, Y, ldy, s, &err)) return err;
+        if (launch_small(L, ceil_div(L.oc, 16), no_tail(), nullptr, X, M, ldx, Y, ldy, s, &err)) return err;
     }
     if (L.kq >= 8 && !getenv("QEFT_DBG_CHUNK")) {
         // unstaged kernel: R tiles per wave share the activation fragments (more rows, more sharing),

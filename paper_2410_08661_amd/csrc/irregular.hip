@@ -6,7 +6,8 @@
 //     Xs[m][j] = X[m][perm[j]]          dX[m][perm[j]] = dXs[m][j]
 // perm (int32 [IC], device) holds the original channel of every stored column.  Entries are
 // clamped to [0, IC) so that a malformed table can give wrong numbers but no access outside
-// the matrices.
+// the matrices.  (The forward for M <= 4 does not come here: the matrix-vector kernel gathers
+// its activations itself.)
 #include "qeft_internal.h"
 
 namespace qeft {
@@ -15,8 +16,64 @@ namespace {
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
 typedef int i4 __attribute__((ext_vector_type(4)));
 
-// One thread per 8 stored columns of one row: two 16-byte reads of the table, eight 2-byte
-// reads of X (scattered over the row, which stays in L2 / the last-level cache), one 16-byte store.
+// A workgroup takes whole rows, one after the other: the row is copied into LDS with 16-byte
+// loads, then every thread assembles 8 stored columns from 2-byte LDS reads through the table
+// and stores them as 16 bytes (rows of up to 32 K channels fit; longer ones take the kernel
+// below).  Table entries are re-read per row; they stay in L1 / L2.
+constexpr int ROW_LDS_MAX = 64 * 1024;
+
+__global__ __launch_bounds__(256) void gather_rows_kernel(const unsigned short* __restrict__ X, int M, int64_t ldx,
+                                                          const int* __restrict__ perm, int ic, int chunks,
+                                                          unsigned short* __restrict__ Xs, int64_t lds_, int rows_per_wg) {
+    extern __shared__ __attribute__((aligned(16))) unsigned short rowbuf[];
+    const int m0 = blockIdx.x * rows_per_wg;
+    const int full = ic >> 3;   // whole 16-byte chunks of a source row
+    for (int m = m0; m < min(m0 + rows_per_wg, M); ++m) {
+        const unsigned short* row = X + (size_t)m * ldx;
+        for (int c = threadIdx.x; c < full; c += 256) *reinterpret_cast<u4*>(rowbuf + 8 * c) = *reinterpret_cast<const u4*>(row + 8 * c);
+        for (int j = 8 * full + threadIdx.x; j < ic; j += 256) rowbuf[j] = row[j];
+        __syncthreads();
+        for (int c = threadIdx.x; c < chunks; c += 256) {
+            uint32_t v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = 8 * c + e;
+                v[e] = j < ic ? rowbuf[min(max(perm[min(j, ic - 1)], 0), ic - 1)] : 0u;
+            }
+            *reinterpret_cast<u4*>(Xs + (size_t)m * lds_ + 8 * c) = u4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+        }
+        __syncthreads();
+    }
+}
+
+// The reverse: stored columns are dropped into an LDS row at their original channels, and the
+// row leaves with 16-byte stores.  Channels that no table entry names (none, for a
+// permutation) receive unspecified values.
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const unsigned short* __restrict__ Ds, int M, int64_t ldd,
+                                                           const int* __restrict__ perm, int ic, int chunks,
+                                                           unsigned short* __restrict__ dX, int64_t lddx, int rows_per_wg) {
+    extern __shared__ __attribute__((aligned(16))) unsigned short rowbuf[];
+    const int m0 = blockIdx.x * rows_per_wg;
+    const int full = ic >> 3;
+    for (int m = m0; m < min(m0 + rows_per_wg, M); ++m) {
+        unsigned short* row = dX + (size_t)m * lddx;
+        for (int c = threadIdx.x; c < chunks; c += 256) {
+            const u4 v = *reinterpret_cast<const u4*>(Ds + (size_t)m * ldd + 8 * c);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = 8 * c + e;
+                if (j < ic) rowbuf[min(max(perm[j], 0), ic - 1)] = (unsigned short)(v[e >> 1] >> (16 * (e & 1)));
+            }
+        }
+        __syncthreads();
+        for (int c = threadIdx.x; c < full; c += 256) *reinterpret_cast<u4*>(row + 8 * c) = *reinterpret_cast<const u4*>(rowbuf + 8 * c);
+        for (int j = 8 * full + threadIdx.x; j < ic; j += 256) row[j] = rowbuf[j];
+        __syncthreads();
+    }
+}
+
+// Rows too long for LDS: one thread per 8 stored columns of one row, two 16-byte reads of the
+// table, eight 2-byte accesses to the row.
 __global__ __launch_bounds__(256) void gather_cols_kernel(const unsigned short* __restrict__ X, int M, int64_t ldx,
                                                           const int* __restrict__ perm, int ic, int chunks,
                                                           unsigned short* __restrict__ Xs, int64_t lds_) {
@@ -52,12 +109,22 @@ __global__ __launch_bounds__(256) void scatter_cols_kernel(const unsigned short*
     }
 }
 
+// rows per workgroup: enough workgroups for every CU a few times over, whole rows each
+inline int rows_per_wg(int64_t M) { return M >= 4096 ? 4 : (M >= 1024 ? 2 : 1); }
+
 }  // namespace
 
 size_t irregular_workspace(int ic, int64_t M) { return (size_t)M * (size_t)((ic + 7) / 8 * 8) * sizeof(__half); }
 
 hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, hipStream_t s) {
     const int chunks = (ic + 7) / 8;
+    const int row_bytes = chunks * 16;
+    if (row_bytes <= ROW_LDS_MAX && (ldx & 7) == 0 && ((uintptr_t)X & 15) == 0) {
+        const int rw = rows_per_wg(M);
+        gather_rows_kernel<<<ceil_div(M, rw), 256, row_bytes, s>>>((const unsigned short*)X, (int)M, ldx, perm, ic, chunks,
+                                                                   (unsigned short*)Xs, (int64_t)chunks * 8, rw);
+        return hipGetLastError();
+    }
     const int64_t n = M * chunks;
     gather_cols_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const unsigned short*)X, (int)M, ldx, perm, ic, chunks,
                                                        (unsigned short*)Xs, (int64_t)chunks * 8);
@@ -66,6 +133,13 @@ hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm,
 
 hipError_t scatter_cols(const __half* Ds, int64_t M, const int* perm, int ic, __half* dX, int64_t lddx, hipStream_t s) {
     const int chunks = (ic + 7) / 8;
+    const int row_bytes = chunks * 16;
+    if (row_bytes <= ROW_LDS_MAX && (lddx & 7) == 0 && ((uintptr_t)dX & 15) == 0) {
+        const int rw = rows_per_wg(M);
+        scatter_rows_kernel<<<ceil_div(M, rw), 256, row_bytes, s>>>((const unsigned short*)Ds, (int)M, (int64_t)chunks * 8, perm, ic,
+                                                                    chunks, (unsigned short*)dX, lddx, rw);
+        return hipGetLastError();
+    }
     const int64_t n = M * chunks;
     scatter_cols_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const unsigned short*)Ds, (int)M, (int64_t)chunks * 8, perm, ic, chunks,
                                                         (unsigned short*)dX, lddx);

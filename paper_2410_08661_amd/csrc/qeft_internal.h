@@ -59,6 +59,10 @@ struct GroupTail {            // layers 1 .. 3 of a group (layer 0 travels as th
     int oc[MAX_GROUP - 1];
     int tile_begin[MAX_GROUP - 1];   // first 16-row tile of the layer; INT_MAX when absent
 };
+// Decode with the activations in original channel order, gathered through perm inside the kernel
+// (weak columns at arbitrary channels); *handled = false when the shape does not fit that kernel.
+hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy,
+                         hipStream_t s, bool* handled);
 // *handled = false (and nothing launched) when the shapes do not fit the one-launch kernel
 hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M, int64_t ldx, __half* const* Y,
                           const int64_t* ldy, hipStream_t s, bool* handled);

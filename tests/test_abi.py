@@ -115,22 +115,26 @@ def test_irregular_validation():
     w = _w()
     fwd, dx = B.raw.qeft_linear_fwd_irregular, B.raw.qeft_linear_bwd_dx_irregular
     X, Y, P, WS = 0x10000, 0x20000, 0x30000, 0x40000
-    need = B.qeft_workspace_bytes(d, B.QEFT_OP_FWD_IRREGULAR, 3)
-    assert need == 3 * 256 * 2 and B.qeft_workspace_bytes(d, B.QEFT_OP_BWD_DX_IRREGULAR, 3) == need
+    M = 6    # more rows than the decode kernel gathers in place: the workspace is required
+    need = B.qeft_workspace_bytes(d, B.QEFT_OP_FWD_IRREGULAR, M)
+    assert need == M * 256 * 2 and B.qeft_workspace_bytes(d, B.QEFT_OP_BWD_DX_IRREGULAR, M) == need
     assert B.qeft_workspace_bytes(B.make_desc(64, 333, 21, 4), B.QEFT_OP_FWD_IRREGULAR, 2) == 2 * 336 * 2   # row pitch rounded up to 8
     assert fwd(C.byref(d), C.byref(w), P, X, 0, 256, Y, 64, None, 0, None) == B.QEFT_OK              # M = 0: no-op
-    assert fwd(C.byref(d), C.byref(w), None, X, 3, 256, Y, 64, WS, need, None) == B.QEFT_ERR_NULL    # no table
-    assert fwd(C.byref(d), C.byref(w), P, X, 3, 256, Y, 64, None, 0, None) == B.QEFT_ERR_WORKSPACE
-    assert fwd(C.byref(d), C.byref(w), P, X, 3, 256, Y, 64, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
-    assert fwd(C.byref(d), C.byref(w), P, X, 3, 256, Y, 64, WS + 4, need, None) == B.QEFT_ERR_WORKSPACE
-    assert fwd(C.byref(d), C.byref(w), P, X, 3, 248, Y, 64, WS, need, None) == B.QEFT_ERR_SHAPE      # ldx < IC
-    assert fwd(C.byref(d), C.byref(w), P, X, 3, 256, Y, 56, WS, need, None) == B.QEFT_ERR_SHAPE      # ldy < OC
-    assert fwd(C.byref(d), C.byref(_w(q=None)), P, X, 3, 256, Y, 64, WS, need, None) == B.QEFT_ERR_NULL
+    assert fwd(C.byref(d), C.byref(w), None, X, M, 256, Y, 64, WS, need, None) == B.QEFT_ERR_NULL    # no table
+    assert fwd(C.byref(d), C.byref(w), P + 4, X, M, 256, Y, 64, WS, need, None) == B.QEFT_ERR_ALIGN
+    assert fwd(C.byref(d), C.byref(w), P, X, M, 256, Y, 64, None, 0, None) == B.QEFT_ERR_WORKSPACE
+    assert fwd(C.byref(d), C.byref(w), P, X, M, 256, Y, 64, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
+    assert fwd(C.byref(d), C.byref(w), P, X, M, 256, Y, 64, WS + 4, need, None) == B.QEFT_ERR_WORKSPACE
+    assert fwd(C.byref(d), C.byref(w), P, X, M, 248, Y, 64, WS, need, None) == B.QEFT_ERR_SHAPE      # ldx < IC
+    assert fwd(C.byref(d), C.byref(w), P, X, M, 256, Y, 56, WS, need, None) == B.QEFT_ERR_SHAPE      # ldy < OC
+    assert fwd(C.byref(d), C.byref(w), P, X, 2, 256, Y, 56, None, 0, None) == B.QEFT_ERR_SHAPE       # decode-sized: same checks
+    assert fwd(C.byref(d), C.byref(_w(q=None)), P, X, M, 256, Y, 64, WS, need, None) == B.QEFT_ERR_NULL
+    assert fwd(C.byref(d), C.byref(_w(q=None)), P, X, 2, 256, Y, 64, None, 0, None) == B.QEFT_ERR_NULL
     assert dx(C.byref(d), C.byref(w), P, X, 0, 64, Y, 256, None, 0, None) == B.QEFT_OK
-    assert dx(C.byref(d), C.byref(w), None, X, 3, 64, Y, 256, WS, need, None) == B.QEFT_ERR_NULL
-    assert dx(C.byref(d), C.byref(w), P, X, 3, 64, Y, 256, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
-    assert dx(C.byref(d), C.byref(w), P, X, 3, 56, Y, 256, WS, need, None) == B.QEFT_ERR_SHAPE       # lddy < OC
-    assert dx(C.byref(d), C.byref(w), P, X, 3, 64, Y, 248, WS, need, None) == B.QEFT_ERR_SHAPE       # lddx < IC
+    assert dx(C.byref(d), C.byref(w), None, X, M, 64, Y, 256, WS, need, None) == B.QEFT_ERR_NULL
+    assert dx(C.byref(d), C.byref(w), P, X, M, 64, Y, 256, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
+    assert dx(C.byref(d), C.byref(w), P, X, M, 56, Y, 256, WS, need, None) == B.QEFT_ERR_SHAPE       # lddy < OC
+    assert dx(C.byref(d), C.byref(w), P, X, M, 64, Y, 248, WS, need, None) == B.QEFT_ERR_SHAPE       # lddx < IC
 
 
 def test_pack_and_weak_grad_validation():

@@ -234,7 +234,9 @@ def test_forward_respects_leading_dimensions_and_is_deterministic():
 
 # ------------------------------------------------------------------------------ weak columns in place
 IRREGULAR_CASES = [  # oc, ic, k, bits, Ms
-    (256, 1024 + 128, 128, 4, [1, 3, 40]),     # decode kernels and the tiled GEMM behind the gather
+    (256, 1024 + 128, 128, 4, [1, 3, 4, 5, 40]),   # gather inside the decode kernel (M <= 4), then behind a gather pass
+    (4096, 4096, 128, 4, [1]),                  # the 7B output projection at full size
+    (528, 2048 + 64, 64, 4, [2]),               # ragged last tile, weak block of two steps
     (272, 640 + 64, 64, 4, [300]),
     (96, 640 + 40, 40, 3, [1, 33]),            # 3-bit
     (64, 333, 21, 4, [5]),                     # odd sizes: generic kernels, ragged last chunk of the table
