@@ -3,6 +3,8 @@
 // packing of externally chosen codes, and the inverse.  Integer results are bit-exact by
 // construction: every float operation is a single correctly rounded IEEE fp32 operation
 // (explicit __fdiv_rn / rintf, no contraction possible).
+#include <type_traits>
+
 #include "qeft_internal.h"
 
 namespace qeft {
@@ -80,6 +82,87 @@ __global__ __launch_bounds__(256) void rtn_words_kernel(Layer L, const __half* _
     qweight[idx] = word;
 }
 
+// ---- both steps in one pass for 4-bit codes and groups of 128 -----------------------------------
+// One wavefront per (row, 512 columns = 4 groups = 64 words): lane l reads the 16 bytes of columns
+// 8 l .. 8 l + 7 - its word - and belongs to group l / 16.  Minimum and maximum go through the 16
+// lanes of the group with four data-parallel-primitive moves; every lane then derives the group's
+// (scale, zero-point) with the same correctly rounded fp32 operations as the two-step kernels
+// (bit-identical results), quantizes its 8 columns and stores its word: W is read once, with
+// 16-byte loads, and the codes leave as 256 contiguous bytes per wavefront.  Columns past Kq count
+// as zeros (neutral: a group's range always contains 0) and give zero codes; the wave of a row's
+// last chunk also zeroes the row's padding parameters.
+__device__ __forceinline__ float dpp16_min(float v) {
+    auto mv = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    v = fminf(v, mv(v, std::integral_constant<int, 0xB1>{}));    // lane ^ 1
+    v = fminf(v, mv(v, std::integral_constant<int, 0x4E>{}));    // lane ^ 2
+    v = fminf(v, mv(v, std::integral_constant<int, 0x141>{}));   // mirrored halves of the row of 16
+    v = fminf(v, mv(v, std::integral_constant<int, 0x140>{}));   // mirrored row
+    return v;
+}
+
+__global__ __launch_bounds__(256) void rtn_fused_w4g128_kernel(Layer L, const __half* __restrict__ W, int64_t ldw,
+                                                               uint32_t* __restrict__ qweight, __half* __restrict__ scales,
+                                                               __half* __restrict__ zeros, int chunks) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (wv >= (int64_t)L.oc * chunks) return;
+    const int o = (int)(wv / chunks), ch = (int)(wv % chunks);
+    const int word = 64 * ch + lane, col = 8 * word;
+    // Kq is a multiple of 8 here, so a word is entirely inside or entirely outside the row
+    const bool live = col < L.kq;
+    const u4 raw = live ? *reinterpret_cast<const u4*>(W + (size_t)o * ldw + col) : u4{0u, 0u, 0u, 0u};
+    const h8 h = __builtin_bit_cast(h8, raw);
+    float v[8], lo = 0.f, hi = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        v[e] = (float)h[e];
+        lo = fminf(lo, v[e]);
+        hi = fmaxf(hi, v[e]);
+    }
+    lo = dpp16_min(lo);
+    hi = -dpp16_min(-hi);
+    const float qmax = 15.f;
+    const float s32 = __fdiv_rn(hi - lo, qmax);
+    __half s16, z16;
+    if (s32 == 0.f) {
+        s16 = __float2half_rn(1.f);
+        z16 = __float2half_rn(0.f);
+    } else {
+        s16 = __float2half_rn(s32);
+        if (__half2float(s16) == 0.f) s16 = __ushort_as_half((unsigned short)1);  // smallest subnormal
+        float z = rintf(__fdiv_rn(0.f - lo, __half2float(s16)));
+        z = fminf(fmaxf(z, 0.f), qmax);
+        z16 = __float2half_rn(z);
+    }
+    const float s = __half2float(s16), z = __half2float(z16);
+    uint32_t out = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        float q = rintf(__fdiv_rn(v[e], s)) + z;
+        q = fminf(fmaxf(q, 0.f), qmax);
+        out |= (uint32_t)q << (4 * e);
+    }
+    if (word < L.stride) qweight[(size_t)o * L.stride + word] = live ? out : 0u;
+    const int gi = 4 * ch + (lane >> 4);
+    if ((lane & 15) == 0 && gi < L.gs) {
+        const bool real = gi < L.ng;
+        scales[(size_t)o * L.gs + gi] = real ? s16 : __float2half_rn(0.f);
+        zeros[(size_t)o * L.gs + gi] = real ? z16 : __float2half_rn(0.f);
+    }
+    // parameter padding past the groups this row's chunks cover
+    if (ch == chunks - 1) {
+        const int gi2 = 4 * chunks + lane;
+        if (gi2 < L.gs) {
+            scales[(size_t)o * L.gs + gi2] = __float2half_rn(0.f);
+            zeros[(size_t)o * L.gs + gi2] = __float2half_rn(0.f);
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void pack_words_kernel(Layer L, const uint8_t* __restrict__ codes,
                                                          uint32_t* __restrict__ qweight) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -135,7 +218,10 @@ void copy2d(const __half* src, int64_t lds, __half* dst, int64_t ldd, int64_t ro
 
 hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,
                     __half* weak, hipStream_t s) {
-    if (L.kq > 0) {
+    if (L.kq > 0 && L.bits == 4 && L.g == 128 && (L.kq & 7) == 0 && (ldw & 7) == 0 && ((uintptr_t)W & 15) == 0) {
+        const int chunks = ceil_div(L.stride, 64);
+        rtn_fused_w4g128_kernel<<<ceil_div((int64_t)L.oc * chunks, 4), 256, 0, s>>>(L, W, ldw, qweight, scales, zeros, chunks);
+    } else if (L.kq > 0) {
         const int64_t pairs = (int64_t)L.oc * L.gs;
         rtn_params_kernel<<<ceil_div(pairs, 4), 256, 0, s>>>(L, W, ldw, scales, zeros);
         rtn_words_kernel<<<ceil_div((int64_t)L.oc * L.stride, 256), 256, 0, s>>>(L, W, ldw, scales, zeros, qweight);
