@@ -88,6 +88,51 @@ def test_decode_forward_full_size(cfg, si, shape, k, bits, Ms):
         _check(y, pairs, ref, f"cfg{cfg} fwd {oc}x{ic} b{bits} M{m}")
 
 
+GROUPS = [  # the launches bench.py times: layers that share their input, one launch each
+    ("q/k/v", [(4096, 4096)] * 3, 128),
+    ("gate/up", [(11008, 4096)] * 2, 128),
+]
+
+
+@pytest.mark.parametrize("name,shapes,k", GROUPS)
+def test_decode_group_full_size(name, shapes, k):
+    ic = shapes[0][1]
+    Ls = [BigLayer(oc, ic, k, 4, synth.seed_for(2, 10 + i)) for i, (oc, _) in enumerate(shapes)]
+    x = synth.make_activations(1, ic, k, synth.seed_for(2, 20))
+    ys = B.qeft_linear_fwd_group([L.desc for L in Ls], [L.dev for L in Ls], torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    for i, (L, y) in enumerate(zip(Ls, ys)):
+        pairs = _pairs(1, L.oc, 30 + i)
+        _check(y, pairs, qo.fwd_samples(*L.args(), x, pairs), f"{name} layer {i} {L.oc}x{ic} M1 (one launch)")
+
+
+@pytest.mark.parametrize("m", [1, 4096])
+def test_irregular_out_proj_full_size(m):
+    """The 7B output projection with its weak columns left at arbitrary channels."""
+    oc = ic = 4096
+    k = 128
+    L = BigLayer(oc, ic, k, 4, synth.seed_for(2, 40))
+    weak_idx = np.sort(np.random.default_rng(41).permutation(ic)[:k])
+    perm = qo.stored_order(ic, weak_idx)
+    x = synth.make_activations(m, ic, 0, synth.seed_for(2, 42))
+    x[:, weak_idx] *= 20.0
+    xs = np.ascontiguousarray(x[:, perm])          # what the stored layer multiplies (gathered on the host for the samples)
+    y = B.qeft_linear_fwd_irregular(L.desc, L.dev, torch.from_numpy(perm).cuda(), torch.from_numpy(x).cuda())
+    torch.cuda.synchronize()
+    pairs = _pairs(m, oc, 43)
+    _check(y, pairs, qo.fwd_samples(*L.args(), xs, pairs), f"irregular fwd 4096x4096 M{m}")
+    if m > 1:
+        dy = synth.make_grad_output(m, oc, 44)
+        dx = B.qeft_linear_bwd_dx_irregular(L.desc, L.dev, torch.from_numpy(perm).cuda(), torch.from_numpy(dy).cuda())
+        torch.cuda.synchronize()
+        pairs = _pairs(m, ic, 45, edge_cols=[int(weak_idx[0]), int(weak_idx[-1]), 0, ic - 1])
+        # sample (row, original channel): the stored column of channel c is inv[c]
+        inv = np.empty(ic, dtype=np.int64)
+        inv[perm] = np.arange(ic)
+        ref = qo.bwd_dx_samples(*L.args(), dy, [(r, int(inv[c])) for r, c in pairs])
+        _check(dx, pairs, ref, f"irregular dX 4096x4096 M{m}")
+
+
 TRAIN = [(4, synth.LLAMA_7B, 128, 4096), (5, synth.LLAMA_70B, 256, 2048)]
 TRAIN_CASES = [(cfg, si, s, k, m) for cfg, shapes, k, m in TRAIN for si, s in enumerate(shapes)]
 
