@@ -17,7 +17,8 @@ What it computes (paper sections in brackets):
       Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . W_weak^T
 * Backward [Sec. 3.3, Eq. 5]: dX = dY . W through the full mixed weight, and a
   weight gradient for the weak block only: dW_weak = dY^T . X[:, Kq:].
-* Quantizer: the paper's data-free fallback, min-max round-to-nearest per group
+* Quantizer: the group-wise grid search with truncation of [Sec. 3.1] (quantize_search; the
+  grid is this build's reading) and the paper's data-free fallback, min-max round-to-nearest per group
   [Sec. 6.1 (70B setting), App. C "Comparison of Quantization Methods",
   App. C "Quantization Cost"].
 
@@ -37,7 +38,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
-    "layout", "pack_codes", "unpack_codes", "quantize_rtn", "dequantize",
+    "layout", "pack_codes", "unpack_codes", "quantize_rtn", "quantize_search", "dequantize",
     "stored_order", "linear_fwd_irregular", "linear_bwd_dx_irregular",
     "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
     "fwd_samples", "bwd_dx_samples", "weak_grad_samples",
@@ -155,6 +156,90 @@ def quantize_rtn(w: np.ndarray, n_weak: int, bits: int, group_size: int):
         codes[:, gi * g:gi * g + blk.shape[1]] = q.astype(np.uint8)
         scales[:, gi] = s16
         zeros[:, gi] = z.astype(np.float16)
+    weak = np.ascontiguousarray(w[:, kq:])
+    return codes, scales, zeros, weak
+
+
+def _group_params(lo, hi, qmax):
+    """(scale fp16, zero-point f32, flat) from a range, with quantize_rtn's rules (float32)."""
+    tiny = np.float16(2.0 ** -24)
+    s32 = ((hi - lo) / qmax).astype(np.float32)
+    flat = s32 == 0
+    s16 = s32.astype(np.float16)
+    s16 = np.where((s16 == 0) & ~flat, tiny, s16)
+    s16 = np.where(flat, np.float16(1.0), s16).astype(np.float16)
+    s = s16.astype(np.float32)
+    z = np.clip(np.rint(((np.float32(0) - lo) / s).astype(np.float32)), np.float32(0), qmax).astype(np.float32)
+    z = np.where(flat, np.float32(0), z).astype(np.float32)
+    return s16, z
+
+
+def quantize_search(w: np.ndarray, n_weak: int, bits: int, group_size: int, n_grid: int, shrink_step: float):
+    """Group-wise grid search with truncation [Sec. 3.1: "a grid search for each group to find the
+    quantization parameters that minimize the squared error of weights after truncation"].
+
+    The paper gives neither the grid nor the error's precision.  Reading taken here: candidate i
+    (i = 0 .. n_grid-1) shrinks the group's min-max range [lo, hi] (0 included, as in
+    quantize_rtn) to [p_i lo, p_i hi] with p_i = 1 - i * shrink_step, derives (s, z) from it by
+    quantize_rtn's rules, quantizes, and scores  E_i = sum_j (w_j - s (q_j - z))^2 ; the first
+    candidate with the smallest E wins, so candidate 0 (p = 1, plain min-max) is kept on ties.
+
+    Decisions are integers taken from floating point, so everything is IEEE float32 with one
+    rounding per operation (no fused multiply-add), and the error sum has a fixed order that any
+    implementation can follow: the group's columns in octets of 8 consecutive columns, each octet
+    summed left to right, the (up to 16) octet sums combined by a balanced binary tree over 16
+    slots (absent octets are zeros).  Requires group_size % 8 == 0, group_size <= 128 and
+    Kq % 8 == 0.  Returns what quantize_rtn returns.
+    """
+    w = np.asarray(w)
+    assert w.dtype == np.float16 and w.ndim == 2
+    oc, ic = w.shape
+    k, g = int(n_weak), int(group_size)
+    kq = ic - k
+    assert g % 8 == 0 and g <= 128 and kq % 8 == 0 and n_grid >= 1
+    f32 = np.float32
+    assert f32(n_grid - 1) * f32(shrink_step) < f32(1)
+    n_groups = -(-kq // g)
+    qmax = f32((1 << bits) - 1)
+    wf = w[:, :kq].astype(np.float32)
+    codes = np.zeros((oc, kq), dtype=np.uint8)
+    scales = np.zeros((oc, n_groups), dtype=np.float16)
+    zeros = np.zeros((oc, n_groups), dtype=np.float16)
+    for gi in range(n_groups):
+        blk = wf[:, gi * g:min((gi + 1) * g, kq)]
+        n = blk.shape[1]
+        lo0 = np.minimum(f32(0), blk.min(axis=1)).astype(np.float32)
+        hi0 = np.maximum(f32(0), blk.max(axis=1)).astype(np.float32)
+        best_e = np.full(oc, np.inf, dtype=np.float32)
+        best_s = np.zeros(oc, dtype=np.float16)
+        best_z = np.zeros(oc, dtype=np.float32)
+        for i in range(n_grid):
+            p = f32(f32(1) - f32(f32(i) * f32(shrink_step)))
+            lo, hi = (p * lo0).astype(np.float32), (p * hi0).astype(np.float32)
+            s16, z = _group_params(lo, hi, qmax)
+            sf = s16.astype(np.float32)
+            q = np.clip(np.rint((blk / sf[:, None]).astype(np.float32)).astype(np.float32) + z[:, None], f32(0), qmax)
+            d = (blk - (sf[:, None] * (q - z[:, None])).astype(np.float32)).astype(np.float32)
+            sq = (d * d).astype(np.float32)
+            octs = np.zeros((oc, 16), dtype=np.float32)          # octet sums, left to right
+            for o8 in range(n // 8):
+                acc = np.zeros(oc, dtype=np.float32)
+                for e in range(8):
+                    acc = (acc + sq[:, 8 * o8 + e]).astype(np.float32)
+                octs[:, o8] = acc
+            t = octs
+            while t.shape[1] > 1:                                  # balanced tree over the 16 slots
+                t = (t[:, 0::2] + t[:, 1::2]).astype(np.float32)
+            e_i = t[:, 0]
+            better = e_i < best_e
+            best_e = np.where(better, e_i, best_e)
+            best_s = np.where(better, s16, best_s)
+            best_z = np.where(better, z, best_z)
+        sf = best_s.astype(np.float32)
+        q = np.clip(np.rint((blk / sf[:, None]).astype(np.float32)).astype(np.float32) + best_z[:, None], f32(0), qmax)
+        codes[:, gi * g:gi * g + n] = q.astype(np.uint8)
+        scales[:, gi] = best_s
+        zeros[:, gi] = best_z.astype(np.float16)
     weak = np.ascontiguousarray(w[:, kq:])
     return codes, scales, zeros, weak
 
