@@ -100,6 +100,19 @@ int qeft_layout(const qeft_desc_t* desc, qeft_layout_t* out);
 int qeft_pack(const qeft_desc_t* desc, const void* W, int64_t ldw,
               const qeft_weight_t* out, void* stream);
 
+/* The same conversion with the paper's group-wise grid search with truncation (Sec. 3.1): for every
+ * (row, group), candidate i = 0 .. n_grid-1 shrinks the min-max range [lo, hi] to [p lo, p hi],
+ * p = 1 - i * shrink_step, derives (s, z) from it by qeft_pack's rules, and the candidate with the
+ * smallest squared weight error sum (w - s (q - z))^2 is kept (the first one on ties; candidate 0 is
+ * qeft_pack's result, so no group gets worse).  The paper fixes neither the grid nor the arithmetic:
+ * everything is fp32 with one rounding per operation, the error summed over a group's columns in
+ * octets left to right and a balanced tree over the octets.  n_grid >= 1, (n_grid - 1) * shrink_step
+ * < 1.  Needs group_size % 8 == 0, group_size <= 128, Kq % 8 == 0 (else QEFT_ERR_UNSUPPORTED).  The
+ * OPTQ step that follows in the paper needs calibration data and is not part of this library:
+ * qeft_pack_codes takes its output. */
+int qeft_pack_search(const qeft_desc_t* desc, const void* W, int64_t ldw, int n_grid, float shrink_step,
+                     const qeft_weight_t* out, void* stream);
+
 /* Build the stored form from already chosen codes (uint8 [OC][Kq], device) and
  * parameters (scales, zeros fp16 [OC][G] compact; weak fp16 [OC][k]): bit-packs the codes
  * and copies scales / zeros / weak into the padded stored arrays.  For quantizers

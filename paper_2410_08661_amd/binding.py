@@ -41,6 +41,8 @@ class qeft_weight_t(C.Structure):
 EXPORTS = {
     "qeft_layout": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_layout_t)]),
     "qeft_pack": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.POINTER(qeft_weight_t), C.c_void_p]),
+    "qeft_pack_search": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int, C.c_float,
+                                   C.POINTER(qeft_weight_t), C.c_void_p]),
     "qeft_pack_codes": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.POINTER(qeft_weight_t), C.c_void_p]),
     "qeft_unpack": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_void_p, C.c_void_p,
@@ -130,6 +132,16 @@ def qeft_pack(desc: qeft_desc_t, W: torch.Tensor, out: Weight | None = None) -> 
     out = out or Weight(desc, W.device)
     ws = out.c_struct()
     _check(raw.qeft_pack(C.byref(desc), _ptr(W), W.stride(0), C.byref(ws), _stream()), "qeft_pack")
+    return out
+
+
+def qeft_pack_search(desc: qeft_desc_t, W: torch.Tensor, n_grid: int = 80, shrink_step: float = 0.01,
+                     out: Weight | None = None) -> Weight:
+    """qeft_pack with the group-wise grid search over truncated ranges."""
+    out = out or Weight(desc, W.device)
+    ws = out.c_struct()
+    _check(raw.qeft_pack_search(C.byref(desc), _ptr(W), W.stride(0), int(n_grid), float(shrink_step), C.byref(ws),
+                                _stream()), "qeft_pack_search")
     return out
 
 

@@ -92,6 +92,19 @@ int qeft_pack(const qeft_desc_t* desc, const void* W, int64_t ldw, const qeft_we
                                (__half*)out->zeros, (__half*)out->weak, (hipStream_t)stream));
 }
 
+int qeft_pack_search(const qeft_desc_t* desc, const void* W, int64_t ldw, int n_grid, float shrink_step,
+                     const qeft_weight_t* out, void* stream) {
+    Layer L;
+    int st = make_layer(desc, out, &L);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(W, L.oc, ldw, L.ic);
+    if (st != QEFT_OK) return st;
+    if (n_grid < 1 || !(shrink_step >= 0.f) || !((float)(n_grid - 1) * shrink_step < 1.f)) return QEFT_ERR_SHAPE;
+    if (!pack_search_supported(L, ldw, W)) return QEFT_ERR_UNSUPPORTED;
+    return hip_status(pack_search(L, (const __half*)W, ldw, n_grid, shrink_step, (uint32_t*)out->qweight,
+                                  (__half*)out->scales, (__half*)out->zeros, (__half*)out->weak, (hipStream_t)stream));
+}
+
 int qeft_pack_codes(const qeft_desc_t* desc, const uint8_t* codes, const void* scales, const void* zeros,
                     const void* weak, const qeft_weight_t* out, void* stream) {
     Layer L;

@@ -163,6 +163,90 @@ __global__ __launch_bounds__(256) void rtn_fused_w4g128_kernel(Layer L, const __
     }
 }
 
+// ---- group-wise grid search with truncation (paper Sec. 3.1) -------------------------------------
+// For every (row, group): candidate i shrinks the min-max range (0 included) by p_i = 1 - i * step,
+// derives (scale, zero-point) with the rules above, quantizes and scores the squared weight error;
+// the first candidate with the smallest error is kept (candidate 0 = plain min-max).  One group per
+// 16 lanes (a lane holds 8 consecutive columns; lanes past the group width hold zeros, which cost
+// nothing), four groups per wavefront.  Every operation is a single correctly rounded fp32
+// operation (the intrinsics keep the compiler from fusing multiply and add) and the error is
+// summed in a fixed order - a lane's 8 columns left to right, then a balanced tree over the 16
+// lanes - so that the decisions can be reproduced exactly elsewhere.
+__device__ __forceinline__ float dpp16_sum(float v) {
+    auto mv = [](float x, auto ctrl) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), decltype(ctrl)::value, 0xf, 0xf, false));
+    };
+    v = __fadd_rn(v, mv(v, std::integral_constant<int, 0xB1>{}));
+    v = __fadd_rn(v, mv(v, std::integral_constant<int, 0x4E>{}));
+    v = __fadd_rn(v, mv(v, std::integral_constant<int, 0x141>{}));
+    v = __fadd_rn(v, mv(v, std::integral_constant<int, 0x140>{}));
+    return v;
+}
+
+__global__ __launch_bounds__(256) void search_params_kernel(Layer L, const __half* __restrict__ W, int64_t ldw,
+                                                            __half* __restrict__ scales, __half* __restrict__ zeros,
+                                                            int chunks, int n_grid, float step) {
+    typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+    typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+    const int64_t wv = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (wv >= (int64_t)L.oc * chunks) return;
+    const int o = (int)(wv / chunks), ch = (int)(wv % chunks);
+    const int grp = 4 * ch + (lane >> 4), t = lane & 15;   // grp < gs: chunks = gs / 4
+    const int col = grp * L.g + 8 * t;
+    const bool live = grp < L.ng && 8 * t < L.g && col < L.kq;   // Kq % 8 == 0: whole octets
+    const u4 raw = live ? *reinterpret_cast<const u4*>(W + (size_t)o * ldw + col) : u4{0u, 0u, 0u, 0u};
+    const h8 h = __builtin_bit_cast(h8, raw);
+    float v[8], lo0 = 0.f, hi0 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        v[e] = (float)h[e];
+        lo0 = fminf(lo0, v[e]);
+        hi0 = fmaxf(hi0, v[e]);
+    }
+    lo0 = dpp16_min(lo0);
+    hi0 = -dpp16_min(-hi0);
+    const float qmax = (float)((1 << L.bits) - 1);
+    float best_e = __builtin_inff();
+    __half best_s = __float2half_rn(1.f), best_z = __float2half_rn(0.f);
+    for (int i = 0; i < n_grid; ++i) {
+        const float p = __fsub_rn(1.f, __fmul_rn((float)i, step));
+        const float lo = __fmul_rn(p, lo0), hi = __fmul_rn(p, hi0);
+        const float s32 = __fdiv_rn(__fsub_rn(hi, lo), qmax);
+        __half s16, z16;
+        if (s32 == 0.f) {
+            s16 = __float2half_rn(1.f);
+            z16 = __float2half_rn(0.f);
+        } else {
+            s16 = __float2half_rn(s32);
+            if (__half2float(s16) == 0.f) s16 = __ushort_as_half((unsigned short)1);
+            float z = rintf(__fdiv_rn(__fsub_rn(0.f, lo), __half2float(s16)));
+            z = fminf(fmaxf(z, 0.f), qmax);
+            z16 = __float2half_rn(z);
+        }
+        const float s = __half2float(s16), z = __half2float(z16);
+        float acc = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float q = __fadd_rn(rintf(__fdiv_rn(v[e], s)), z);
+            q = fminf(fmaxf(q, 0.f), qmax);
+            const float d = __fsub_rn(v[e], __fmul_rn(s, __fsub_rn(q, z)));
+            acc = __fadd_rn(acc, __fmul_rn(d, d));
+        }
+        const float err = dpp16_sum(acc);
+        if (err < best_e) {
+            best_e = err;
+            best_s = s16;
+            best_z = z16;
+        }
+    }
+    if (t == 0) {
+        const bool real = grp < L.ng;
+        scales[(size_t)o * L.gs + grp] = real ? best_s : __float2half_rn(0.f);
+        zeros[(size_t)o * L.gs + grp] = real ? best_z : __float2half_rn(0.f);
+    }
+}
+
 __global__ __launch_bounds__(256) void pack_words_kernel(Layer L, const uint8_t* __restrict__ codes,
                                                          uint32_t* __restrict__ qweight) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -224,6 +308,21 @@ hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qwei
     } else if (L.kq > 0) {
         const int64_t pairs = (int64_t)L.oc * L.gs;
         rtn_params_kernel<<<ceil_div(pairs, 4), 256, 0, s>>>(L, W, ldw, scales, zeros);
+        rtn_words_kernel<<<ceil_div((int64_t)L.oc * L.stride, 256), 256, 0, s>>>(L, W, ldw, scales, zeros, qweight);
+    }
+    copy2d(W + L.kq, ldw, weak, L.k, L.oc, L.k, s);
+    return hipGetLastError();
+}
+
+bool pack_search_supported(const Layer& L, int64_t ldw, const void* W) {
+    return (L.g & 7) == 0 && L.g <= 128 && (L.kq & 7) == 0 && (ldw & 7) == 0 && ((uintptr_t)W & 15) == 0;
+}
+
+hipError_t pack_search(const Layer& L, const __half* W, int64_t ldw, int n_grid, float step, uint32_t* qweight,
+                       __half* scales, __half* zeros, __half* weak, hipStream_t s) {
+    if (L.kq > 0) {
+        const int chunks = L.gs / 4;
+        search_params_kernel<<<ceil_div((int64_t)L.oc * chunks, 4), 256, 0, s>>>(L, W, ldw, scales, zeros, chunks, n_grid, step);
         rtn_words_kernel<<<ceil_div((int64_t)L.oc * L.stride, 256), 256, 0, s>>>(L, W, ldw, scales, zeros, qweight);
     }
     copy2d(W + L.kq, ldw, weak, L.k, L.oc, L.k, s);

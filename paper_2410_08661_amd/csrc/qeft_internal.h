@@ -39,6 +39,9 @@ hipError_t scatter_cols(const __half* Ds, int64_t M, const int* perm, int ic, __
 // ---- format conversion (pack.hip) ----------------------------------------------------
 hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,
                     __half* weak, hipStream_t s);
+bool pack_search_supported(const Layer& L, int64_t ldw, const void* W);
+hipError_t pack_search(const Layer& L, const __half* W, int64_t ldw, int n_grid, float step, uint32_t* qweight,
+                       __half* scales, __half* zeros, __half* weak, hipStream_t s);
 hipError_t pack_codes(const Layer& L, const uint8_t* codes, const __half* scales_in, const __half* zeros_in,
                       const __half* weak_in, uint32_t* qweight, __half* scales, __half* zeros, __half* weak, hipStream_t s);
 hipError_t unpack(const Layer& L, uint8_t* codes, __half* scales, __half* zeros, __half* weak, hipStream_t s);

@@ -140,6 +140,14 @@ def test_irregular_validation():
 def test_pack_and_weak_grad_validation():
     d = B.make_desc(64, 256, 128, 4)
     w = _w()
+    ps = B.raw.qeft_pack_search
+    assert ps(C.byref(d), None, 256, 80, 0.01, C.byref(w), None) == B.QEFT_ERR_NULL
+    assert ps(C.byref(d), 0x10000, 128, 80, 0.01, C.byref(w), None) == B.QEFT_ERR_SHAPE           # ldw < IC
+    assert ps(C.byref(d), 0x10000, 256, 0, 0.01, C.byref(w), None) == B.QEFT_ERR_SHAPE            # no candidate
+    assert ps(C.byref(d), 0x10000, 256, 101, 0.01, C.byref(w), None) == B.QEFT_ERR_SHAPE          # range would vanish
+    assert ps(C.byref(d), 0x10000, 256, 80, -0.5, C.byref(w), None) == B.QEFT_ERR_SHAPE
+    assert ps(C.byref(B.make_desc(64, 256, 128, 4, 100)), 0x10000, 256, 80, 0.01, C.byref(w), None) == B.QEFT_ERR_UNSUPPORTED   # g % 8
+    assert ps(C.byref(B.make_desc(64, 256 + 4, 128, 4)), 0x10000, 264, 80, 0.01, C.byref(w), None) == B.QEFT_ERR_UNSUPPORTED  # Kq % 8
     assert B.raw.qeft_pack(C.byref(d), None, 256, C.byref(w), None) == B.QEFT_ERR_NULL
     assert B.raw.qeft_pack(C.byref(d), 0x10000, 128, C.byref(w), None) == B.QEFT_ERR_SHAPE
     assert B.raw.qeft_pack(C.byref(d), 0x10000, 256, None, None) == B.QEFT_ERR_NULL

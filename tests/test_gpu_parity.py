@@ -57,6 +57,43 @@ def test_pack_rtn_bit_exact(oc, ic, k, bits, g):
     assert np.array_equal(out.weak.cpu().numpy().view(np.uint16), weak.view(np.uint16))
 
 
+SEARCH_SHAPES = [  # oc, ic, k, bits, g, n_grid, step
+    (512, 512, 8, 4, 128, 80, 0.01),          # config 1: partial last group
+    (96, 1024 + 128, 128, 4, 128, 40, 0.02),
+    (80, 1280 + 128, 128, 3, 128, 80, 0.01),  # 3-bit
+    (40, 200, 40, 4, 32, 25, 0.03125),        # narrow groups: most lanes of a group idle
+    (24, 136, 0, 3, 64, 1, 0.01),             # one candidate: plain min-max
+]
+
+
+@pytest.mark.parametrize("oc,ic,k,bits,g,n_grid,step", SEARCH_SHAPES)
+def test_pack_search_bit_exact(oc, ic, k, bits, g, n_grid, step):
+    """Grid-search quantizer (Sec. 3.1): scales, zero-points and codes equal the oracle's bit for bit."""
+    w = synth.make_weight(oc, ic, seed=3 * oc + ic)
+    w[1, 3] = np.float16(0.3)                # outliers, where truncation changes the choice
+    w[2, min(g + 1, ic - k - 1)] = np.float16(-0.45)
+    w[3, :min(g, ic - k)] = 0                # an all-zero group
+    codes, scales, zeros, weak = qo.quantize_search(w, k, bits, g, n_grid, step)
+    lay = qo.layout(oc, ic, k, bits, g)
+    ref_words = qo.pack_codes(codes, bits, lay["row_stride_words"])
+    desc = B.make_desc(oc, ic, k, bits, g)
+    _, wbuf = pad_cols(w)
+    out = B.Weight(desc)
+    out.qweight.fill_(-1)
+    out.scales.fill_(1.0)
+    B.qeft_pack_search(desc, wbuf[:, :ic], n_grid, step, out)
+    torch.cuda.synchronize()
+    ng = lay["n_groups"]
+    assert np.array_equal(out.scales[:, :ng].cpu().numpy().view(np.uint16), scales.view(np.uint16))
+    assert np.array_equal(out.zeros[:, :ng].cpu().numpy().view(np.uint16), zeros.view(np.uint16))
+    assert torch.all(out.scales[:, ng:] == 0) and torch.all(out.zeros[:, ng:] == 0)
+    assert np.array_equal(out.qweight.cpu().numpy().view(np.uint32), ref_words)
+    assert np.array_equal(out.weak.cpu().numpy().view(np.uint16), weak.view(np.uint16))
+    if n_grid > 1:   # the search moved at least the outlier groups away from min-max
+        _, s_rtn, _, _ = qo.quantize_rtn(w, k, bits, g)
+        assert np.any(scales.view(np.uint16) != s_rtn.view(np.uint16))
+
+
 @pytest.mark.parametrize("oc,ic,k,bits,g", PACK_SHAPES)
 def test_pack_codes_and_unpack_bit_exact(oc, ic, k, bits, g):
     h = HostLayer(oc, ic, k, bits, g, seed=7 + oc)
