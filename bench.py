@@ -34,8 +34,8 @@ MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
 # the launches of the kernel in one step
-TRAFFIC_DX_BYTES = (2 * (223.4e6 + 34.3e6) + (484.4e6 + 90.9e6)) / 3      # three dX launches
-TRAFFIC_GEMV_BYTES = (29.34e6 + 9.90e6 + 52.86e6 + 25.14e6) / 4          # the four decode launches of a block
+TRAFFIC_DX_BYTES = (2 * (223.0e6 + 34.3e6) + (485.3e6 + 90.9e6)) / 3      # three dX launches
+TRAFFIC_GEMV_BYTES = (29.34e6 + 9.89e6 + 52.87e6 + 25.14e6) / 4          # the four decode launches of a block
 
 
 def main():
