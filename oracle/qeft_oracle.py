@@ -40,6 +40,7 @@ import numpy as np
 __all__ = [
     "layout", "pack_codes", "unpack_codes", "quantize_rtn", "quantize_search", "dequantize",
     "stored_order", "linear_fwd_irregular", "linear_bwd_dx_irregular",
+    "sensitivity", "top_k", "vote", "global_weak_columns", "reorder",
     "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
     "fwd_samples", "bwd_dx_samples", "weak_grad_samples",
 ]
@@ -308,6 +309,54 @@ def linear_bwd_dx_irregular(w_stored: np.ndarray, perm: np.ndarray, dy: np.ndarr
     out = np.empty_like(d)
     out[:, np.asarray(perm, dtype=np.int64)] = d
     return out
+
+
+# --------------------------------------------------------------------------- global weak columns and reordering
+# Which input channels are weak is decided once for the whole network [Sec. 3.2, App. B]: every
+# layer ranks its input channels by the diagonal of the Hessian of its input, its k best vote
+# with their sensitivity relative to the layer's mean, and the k channels with the largest
+# accumulated vote win.  The model is then reordered offline so that they are contiguous.
+def sensitivity(x: np.ndarray, n_batch: int) -> np.ndarray:
+    """Diagonal of H = mean over the batch of 2 X_b^T X_b  [App. B; lambda_j of Sec. 3.1]:
+    x [tokens][d] holds the n_batch sequences one after the other; -> float64 [d],
+    s_j = (2 / n_batch) * sum_t x[t][j]^2."""
+    x = np.asarray(x).astype(np.float64)
+    return 2.0 * np.sum(x * x, axis=0) / float(n_batch)
+
+
+def top_k(v: np.ndarray, k: int) -> np.ndarray:
+    """Indices of the k largest entries, largest first; equal values: lower index first."""
+    v = np.asarray(v, dtype=np.float64)
+    order = sorted(range(len(v)), key=lambda i: (-v[i], i))
+    return np.array(order[:k], dtype=np.int32)
+
+
+def vote(s_local: np.ndarray, k: int, s_global: np.ndarray) -> np.ndarray:
+    """One layer's contribution [App. B]: its k most sensitive channels add their sensitivity
+    divided by the layer's mean sensitivity to s_global (in place); returns those channels."""
+    s_local = np.asarray(s_local, dtype=np.float64)
+    ids = top_k(s_local, k)
+    s_global[ids] += s_local[ids] / s_local.mean()
+    return ids
+
+
+def global_weak_columns(layer_inputs, k: int) -> np.ndarray:
+    """layer_inputs: iterable of (x [tokens][d], n_batch), one per linear layer that reads the
+    hidden state.  -> the k global weak channels, largest accumulated vote first."""
+    s_global = None
+    for x, n_batch in layer_inputs:
+        s_local = sensitivity(x, n_batch)
+        if s_global is None:
+            s_global = np.zeros(len(s_local), dtype=np.float64)
+        vote(s_local, k, s_global)
+    return top_k(s_global, k)
+
+
+def reorder(a: np.ndarray, perm: np.ndarray, axis: int) -> np.ndarray:
+    """Offline reordering of one weight (or activation) matrix along `axis`: position j of the
+    result holds index perm[j] of the original (columns for the layers that read the hidden state,
+    rows for the ones that write it) [Sec. 3.2, Fig. 3(b)]."""
+    return np.take(np.asarray(a), np.asarray(perm, dtype=np.int64), axis=axis)
 
 
 def round_fp16(a: np.ndarray) -> np.ndarray:
