@@ -173,6 +173,32 @@ int qeft_linear_bwd_dx_irregular(const qeft_desc_t* desc, const qeft_weight_t* w
                                  const void* dY, int64_t M, int64_t lddy, void* dX, int64_t lddx,
                                  void* ws, size_t ws_bytes, void* stream);
 
+/* ---- one-time preparation: global weak columns and offline reordering (Sec. 3.2, App. B) ----
+ *
+ * qeft_sensitivity: the diagonal of the Hessian of a layer's input, out[j] = (2 / n_batch) *
+ * sum_t X[t][j]^2 (fp32), for X fp16 [tokens][ldx] holding n_batch sequences one after the other;
+ * d % 8 == 0.  Needs qeft_sensitivity_workspace(d, tokens) bytes of workspace.
+ *
+ * qeft_vote: the k entries of s (fp32 [d], device) with the largest values - equal values: lower
+ * index first - are written to idx_out[0 .. k) in that order; if s_global is not NULL each of them
+ * also adds s[j] / mean(s) to s_global[j] (a layer's vote, App. B).  With s_global == NULL this is a
+ * plain top-k, which is also the final selection from the accumulated votes.
+ *
+ * qeft_weak_order: perm (int32 [d]) = the channels not in idx[0 .. k) in ascending order, then
+ * idx[0 .. k) as given; idx must hold k distinct channels.
+ *
+ * qeft_reorder: out = A with its columns (axis 1) or rows (axis 0) taken in the order perm:
+ * out[r][j] = A[r][perm[j]] or out[r][:] = A[perm[r]][:]; fp16 matrices [rows][ld], not in place.
+ * Columns for the layers that read the hidden state, rows for the ones that write it (Fig. 3(b)).
+ * Entries of perm are clamped to the valid range.  axis 0 needs cols % 8 == 0. */
+size_t qeft_sensitivity_workspace(int32_t d, int64_t tokens);
+int qeft_sensitivity(const void* X, int64_t tokens, int64_t ldx, int32_t d, int32_t n_batch, float* out,
+                     void* ws, size_t ws_bytes, void* stream);
+int qeft_vote(const float* s, int32_t d, int32_t k, int32_t* idx_out, float* s_global, void* stream);
+int qeft_weak_order(const int32_t* idx, int32_t k, int32_t d, int32_t* perm, void* stream);
+int qeft_reorder(const void* A, int64_t rows, int64_t cols, int64_t lda, const int32_t* perm, int axis,
+                 void* out, int64_t ldo, void* stream);
+
 /* Weight gradient of the weak block only (Sec. 3.3, Eq. 5): dW[o][c] = sum_m dY[m][o] * Xw[m][c].
  * Xw fp16 [M][ldxw] holds the k weak activations of each token: either a view into X
  * (pointer X + Kq, ldxw = ldx) or the compact copy saved for backward (ldxw = k).

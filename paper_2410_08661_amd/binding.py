@@ -58,6 +58,13 @@ EXPORTS = {
                                             C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_linear_bwd_dx_irregular": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_void_p,
                                                C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_sensitivity_workspace": (C.c_size_t, [C.c_int32, C.c_int64]),
+    "qeft_sensitivity": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p,
+                                   C.c_size_t, C.c_void_p]),
+    "qeft_vote": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "qeft_weak_order": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
+    "qeft_reorder": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
+                               C.c_void_p]),
     "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_status_string": (C.c_char_p, [C.c_int]),
@@ -262,6 +269,38 @@ def qeft_linear_bwd_dx_irregular(desc, w: Weight, perm: torch.Tensor, dY: torch.
                                             ws.numel() if ws is not None else 0, _stream()),
            "qeft_linear_bwd_dx_irregular")
     return dX
+
+
+def qeft_sensitivity(X: torch.Tensor, n_batch: int) -> torch.Tensor:
+    """Diagonal of the layer input's Hessian, fp32 [d]."""
+    tokens, d = X.shape
+    out = torch.empty(d, dtype=torch.float32, device=X.device)
+    n = int(raw.qeft_sensitivity_workspace(d, tokens))
+    ws = torch.empty(max(n, 16), dtype=torch.uint8, device=X.device)
+    _check(raw.qeft_sensitivity(_ptr(X), tokens, X.stride(0), d, int(n_batch), _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "qeft_sensitivity")
+    return out
+
+
+def qeft_vote(s: torch.Tensor, k: int, s_global: torch.Tensor | None = None) -> torch.Tensor:
+    """Top-k channels of s (int32 [k], largest first); with s_global their votes are added to it."""
+    idx = torch.empty(k, dtype=torch.int32, device=s.device)
+    _check(raw.qeft_vote(_ptr(s), s.numel(), int(k), _ptr(idx), _ptr(s_global), _stream()), "qeft_vote")
+    return idx
+
+
+def qeft_weak_order(idx: torch.Tensor, d: int) -> torch.Tensor:
+    perm = torch.empty(d, dtype=torch.int32, device=idx.device)
+    _check(raw.qeft_weak_order(_ptr(idx), idx.numel(), int(d), _ptr(perm), _stream()), "qeft_weak_order")
+    return perm
+
+
+def qeft_reorder(A: torch.Tensor, perm: torch.Tensor, axis: int) -> torch.Tensor:
+    rows, cols = A.shape
+    out = _empty_rows(rows, cols, torch.float16, A.device)
+    _check(raw.qeft_reorder(_ptr(A), rows, cols, A.stride(0), _ptr(perm), int(axis), _ptr(out), out.stride(0), _stream()),
+           "qeft_reorder")
+    return out
 
 
 def qeft_weak_grad(desc, dY: torch.Tensor, Xw: torch.Tensor, dW: torch.Tensor | None = None, accumulate=False,

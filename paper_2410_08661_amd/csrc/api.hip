@@ -239,7 +239,7 @@ int qeft_linear_fwd_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, c
     if (st != QEFT_OK) return st;
     st = check_matrix(Y, M, ldy, desc->out_features);
     if (st != QEFT_OK) return st;
-    if (gather_cols((const __half*)X, M, ldx, perm, ic, (__half*)ws, (hipStream_t)stream) != hipSuccess) return QEFT_ERR_HIP;
+    if (gather_cols((const __half*)X, M, ldx, perm, ic, (__half*)ws, (ic + 7) / 8 * 8, (hipStream_t)stream) != hipSuccess) return QEFT_ERR_HIP;
     return qeft_linear_fwd(desc, w, ws, M, (ic + 7) / 8 * 8, Y, ldy, nullptr, 0, stream);
 }
 
@@ -259,6 +259,49 @@ int qeft_linear_bwd_dx_irregular(const qeft_desc_t* desc, const qeft_weight_t* w
     st = qeft_linear_bwd_dx(desc, w, dY, M, lddy, ws, (ic + 7) / 8 * 8, nullptr, 0, stream);
     if (st != QEFT_OK) return st;
     return hip_status(scatter_cols((const __half*)ws, M, perm, ic, (__half*)dX, lddx, (hipStream_t)stream));
+}
+
+size_t qeft_sensitivity_workspace(int32_t d, int64_t tokens) {
+    if (d <= 0 || tokens <= 0) return 0;
+    return sens_workspace(d, tokens);
+}
+
+int qeft_sensitivity(const void* X, int64_t tokens, int64_t ldx, int32_t d, int32_t n_batch, float* out, void* ws,
+                     size_t ws_bytes, void* stream) {
+    if (d <= 0 || (d & 7) != 0 || tokens <= 0 || n_batch <= 0) return QEFT_ERR_SHAPE;
+    int st = check_matrix(X, tokens, ldx, d);
+    if (st != QEFT_OK) return st;
+    if (!out) return QEFT_ERR_NULL;
+    if (!ws || ws_bytes < sens_workspace(d, tokens) || !aligned16(ws)) return QEFT_ERR_WORKSPACE;
+    return hip_status(sensitivity((const __half*)X, tokens, ldx, d, n_batch, out, (float*)ws, (hipStream_t)stream));
+}
+
+int qeft_vote(const float* s, int32_t d, int32_t k, int32_t* idx_out, float* s_global, void* stream) {
+    if (d <= 0 || k < 0 || k > d) return QEFT_ERR_SHAPE;
+    if (!s || (k > 0 && !idx_out)) return QEFT_ERR_NULL;
+    if (k == 0) return QEFT_OK;
+    return hip_status(topk_vote(s, d, k, idx_out, s_global, (hipStream_t)stream));
+}
+
+int qeft_weak_order(const int32_t* idx, int32_t k, int32_t d, int32_t* perm, void* stream) {
+    if (d <= 0 || k < 0 || k > d) return QEFT_ERR_SHAPE;
+    if (!perm || (k > 0 && !idx)) return QEFT_ERR_NULL;
+    return hip_status(weak_order(idx, k, d, perm, (hipStream_t)stream));
+}
+
+int qeft_reorder(const void* A, int64_t rows, int64_t cols, int64_t lda, const int32_t* perm, int axis, void* out,
+                 int64_t ldo, void* stream) {
+    if (rows < 0 || cols < 0 || (axis != 0 && axis != 1)) return QEFT_ERR_SHAPE;
+    if (rows == 0 || cols == 0) return QEFT_OK;
+    int st = check_matrix(A, rows, lda, cols);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(out, rows, ldo, cols);
+    if (st != QEFT_OK) return st;
+    if (!perm) return QEFT_ERR_NULL;
+    if (A == out) return QEFT_ERR_SHAPE;   // not in place
+    if (axis == 1) return hip_status(gather_cols((const __half*)A, rows, lda, perm, (int)cols, (__half*)out, ldo, (hipStream_t)stream));
+    if ((cols & 7) != 0) return QEFT_ERR_UNSUPPORTED;
+    return hip_status(gather_rows16((const __half*)A, lda, perm, (int)rows, (int)rows, (int)cols, (__half*)out, ldo, (hipStream_t)stream));
 }
 
 int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy, const void* Xw, int64_t ldxw,

@@ -116,18 +116,18 @@ inline int rows_per_wg(int64_t M) { return M >= 4096 ? 4 : (M >= 1024 ? 2 : 1); 
 
 size_t irregular_workspace(int ic, int64_t M) { return (size_t)M * (size_t)((ic + 7) / 8 * 8) * sizeof(__half); }
 
-hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, hipStream_t s) {
-    const int chunks = (ic + 7) / 8;
+hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, int64_t ldo, hipStream_t s) {
+    const int chunks = (ic + 7) / 8;   // ldo >= 8 * chunks, a multiple of 8
     const int row_bytes = chunks * 16;
     if (row_bytes <= ROW_LDS_MAX && (ldx & 7) == 0 && ((uintptr_t)X & 15) == 0) {
         const int rw = rows_per_wg(M);
         gather_rows_kernel<<<ceil_div(M, rw), 256, row_bytes, s>>>((const unsigned short*)X, (int)M, ldx, perm, ic, chunks,
-                                                                   (unsigned short*)Xs, (int64_t)chunks * 8, rw);
+                                                                   (unsigned short*)Xs, ldo, rw);
         return hipGetLastError();
     }
     const int64_t n = M * chunks;
     gather_cols_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const unsigned short*)X, (int)M, ldx, perm, ic, chunks,
-                                                       (unsigned short*)Xs, (int64_t)chunks * 8);
+                                                       (unsigned short*)Xs, ldo);
     return hipGetLastError();
 }
 

@@ -33,8 +33,16 @@ hipError_t weak_grad_generic(int oc, int k, const __half* dY, int64_t M, int64_t
 
 // ---- weak columns at arbitrary channels: gather / scatter through a workspace (irregular.hip) ----
 size_t irregular_workspace(int ic, int64_t M);   // [M][IC rounded up to 8] fp16
-hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, hipStream_t s);
+hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, int64_t ldo, hipStream_t s);
 hipError_t scatter_cols(const __half* Ds, int64_t M, const int* perm, int ic, __half* dX, int64_t lddx, hipStream_t s);
+
+// ---- global weak-column selection and offline reordering (reorder.hip) --------------------------
+size_t sens_workspace(int d, int64_t tokens);
+hipError_t sensitivity(const __half* X, int64_t tokens, int64_t ldx, int d, int n_batch, float* out, float* ws, hipStream_t s);
+hipError_t topk_vote(const float* v, int d, int k, int* idx_out, float* s_global, hipStream_t s);
+hipError_t weak_order(const int* idx, int k, int d, int* perm, hipStream_t s);
+hipError_t gather_rows16(const __half* W, int64_t ldw, const int* perm, int rows, int src_rows, int cols, __half* out, int64_t ldo,
+                         hipStream_t s);
 
 // ---- format conversion (pack.hip) ----------------------------------------------------
 hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,

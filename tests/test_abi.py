@@ -137,6 +137,32 @@ def test_irregular_validation():
     assert dx(C.byref(d), C.byref(w), P, X, M, 64, Y, 248, WS, need, None) == B.QEFT_ERR_SHAPE       # lddx < IC
 
 
+def test_reordering_validation():
+    R = B.raw
+    X, O, P, WS = 0x10000, 0x20000, 0x30000, 0x40000
+    assert R.qeft_sensitivity_workspace(4096, 1000) > 0 and R.qeft_sensitivity_workspace(0, 5) == 0
+    need = R.qeft_sensitivity_workspace(96, 64)
+    assert R.qeft_sensitivity(X, 64, 96, 100, 4, O, WS, need, None) == B.QEFT_ERR_SHAPE          # d % 8
+    assert R.qeft_sensitivity(X, 64, 88, 96, 4, O, WS, need, None) == B.QEFT_ERR_SHAPE           # ldx < d
+    assert R.qeft_sensitivity(X, 64, 96, 96, 0, O, WS, need, None) == B.QEFT_ERR_SHAPE           # n_batch
+    assert R.qeft_sensitivity(None, 64, 96, 96, 4, O, WS, need, None) == B.QEFT_ERR_NULL
+    assert R.qeft_sensitivity(X, 64, 96, 96, 4, None, WS, need, None) == B.QEFT_ERR_NULL
+    assert R.qeft_sensitivity(X, 64, 96, 96, 4, O, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
+    assert R.qeft_vote(X, 96, 97, O, None, None) == B.QEFT_ERR_SHAPE                               # k > d
+    assert R.qeft_vote(None, 96, 4, O, None, None) == B.QEFT_ERR_NULL
+    assert R.qeft_vote(X, 96, 4, None, None, None) == B.QEFT_ERR_NULL
+    assert R.qeft_vote(X, 96, 0, None, None, None) == B.QEFT_OK                                    # nothing to select
+    assert R.qeft_weak_order(P, 4, 0, O, None) == B.QEFT_ERR_SHAPE
+    assert R.qeft_weak_order(None, 4, 96, O, None) == B.QEFT_ERR_NULL
+    assert R.qeft_weak_order(P, 4, 96, None, None) == B.QEFT_ERR_NULL
+    assert R.qeft_reorder(X, 8, 96, 96, P, 2, O, 96, None) == B.QEFT_ERR_SHAPE                     # axis
+    assert R.qeft_reorder(X, 8, 96, 88, P, 1, O, 96, None) == B.QEFT_ERR_SHAPE                     # lda < cols
+    assert R.qeft_reorder(X, 8, 96, 96, None, 1, O, 96, None) == B.QEFT_ERR_NULL
+    assert R.qeft_reorder(X, 8, 96, 96, P, 1, X, 96, None) == B.QEFT_ERR_SHAPE                     # in place
+    assert R.qeft_reorder(X, 8, 100, 104, P, 0, O, 104, None) == B.QEFT_ERR_UNSUPPORTED            # rows of odd width
+    assert R.qeft_reorder(X, 0, 96, 96, P, 1, O, 96, None) == B.QEFT_OK
+
+
 def test_pack_and_weak_grad_validation():
     d = B.make_desc(64, 256, 128, 4)
     w = _w()

@@ -321,6 +321,71 @@ def test_irregular_malformed_table_stays_in_bounds():
     assert torch.all(dbuf[0] == 5.0) and torch.all(dbuf[-1] == 5.0)  # no guard row was written
 
 
+# ------------------------------------------------------------------------------ global weak columns, reordering
+@pytest.mark.parametrize("tokens,d,n_batch", [(64, 96, 4), (700, 4096, 7), (33, 1032, 3)])
+def test_sensitivity_parity(tokens, d, n_batch):
+    x = synth.make_activations(tokens, d, 16, tokens + d)
+    got = B.qeft_sensitivity(pad_cols(x)[0], n_batch).cpu().numpy().astype(np.float64)
+    ref = qo.sensitivity(x, n_batch)
+    np.testing.assert_allclose(got, ref, rtol=2e-6)            # fp32 sums of fp32 squares
+
+
+def test_global_weak_columns_end_to_end():
+    """Planted outlier channels (Sec. 3.2): sensitivity, per-layer votes, global top-k, the reordering
+    permutation and the reordered matrices all equal the oracle's; the reordered layer's output does not change."""
+    r = np.random.default_rng(8)
+    d, k, oc, planted = 1024, 16, 128, sorted(r.permutation(1024)[:16].tolist())
+    layers = []
+    for li in range(4):
+        x = r.standard_normal((96, d)).astype(np.float32) * (1.0 + li)      # layers of different overall scale
+        x[:, planted] *= 15.0
+        if li == 1:
+            x[:, (planted[0] + 1) % d] *= 20.0                               # an outlier only this layer has: one vote, not four
+        layers.append(x.astype(np.float16))
+    s_global = torch.zeros(d, dtype=torch.float32, device="cuda")
+    ref_global = np.zeros(d)
+    for x in layers:
+        s_local = B.qeft_sensitivity(torch.from_numpy(x).cuda(), 4)
+        ids = B.qeft_vote(s_local, k, s_global)
+        ref_ids = qo.vote(qo.sensitivity(x, 4), k, ref_global)
+        assert sorted(ids.cpu().tolist()) == sorted(ref_ids.tolist())        # clear margins: the same channels
+    np.testing.assert_allclose(s_global.cpu().numpy(), ref_global, rtol=1e-5)
+    idx = B.qeft_vote(s_global, k)
+    ref_idx = qo.global_weak_columns([(x, 4) for x in layers], k)
+    assert sorted(idx.cpu().tolist()) == planted == sorted(ref_idx.tolist())
+    perm = B.qeft_weak_order(idx, d)
+    assert np.array_equal(perm.cpu().numpy(), qo.stored_order(d, idx.cpu().numpy()))
+    # reorder a weight along its columns and the activations with it; along its rows for a producer
+    w = synth.make_weight(oc, d, seed=5)
+    wr = B.qeft_reorder(torch.from_numpy(w).cuda(), perm, 1)
+    xr = B.qeft_reorder(torch.from_numpy(layers[0]).cuda(), perm, 1)
+    p = perm.cpu().numpy()
+    assert np.array_equal(wr.cpu().numpy().view(np.uint16), qo.reorder(w, p, 1).view(np.uint16))
+    assert np.array_equal(xr.cpu().numpy().view(np.uint16), qo.reorder(layers[0], p, 1).view(np.uint16))
+    v = synth.make_weight(d, 256, seed=6)
+    vr = B.qeft_reorder(torch.from_numpy(v).cuda(), perm, 0)
+    assert np.array_equal(vr.cpu().numpy().view(np.uint16), qo.reorder(v, p, 0).view(np.uint16))
+    # the reordered layer, quantized with its weak columns now last, reproduces the original product
+    desc = B.make_desc(oc, d, k, 4, 128)
+    y = B.qeft_linear_fwd(desc, B.qeft_pack(desc, wr), xr[:8])
+    wq = qo.quantize_rtn(qo.reorder(w, p, 1), k, 4, 128)
+    w64 = qo.dequantize(*wq, 128)
+    assert_close(y.cpu().numpy(), qo.linear_fwd(w64, qo.reorder(layers[0][:8], p, 1)), "reordered layer")
+    dense = layers[0][:8].astype(np.float64) @ w.astype(np.float64).T        # the un-reordered fp16 layer
+    rel = np.linalg.norm(y.cpu().numpy() - dense) / np.linalg.norm(dense)
+    assert rel < 0.05                                                        # quantization error only
+
+
+def test_vote_ties_and_plain_top_k():
+    v = torch.tensor([1.0, 5.0, 3.0, 5.0, 0.0, 3.0], device="cuda")
+    assert B.qeft_vote(v, 4).cpu().tolist() == qo.top_k(v.cpu().numpy(), 4).tolist() == [1, 3, 2, 5]
+    sg = torch.zeros(6, device="cuda")
+    B.qeft_vote(v, 2, sg)
+    ref = np.zeros(6)
+    qo.vote(v.cpu().numpy(), 2, ref)
+    np.testing.assert_allclose(sg.cpu().numpy(), ref, rtol=1e-6)
+
+
 # ------------------------------------------------------------------------------ backward
 BWD_CASES = [  # oc, ic, k, bits, g, M
     (256, 512 + 128, 128, 4, 128, 300),
