@@ -40,7 +40,7 @@ import numpy as np
 __all__ = [
     "layout", "pack_codes", "unpack_codes", "quantize_rtn", "quantize_search", "dequantize",
     "stored_order", "linear_fwd_irregular", "linear_bwd_dx_irregular",
-    "sensitivity", "top_k", "vote", "global_weak_columns", "reorder",
+    "sensitivity", "top_k", "vote", "global_weak_columns", "reorder", "merge_weak",
     "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
     "fwd_samples", "bwd_dx_samples", "weak_grad_samples",
 ]
@@ -357,6 +357,19 @@ def reorder(a: np.ndarray, perm: np.ndarray, axis: int) -> np.ndarray:
     result holds index perm[j] of the original (columns for the layers that read the hidden state,
     rows for the ones that write it) [Sec. 3.2, Fig. 3(b)]."""
     return np.take(np.asarray(a), np.asarray(perm, dtype=np.int64), axis=axis)
+
+
+def merge_weak(target: np.ndarray, tuned: np.ndarray, base: np.ndarray, idx=None) -> np.ndarray:
+    """QEFT merging [Sec. 5, "QEFT merging"]: the update of the fine-tuned weak columns,
+    Delta = A' - A, is added to the corresponding columns of another model's weight: to the
+    columns idx of a full-precision target, or (idx None) to the target's own weak block.
+    All fp16; the arithmetic is float32 with one rounding per operation, then one to fp16
+    (a difference of two fp16 numbers is exact in float32)."""
+    t = np.array(target, dtype=np.float16, copy=True)
+    delta = np.asarray(tuned, dtype=np.float16).astype(np.float32) - np.asarray(base, dtype=np.float16).astype(np.float32)
+    cols = np.arange(delta.shape[1]) if idx is None else np.asarray(idx, dtype=np.int64)
+    t[:, cols] = (t[:, cols].astype(np.float32) + delta).astype(np.float32).astype(np.float16)
+    return t
 
 
 def round_fp16(a: np.ndarray) -> np.ndarray:

@@ -68,3 +68,28 @@ def test_output_is_invariant_under_the_reordering():
     v = r.standard_normal((d, 7))
     h = r.standard_normal((m, 7))
     np.testing.assert_allclose(qo.linear_fwd(qo.reorder(v, perm, axis=0), h), qo.reorder(h @ v.T, perm, axis=1), rtol=1e-12)
+
+
+def test_merge_weak_by_hand_and_consistency():
+    from fractions import Fraction
+    base = np.array([[1.0, 2.0], [0.5, -1.0]], dtype=np.float16)
+    tuned = np.array([[1.5, 2.0], [0.25, 1.0]], dtype=np.float16)           # Delta = [[0.5, 0], [-0.25, 2]]
+    target = np.array([[10, 20, 30, 40], [1, 2, 3, 4]], dtype=np.float16)
+    got = qo.merge_weak(target, tuned, base, idx=[3, 0])                     # weak columns 3 and 0 of the target
+    assert got.tolist() == [[10.0, 20.0, 30.0, 40.5], [3.0, 2.0, 3.0, 3.75]]
+    assert target.tolist() == [[10, 20, 30, 40], [1, 2, 3, 4]]               # input untouched
+    blk = np.array([[7.0, 8.0], [9.0, 10.0]], dtype=np.float16)
+    assert qo.merge_weak(blk, tuned, base).tolist() == [[7.5, 8.0], [8.75, 12.0]]   # the target's own weak block
+    # merging into a full-precision target at idx, then taking its weak columns, equals merging into the block
+    r = np.random.default_rng(4)
+    t = r.standard_normal((6, 20)).astype(np.float16)
+    a0, a1 = r.standard_normal((6, 5)).astype(np.float16), r.standard_normal((6, 5)).astype(np.float16)
+    idx = [17, 3, 4, 11, 0]
+    full = qo.merge_weak(t, a1, a0, idx)
+    assert np.array_equal(full[:, idx], qo.merge_weak(t[:, idx], a1, a0))
+    untouched = [c for c in range(20) if c not in idx]
+    assert np.array_equal(full[:, untouched], t[:, untouched])
+    # each element is the correctly rounded fp16 of the exact sum when that sum is exact in float32
+    o, c = 2, 1
+    exact = Fraction(float(t[o, idx[c]])) + Fraction(float(a1[o, c])) - Fraction(float(a0[o, c]))
+    assert abs(Fraction(float(full[o, idx[c]])) - exact) <= abs(exact) * Fraction(1, 2048) + Fraction(1, 2 ** 24)
