@@ -199,6 +199,15 @@ int qeft_weak_order(const int32_t* idx, int32_t k, int32_t d, int32_t* perm, voi
 int qeft_reorder(const void* A, int64_t rows, int64_t cols, int64_t lda, const int32_t* perm, int axis,
                  void* out, int64_t ldo, void* stream);
 
+/* QEFT merging (Sec. 5): the update of a fine-tuned weak block, tuned - base (both fp16 [OC][k],
+ * compact), is added to another model's weight of the same layer: with idx (int32 [k], device) to
+ * the columns idx[c] of a full-precision target fp16 [OC][ldt] with target_cols columns, with
+ * idx == NULL to columns 0 .. k-1 of target (the target's own weak block: pass its pointer and
+ * ldt = k).  fp32 arithmetic, one rounding to fp16 per element.  idx entries must be distinct
+ * (they are clamped to the target's width). */
+int qeft_merge_weak(const void* tuned, const void* base, int64_t out_features, int32_t k, const int32_t* idx,
+                    void* target, int64_t ldt, int32_t target_cols, void* stream);
+
 /* Weight gradient of the weak block only (Sec. 3.3, Eq. 5): dW[o][c] = sum_m dY[m][o] * Xw[m][c].
  * Xw fp16 [M][ldxw] holds the k weak activations of each token: either a view into X
  * (pointer X + Kq, ldxw = ldx) or the compact copy saved for backward (ldxw = k).

@@ -65,6 +65,8 @@ EXPORTS = {
     "qeft_weak_order": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]),
     "qeft_reorder": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int, C.c_void_p, C.c_int64,
                                C.c_void_p]),
+    "qeft_merge_weak": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32,
+                                  C.c_void_p]),
     "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_status_string": (C.c_char_p, [C.c_int]),
@@ -301,6 +303,14 @@ def qeft_reorder(A: torch.Tensor, perm: torch.Tensor, axis: int) -> torch.Tensor
     _check(raw.qeft_reorder(_ptr(A), rows, cols, A.stride(0), _ptr(perm), int(axis), _ptr(out), out.stride(0), _stream()),
            "qeft_reorder")
     return out
+
+
+def qeft_merge_weak(tuned: torch.Tensor, base: torch.Tensor, target: torch.Tensor, idx: torch.Tensor | None = None) -> torch.Tensor:
+    """target[:, idx] (or target[:, :k]) += tuned - base, in place."""
+    oc, k = tuned.shape
+    _check(raw.qeft_merge_weak(_ptr(tuned), _ptr(base), oc, k, _ptr(idx), _ptr(target), target.stride(0), target.shape[1],
+                               _stream()), "qeft_merge_weak")
+    return target
 
 
 def qeft_weak_grad(desc, dY: torch.Tensor, Xw: torch.Tensor, dW: torch.Tensor | None = None, accumulate=False,

@@ -304,6 +304,15 @@ int qeft_reorder(const void* A, int64_t rows, int64_t cols, int64_t lda, const i
     return hip_status(gather_rows16((const __half*)A, lda, perm, (int)rows, (int)rows, (int)cols, (__half*)out, ldo, (hipStream_t)stream));
 }
 
+int qeft_merge_weak(const void* tuned, const void* base, int64_t out_features, int32_t k, const int32_t* idx, void* target,
+                    int64_t ldt, int32_t target_cols, void* stream) {
+    if (out_features < 0 || k < 0 || target_cols < k || ldt < target_cols) return QEFT_ERR_SHAPE;
+    if (out_features == 0 || k == 0) return QEFT_OK;
+    if (!tuned || !base || !target) return QEFT_ERR_NULL;
+    return hip_status(merge_weak((const __half*)tuned, (const __half*)base, out_features, k, idx, target_cols, (__half*)target,
+                                 ldt, (hipStream_t)stream));
+}
+
 int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy, const void* Xw, int64_t ldxw,
                    void* dW, int out_dtype, int accumulate, void* ws, size_t ws_bytes, void* stream) {
     int st = check_desc(desc);

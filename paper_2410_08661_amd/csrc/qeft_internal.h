@@ -44,6 +44,9 @@ hipError_t weak_order(const int* idx, int k, int d, int* perm, hipStream_t s);
 hipError_t gather_rows16(const __half* W, int64_t ldw, const int* perm, int rows, int src_rows, int cols, __half* out, int64_t ldo,
                          hipStream_t s);
 
+hipError_t merge_weak(const __half* tuned, const __half* base, int64_t oc, int k, const int* idx, int target_cols,
+                      __half* target, int64_t ldt, hipStream_t s);
+
 // ---- format conversion (pack.hip) ----------------------------------------------------
 hipError_t pack_rtn(const Layer& L, const __half* W, int64_t ldw, uint32_t* qweight, __half* scales, __half* zeros,
                     __half* weak, hipStream_t s);

@@ -111,7 +111,28 @@ __global__ __launch_bounds__(256) void gather_rows16_kernel(const __half* __rest
     *reinterpret_cast<u4*>(out + (size_t)r * ldo + 8 * c) = *reinterpret_cast<const u4*>(W + (size_t)src * ldw + 8 * c);
 }
 
+// target[o][idx[c]] (or target[o][c] without idx) += tuned[o][c] - base[o][c]: the difference is exact
+// in fp32, the sum is one fp32 addition, the result one rounding to fp16
+__global__ __launch_bounds__(256) void merge_weak_kernel(const __half* __restrict__ tuned, const __half* __restrict__ base,
+                                                         int64_t oc, int k, const int* __restrict__ idx, int target_cols,
+                                                         __half* __restrict__ target, int64_t ldt) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= oc * k) return;
+    const int64_t o = t / k;
+    const int c = (int)(t % k);
+    const int col = idx ? min(max(idx[c], 0), target_cols - 1) : c;
+    const float delta = __fsub_rn(__half2float(tuned[t]), __half2float(base[t]));
+    __half* p = target + (size_t)o * ldt + col;
+    *p = __float2half_rn(__fadd_rn(__half2float(*p), delta));
+}
+
 }  // namespace
+
+hipError_t merge_weak(const __half* tuned, const __half* base, int64_t oc, int k, const int* idx, int target_cols,
+                      __half* target, int64_t ldt, hipStream_t s) {
+    merge_weak_kernel<<<ceil_div(oc * k, 256), 256, 0, s>>>(tuned, base, oc, k, idx, target_cols, target, ldt);
+    return hipGetLastError();
+}
 
 int sens_splits(int d, int64_t tokens) {
     const int chunks = ceil_div(d, 256);

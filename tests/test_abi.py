@@ -163,6 +163,18 @@ def test_reordering_validation():
     assert R.qeft_reorder(X, 0, 96, 96, P, 1, O, 96, None) == B.QEFT_OK
 
 
+def test_merge_validation():
+    mg = B.raw.qeft_merge_weak
+    A1, A0, T, P = 0x10000, 0x20000, 0x30000, 0x40000
+    assert mg(A1, A0, 8, 4, P, T, 16, 2, None) == B.QEFT_ERR_SHAPE            # fewer target columns than weak ones
+    assert mg(A1, A0, 8, 4, P, T, 8, 16, None) == B.QEFT_ERR_SHAPE            # ldt < columns
+    assert mg(A1, A0, -1, 4, P, T, 16, 16, None) == B.QEFT_ERR_SHAPE
+    assert mg(None, A0, 8, 4, P, T, 16, 16, None) == B.QEFT_ERR_NULL
+    assert mg(A1, A0, 8, 4, P, None, 16, 16, None) == B.QEFT_ERR_NULL
+    assert mg(A1, A0, 0, 4, P, T, 16, 16, None) == B.QEFT_OK
+    assert mg(A1, A0, 8, 0, None, T, 16, 16, None) == B.QEFT_OK
+
+
 def test_pack_and_weak_grad_validation():
     d = B.make_desc(64, 256, 128, 4)
     w = _w()

@@ -386,6 +386,22 @@ def test_vote_ties_and_plain_top_k():
     np.testing.assert_allclose(sg.cpu().numpy(), ref, rtol=1e-6)
 
 
+def test_merge_weak_bit_exact():
+    """QEFT merging (Sec. 5): into the columns of a full-precision target and into a weak block."""
+    r = np.random.default_rng(12)
+    oc, ic, k = 300, 520, 40
+    t = r.standard_normal((oc, ic)).astype(np.float16)
+    a0 = (r.standard_normal((oc, k)) * 0.02).astype(np.float16)
+    a1 = (a0.astype(np.float32) + r.standard_normal((oc, k)).astype(np.float32) * 0.003).astype(np.float16)
+    idx = r.permutation(ic)[:k].astype(np.int32)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    full = B.qeft_merge_weak(dev(a1), dev(a0), dev(t), dev(idx))
+    blk = B.qeft_merge_weak(dev(a1), dev(a0), dev(t[:, idx]))
+    torch.cuda.synchronize()
+    assert np.array_equal(full.cpu().numpy().view(np.uint16), qo.merge_weak(t, a1, a0, idx).view(np.uint16))
+    assert np.array_equal(blk.cpu().numpy().view(np.uint16), qo.merge_weak(t[:, idx], a1, a0).view(np.uint16))
+
+
 # ------------------------------------------------------------------------------ backward
 BWD_CASES = [  # oc, ic, k, bits, g, M
     (256, 512 + 128, 128, 4, 128, 300),
