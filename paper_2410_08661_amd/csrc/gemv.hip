@@ -875,18 +875,20 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
                   int64_t ldy, hipStream_t s, hipError_t* err) {
     const int units = (L.ng + 3) / 4;
     const int nweak = (L.k + 31) / 32;
-    // ~12 waves per CU over 256 CUs, at most 16 waves per workgroup, K split in units of 4 steps
-    int ks = ceil_div(3072, tiles);
+    // K split in units of 4 steps over the waves of a workgroup, one row tile per workgroup.  Measured over the
+    // Llama-2 7B / 13B / 70B launches (1 - 3 layers each): four waves - one per SIMD - are the best or within 3 %
+    // of it whenever there are more row tiles than CUs, whatever the number of tiles (768 ... 3584) or units
+    // (8 ... 56); more waves per tile only pay when there is at most one tile per CU and the rows are long
+    // (4096 x 11008: six waves of <= 4 units).  Several tiles per workgroup were never faster.
     const int ks_max = units < 1 ? 1 : (units > 16 ? 16 : units);
-    ks = ks < 1 ? 1 : (ks > ks_max ? ks_max : ks);
+    int ks = 4;
+    if (tiles <= 256 && units > 16) ks = ceil_div(units, 4);
+    ks = ks > ks_max ? ks_max : ks;
     while (ks > 1 && ceil_div(units, ks - 1) == ceil_div(units, ks)) --ks;   // no wave with less than the longest share
-    int tw = 16 / ks;
-    tw = tw < 1 ? 1 : (tw > 4 ? 4 : tw);
-    while (tw > 1 && ceil_div(tiles, tw) < 512) tw >>= 1;  // keep every CU busy
-    if (small_lds(M, L.ng, tw, ks).total > 64 * 1024) {     // one workgroup per CU: make it a full one
-        tw = 1;
-        ks = ks_max;
-    }
+    // the per-wave shares of the weak block and of the group parameters must fit the kernel's registers
+    while (ks < ks_max && (ceil_div(nweak, ks) > 4 || ceil_div(2 * ceil_div(L.ng, 32), ks) > 3)) ++ks;
+    int tw = 1;
+    if (small_lds(M, L.ng, tw, ks).total > 64 * 1024) ks = ks_max;   // one workgroup per CU: make it a full one
     const SmallLds ld = small_lds(M, L.ng, tw, ks);
     const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
     if (!(ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3)) return false;
