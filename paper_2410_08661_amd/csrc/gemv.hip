@@ -825,14 +825,20 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
                     [&](int w) { return reinterpret_cast<float*>(lds) + (size_t)(w - 1) * R * 4 * 64; });
 }
 
+// K-split waves of the 3-bit kernel: four (one per SIMD; measured best for 4096 ... 11008 rows), more only
+// when the (zero-point, scale) table would otherwise take more than 4 requests per wave
+int w3_split(const Layer& L, int R) {
+    const int nsteps = ceil_div(L.words, 16), nchunks = 2 * ceil_div(L.ng, 32) * R;
+    int ks = nsteps < 4 ? (nsteps < 1 ? 1 : nsteps) : 4;
+    while (ks < 8 && ks < nsteps && ceil_div(nchunks, ks) > 4) ++ks;
+    return ks;
+}
+
 template <int R>
 hipError_t launch_w3(const Layer& L, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int tiles = ceil_div(L.oc, 16 * R);
     const int nsteps = ceil_div(L.words, 16);
-    int ks = ceil_div(3072, tiles);
-    ks = ks > 8 ? 8 : ks;
-    ks = ks > nsteps ? nsteps : ks;
-    ks = ks < 1 ? 1 : ks;
+    const int ks = w3_split(L, R);
     const int nchunks = 2 * ceil_div(L.ng, 32) * R;
     const int nsz = ceil_div(nchunks, ks);
     const size_t table = (size_t)L.ng * 16 * R * 4, red = (size_t)(ks > 1 ? ks - 1 : 1) * R * 4 * 64 * sizeof(float);
@@ -851,11 +857,7 @@ constexpr int SMALL_LDS_LIMIT = 144 * 1024;   // of the 160 KB a CU has
 // the 3-bit kernel: its (zero-point, scale) table must fit in LDS and be loadable in 4 requests per wave
 static bool w3_fits(const Layer& L) {
     for (int R = 1; R <= 2; ++R) {
-        const int tiles = ceil_div(L.oc, 16 * R), nsteps = ceil_div(L.words, 16);
-        int ks = ceil_div(3072, tiles);
-        ks = ks > 8 ? 8 : ks;
-        ks = ks > nsteps ? nsteps : ks;
-        ks = ks < 1 ? 1 : ks;
+        const int ks = w3_split(L, R);
         if (ceil_div(2 * ceil_div(L.ng, 32) * R, ks) > 4 || (size_t)L.ng * 16 * R * 4 > 64 * 1024) return false;
     }
     return true;
@@ -964,14 +966,13 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
         if (launch_small(L, ceil_div(L.oc, 16), no_tail(), nullptr, X, M, ldx, Y, ldy, s, &err)) return err;
     }
     if (L.kq >= 8 && !getenv("QEFT_DBG_CHUNK")) {
-        // unstaged kernel: R tiles per wave share the activation fragments (more rows, more sharing),
-        // and enough K-split waves for ~8-12 per CU
+        // unstaged kernel: R tiles per wave share the activation fragments; four K-split waves per workgroup
+        // (one per SIMD), and four tiles per wave once that still leaves every CU more than two waves
+        // (measured at M = 8 and 16: 4096 ... 8192 rows are 30 - 50 % faster with R = 2, 11008 ... 28672 rows
+        // 5 - 25 % faster with R = 4; KS = 4 first or within 3 % of first on every shape)
         const int units = (L.ng + 3) / 4;
-        const int R = (M > 8 && ceil_div(L.oc, 64) * (units < 8 ? units : 8) >= 1536) ? 4 : 2;
-        const int tiles = ceil_div(L.oc, 16 * R);
-        int ks = ceil_div(R == 4 ? 2048 : 3072, tiles);
-        ks = ks > 8 ? 8 : ks;
-        ks = ks > units ? units : ks;
+        const int R = ceil_div(L.oc, 64) >= 160 ? 4 : 2;
+        int ks = units < 4 ? units : 4;
         ks = ks < 1 ? 1 : ks;
         if (R == 4) return launch_rows<4, 4>(L, X, M, ldx, Y, ldy, ks, s);
         return launch_rows<2, 4>(L, X, M, ldx, Y, ldy, ks, s);
