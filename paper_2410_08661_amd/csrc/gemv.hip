@@ -881,7 +881,7 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
     // Llama-2 7B / 13B / 70B launches (1 - 3 layers each): four waves - one per SIMD - are the best or within 3 %
     // of it whenever there are more row tiles than CUs, whatever the number of tiles (768 ... 3584) or units
     // (8 ... 56); more waves per tile only pay when there is at most one tile per CU and the rows are long
-    // (4096 x 11008: six waves of <= 4 units).  Several tiles per workgroup were never faster.
+    // (4096 x 11008: six waves of <= 4 units).  At M = 1 several tiles per workgroup were never faster.
     const int ks_max = units < 1 ? 1 : (units > 16 ? 16 : units);
     int ks = 4;
     if (tiles <= 256 && units > 16) ks = ceil_div(units, 4);
@@ -889,8 +889,16 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
     while (ks > 1 && ceil_div(units, ks - 1) == ceil_div(units, ks)) --ks;   // no wave with less than the longest share
     // the per-wave shares of the weak block and of the group parameters must fit the kernel's registers
     while (ks < ks_max && (ceil_div(nweak, ks) > 4 || ceil_div(2 * ceil_div(L.ng, 32), ks) > 3)) ++ks;
+    // Every workgroup stages all of X (2 M IC bytes against the 8 IC bytes of a tile's codes): from M = 2 on,
+    // 2 or 4 tiles share a workgroup's copy where that leaves at least a workgroup per CU, spread evenly
+    // (28672 x 8192, M = 4: 36 us against 45; 8192 x 8192: 13.3 against 15.1; 11008 rows: no gain, 344
+    // workgroups on 256 CUs)
+    const auto even = [](int wgs) { return 5 * wgs >= 4 * 256 * ceil_div(wgs, 256); };
     int tw = 1;
-    if (small_lds(M, L.ng, tw, ks).total > 64 * 1024) ks = ks_max;   // one workgroup per CU: make it a full one
+    if (M >= 2 && tiles >= 512 && even(ceil_div(tiles, 2))) tw = 2;
+    if (M >= 3 && tiles >= 1024 && even(ceil_div(tiles, 4))) tw = 4;
+    if (ks * tw > 16) tw = 1;
+    if (tw == 1 && ks < 8 && ks_max >= 8 && small_lds(M, L.ng, tw, ks).total > 64 * 1024) ks = 8;   // two workgroups per CU at most: larger ones
     const SmallLds ld = small_lds(M, L.ng, tw, ks);
     const int wmax = ceil_div(nweak, ks), nsz = ceil_div(2 * ceil_div(L.ng, 32), ks);
     if (!(ld.total <= SMALL_LDS_LIMIT && wmax <= 4 && nsz <= 3)) return false;

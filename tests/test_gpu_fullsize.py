@@ -68,8 +68,8 @@ def _check(actual_t, pairs, ref, what):
 
 DECODE = [  # config, shapes, k, bits list, M list
     (2, synth.LLAMA_7B, 128, [4], [1, 8]),
-    (3, synth.LLAMA_13B, 128, [3, 4], [1, 5, 16]),
-    (5, synth.LLAMA_70B, 256, [4], [1]),
+    (3, synth.LLAMA_13B, 128, [3, 4], [1, 3, 5, 16]),
+    (5, synth.LLAMA_70B, 256, [4], [1, 4]),
 ]
 DECODE_CASES = [(cfg, si, s, k, b, Ms) for cfg, shapes, k, bl, Ms in DECODE for si, s in enumerate(shapes) for b in bl]
 
