@@ -38,7 +38,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
-    "layout", "pack_codes", "unpack_codes", "quantize_rtn", "quantize_search", "dequantize",
+    "layout", "pack_codes", "unpack_codes", "pack_codes_dense3", "unpack_codes_dense3", "quantize_rtn", "quantize_search", "dequantize",
     "stored_order", "linear_fwd_irregular", "linear_bwd_dx_irregular",
     "sensitivity", "top_k", "vote", "global_weak_columns", "reorder", "merge_weak",
     "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
@@ -47,8 +47,12 @@ __all__ = [
 
 
 # --------------------------------------------------------------------------- layout
-def layout(out_features: int, in_features: int, n_weak: int, bits: int, group_size: int) -> dict:
+def layout(out_features: int, in_features: int, n_weak: int, bits: int, group_size: int, dense: bool = False) -> dict:
     """Sizes of the three stored components [Sec. 3.1].
+
+    dense=True (3-bit only) is the second stored layout: a row's codes as one bit string with
+    no unused bits, 3.0 bits per weight, which is what the model sizes of [Tab. 5] imply for
+    the 3-bit models (see pack_codes_dense3).
 
     Kq = IC - k columns are quantized.  Groups of g adjacent quantized columns
     tile [0, Kq); the last one may be partial.  Codes are bit-packed into 32-bit
@@ -63,14 +67,16 @@ def layout(out_features: int, in_features: int, n_weak: int, bits: int, group_si
     oc, ic, k, g = int(out_features), int(in_features), int(n_weak), int(group_size)
     if oc <= 0 or ic <= 0 or g <= 0 or not (0 <= k <= ic):
         raise ValueError("bad shape")
+    if dense and bits != 3:
+        raise ValueError("the dense layout is defined for 3-bit codes only")
     per = 8 if bits == 4 else 10
     kq = ic - k
     n_groups = -(-kq // g)
-    words = -(-kq // per)
+    words = -(-(3 * kq) // 32) if dense else -(-kq // per)
     stride = -(-words // 16) * 16
     gstride = -(-n_groups // 8) * 8
     return {
-        "kq": kq, "n_groups": n_groups, "codes_per_word": per,
+        "kq": kq, "n_groups": n_groups, "codes_per_word": 32.0 / 3.0 if dense else per,
         "words_per_row": words, "row_stride_words": stride, "group_stride": gstride,
         "qweight_bytes": oc * stride * 4,
         "scales_bytes": oc * gstride * 2,
@@ -109,6 +115,36 @@ def unpack_codes(qweight: np.ndarray, kq: int, bits: int) -> np.ndarray:
     for r0 in range(0, oc, 1024):          # row blocks only bound the temporary's size
         blk = qweight[r0:r0 + 1024]
         out[r0:r0 + 1024] = ((blk[:, word_of] >> shift_of[None, :]) & mask).astype(np.uint8)
+    return out
+
+
+def pack_codes_dense3(codes: np.ndarray, row_stride_words: int) -> np.ndarray:
+    """Dense 3-bit layout: codes uint8 [OC][Kq] -> uint32 [OC][row_stride_words].
+
+    A row is one little-endian bit string: code j occupies bits 3j, 3j+1, 3j+2 of the row
+    (lowest bit of the code first), bit b of the row is bit b % 32 of word b // 32.  32 codes
+    fill exactly 3 words; a code may straddle two words.  Bits past 3 Kq are zero.
+    [Tab. 5: the 3-bit model sizes correspond to 3.0 bits per quantized weight.]
+    """
+    codes = np.asarray(codes, dtype=np.uint8)
+    oc, kq = codes.shape
+    if kq and int(codes.max()) >= 8:
+        raise ValueError("code out of range")
+    bits = np.zeros((oc, row_stride_words * 32), dtype=np.uint8)
+    for b in range(3):
+        bits[:, b:3 * kq:3] = (codes >> b) & 1
+    by = np.packbits(bits, axis=1, bitorder="little")            # byte i = bits 8i .. 8i+7
+    return np.ascontiguousarray(by).view("<u4").astype(np.uint32).reshape(oc, row_stride_words)
+
+
+def unpack_codes_dense3(qweight: np.ndarray, kq: int) -> np.ndarray:
+    """Inverse of pack_codes_dense3: uint32 [OC][stride] -> uint8 [OC][Kq]."""
+    qweight = np.ascontiguousarray(np.asarray(qweight, dtype=np.uint32)).astype("<u4")
+    oc = qweight.shape[0]
+    out = np.zeros((oc, kq), dtype=np.uint8)
+    for r0 in range(0, oc, 1024):          # row blocks only bound the temporary's size
+        bits = np.unpackbits(qweight[r0:r0 + 1024].view(np.uint8), axis=1, bitorder="little")[:, :3 * kq]
+        out[r0:r0 + 1024] = bits[:, 0::3] | (bits[:, 1::3] << 1) | (bits[:, 2::3] << 2)
     return out
 
 
@@ -382,7 +418,8 @@ def round_fp16(a: np.ndarray) -> np.ndarray:
 # single outputs one by one from the packed arrays: unpack the row (or column),
 # dequantize it, take the dot product.
 def _row(qweight, scales, zeros, weak, o, kq, bits, group_size):
-    codes = unpack_codes(qweight[o:o + 1], kq, bits)
+    # bits == "3d" names the dense 3-bit layout
+    codes = unpack_codes_dense3(qweight[o:o + 1], kq) if bits == "3d" else unpack_codes(qweight[o:o + 1], kq, bits)
     return dequantize(codes, scales[o:o + 1], zeros[o:o + 1], weak[o:o + 1], group_size)[0]
 
 
@@ -399,14 +436,23 @@ def fwd_samples(qweight, scales, zeros, weak, kq, bits, group_size, x, pairs):
 
 def bwd_dx_samples(qweight, scales, zeros, weak, kq, bits, group_size, dy, pairs):
     """dX[m, c] for each (m, c) in pairs."""
-    per = 8 if bits == 4 else 10
-    mask = (1 << bits) - 1
+    dense = bits == "3d"
+    if not dense:
+        per = 8 if bits == 4 else 10
+        mask = (1 << bits) - 1
     out = np.empty(len(pairs), dtype=np.float64)
     cols = {}
     for i, (m, c) in enumerate(pairs):
         if c not in cols:
             if c < kq:
-                q = (np.asarray(qweight[:, c // per]).astype(np.uint32) >> np.uint32(bits * (c % per))) & np.uint32(mask)
+                if dense:   # the three bits 3c .. 3c+2 of the row's bit string
+                    w0, sh = (3 * c) // 32, (3 * c) % 32
+                    two = np.asarray(qweight[:, w0]).astype(np.uint64)
+                    if sh > 29:
+                        two = two | (np.asarray(qweight[:, w0 + 1]).astype(np.uint64) << np.uint64(32))
+                    q = (two >> np.uint64(sh)) & np.uint64(7)
+                else:
+                    q = (np.asarray(qweight[:, c // per]).astype(np.uint32) >> np.uint32(bits * (c % per))) & np.uint32(mask)
                 gi = c // group_size
                 cols[c] = np.asarray(scales[:, gi]).astype(np.float64) * (
                     q.astype(np.float64) - np.asarray(zeros[:, gi]).astype(np.float64))
