@@ -44,6 +44,17 @@ typedef enum {
     QEFT_ERR_HIP = -7          /* the HIP runtime reported an error at launch                  */
 } qeft_status;
 
+/* How the codes of a row are laid out in its 32-bit words.
+ *   QEFT_LAYOUT_CANONICAL  whole codes per word: 8 four-bit or 10 three-bit codes (bits 30..31 zero).
+ *   QEFT_LAYOUT_DENSE3     3-bit only: the row is one bit string, code j at bits 3j .. 3j+2 of the row
+ *                          (bit b of the row = bit b % 32 of word b / 32), 32 codes in 3 words, codes may
+ *                          straddle words: 3.0 bits per quantized weight, the storage that the 3-bit model
+ *                          sizes of the paper's Tab. 5 correspond to.  Every entry point takes either layout
+ *                          (decode, M <= 16: a kernel of its own when the padded row holds whole groups, i.e.
+ *                          12 * G <= row_stride_words, which every Kq that is a multiple of 128 satisfies;
+ *                          larger M and the backward pass: the general kernels, as for all 3-bit layers). */
+enum { QEFT_LAYOUT_CANONICAL = 0, QEFT_LAYOUT_DENSE3 = 1 };
+
 /* Description of one layer (plain data, passed by pointer, host memory). */
 typedef struct {
     int32_t out_features; /* OC                                                     */
@@ -51,14 +62,14 @@ typedef struct {
     int32_t n_weak;       /* k, number of fp16 weak input channels, 0 <= k <= IC    */
     int32_t bits;         /* 4 or 3                                                 */
     int32_t group_size;   /* g, quantized columns sharing one (scale, zero) pair    */
-    int32_t layout;       /* 0 = canonical (the only layout defined so far)         */
+    int32_t layout;       /* QEFT_LAYOUT_CANONICAL, or QEFT_LAYOUT_DENSE3 (bits == 3 only) */
 } qeft_desc_t;
 
 /* Sizes derived from a description (host memory). */
 typedef struct {
     int64_t kq;               /* IC - k                                              */
     int64_t n_groups;         /* G = ceil(Kq / g)                                    */
-    int64_t words_per_row;    /* ceil(Kq / 8) for 4-bit, ceil(Kq / 10) for 3-bit     */
+    int64_t words_per_row;    /* ceil(Kq / 8) for 4-bit, ceil(Kq / 10) for 3-bit, ceil(3 Kq / 32) dense 3-bit */
     int64_t row_stride_words; /* words_per_row rounded up to a multiple of 16 (64 B) */
     int64_t group_stride;     /* G rounded up to a multiple of 8: row pitch of scales/zeros */
     size_t qweight_bytes;     /* OC * row_stride_words * 4                           */

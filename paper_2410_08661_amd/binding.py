@@ -20,6 +20,7 @@ QEFT_ERR_NULL, QEFT_ERR_SHAPE, QEFT_ERR_BITS, QEFT_ERR_ALIGN = -1, -2, -3, -4
 QEFT_ERR_WORKSPACE, QEFT_ERR_UNSUPPORTED, QEFT_ERR_HIP = -5, -6, -7
 QEFT_OP_FWD, QEFT_OP_BWD_DX, QEFT_OP_WEAK_GRAD, QEFT_OP_FWD_IRREGULAR, QEFT_OP_BWD_DX_IRREGULAR = 0, 1, 2, 3, 4
 QEFT_DTYPE_F16, QEFT_DTYPE_F32 = 0, 1
+QEFT_LAYOUT_CANONICAL, QEFT_LAYOUT_DENSE3 = 0, 1
 
 
 class qeft_desc_t(C.Structure):

@@ -14,7 +14,7 @@ int check_desc(const qeft_desc_t* d) {
     if (d->out_features <= 0 || d->in_features <= 0 || d->group_size <= 0 || d->n_weak < 0 ||
         d->n_weak > d->in_features)
         return QEFT_ERR_SHAPE;
-    if (d->layout != 0) return QEFT_ERR_UNSUPPORTED;
+    if (d->layout != QEFT_LAYOUT_CANONICAL && !(d->layout == QEFT_LAYOUT_DENSE3 && d->bits == 3)) return QEFT_ERR_UNSUPPORTED;
     return QEFT_OK;
 }
 
@@ -22,7 +22,7 @@ void fill_layout(const qeft_desc_t* d, qeft_layout_t* o) {
     const int64_t per = (d->bits == 4) ? 8 : 10;
     o->kq = (int64_t)d->in_features - d->n_weak;
     o->n_groups = (o->kq + d->group_size - 1) / d->group_size;
-    o->words_per_row = (o->kq + per - 1) / per;
+    o->words_per_row = d->layout == QEFT_LAYOUT_DENSE3 ? (3 * o->kq + 31) / 32 : (o->kq + per - 1) / per;
     o->row_stride_words = (o->words_per_row + 15) / 16 * 16;
     o->qweight_bytes = (size_t)d->out_features * (size_t)o->row_stride_words * 4u;
     o->group_stride = (o->n_groups + 7) / 8 * 8;
@@ -47,6 +47,7 @@ int make_layer(const qeft_desc_t* d, const qeft_weight_t* w, Layer* L) {
     L->k = d->n_weak;
     L->bits = d->bits;
     L->g = d->group_size;
+    L->dense = d->layout == QEFT_LAYOUT_DENSE3;
     L->kq = (int)lay.kq;
     L->ng = (int)lay.n_groups;
     L->gs = (int)lay.group_stride;

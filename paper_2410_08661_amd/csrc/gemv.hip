@@ -686,7 +686,11 @@ hipError_t launch_rows(const Layer& L, const __half* X, int M, int64_t ldx, __ha
 //     weights, and shared by the R tiles of a wave; octets past Kq are zeroed.
 // LDS: (z, s) fp16 pairs [groups][16 R rows] | reduction slots
 // =============================================================================================
-template <int R, int D, int NSZ>
+// DENSE: the dense 3-bit layout (a row is one bit string, 32 codes in 3 words).  A lane then takes
+// 12 bytes = 32 codes = four fragments per step, a step of the four k-slot lanes covers exactly one group
+// of 128 columns (so a lane's fragments all use one (zero-point, scale) pair), and pair P of a lane sits at
+// bits 6 P of its 96: two of the sixteen pairs straddle words and take one funnel shift more.
+template <int R, int D, int NSZ, bool DENSE>
 __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                       __half* __restrict__ Y, int64_t ldy, int ks_magic, int nsteps) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -713,21 +717,33 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
         const int g0 = min(32 * (cc >> 1) + 8 * kb, (int)L.gs - 8);
         pv[i] = load16(((cc & 1) ? L.zeros : L.scales) + (size_t)o * L.gs + g0);
     }
+    constexpr int NF = DENSE ? 4 : 5;                 // fragments (octets of columns) per lane and step
+    constexpr int STEP_COLS = 32 * NF, LANE_COLS = 8 * NF;
+    constexpr int STEP_BYTES = DENSE ? 48 : 64, LANE_BYTES = DENSE ? 12 : 16;
     const unsigned char* wrow[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int o = min(row0 + 16 * r + n, L.oc - 1);
-        wrow[r] = reinterpret_cast<const unsigned char*>(L.qweight + (size_t)o * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+        wrow[r] = reinterpret_cast<const unsigned char*>(L.qweight + (size_t)o * L.stride);
     }
+    const int woff0 = STEP_BYTES * q_beg + LANE_BYTES * kb;
+    const int woff_max = 4 * L.stride - LANE_BYTES;   // never reached: the host admits only rows that hold whole steps
     const __half* xrow = X + (size_t)min(n, M - 1) * ldx;
-    const int col0 = 160 * q_beg + 40 * kb;
-    u4 xq[D][5], wq[D][R];
+    const int col0 = STEP_COLS * q_beg + LANE_COLS * kb;
+    u4 xq[D][NF], wq[D][R];
     auto load_step = [&](int d, int j) {   // straight-line: the step index is clamped, never tested
         const int jc = min(j, j_last);
 #pragma unroll
-        for (int s = 0; s < 5; ++s) xq[d][s] = load16(xrow + min(col0 + 160 * jc + 8 * s, L.kq - 8));
+        for (int s = 0; s < NF; ++s) xq[d][s] = load16(xrow + min(col0 + STEP_COLS * jc + 8 * s, L.kq - 8));
 #pragma unroll
-        for (int r = 0; r < R; ++r) wq[d][r] = load16(wrow[r] + 64 * (size_t)jc);
+        for (int r = 0; r < R; ++r) {
+            if (DENSE) {
+                const uint32_t* p = reinterpret_cast<const uint32_t*>(wrow[r] + min(woff0 + STEP_BYTES * jc, woff_max));
+                wq[d][r] = u4{p[0], p[1], p[2], 0u};
+            } else {
+                wq[d][r] = load16(wrow[r] + woff0 + STEP_BYTES * (size_t)jc);
+            }
+        }
     };
 #pragma unroll
     for (int d = 0; d < D; ++d) load_step(d, d);
@@ -762,7 +778,7 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
     uint32_t zs_lo[R], zs_hi[R];
     const uint32_t* szl = sz32 + n;
     auto read_zs = [&](int j) {
-        const int g = min((col0 + 160 * j) >> 7, nq - 1), gh = min(g + 1, nq - 1);
+        const int g = min((col0 + STEP_COLS * j) >> 7, nq - 1), gh = min(g + 1, nq - 1);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             zs_lo[r] = szl[g * (16 * R) + 16 * r];
@@ -771,8 +787,8 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
     };
     read_zs(0);
     auto step = [&](int d, int j) {
-        const int col = col0 + 160 * j;
-        const int split = ((col >> 7) + 1) << 7;   // first column of the next group
+        const int col = col0 + STEP_COLS * j;
+        const int split = ((col >> 7) + 1) << 7;   // first column of the next group (dense: past the lane's columns)
         h2 zsl[R], zsh[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -784,9 +800,9 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
 #pragma unroll
         for (int r = 0; r < R; ++r) ya[r] = yb[r] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int s = 0; s < 5; ++s) {
+        for (int s = 0; s < NF; ++s) {
             const u4 xa = (col + 8 * s < L.kq && j < nj) ? xq[d][s] : zero4;
-            const bool hi = col + 8 * s >= split;
+            const bool hi = !DENSE && col + 8 * s >= split;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const h2 zs = hi ? zsh[r] : zsl[r];
@@ -795,7 +811,14 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     const int P = 4 * s + p;   // pair P of the lane's 20: word P / 5, codes 2 (P % 5) and the next
-                    const uint32_t six = __builtin_amdgcn_ubfe(wq[d][r][P / 5], 6 * (P % 5), 6);
+                    uint32_t six;
+                    if (DENSE) {               // pair P of the lane's 16 at bits 6 P .. 6 P + 5 of its three words
+                        const int wi = (6 * P) >> 5, sh = (6 * P) & 31;
+                        six = sh <= 26 ? __builtin_amdgcn_ubfe(wq[d][r][wi], sh, 6)
+                                       : __builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(wq[d][r][(wi + 1) & 3], wq[d][r][wi], sh), 0, 6);
+                    } else {
+                        six = __builtin_amdgcn_ubfe(wq[d][r][P / 5], 6 * (P % 5), 6);
+                    }
                     const uint32_t codes = ((six * 0x2001u) & cmask) | cmagic;   // fp16 pair (1024 + q0, 1024 + q1)
                     b[p] = __builtin_bit_cast(uint32_t, ((__builtin_bit_cast(h2, codes) - k1024) - z2) * s2);
                 }
@@ -827,8 +850,10 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
 
 // K-split waves of the 3-bit kernel: four (one per SIMD; measured best for 4096 ... 11008 rows), more only
 // when the (zero-point, scale) table would otherwise take more than 4 requests per wave
+int w3_steps(const Layer& L) { return L.dense ? L.ng : ceil_div(L.words, 16); }   // dense: one step per group
+
 int w3_split(const Layer& L, int R) {
-    const int nsteps = ceil_div(L.words, 16), nchunks = 2 * ceil_div(L.ng, 32) * R;
+    const int nsteps = w3_steps(L), nchunks = 2 * ceil_div(L.ng, 32) * R;
     int ks = nsteps < 4 ? (nsteps < 1 ? 1 : nsteps) : 4;
     while (ks < 8 && ks < nsteps && ceil_div(nchunks, ks) > 4) ++ks;
     return ks;
@@ -837,16 +862,18 @@ int w3_split(const Layer& L, int R) {
 template <int R>
 hipError_t launch_w3(const Layer& L, const __half* X, int M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int tiles = ceil_div(L.oc, 16 * R);
-    const int nsteps = ceil_div(L.words, 16);
+    const int nsteps = w3_steps(L);
     const int ks = w3_split(L, R);
     const int nchunks = 2 * ceil_div(L.ng, 32) * R;
     const int nsz = ceil_div(nchunks, ks);
     const size_t table = (size_t)L.ng * 16 * R * 4, red = (size_t)(ks > 1 ? ks - 1 : 1) * R * 4 * 64 * sizeof(float);
     const size_t lds_bytes = table > red ? table : red;
     using Kern = void (*)(Layer, const __half*, int, int64_t, __half*, int64_t, int, int);
-    static const Kern table_k[4] = {gemv_w3_kernel<R, 4, 1>, gemv_w3_kernel<R, 4, 2>, gemv_w3_kernel<R, 4, 3>, gemv_w3_kernel<R, 4, 4>};
+    static const Kern table_k[2][4] = {
+        {gemv_w3_kernel<R, 4, 1, false>, gemv_w3_kernel<R, 4, 2, false>, gemv_w3_kernel<R, 4, 3, false>, gemv_w3_kernel<R, 4, 4, false>},
+        {gemv_w3_kernel<R, 4, 1, true>, gemv_w3_kernel<R, 4, 2, true>, gemv_w3_kernel<R, 4, 3, true>, gemv_w3_kernel<R, 4, 4, true>}};
     if (nsz > 4 || lds_bytes > 64 * 1024) return hipErrorInvalidValue;   // not reached for the shapes gemv_supported admits
-    table_k[nsz - 1]<<<tiles, 64 * ks, lds_bytes, s>>>(L, X, M, ldx, Y, ldy, ceil_div(65536, ks), nsteps);
+    table_k[L.dense ? 1 : 0][nsz - 1]<<<tiles, 64 * ks, lds_bytes, s>>>(L, X, M, ldx, Y, ldy, ceil_div(65536, ks), nsteps);
     return hipGetLastError();
 }
 
@@ -856,6 +883,9 @@ constexpr int SMALL_LDS_LIMIT = 144 * 1024;   // of the 160 KB a CU has
 
 // the 3-bit kernel: its (zero-point, scale) table must fit in LDS and be loadable in 4 requests per wave
 static bool w3_fits(const Layer& L) {
+    // dense layout: a lane reads 12 bytes per group of its row, so whole groups must fit the padded row
+    // (always true when Kq is a multiple of 128: 12 words per group)
+    if (L.dense && 12 * L.ng > L.stride) return false;
     for (int R = 1; R <= 2; ++R) {
         const int ks = w3_split(L, R);
         if (ceil_div(2 * ceil_div(L.ng, 32) * R, ks) > 4 || (size_t)L.ng * 16 * R * 4 > 64 * 1024) return false;

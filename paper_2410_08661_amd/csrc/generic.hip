@@ -11,9 +11,7 @@ constexpr int MB = 8;  // rows of X / dY handled per thread block
 // One element of the mixed weight (Sec. 3.1): s * (q - z) for j < Kq, the fp16 weak block otherwise.
 __device__ __forceinline__ float weight_at(const Layer& L, int o, int j) {
     if (j >= L.kq) return __half2float(L.weak[(size_t)o * L.k + (j - L.kq)]);
-    const int per = (L.bits == 4) ? 8 : 10;
-    const uint32_t word = L.qweight[(size_t)o * L.stride + j / per];
-    const uint32_t code = (word >> (L.bits * (j % per))) & ((1u << L.bits) - 1u);
+    const uint32_t code = code_at(L, L.qweight + (size_t)o * L.stride, j);
     const size_t gi = (size_t)o * L.gs + j / L.g;
     return __half2float(L.scales[gi]) * ((float)code - __half2float(L.zeros[gi]));
 }

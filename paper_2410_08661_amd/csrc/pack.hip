@@ -57,6 +57,30 @@ __global__ __launch_bounds__(256) void rtn_params_kernel(Layer L, const __half* 
     }
 }
 
+// Word wd of a row from the codes of its columns (code(j) is asked for j < Kq only).  Whole codes per word:
+// columns per * wd .. + per - 1 at bits b i.  Dense 3-bit: every code whose bits 3j .. 3j+2 meet bits
+// 32 wd .. 32 wd + 31 of the row, shifted to its place (the two codes at the ends may lie partly outside).
+template <class F>
+__device__ __forceinline__ uint32_t build_word(const Layer& L, int wd, F code) {
+    uint32_t word = 0;
+    if (L.dense) {
+        const int j0 = (32 * wd) / 3, j1 = (32 * wd + 31) / 3;
+        for (int j = j0; j <= j1; ++j) {
+            if (j >= L.kq) break;
+            const int sh = 3 * j - 32 * wd;   // -2 .. 31
+            const uint32_t c = code(j);
+            word |= sh >= 0 ? c << sh : c >> -sh;
+        }
+        return word;
+    }
+    const int per = (L.bits == 4) ? 8 : 10;
+    for (int i = 0; i < per; ++i) {
+        const int j = wd * per + i;
+        if (j < L.kq) word |= code(j) << (L.bits * i);
+    }
+    return word;
+}
+
 // ---- step 2: one thread per 32-bit word: quantize its 8 / 10 columns and pack ------------
 __global__ __launch_bounds__(256) void rtn_words_kernel(Layer L, const __half* __restrict__ W, int64_t ldw,
                                                         const __half* __restrict__ scales,
@@ -64,22 +88,15 @@ __global__ __launch_bounds__(256) void rtn_words_kernel(Layer L, const __half* _
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)L.oc * L.stride) return;
     const int o = (int)(idx / L.stride), wd = (int)(idx % L.stride);
-    const int per = (L.bits == 4) ? 8 : 10;
     const float qmax = (float)((1 << L.bits) - 1);
-    uint32_t word = 0;
-    for (int i = 0; i < per; ++i) {
-        const int j = wd * per + i;
-        if (j < L.kq) {
-            const size_t gi = (size_t)o * L.gs + j / L.g;
-            const float s = __half2float(scales[gi]);
-            const float z = __half2float(zeros[gi]);
-            const float v = __half2float(W[(size_t)o * ldw + j]);
-            float q = rintf(__fdiv_rn(v, s)) + z;
-            q = fminf(fmaxf(q, 0.f), qmax);
-            word |= (uint32_t)q << (L.bits * i);
-        }
-    }
-    qweight[idx] = word;
+    qweight[idx] = build_word(L, wd, [&](int j) {
+        const size_t gi = (size_t)o * L.gs + j / L.g;
+        const float s = __half2float(scales[gi]);
+        const float z = __half2float(zeros[gi]);
+        const float v = __half2float(W[(size_t)o * ldw + j]);
+        const float q = rintf(__fdiv_rn(v, s)) + z;
+        return (uint32_t)fminf(fmaxf(q, 0.f), qmax);
+    });
 }
 
 // ---- both steps in one pass for 4-bit codes and groups of 128 -----------------------------------
@@ -252,23 +269,15 @@ __global__ __launch_bounds__(256) void pack_words_kernel(Layer L, const uint8_t*
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)L.oc * L.stride) return;
     const int o = (int)(idx / L.stride), wd = (int)(idx % L.stride);
-    const int per = (L.bits == 4) ? 8 : 10;
     const uint32_t mask = (1u << L.bits) - 1u;
-    uint32_t word = 0;
-    for (int i = 0; i < per; ++i) {
-        const int j = wd * per + i;
-        if (j < L.kq) word |= ((uint32_t)codes[(size_t)o * L.kq + j] & mask) << (L.bits * i);
-    }
-    qweight[idx] = word;
+    qweight[idx] = build_word(L, wd, [&](int j) { return (uint32_t)codes[(size_t)o * L.kq + j] & mask; });
 }
 
 __global__ __launch_bounds__(256) void unpack_codes_kernel(Layer L, uint8_t* __restrict__ codes) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (int64_t)L.oc * L.kq) return;
     const int o = (int)(idx / L.kq), j = (int)(idx % L.kq);
-    const int per = (L.bits == 4) ? 8 : 10;
-    const uint32_t word = L.qweight[(size_t)o * L.stride + j / per];
-    codes[idx] = (uint8_t)((word >> (L.bits * (j % per))) & ((1u << L.bits) - 1u));
+    codes[idx] = (uint8_t)code_at(L, L.qweight + (size_t)o * L.stride, j);
 }
 
 // compact [OC][G] parameters into the padded [OC][group_stride] arrays (padding zero)

@@ -12,6 +12,7 @@ namespace qeft {
 // Everything a kernel needs to know about one stored layer (see qeft.h for the format).
 struct Layer {
     int oc, ic, k, bits, g;
+    int dense;     // 1: dense 3-bit layout (a row's codes as one bit string), 0: whole codes per word
     int kq;        // ic - k
     int ng;        // groups per row
     int gs;        // row pitch of scales / zeros in elements (ng rounded up to a multiple of 8)
@@ -24,6 +25,18 @@ struct Layer {
 };
 
 inline int ceil_div(int64_t a, int64_t b) { return (int)((a + b - 1) / b); }
+
+// Code of column j of a row of packed words, either layout (the plain definition: conversion and fallback kernels).
+__device__ __forceinline__ uint32_t code_at(const Layer& L, const uint32_t* __restrict__ row, int j) {
+    if (L.dense) {
+        const int bit = 3 * j, w0 = bit >> 5, sh = bit & 31;
+        uint32_t v = row[w0] >> sh;
+        if (sh > 29) v |= row[w0 + 1] << (32 - sh);   // the code straddles two words (never the row's last one)
+        return v & 7u;
+    }
+    const int per = (L.bits == 4) ? 8 : 10;
+    return (row[j / per] >> (L.bits * (j % per))) & ((1u << L.bits) - 1u);
+}
 
 // ---- generic kernels: any shape, bits and alignment; plain loops (generic.hip) ------
 hipError_t fwd_generic(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s);

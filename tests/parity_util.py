@@ -30,18 +30,21 @@ def assert_close(actual, ref64, what=""):
 class HostLayer:
     """One layer as the oracle sees it (host arrays) plus its device twin."""
 
-    def __init__(self, oc, ic, k, bits, g, seed, quantizer="codes"):
+    def __init__(self, oc, ic, k, bits, g, seed, quantizer="codes", dense=False):
         self.oc, self.ic, self.k, self.bits, self.g = oc, ic, k, bits, g
-        self.lay = qo.layout(oc, ic, k, bits, g)
+        self.lay = qo.layout(oc, ic, k, bits, g, dense=dense)
         self.kq = self.lay["kq"]
-        self.desc = B.make_desc(oc, ic, k, bits, g)
+        self.desc = B.make_desc(oc, ic, k, bits, g, layout=B.QEFT_LAYOUT_DENSE3 if dense else B.QEFT_LAYOUT_CANONICAL)
         w = synth.make_weight(oc, ic, seed)
         if quantizer == "rtn":
             self.codes, self.scales, self.zeros, self.weak = qo.quantize_rtn(w, k, bits, g)
         else:
             self.codes, self.scales, self.zeros = synth.make_codes(oc, self.kq, self.lay["n_groups"], bits, seed)
             self.weak = np.ascontiguousarray(w[:, ic - k:])
-        self.qweight = qo.pack_codes(self.codes, bits, self.lay["row_stride_words"])
+        if dense:
+            self.qweight = qo.pack_codes_dense3(self.codes, self.lay["row_stride_words"])
+        else:
+            self.qweight = qo.pack_codes(self.codes, bits, self.lay["row_stride_words"])
         self._w64 = None
 
     @property

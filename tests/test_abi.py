@@ -58,6 +58,19 @@ def test_descriptor_validation():
     assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4, 0)), C.byref(lay)) == B.QEFT_ERR_SHAPE
     assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4, 128, 7)), C.byref(lay)) == B.QEFT_ERR_UNSUPPORTED
     assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4)), None) == B.QEFT_ERR_NULL
+    # the dense layout exists for 3-bit codes only
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 4, 128, B.QEFT_LAYOUT_DENSE3)), C.byref(lay)) == B.QEFT_ERR_UNSUPPORTED
+    assert B.raw.qeft_layout(C.byref(B.make_desc(8, 8, 0, 3, 128, B.QEFT_LAYOUT_DENSE3)), C.byref(lay)) == B.QEFT_OK
+
+
+@pytest.mark.parametrize("oc,ic,k", [(4096, 4096, 128), (13824, 5120, 128), (5120, 13824, 128), (33, 200, 24), (7, 11, 0)])
+def test_dense3_layout_matches_oracle(oc, ic, k):
+    lay = B.qeft_layout(B.make_desc(oc, ic, k, 3, 128, B.QEFT_LAYOUT_DENSE3))
+    ref = qo.layout(oc, ic, k, 3, 128, dense=True)
+    assert lay.kq == ref["kq"] and lay.n_groups == ref["n_groups"]
+    assert lay.words_per_row == ref["words_per_row"] == (3 * (ic - k) + 31) // 32
+    assert lay.row_stride_words == ref["row_stride_words"]
+    assert lay.qweight_bytes == ref["qweight_bytes"] and lay.scales_bytes == ref["scales_bytes"]
 
 
 def test_forward_and_backward_validation():

@@ -22,14 +22,20 @@ N_SAMPLES = 192
 
 class BigLayer:
     def __init__(self, oc, ic, k, bits, seed):
+        # bits "3d": 3-bit codes in the dense layout
+        dense = bits == "3d"
+        nbits = 3 if dense else bits
         self.oc, self.ic, self.k, self.bits, self.g = oc, ic, k, bits, 128
-        self.lay = qo.layout(oc, ic, k, bits, 128)
+        self.lay = qo.layout(oc, ic, k, nbits, 128, dense=dense)
         self.kq = self.lay["kq"]
-        codes, self.scales, self.zeros = synth.make_codes(oc, self.kq, self.lay["n_groups"], bits, seed)
-        self.qweight = qo.pack_codes(codes, bits, self.lay["row_stride_words"])
+        codes, self.scales, self.zeros = synth.make_codes(oc, self.kq, self.lay["n_groups"], nbits, seed)
+        if dense:
+            self.qweight = qo.pack_codes_dense3(codes, self.lay["row_stride_words"])
+        else:
+            self.qweight = qo.pack_codes(codes, bits, self.lay["row_stride_words"])
         del codes
         self.weak = (np.random.default_rng(seed).standard_normal((oc, k), dtype=np.float32) * 0.02).astype(np.float16)
-        self.desc = B.make_desc(oc, ic, k, bits, 128)
+        self.desc = B.make_desc(oc, ic, k, nbits, 128, layout=B.QEFT_LAYOUT_DENSE3 if dense else B.QEFT_LAYOUT_CANONICAL)
         w = B.Weight(self.desc)
         ng = self.lay["n_groups"]
         w.qweight.copy_(torch.from_numpy(self.qweight.view(np.int32)))
@@ -69,6 +75,7 @@ def _check(actual_t, pairs, ref, what):
 DECODE = [  # config, shapes, k, bits list, M list
     (2, synth.LLAMA_7B, 128, [4], [1, 8]),
     (3, synth.LLAMA_13B, 128, [3, 4], [1, 3, 5, 16]),
+    (3, synth.LLAMA_13B, 128, ["3d"], [1, 5, 16]),      # the dense 3-bit layout
     (5, synth.LLAMA_70B, 256, [4], [1, 4]),
 ]
 DECODE_CASES = [(cfg, si, s, k, b, Ms) for cfg, shapes, k, bl, Ms in DECODE for si, s in enumerate(shapes) for b in bl]
