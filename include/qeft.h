@@ -136,7 +136,12 @@ int qeft_pack_codes(const qeft_desc_t* desc, const uint8_t* codes, const void* s
 int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
                 void* scales, void* zeros, void* weak, void* stream);
 
-/* Bytes of device workspace an operation needs for M rows (0 if none). */
+/* Bytes of device workspace an operation can use for M rows (0 if none).  QEFT_OP_WEAK_GRAD and the
+ * irregular operations require theirs.  QEFT_OP_FWD / QEFT_OP_BWD_DX report OC * IC * 2 bytes for 3-bit layers
+ * at M > 16: with that workspace (16-byte aligned) the call dequantizes the layer once into it as fp16 and
+ * runs the tensor-core kernels on the copy - the paper's own training path, dequantize then a dense product
+ * (Sec. 4.3, App. A.2) - and without it (ws NULL) the slow general kernel; a workspace that is too small is
+ * QEFT_ERR_WORKSPACE.  The copy is rewritten by every call (the weak block may have changed). */
 size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
 
 /* Forward of the fused layer (Sec. 3.2.1): Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . weak^T in

@@ -192,9 +192,15 @@ def _workspace(desc, op, M, device):
 
 
 def qeft_linear_fwd(desc, w: Weight, X: torch.Tensor, Y: torch.Tensor | None = None, ws=None) -> torch.Tensor:
+    """ws: a uint8 device tensor of qeft_workspace_bytes(desc, QEFT_OP_FWD, M) bytes; None allocates one when the
+    operation can use it (3-bit layers at M > 16), False passes none (the library then runs its general kernel)."""
     M = X.shape[0]
     if Y is None:
         Y = _empty_rows(M, desc.out_features, torch.float16, X.device)
+    if ws is None:
+        ws, _ = _workspace(desc, QEFT_OP_FWD, M, X.device)
+    elif ws is False:
+        ws = None
     wst = w.c_struct()
     _check(raw.qeft_linear_fwd(C.byref(desc), C.byref(wst), _ptr(X), M, X.stride(0) if M else desc.in_features,
                                _ptr(Y), Y.stride(0) if M else desc.out_features, _ptr(ws),
@@ -235,6 +241,10 @@ def qeft_linear_bwd_dx(desc, w: Weight, dY: torch.Tensor, dX: torch.Tensor | Non
     M = dY.shape[0]
     if dX is None:
         dX = _empty_rows(M, desc.in_features, torch.float16, dY.device)
+    if ws is None:
+        ws, _ = _workspace(desc, QEFT_OP_BWD_DX, M, dY.device)
+    elif ws is False:
+        ws = None
     wst = w.c_struct()
     _check(raw.qeft_linear_bwd_dx(C.byref(desc), C.byref(wst), _ptr(dY), M, dY.stride(0) if M else desc.out_features,
                                   _ptr(dX), dX.stride(0) if M else desc.in_features, _ptr(ws),

@@ -71,6 +71,27 @@ int check_matrix(const void* p, int64_t M, int64_t ld, int64_t width) {
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? QEFT_OK : QEFT_ERR_HIP; }
 
+// 3-bit layers at GEMM sizes: the tiled kernels convert 4-bit codes only, so the layer is dequantized once
+// into a caller-provided fp16 [OC][IC] workspace and multiplied as a layer whose columns are all weak
+// (the paper's own training path: dequantize, then a dense product; Sec. 4.3 / App. A.2).
+bool dense_copy_applies(const Layer& L, int64_t M) {
+    return L.bits == 3 && L.kq > 0 && M > 16 && (L.ic % 8) == 0 && (L.oc % 8) == 0;
+}
+size_t dense_copy_bytes(const Layer& L) { return (size_t)L.oc * (size_t)L.ic * sizeof(__half); }
+Layer dense_copy_layer(const Layer& L, const void* ws) {
+    Layer D = L;
+    D.bits = 4;
+    D.dense = 0;
+    D.g = 128;
+    D.kq = 0;
+    D.ng = D.gs = D.words = D.stride = 0;
+    D.k = L.ic;
+    D.qweight = nullptr;
+    D.scales = D.zeros = nullptr;
+    D.weak = (const __half*)ws;
+    return D;
+}
+
 }  // namespace
 
 extern "C" {
@@ -131,13 +152,19 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
     if (op == QEFT_OP_WEAK_GRAD && weak_grad_mfma_supported(desc->out_features, desc->n_weak, M))
         return weak_grad_mfma_workspace(desc->out_features, desc->n_weak, M);
     if (op == QEFT_OP_FWD_IRREGULAR || op == QEFT_OP_BWD_DX_IRREGULAR) return irregular_workspace(desc->in_features, M);
+    if (op == QEFT_OP_FWD || op == QEFT_OP_BWD_DX) {
+        Layer L = {};
+        L.bits = desc->bits;
+        L.oc = desc->out_features;
+        L.ic = desc->in_features;
+        L.kq = desc->in_features - desc->n_weak;
+        if (dense_copy_applies(L, M)) return dense_copy_bytes(L);
+    }
     return 0;
 }
 
 int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* X, int64_t M, int64_t ldx,
                     void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream) {
-    (void)ws;
-    (void)ws_bytes;
     Layer L;
     int st = make_layer(desc, w, &L);
     if (st != QEFT_OK) return st;
@@ -150,6 +177,16 @@ int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
     const __half* x = (const __half*)X;
     __half* y = (__half*)Y;
     if (M > 16 && gemm_fwd_supported(L, M)) return hip_status(gemm_fwd(L, x, M, ldx, y, ldy, s));
+    if (ws && dense_copy_applies(L, M)) {
+        if (!aligned16(ws)) return QEFT_ERR_ALIGN;
+        if (ws_bytes < dense_copy_bytes(L)) return QEFT_ERR_WORKSPACE;
+        const Layer D = dense_copy_layer(L, ws);
+        if (gemm_fwd_supported(D, M)) {
+            hipError_t e = dequantize_fp16(L, (__half*)ws, s);
+            if (e != hipSuccess) return QEFT_ERR_HIP;
+            return hip_status(gemm_fwd(D, x, M, ldx, y, ldy, s));
+        }
+    }
     if (gemv_supported(L, M, ldx)) {
         // the matrix-vector kernel takes up to 16 rows per pass
         for (int64_t m0 = 0; m0 < M; m0 += 16) {
@@ -195,8 +232,6 @@ int qeft_linear_fwd_group(int n, const qeft_desc_t* descs, const qeft_weight_t* 
 
 int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M, int64_t lddy,
                        void* dX, int64_t lddx, void* ws, size_t ws_bytes, void* stream) {
-    (void)ws;
-    (void)ws_bytes;
     Layer L;
     int st = make_layer(desc, w, &L);
     if (st != QEFT_OK) return st;
@@ -207,6 +242,16 @@ int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const vo
     if (M == 0) return QEFT_OK;
     hipStream_t s = (hipStream_t)stream;
     if (gemm_dx_supported(L, M)) return hip_status(gemm_dx(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+    if (ws && dense_copy_applies(L, M)) {
+        if (!aligned16(ws)) return QEFT_ERR_ALIGN;
+        if (ws_bytes < dense_copy_bytes(L)) return QEFT_ERR_WORKSPACE;
+        const Layer D = dense_copy_layer(L, ws);
+        if (gemm_dx_supported(D, M)) {
+            hipError_t e = dequantize_fp16(L, (__half*)ws, s);
+            if (e != hipSuccess) return QEFT_ERR_HIP;
+            return hip_status(gemm_dx(D, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+        }
+    }
     return hip_status(bwd_dx_generic(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
 }
 

@@ -280,6 +280,27 @@ __global__ __launch_bounds__(256) void unpack_codes_kernel(Layer L, uint8_t* __r
     codes[idx] = (uint8_t)code_at(L, L.qweight + (size_t)o * L.stride, j);
 }
 
+// One thread per 8 columns of a row of the mixed weight: 16 bytes out.
+__global__ __launch_bounds__(256) void dequantize_kernel(Layer L, __half* __restrict__ out) {
+    const int chunks = L.ic >> 3;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)L.oc * chunks) return;
+    const int o = (int)(idx / chunks), j0 = 8 * (int)(idx % chunks);
+    const uint32_t* row = L.qweight + (size_t)o * L.stride;
+    __half v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int j = j0 + e;
+        if (j < L.kq) {
+            const size_t gi = (size_t)o * L.gs + j / L.g;
+            v[e] = __float2half_rn(__half2float(L.scales[gi]) * ((float)code_at(L, row, j) - __half2float(L.zeros[gi])));
+        } else {
+            v[e] = L.weak[(size_t)o * L.k + (j - L.kq)];
+        }
+    }
+    *reinterpret_cast<uint4*>(out + (size_t)o * L.ic + j0) = *reinterpret_cast<const uint4*>(v);
+}
+
 // compact [OC][G] parameters into the padded [OC][group_stride] arrays (padding zero)
 __global__ __launch_bounds__(256) void pad_groups_kernel(Layer L, const __half* __restrict__ s_in,
                                                          const __half* __restrict__ z_in, __half* __restrict__ s_out,
@@ -345,6 +366,12 @@ hipError_t pack_codes(const Layer& L, const uint8_t* codes, const __half* scales
         pad_groups_kernel<<<ceil_div((int64_t)L.oc * L.gs, 256), 256, 0, s>>>(L, scales_in, zeros_in, scales, zeros);
     }
     copy2d(weak_in, L.k, weak, L.k, L.oc, L.k, s);
+    return hipGetLastError();
+}
+
+hipError_t dequantize_fp16(const Layer& L, __half* out, hipStream_t s) {
+    const int64_t n = (int64_t)L.oc * (L.ic >> 3);
+    dequantize_kernel<<<ceil_div(n, 256), 256, 0, s>>>(L, out);
     return hipGetLastError();
 }
 

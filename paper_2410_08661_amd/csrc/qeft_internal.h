@@ -69,6 +69,8 @@ hipError_t pack_search(const Layer& L, const __half* W, int64_t ldw, int n_grid,
 hipError_t pack_codes(const Layer& L, const uint8_t* codes, const __half* scales_in, const __half* zeros_in,
                       const __half* weak_in, uint32_t* qweight, __half* scales, __half* zeros, __half* weak, hipStream_t s);
 hipError_t unpack(const Layer& L, uint8_t* codes, __half* scales, __half* zeros, __half* weak, hipStream_t s);
+// The whole mixed weight as fp16 [OC][IC] (IC a multiple of 8): s (q - z) rounded once, then the weak block.
+hipError_t dequantize_fp16(const Layer& L, __half* out, hipStream_t s);
 
 // ---- decode path: fused dequant matrix-vector product for M <= 16 (gemv.hip) -------------
 bool gemv_supported(const Layer& L, int64_t M, int64_t ldx);

@@ -459,6 +459,35 @@ def test_weak_grad_parity(oc, ic, k, bits, g, m, compact):
     assert_close(dw16.cpu().numpy(), ref, f"dW overwrite {oc}x{k}")
 
 
+@pytest.mark.parametrize("dense", [False, True])
+@pytest.mark.parametrize("oc,ic,k,m", [(320, 1280 + 128, 128, 300), (264, 512 + 64, 64, 40)])
+def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
+    """3-bit layers at M > 16: dequantized once into the workspace, then the tensor-core kernels; the same
+    results (to the bar) without a workspace, from the general kernel."""
+    h = HostLayer(oc, ic, k, 3, 128, seed=oc + ic, dense=dense)
+    w = h.to_device()
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m)
+    assert n == oc * ic * 2 == B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    assert B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, 16) == 0
+    x = synth.make_activations(m, ic, k, seed=m)
+    dy = synth.make_grad_output(m, oc, seed=m)
+    xd, dyd = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+    ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
+    for use_ws in (ws[:n], False):
+        y = B.qeft_linear_fwd(h.desc, w, xd, ws=use_ws)
+        dx = B.qeft_linear_bwd_dx(h.desc, w, dyd, ws=use_ws)
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), f"3-bit fwd M{m} ws={use_ws is not False}")
+        assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), f"3-bit dX M{m} ws={use_ws is not False}")
+    assert torch.all(ws[n:] == 0x7f)                       # nothing written past the stated size
+    # the copy is the dequantized layer, rounded once to fp16
+    copy = ws[:n].view(torch.float16).reshape(oc, ic).cpu().numpy()
+    assert np.array_equal(copy, h.w64.astype(np.float32).astype(np.float16)) or \
+        np.max(np.abs(copy.astype(np.float64) - h.w64)) <= np.max(np.abs(h.w64)) * 2.0 ** -11
+    with pytest.raises(B.QeftError):
+        B.qeft_linear_fwd(h.desc, w, xd, ws=ws[:n - 16])   # too small
+
+
 def test_backward_uses_current_weak_values():
     """dX goes through whatever the weak block holds now (it is the trainable tensor)."""
     h = HostLayer(128, 256 + 64, 64, 4, 128, seed=2)
