@@ -210,6 +210,10 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const int nq = L.kq / BK;
+    // weak stages: whole 64-column stages take the direct path below (A fragments straight from the fp16
+    // block), a ragged block the LDS-staged stages at the end
+    const int nwf = (L.k % BK == 0) ? L.k / BK : 0;
+    const int ns = nq + nwf;
     const RegConsts cst = make_reg_consts();
     using lds_u4 = __attribute__((address_space(3))) u4;
     using lds_h8 = __attribute__((address_space(3))) h8;
@@ -223,6 +227,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const char* st_ = reinterpret_cast<const char*>(L.scales + (size_t)oc0 * L.gs);
     const char* zt = reinterpret_cast<const char*>(L.zeros + (size_t)oc0 * L.gs);
     const char* xt = reinterpret_cast<const char*>(X + (size_t)m0 * ldx);
+    const char* wk = reinterpret_cast<const char*>(L.weak + (size_t)oc0 * L.k);
     uint32_t aoff[2], szoff[2], xoff[8];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -293,7 +298,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
 
     // weak block operands: chunk u of this thread is tile row xr + 32 u, 16-byte column xc of the stage
     // (branch-free fetches: columns past k read the row's last 8 and are zeroed when stored)
-    const int nw = (L.k + BK - 1) / BK;
+    const int nw = nwf ? 0 : (L.k + BK - 1) / BK;
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
     u4 wa[8], wb[8];
     auto load_weak = [&](int w) {
@@ -307,7 +312,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     };
 
     if (nq > 0) {
-        const int s1 = min(1, nq - 1);
+        const int s1 = min(1, nq - 1), s1x = min(1, ns - 1);
 #pragma unroll
         for (int u = 0; u < 8; ++u) load_x(u, 0);
 #pragma unroll
@@ -318,7 +323,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             put_x(u, 0);
-            load_x(u, s1);
+            load_x(u, s1x);
         }
         latch(0);
 #pragma unroll
@@ -337,7 +342,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
         // stage st: X in buffer CUR, codes in set CUR
         auto stage = [&](int st, auto cur_c) {
             constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
-            const int sl = min(st + 2, nq - 1);
+            const int sl = min(st + 2, nq - 1), slx = min(st + 2, ns - 1);   // the activations run on into the weak stages
             // keep "base + constant" from being hoisted out of the loop into a register per constant:
             // inside the stage it folds into the instruction's offset field
             asm volatile("" : "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]), "+v"(fb[4]), "+v"(fb[5]), "+v"(fb[6]), "+v"(fb[7]));
@@ -386,7 +391,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
                         } else {
                             px.z = __builtin_amdgcn_perm(xv[u].w, xv[u].y, 0x05040100u);
                             px.w = __builtin_amdgcn_perm(xv[u].w, xv[u].y, 0x07060302u);
-                            load_x(u, sl);
+                            load_x(u, slx);
                         }
                     }
                     if (ks == 3 && j == 7) load_a(CUR, i, sl);
@@ -420,6 +425,130 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
             stage(st + 1, std::integral_constant<int, 1>{});
         }
         if (nq & 1) stage(st, std::integral_constant<int, 0>{});
+        if (nwf == 0) __syncthreads();
+    }
+
+    // ---- weak block, whole stages: the same 64-step stage without a conversion ------------------------
+    // The activation pipeline above simply runs on (the weak columns follow the quantized ones in X), so the
+    // tiles keep the chunk order of the 4-bit conversion.  A lane's A fragment of k-block kn is 16 contiguous
+    // bytes of its row of the fp16 block: it is fetched one stage ahead into the register of the k-block just
+    // consumed and brought into the tiles' chunk order by four byte permutes while the previous k-block is
+    // multiplied.  No weight passes through LDS.
+    if (nwf > 0) {
+        u4 wfr[2][4];      // [row block][k-block]
+        uint32_t woff[2];  // (computed here: the stage loop above has no register to carry them)
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            woff[i] = ((uint32_t)min(wave * 64 + 32 * i + fr, L.oc - 1 - oc0) * (uint32_t)L.k + 32u * fk) * 2u;
+        auto load_w = [&](int i, int kn, uint32_t off) {   // scalar base + lane offset + immediate
+            wfr[i][kn] = *reinterpret_cast<g_u4*>(((gptr)wk + off) + 16 * kn);
+        };
+        auto order_w = [&](int i, int kn, int dst) {   // A fragment in the tiles' chunk order
+            const u4 v = wfr[i][kn];
+            afr[dst][i].x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);
+            afr[dst][i].y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);
+            afr[dst][i].z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);
+            afr[dst][i].w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);
+        };
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int kn = 0; kn < 4; ++kn) load_w(i, kn, woff[i]);
+        if (nq == 0) {   // no stage has run yet: start the activation pipeline here
+            const int s1x = min(1, ns - 1);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) load_x(u, 0);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                put_x(u, 0);
+                load_x(u, s1x);
+            }
+            px = u4{0u, 0u, 0u, 0u};
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) read_b(0, j, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            order_w(i, 0, 0);
+            load_w(i, 0, woff[i] + (uint32_t)(2 * BK * min(1, nwf - 1)));
+        }
+
+        // weak stage w: X in buffer CUR
+        auto wstage = [&](int w, auto cur_c) {
+            constexpr int CUR = decltype(cur_c)::value, NXT = CUR ^ 1;
+            const int slx = min(nq + w + 2, ns - 1);
+            uint32_t wo1[2], wo2[2];   // this thread's rows in the next stage and in the one after
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                wo1[i] = woff[i] + (uint32_t)(2 * BK * min(w + 1, nwf - 1));
+                wo2[i] = woff[i] + (uint32_t)(2 * BK * min(w + 2, nwf - 1));
+            }
+            asm volatile("" : "+v"(fb[0]), "+v"(fb[1]), "+v"(fb[2]), "+v"(fb[3]), "+v"(fb[4]), "+v"(fb[5]), "+v"(fb[6]), "+v"(fb[7]));
+            asm volatile("" : "+v"(xw[0]), "+v"(xw[1]), "+v"(wo1[0]), "+v"(wo1[1]), "+v"(wo2[0]), "+v"(wo2[1]));
+            asm volatile("" : "+v"(xoff[0]), "+v"(xoff[1]), "+v"(xoff[2]), "+v"(xoff[3]), "+v"(xoff[4]), "+v"(xoff[5]), "+v"(xoff[6]), "+v"(xoff[7]));
+            auto step = [&](auto t_c) {
+                constexpr int T = decltype(t_c)::value, ks = T >> 4, t = T & 15, i = t >> 3, j = t & 7, kn = (ks + 1) & 3;
+                constexpr int SRC = ks < 3 ? CUR : NXT;          // tile of the next k-block
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, afr[ks & 1][i]), bfr[ks & 1][j], acc[i][j], 0, 0, 0);
+                if ((t & 1) == 0) {
+                    read_b(kn & 1, t >> 1, SRC, kn);
+                    if (T >= 4 && T <= 32 && (T & 3) == 0) {   // the chunk permuted in the two odd steps before
+                        constexpr int u = (T >> 2) - 1;
+                        *reinterpret_cast<lds_u4*>(xw[u & 1] + (uint32_t)((u >> 1) * 8192 + NXT * TILE_BYTES)) = px;
+                    }
+                    // the next k-block's fragments (k-block 0 of the next stage behind the last one), one row block
+                    // per step; each register is then refilled with the same k-block one stage on
+                    if (t == 4) order_w(0, kn, kn & 1);
+                    if (t == 6) order_w(1, kn, kn & 1);
+                    if (t == 10) load_w(0, kn, ks < 3 ? wo1[0] : wo2[0]);
+                    if (t == 12) load_w(1, kn, ks < 3 ? wo1[1] : wo2[1]);
+                } else {
+                    if (T < 32) {   // X chunk u of the next stage: half of the permutation per odd step
+                        constexpr int u = T >> 2;
+                        if ((T & 2) == 0) {
+                            px.x = __builtin_amdgcn_perm(xv[u].z, xv[u].x, 0x05040100u);
+                            px.y = __builtin_amdgcn_perm(xv[u].z, xv[u].x, 0x07060302u);
+                        } else {
+                            px.z = __builtin_amdgcn_perm(xv[u].w, xv[u].y, 0x05040100u);
+                            px.w = __builtin_amdgcn_perm(xv[u].w, xv[u].y, 0x07060302u);
+                            load_x(u, slx);
+                        }
+                    }
+                }
+                if (T == 47) __syncthreads();
+                __builtin_amdgcn_sched_barrier(0);
+            };
+            auto steps8 = [&](auto b_c) {
+                constexpr int B = decltype(b_c)::value;
+                step(std::integral_constant<int, B + 0>{});
+                step(std::integral_constant<int, B + 1>{});
+                step(std::integral_constant<int, B + 2>{});
+                step(std::integral_constant<int, B + 3>{});
+                step(std::integral_constant<int, B + 4>{});
+                step(std::integral_constant<int, B + 5>{});
+                step(std::integral_constant<int, B + 6>{});
+                step(std::integral_constant<int, B + 7>{});
+            };
+            steps8(std::integral_constant<int, 0>{});
+            steps8(std::integral_constant<int, 8>{});
+            steps8(std::integral_constant<int, 16>{});
+            steps8(std::integral_constant<int, 24>{});
+            steps8(std::integral_constant<int, 32>{});
+            steps8(std::integral_constant<int, 40>{});
+            steps8(std::integral_constant<int, 48>{});
+            steps8(std::integral_constant<int, 56>{});
+        };
+        int w = 0;
+        if (nq & 1) {   // the first weak stage sits in tile 1
+            wstage(0, std::integral_constant<int, 1>{});
+            w = 1;
+        }
+        for (; w + 1 < nwf; w += 2) {
+            wstage(w, std::integral_constant<int, 0>{});
+            wstage(w + 1, std::integral_constant<int, 1>{});
+        }
+        if (w < nwf) wstage(w, std::integral_constant<int, 0>{});
         __syncthreads();
     }
     if (nw > 0) load_weak(0);
@@ -1185,7 +1314,7 @@ bool gemm_fwd_supported(const Layer& L, int64_t M) {
 hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int tiles_oc = ceil_div(L.oc, BT), tiles_m = ceil_div(M, BT);
     hipError_t e;
-    if (L.kq > 0 && L.kq % BK == 0) {   // whole quantized stages: weights dequantized in registers
+    if (L.kq % BK == 0 && (L.kq > 0 || (L.k > 0 && L.k % BK == 0))) {   // whole stages: weights straight into MFMA operand registers
         static bool attr = false;
         if (!attr) {
             e = hipFuncSetAttribute((const void*)gemm_fwd_rega_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, REGA_LDS);
