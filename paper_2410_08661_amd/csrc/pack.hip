@@ -288,14 +288,33 @@ __global__ __launch_bounds__(256) void dequantize_kernel(Layer L, __half* __rest
     const int o = (int)(idx / chunks), j0 = 8 * (int)(idx % chunks);
     const uint32_t* row = L.qweight + (size_t)o * L.stride;
     __half v[8];
+    if (j0 + 8 <= L.kq && (L.g & 7) == 0) {   // the usual case: eight quantized columns of one group
+        const size_t gi = (size_t)o * L.gs + j0 / L.g;
+        const float sc = __half2float(L.scales[gi]), zp = __half2float(L.zeros[gi]);
+        if (L.dense) {                        // 24 bits starting at bit 3 j0 = 24 (j0 / 8) of the row
+            const int bit = 3 * j0, w0 = bit >> 5, sh = bit & 31;
+            uint32_t c = row[w0] >> sh;
+            if (sh > 8) c |= row[w0 + 1] << (32 - sh);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const int j = j0 + e;
-        if (j < L.kq) {
-            const size_t gi = (size_t)o * L.gs + j / L.g;
-            v[e] = __float2half_rn(__half2float(L.scales[gi]) * ((float)code_at(L, row, j) - __half2float(L.zeros[gi])));
+            for (int e = 0; e < 8; ++e) v[e] = __float2half_rn(sc * ((float)((c >> (3 * e)) & 7u) - zp));
+        } else if (L.bits == 4) {
+            const uint32_t c = row[j0 >> 3];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = __float2half_rn(sc * ((float)((c >> (4 * e)) & 15u) - zp));
         } else {
-            v[e] = L.weak[(size_t)o * L.k + (j - L.kq)];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = __float2half_rn(sc * ((float)code_at(L, row, j0 + e) - zp));
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = j0 + e;
+            if (j < L.kq) {
+                const size_t gi = (size_t)o * L.gs + j / L.g;
+                v[e] = __float2half_rn(__half2float(L.scales[gi]) * ((float)code_at(L, row, j) - __half2float(L.zeros[gi])));
+            } else {
+                v[e] = L.weak[(size_t)o * L.k + (j - L.kq)];
+            }
         }
     }
     *reinterpret_cast<uint4*>(out + (size_t)o * L.ic + j0) = *reinterpret_cast<const uint4*>(v);
