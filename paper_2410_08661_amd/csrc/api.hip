@@ -207,7 +207,7 @@ int qeft_linear_fwd_group(int n, const qeft_desc_t* descs, const qeft_weight_t* 
     for (int i = 0; i < n; ++i) {
         int st = make_layer(&descs[i], &w[i], &Ls[i]);
         if (st != QEFT_OK) return st;
-        if (Ls[i].ic != Ls[0].ic || Ls[i].k != Ls[0].k || Ls[i].bits != Ls[0].bits || Ls[i].g != Ls[0].g) return QEFT_ERR_SHAPE;
+        if (Ls[i].ic != Ls[0].ic || Ls[i].k != Ls[0].k || Ls[i].bits != Ls[0].bits || Ls[i].g != Ls[0].g || Ls[i].dense != Ls[0].dense) return QEFT_ERR_SHAPE;
         st = check_matrix(Y[i], M, ldy[i], Ls[i].oc);
         if (st != QEFT_OK) return st;
     }

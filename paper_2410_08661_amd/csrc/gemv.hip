@@ -61,8 +61,8 @@ __device__ __forceinline__ float half_at(u2 v, int i) { return (float)__builtin_
 struct Consts {
     uint32_t mask, magic;
 };
-__device__ __forceinline__ Consts make_consts() {
-    Consts c{0x000f000fu, 0x64006400u};
+__device__ __forceinline__ Consts make_consts(uint32_t mask = 0x000f000fu) {
+    Consts c{mask, 0x64006400u};
     asm volatile("" : "+v"(c.mask), "+v"(c.magic));
     return c;
 }
@@ -111,14 +111,31 @@ __device__ __forceinline__ float sum16(float t) {
 
 __device__ __forceinline__ void wave_lds_fence() { __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront"); }
 
+// Dense 3-bit layout: the lane's 32 codes are the 96 bits w.x, w.y, w.z; octet I is its fragment I, pair P
+// of the 16 sits at bits 6 P .. 6 P + 5 (two pairs straddle words).  One field extract, one multiplication
+// by 2^13 + 1 (second code to bit 16) and the and-or give the fp16 pair (1024 + q0, 1024 + q1), in column order.
+template <int I>
+__device__ __forceinline__ h8 dense3_to_h8(u4 w, Consts c) {
+    u4 r;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const int P = 4 * I + p, wi = (6 * P) >> 5, sh = (6 * P) & 31;
+        const uint32_t six = sh <= 26 ? __builtin_amdgcn_ubfe(w[wi], sh, 6)
+                                      : __builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(w[(wi + 1) & 3], w[wi], sh), 0, 6);
+        r[p] = ((six * 0x2001u) & c.mask) | c.magic;
+    }
+    return as_h8(r);
+}
+
 // One quantized step of one 16-row tile: 4 MFMAs on the codes, then the group's scale and
 // zero-point on the accumulator.  c = 1024 + z.
+template <bool W3 = false>
 __device__ __forceinline__ void step_tile(f4& y, const u4 (&xa)[4], u4 w, f4 sx, float sf, float c, Consts magic) {
     f4 acc = f4{0.f, 0.f, 0.f, 0.f};
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[0]), codes_to_h8(w.x, magic), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[1]), codes_to_h8(w.y, magic), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[2]), codes_to_h8(w.z, magic), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[3]), codes_to_h8(w.w, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[0]), W3 ? dense3_to_h8<0>(w, magic) : codes_to_h8(w.x, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[1]), W3 ? dense3_to_h8<1>(w, magic) : codes_to_h8(w.y, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[2]), W3 ? dense3_to_h8<2>(w, magic) : codes_to_h8(w.z, magic), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[3]), W3 ? dense3_to_h8<3>(w, magic) : codes_to_h8(w.w, magic), acc, 0, 0, 0);
 #pragma unroll
     for (int e = 0; e < 4; ++e) y[e] = fmaf(sf, fmaf(-c, sx[e], acc[e]), y[e]);
 }
@@ -214,7 +231,10 @@ inline SmallLds small_lds(int M, int ng, int tw, int ks) {
 // PERM: the activations are in the layer's ORIGINAL channel order and stored column j reads
 // X[perm[j]] (weak columns left at arbitrary channels): the 16-byte fragment loads become eight
 // 2-byte gathers through the table, whose own requests head the stream.
-template <int D, int WMAX, int NSZ, bool PERM>
+// W3: 3-bit codes in the dense layout.  A lane's 12 bytes hold the 32 codes of its quarter of a group, so the
+// kernel is the same step for step (one group per step, 48 bytes of a row); the activations stay in column
+// order, which is the order the 3-bit conversion produces.
+template <int D, int WMAX, int NSZ, bool PERM, bool W3 = false>
 __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                              __half* __restrict__ Y, int64_t ldy, SmallLds ld, int KS, int ks_magic,
                                                              GroupTail G, const int* __restrict__ perm) {
@@ -295,7 +315,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
             if (8 * xf[u] >= L.kq) xv[u] = zero4;
             const float t = sum16(sum8(xv[u]));
             if (xm[u] >= 0) {
-                *reinterpret_cast<u4*>(lds + xm[u] * ld.xrow + xf[u] * 16) = permute_x(xv[u]);
+                *reinterpret_cast<u4*>(lds + xm[u] * ld.xrow + xf[u] * 16) = W3 ? xv[u] : permute_x(xv[u]);
                 if ((xf[u] & 15) == 0) reinterpret_cast<float*>(lds + ld.sx_off)[(xf[u] >> 4) * 4 + xm[u]] = t;
             }
         }
@@ -312,12 +332,20 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
         pv[i] = load16(((c & 1) ? L.zeros : L.scales) + (size_t)orow * L.gs + g0);
     }
     // weights: steps past the wave's range re-read its last step (never consumed)
+    constexpr int WSTEP = W3 ? 48 : 64, WLANE = W3 ? 12 : 16;   // bytes of a row per step, and per lane
     const unsigned char* wp =
-        reinterpret_cast<const unsigned char*>(L.qweight + (size_t)orow * L.stride) + 64 * (size_t)q_beg + 16 * kb;
+        reinterpret_cast<const unsigned char*>(L.qweight + (size_t)orow * L.stride) + WSTEP * (size_t)q_beg + WLANE * kb;
+    auto load_w = [&](const unsigned char* p) {
+        if (W3) {
+            const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+            return u4{q[0], q[1], q[2], 0u};
+        }
+        return load16(p);
+    };
     const int j_last = max(min(nj, nq - q_beg) - 1, 0);
     u4 wq[D];
 #pragma unroll
-    for (int d = 0; d < D; ++d) wq[d] = load16(wp + 64 * min(d, j_last));
+    for (int d = 0; d < D; ++d) wq[d] = load_w(wp + WSTEP * min(d, j_last));
     // weak steps of 32 fp16 columns are dealt to the K-split waves from the last one back
     // (columns past k are clamped here and zeroed where they are used; k >= 8)
     u4 wk[WMAX], xw[WMAX], wlo[WMAX], whi[WMAX];
@@ -367,7 +395,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
     // ---- stream this wave's steps ---------------------------------------------------------------------
     f4 y[1];
     y[0] = f4{0.f, 0.f, 0.f, 0.f};
-    const Consts magic = make_consts();
+    const Consts magic = make_consts(W3 ? 0x00070007u : 0x000f000fu);
     // lanes without an activation row (n >= M), and accumulator rows >= 4 for Sx, read zero bytes
     const bool has_sx = kb == 0;
     int xa_addr = has_x ? n * ld.xrow + kb * 64 + q_beg * 256 : ld.zero_off;
@@ -381,10 +409,10 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
         for (int i = 0; i < 4; ++i) xa[i] = *reinterpret_cast<const u4*>(lds + xa_addr + d * 256 + 16 * i);
         const f4 sx = *reinterpret_cast<const f4*>(lds + sx_addr + d * 16);
         const float2 sz = *reinterpret_cast<const float2*>(lds + sz_addr + d * 128);
-        step_tile(y[0], xa, wq[d], sx, sz.x, sz.y, magic);
+        step_tile<W3>(y[0], xa, wq[d], sx, sz.x, sz.y, magic);
     };
     auto advance = [&]() {
-        wp += 64 * D;
+        wp += WSTEP * D;
         xa_addr += xa_inc;
         sx_addr += sx_inc;
         sz_addr += 128 * D;
@@ -395,7 +423,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
 #pragma unroll
         for (int d = 0; d < D; ++d) {
             step(d);
-            wq[d] = load16(wp + 64 * (d + D));
+            wq[d] = load_w(wp + WSTEP * (d + D));
             __builtin_amdgcn_sched_barrier(0);  // keep the refill right behind its step: D loads stay in flight
         }
         advance();
@@ -405,7 +433,7 @@ __global__ __launch_bounds__(1024) void gemv_w4_small_kernel(Layer L, const __ha
         for (int d = 0; d < D; ++d) {
             if (j0 + d < nj) {
                 step(d);
-                if (j0 + d + D < nj) wq[d] = load16(wp + 64 * (d + D));
+                if (j0 + d + D < nj) wq[d] = load_w(wp + WSTEP * (d + D));
             }
         }
         advance();
@@ -688,8 +716,9 @@ hipError_t launch_rows(const Layer& L, const __half* X, int M, int64_t ldx, __ha
 // =============================================================================================
 // DENSE: the dense 3-bit layout (a row is one bit string, 32 codes in 3 words).  A lane then takes
 // 12 bytes = 32 codes = four fragments per step, a step of the four k-slot lanes covers exactly one group
-// of 128 columns (so a lane's fragments all use one (zero-point, scale) pair), and pair P of a lane sits at
-// bits 6 P of its 96: two of the sixteen pairs straddle words and take one funnel shift more.
+// of 128 columns, and pair P of a lane sits at bits 6 P of its 96: two of the sixteen pairs straddle words
+// and take one funnel shift more.  Group = step is what lets the dequantization move to the accumulator
+// side (see step_dense): about half the vector instructions of the whole-codes-per-word layout.
 template <int R, int D, int NSZ, bool DENSE>
 __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                       __half* __restrict__ Y, int64_t ldy, int ks_magic, int nsteps) {
@@ -786,9 +815,56 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
         }
     };
     read_zs(0);
-    auto step = [&](int d, int j) {
+    u4 ones = u4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+    asm volatile("" : "+v"(ones.x), "+v"(ones.y), "+v"(ones.z), "+v"(ones.w));
+    // Dense layout: a step is one group, so the dequantization moves behind the matrix cores as in the
+    // 4-bit kernels: the codes enter as the exact fp16 numbers 1024 + q (three instructions per pair), the
+    // step's sum over its 128 columns is taken in a fresh accumulator, and the group contributes
+    // s (sum x (1024 + q) - (1024 + z) sum x); sum x comes from four more MFMAs against an all-ones
+    // operand, shared by the R tiles, and lands in the accumulator's own layout.
+    auto step_dense = [&](int d, int j) {
         const int col = col0 + STEP_COLS * j;
-        const int split = ((col >> 7) + 1) << 7;   // first column of the next group (dense: past the lane's columns)
+        float sc[R], tc[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const h2 zs = __builtin_bit_cast(h2, zs_lo[r]);
+            sc[r] = (float)zs.y;
+            tc[r] = sc[r] * (1024.f + (float)zs.x);
+        }
+        read_zs(j + 1);
+        f4 sx = f4{0.f, 0.f, 0.f, 0.f}, ya[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) ya[r] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < NF; ++s) {
+            const u4 xa = (col + 8 * s < L.kq && j < nj) ? xq[d][s] : zero4;
+            sx = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa), as_h8(ones), sx, 0, 0, 0);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                u4 b;
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const int P = 4 * s + p;   // pair P of the lane's 16 at bits 6 P .. 6 P + 5 of its three words
+                    const int wi = (6 * P) >> 5, sh = (6 * P) & 31;
+                    const uint32_t six = sh <= 26 ? __builtin_amdgcn_ubfe(wq[d][r][wi], sh, 6)
+                                                  : __builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(wq[d][r][(wi + 1) & 3], wq[d][r][wi], sh), 0, 6);
+                    b[p] = ((six * 0x2001u) & cmask) | cmagic;   // fp16 pair (1024 + q0, 1024 + q1)
+                }
+                ya[r] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa), as_h8(b), ya[r], 0, 0, 0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[r][e] += sc[r] * ya[r][e] - tc[r] * sx[e];
+    };
+    auto step = [&](int d, int j) {
+        if (DENSE) {
+            step_dense(d, j);
+            return;
+        }
+        const int col = col0 + STEP_COLS * j;
+        const int split = ((col >> 7) + 1) << 7;   // first column of the next group
         h2 zsl[R], zsh[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
@@ -802,7 +878,7 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
 #pragma unroll
         for (int s = 0; s < NF; ++s) {
             const u4 xa = (col + 8 * s < L.kq && j < nj) ? xq[d][s] : zero4;
-            const bool hi = !DENSE && col + 8 * s >= split;
+            const bool hi = col + 8 * s >= split;
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const h2 zs = hi ? zsh[r] : zsl[r];
@@ -811,14 +887,7 @@ __global__ __launch_bounds__(512) void gemv_w3_kernel(Layer L, const __half* __r
 #pragma unroll
                 for (int p = 0; p < 4; ++p) {
                     const int P = 4 * s + p;   // pair P of the lane's 20: word P / 5, codes 2 (P % 5) and the next
-                    uint32_t six;
-                    if (DENSE) {               // pair P of the lane's 16 at bits 6 P .. 6 P + 5 of its three words
-                        const int wi = (6 * P) >> 5, sh = (6 * P) & 31;
-                        six = sh <= 26 ? __builtin_amdgcn_ubfe(wq[d][r][wi], sh, 6)
-                                       : __builtin_amdgcn_ubfe(__builtin_amdgcn_alignbit(wq[d][r][(wi + 1) & 3], wq[d][r][wi], sh), 0, 6);
-                    } else {
-                        six = __builtin_amdgcn_ubfe(wq[d][r][P / 5], 6 * (P % 5), 6);
-                    }
+                    const uint32_t six = __builtin_amdgcn_ubfe(wq[d][r][P / 5], 6 * (P % 5), 6);
                     const uint32_t codes = ((six * 0x2001u) & cmask) | cmagic;   // fp16 pair (1024 + q0, 1024 + q1)
                     b[p] = __builtin_bit_cast(uint32_t, ((__builtin_bit_cast(h2, codes) - k1024) - z2) * s2);
                 }
@@ -936,15 +1005,17 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
     // prefetch depth: all of a wave's steps when it has at most 4, else 8 steps per lane unless
     // the weak prefetch already takes the registers (a request past the range would only repeat
     // the last one, but it still occupies the CU's address path at launch)
-#define QEFT_SMALL_ROW(P, D, W) {gemv_w4_small_kernel<D, W, 1, P>, gemv_w4_small_kernel<D, W, 2, P>, gemv_w4_small_kernel<D, W, 3, P>}
-    static const Kern table[2][4][3] = {
-        {QEFT_SMALL_ROW(false, 4, 1), QEFT_SMALL_ROW(false, 8, 1), QEFT_SMALL_ROW(false, 8, 2), QEFT_SMALL_ROW(false, 4, 4)},
-        {QEFT_SMALL_ROW(true, 4, 1), QEFT_SMALL_ROW(true, 8, 1), QEFT_SMALL_ROW(true, 8, 2), QEFT_SMALL_ROW(true, 4, 4)}};
+#define QEFT_SMALL_ROW(P, D, W, T) {gemv_w4_small_kernel<D, W, 1, P, T>, gemv_w4_small_kernel<D, W, 2, P, T>, gemv_w4_small_kernel<D, W, 3, P, T>}
+    static const Kern table[3][4][3] = {
+        {QEFT_SMALL_ROW(false, 4, 1, false), QEFT_SMALL_ROW(false, 8, 1, false), QEFT_SMALL_ROW(false, 8, 2, false), QEFT_SMALL_ROW(false, 4, 4, false)},
+        {QEFT_SMALL_ROW(true, 4, 1, false), QEFT_SMALL_ROW(true, 8, 1, false), QEFT_SMALL_ROW(true, 8, 2, false), QEFT_SMALL_ROW(true, 4, 4, false)},
+        {QEFT_SMALL_ROW(false, 4, 1, true), QEFT_SMALL_ROW(false, 8, 1, true), QEFT_SMALL_ROW(false, 8, 2, true), QEFT_SMALL_ROW(false, 4, 4, true)}};
 #undef QEFT_SMALL_ROW
-    static bool attr_set[2][4][3] = {};
+    static bool attr_set[3][4][3] = {};
     const int nj_max = 4 * ceil_div(units, ks);
     const int wi = wmax <= 1 ? (nj_max <= 4 ? 0 : 1) : (wmax <= 2 ? 2 : 3), si = nsz - 1;
-    const int pi = perm ? 1 : 0;
+    if (L.dense && perm) return false;   // no gathering variant for 3-bit codes
+    const int pi = L.dense ? 2 : (perm ? 1 : 0);
     const Kern kern = table[pi][wi][si];
     if (!attr_set[pi][wi][si]) {
         *err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMALL_LDS_LIMIT);
@@ -967,7 +1038,7 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, 
                           const int64_t* ldy, hipStream_t s, bool* handled) {
     *handled = false;
     const Layer& L = Ls[0];
-    if (n < 1 || n > MAX_GROUP || M64 > 4 || L.bits != 4 || L.kq < 8 || L.k < 8) return hipSuccess;
+    if (n < 1 || n > MAX_GROUP || M64 > 4 || !(L.bits == 4 || L.dense) || L.kq < 8 || L.k < 8) return hipSuccess;
     GroupTail tail = no_tail();
     int tiles = ceil_div(L.oc, 16);
     for (int i = 1; i < n; ++i) {
@@ -997,12 +1068,12 @@ hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64
 
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int M = (int)M64;
-    if (L.bits == 3) return M > 4 ? launch_w3<2>(L, X, M, ldx, Y, ldy, s) : launch_w3<1>(L, X, M, ldx, Y, ldy, s);
-    const int steps = L.ng + (L.k + 31) / 32;
-    if (M <= 4 && L.kq >= 8 && L.k >= 8) {
+    if (M <= 4 && L.kq >= 8 && L.k >= 8 && (L.bits == 4 || L.dense)) {   // (dense 3-bit: gemv_supported has checked that rows hold whole steps)
         hipError_t err = hipSuccess;
         if (launch_small(L, ceil_div(L.oc, 16), no_tail(), nullptr, X, M, ldx, Y, ldy, s, &err)) return err;
     }
+    if (L.bits == 3) return M > 4 ? launch_w3<2>(L, X, M, ldx, Y, ldy, s) : launch_w3<1>(L, X, M, ldx, Y, ldy, s);
+    const int steps = L.ng + (L.k + 31) / 32;
     if (L.kq >= 8 && !getenv("QEFT_DBG_CHUNK")) {
         // unstaged kernel: R tiles per wave share the activation fragments; four K-split waves per workgroup
         // (one per SIMD), and four tiles per wave once that still leaves every CU more than two waves
