@@ -34,8 +34,8 @@ MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
 # the launches of the kernel in one step
-TRAFFIC_DX_BYTES = (2 * (223.0e6 + 34.3e6) + (485.3e6 + 90.9e6)) / 3      # three dX launches
-TRAFFIC_GEMV_BYTES = (29.34e6 + 9.89e6 + 52.87e6 + 25.14e6) / 4          # the four decode launches of a block
+TRAFFIC_DX_BYTES = (113.5e6 + 34.3e6 + 331.9e6 + 34.3e6 + 484.5e6 + 90.9e6) / 3
+TRAFFIC_GEMV_BYTES = (29.34e6 + 9.94e6 + 52.38e6 + 25.22e6) / 4
 
 
 def main():
@@ -230,6 +230,46 @@ def main():
     torch.cuda.synchronize()
     pack_search_us = e0.elapsed_time(e1) * 1e3 / 5
 
+    # 3-bit storage of the same up-projection (Tab. 5's 3-bit models), both layouts: decode over rotating packed
+    # copies, and the forward at M = 4096 through the dequantized fp16 copy
+    three_bit = {"layer": "11008x4096, w3 g128 k=128"}
+    w3 = synth_weight(11008, 4096)
+    f1 = ft[1]
+    for lname, lid in (("canonical", B.QEFT_LAYOUT_CANONICAL), ("dense", B.QEFT_LAYOUT_DENSE3)):
+        d3 = B.make_desc(11008, 4096, k, 3, g, layout=lid)
+        copies = [B.qeft_pack(d3, w3) for _ in range(n_blocks)]
+        B.qeft_linear_fwd(d3, copies[0], x1[4096], y1[4])
+        g3 = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g3, stream=cap_stream):
+            for b in range(n_blocks):
+                B.qeft_linear_fwd(d3, copies[b], x1[4096], y1[4])
+        g3.replay()
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for r in range(n_rep):
+            g3.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (n_rep * n_blocks)
+        three_bit[f"decode_us_{lname}"] = round(us, 2)
+        three_bit[f"decode_gbs_{lname}"] = round(copies[0].nbytes() / us / 1e3, 1)
+        three_bit[f"bytes_{lname}"] = copies[0].nbytes()
+        ws3 = torch.empty(B.qeft_workspace_bytes(d3, B.QEFT_OP_FWD, M_ft), dtype=torch.uint8, device=dev)
+        for _ in range(2):
+            B.qeft_linear_fwd(d3, copies[0], f1["x"], f1["y"], ws=ws3)
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(5):
+            B.qeft_linear_fwd(d3, copies[0], f1["x"], f1["y"], ws=ws3)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / 5
+        three_bit[f"fwd_M4096_us_{lname}"] = round(us, 1)
+        three_bit[f"fwd_M4096_tflops_{lname}"] = round(2.0 * M_ft * 11008 * 4096 / us / 1e6, 1)
+        del copies, ws3
+    del w3
+
     # a plain device copy of known size: the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
     cal = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
     cal2 = torch.empty_like(cal)
@@ -289,6 +329,7 @@ def main():
                                "decode_us": round(irr_decode_us, 2),
                                "decode_us_reordered": next(dk["us"] for dk in decode_kernels if dk["launch"] == "o"),
                                "fwd_M4096_us": round(irr_ft_us, 1), "fwd_M4096_us_reordered": kernels[0]["fwd_us"]},
+        "three_bit": three_bit,
         "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_kernel_gbs / HBM_PEAK_GBS, 4),
                           "traffic": round(TRAFFIC_GEMV_BYTES),
