@@ -1340,7 +1340,7 @@ bool gemm_dx_supported(const Layer& L, int64_t M) {
 hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s) {
     const int tiles_m = ceil_div(M, BT), tiles_ic = ceil_div(L.ic, BT);
     hipError_t e;
-    if (L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0 && !getenv("QEFT_DBG_OLDDX")) {
+    if (L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0) {
         static bool attr = false;
         if (!attr) {
             e = hipFuncSetAttribute((const void*)gemm_dx_rega_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, DX_LDS);

@@ -1074,7 +1074,7 @@ hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, _
     }
     if (L.bits == 3) return M > 4 ? launch_w3<2>(L, X, M, ldx, Y, ldy, s) : launch_w3<1>(L, X, M, ldx, Y, ldy, s);
     const int steps = L.ng + (L.k + 31) / 32;
-    if (L.kq >= 8 && !getenv("QEFT_DBG_CHUNK")) {
+    if (L.kq >= 8) {
         // unstaged kernel: R tiles per wave share the activation fragments; four K-split waves per workgroup
         // (one per SIMD), and four tiles per wave once that still leaves every CU more than two waves
         // (measured at M = 8 and 16: 4096 ... 8192 rows are 30 - 50 % faster with R = 2, 11008 ... 28672 rows

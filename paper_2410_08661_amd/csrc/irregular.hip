@@ -72,6 +72,95 @@ __global__ __launch_bounds__(256) void scatter_rows_kernel(const unsigned short*
     }
 }
 
+// Rows of up to 8 K channels: the same, with this thread's table entries held in registers for all rows of
+// the workgroup (NC chunks of 8 columns per thread), two row buffers so that one barrier per row suffices,
+// and the next row's 16-byte loads in flight while the current one is assembled.
+template <int NC>
+__global__ __launch_bounds__(256) void gather_rows_reg_kernel(const unsigned short* __restrict__ X, int M, int64_t ldx,
+                                                              const int* __restrict__ perm, int ic, int chunks,
+                                                              unsigned short* __restrict__ Xs, int64_t lds_, int rows_per_wg) {
+    extern __shared__ __attribute__((aligned(16))) unsigned short rowbuf[];   // [2][8 * chunks]
+    const int pitch = 8 * chunks;
+    int p[NC][8];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x + 256 * i;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = 8 * c + e;
+            p[i][e] = j < ic ? min(max(perm[j], 0), ic - 1) : -1;
+        }
+    }
+    const int m0 = blockIdx.x * rows_per_wg, m1 = min(m0 + rows_per_wg, M);
+    u4 nxt[NC];
+    auto fetch = [&](int m) {   // chunk indices are clamped, not tested: the loads stay straight-line (ldx >= 8 * chunks)
+        const unsigned short* row = X + (size_t)m * ldx;
+#pragma unroll
+        for (int i = 0; i < NC; ++i) nxt[i] = *reinterpret_cast<const u4*>(row + 8 * min((int)threadIdx.x + 256 * i, chunks - 1));
+    };
+    if (m0 < m1) fetch(m0);
+    for (int m = m0; m < m1; ++m) {
+        unsigned short* buf = rowbuf + ((m - m0) & 1) * pitch;
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int c = threadIdx.x + 256 * i;
+            if (c < chunks) *reinterpret_cast<u4*>(buf + 8 * c) = nxt[i];
+        }
+        fetch(min(m + 1, m1 - 1));
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NC; ++i) {
+            const int c = threadIdx.x + 256 * i;
+            if (c < chunks) {
+                uint32_t v[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = p[i][e] >= 0 ? buf[p[i][e]] : 0u;
+                *reinterpret_cast<u4*>(Xs + (size_t)m * lds_ + 8 * c) = u4{v[0] | (v[1] << 16), v[2] | (v[3] << 16), v[4] | (v[5] << 16), v[6] | (v[7] << 16)};
+            }
+        }
+        // the buffer written two rows later is this one: every thread passes the next row's barrier first
+    }
+}
+
+template <int NC>
+__global__ __launch_bounds__(256) void scatter_rows_reg_kernel(const unsigned short* __restrict__ Ds, int M, int64_t ldd,
+                                                               const int* __restrict__ perm, int ic, int chunks,
+                                                               unsigned short* __restrict__ dX, int64_t lddx, int rows_per_wg) {
+    extern __shared__ __attribute__((aligned(16))) unsigned short rowbuf[];   // [2][8 * chunks]
+    const int pitch = 8 * chunks, full = ic >> 3;
+    int p[NC][8];
+#pragma unroll
+    for (int i = 0; i < NC; ++i) {
+        const int c = threadIdx.x + 256 * i;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = 8 * c + e;
+            p[i][e] = j < ic ? min(max(perm[j], 0), ic - 1) : -1;
+        }
+    }
+    const int m0 = blockIdx.x * rows_per_wg, m1 = min(m0 + rows_per_wg, M);
+    u4 nxt[NC];
+    auto fetch = [&](int m) {
+        const unsigned short* row = Ds + (size_t)m * ldd;
+#pragma unroll
+        for (int i = 0; i < NC; ++i) nxt[i] = *reinterpret_cast<const u4*>(row + 8 * min((int)threadIdx.x + 256 * i, chunks - 1));
+    };
+    if (m0 < m1) fetch(m0);
+    for (int m = m0; m < m1; ++m) {
+        unsigned short* buf = rowbuf + ((m - m0) & 1) * pitch;
+        unsigned short* row = dX + (size_t)m * lddx;
+#pragma unroll
+        for (int i = 0; i < NC; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (p[i][e] >= 0) buf[p[i][e]] = (unsigned short)(nxt[i][e >> 1] >> (16 * (e & 1)));
+        fetch(min(m + 1, m1 - 1));
+        __syncthreads();
+        for (int c = threadIdx.x; c < full; c += 256) *reinterpret_cast<u4*>(row + 8 * c) = *reinterpret_cast<const u4*>(buf + 8 * c);
+        for (int j = 8 * full + threadIdx.x; j < ic; j += 256) row[j] = buf[j];
+    }
+}
+
 // Rows too long for LDS: one thread per 8 stored columns of one row, two 16-byte reads of the
 // table, eight 2-byte accesses to the row.
 __global__ __launch_bounds__(256) void gather_cols_kernel(const unsigned short* __restrict__ X, int M, int64_t ldx,
@@ -119,6 +208,13 @@ size_t irregular_workspace(int ic, int64_t M) { return (size_t)M * (size_t)((ic 
 hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm, int ic, __half* Xs, int64_t ldo, hipStream_t s) {
     const int chunks = (ic + 7) / 8;   // ldo >= 8 * chunks, a multiple of 8
     const int row_bytes = chunks * 16;
+    if (chunks <= 1024 && (ic & 7) == 0 && (ldx & 7) == 0 && ((uintptr_t)X & 15) == 0) {   // whole 16-byte chunks only: no read past a row's IC elements
+        const int rw = M >= 2048 ? 8 : (M >= 512 ? 4 : 1);   // table entries are fetched once per workgroup: several rows each
+        const int nc = ceil_div(chunks, 256);
+        auto kern = nc <= 1 ? gather_rows_reg_kernel<1> : (nc <= 2 ? gather_rows_reg_kernel<2> : gather_rows_reg_kernel<4>);
+        kern<<<ceil_div(M, rw), 256, 2 * row_bytes, s>>>((const unsigned short*)X, (int)M, ldx, perm, ic, chunks, (unsigned short*)Xs, ldo, rw);
+        return hipGetLastError();
+    }
     if (row_bytes <= ROW_LDS_MAX && (ldx & 7) == 0 && ((uintptr_t)X & 15) == 0) {
         const int rw = rows_per_wg(M);
         gather_rows_kernel<<<ceil_div(M, rw), 256, row_bytes, s>>>((const unsigned short*)X, (int)M, ldx, perm, ic, chunks,
@@ -134,6 +230,14 @@ hipError_t gather_cols(const __half* X, int64_t M, int64_t ldx, const int* perm,
 hipError_t scatter_cols(const __half* Ds, int64_t M, const int* perm, int ic, __half* dX, int64_t lddx, hipStream_t s) {
     const int chunks = (ic + 7) / 8;
     const int row_bytes = chunks * 16;
+    if (chunks <= 1024 && (lddx & 7) == 0 && ((uintptr_t)dX & 15) == 0) {
+        const int rw = M >= 2048 ? 8 : (M >= 512 ? 4 : 1);
+        const int nc = ceil_div(chunks, 256);
+        auto kern = nc <= 1 ? scatter_rows_reg_kernel<1> : (nc <= 2 ? scatter_rows_reg_kernel<2> : scatter_rows_reg_kernel<4>);
+        kern<<<ceil_div(M, rw), 256, 2 * row_bytes, s>>>((const unsigned short*)Ds, (int)M, (int64_t)chunks * 8, perm, ic, chunks,
+                                                        (unsigned short*)dX, lddx, rw);
+        return hipGetLastError();
+    }
     if (row_bytes <= ROW_LDS_MAX && (lddx & 7) == 0 && ((uintptr_t)dX & 15) == 0) {
         const int rw = rows_per_wg(M);
         scatter_rows_kernel<<<ceil_div(M, rw), 256, row_bytes, s>>>((const unsigned short*)Ds, (int)M, (int64_t)chunks * 8, perm, ic,
