@@ -127,7 +127,8 @@ FWD_CASES = [  # oc, ic, k, bits, g, Ms
     (512, 13696 % 1280 + 1280 + 128, 128, 3, 128, [1, 7]),   # 3-bit, row tail not a multiple of 40 codes
     (64, 333, 21, 4, 128, [1, 3]),                   # odd everything: generic path
     (64, 333, 21, 3, 32, [2]),
-    (48, 256, 256, 4, 128, [1, 9]),                  # k = IC: plain fp16 layer
+    (48, 256, 256, 4, 128, [1, 9, 40]),              # k = IC: plain fp16 layer (M = 40: the GEMM's direct fp16 stages alone)
+    (200, 320, 320, 4, 128, [270]),                  # k = IC, odd number of stages, ragged OC and M
     (48, 384, 0, 4, 128, [1, 9]),                    # k = 0: pure group quantization
     (256, 1024 + 128, 128, 4, 128, [64, 300]),       # larger M: GEMM path, ragged M
     (384, 512 + 72, 72, 4, 128, [130]),              # k not a multiple of 32
