@@ -101,6 +101,25 @@ def test_forward_and_backward_validation():
     assert fwd(C.byref(d3), C.byref(_w(k=None)), X, 0, 128, Y, 64, None, 0, None) == B.QEFT_OK
 
 
+def test_three_bit_workspace_rules():
+    """3-bit layers at M > 16 may take an fp16 copy in a caller workspace: its size, and the errors that
+    precede any launch (too small, misaligned)."""
+    fwd, dx = B.raw.qeft_linear_fwd, B.raw.qeft_linear_bwd_dx
+    X, Y, WS = 0x10000, 0x200000, 0x4000000
+    for layout in (B.QEFT_LAYOUT_CANONICAL, B.QEFT_LAYOUT_DENSE3):
+        d = B.make_desc(64, 256, 128, 3, 128, layout)
+        need = 64 * 256 * 2
+        assert B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 17) == need == B.qeft_workspace_bytes(d, B.QEFT_OP_BWD_DX, 4096)
+        assert B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 16) == 0          # decode sizes use no copy
+        assert fwd(C.byref(d), C.byref(_w()), X, 32, 256, Y, 64, WS, need - 2, None) == B.QEFT_ERR_WORKSPACE
+        assert fwd(C.byref(d), C.byref(_w()), X, 32, 256, Y, 64, WS + 8, need, None) == B.QEFT_ERR_ALIGN
+        assert dx(C.byref(d), C.byref(_w()), X, 32, 64, Y, 256, WS, need - 2, None) == B.QEFT_ERR_WORKSPACE
+        assert dx(C.byref(d), C.byref(_w()), X, 32, 64, Y, 256, WS + 8, need, None) == B.QEFT_ERR_ALIGN
+    assert B.qeft_workspace_bytes(B.make_desc(64, 256, 128, 4), B.QEFT_OP_FWD, 4096) == 0       # 4-bit layers never take a copy
+    assert B.qeft_workspace_bytes(B.make_desc(64, 256, 256, 3), B.QEFT_OP_FWD, 4096) == 0       # nothing quantized
+    assert B.qeft_workspace_bytes(B.make_desc(64, 260, 128, 3), B.QEFT_OP_FWD, 4096) == 0       # IC not a multiple of 8: general kernel
+
+
 def test_forward_group_validation():
     grp = B.raw.qeft_linear_fwd_group
     X = 0x10000
