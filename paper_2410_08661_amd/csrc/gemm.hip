@@ -1167,33 +1167,66 @@ __global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int 
     // br + 32 u, chunk bc).  Chunks past k or past the last channel read column 0 and are zeroed.
     const int ar = tid >> 4, ac = tid & 15, br = tid >> 3, bc = tid & 7;
     const bool a_ok = 8 * ac < k, b_ok = oc0 + 8 * bc < oc_total;
-    const __half* a_src = Xw + (a_ok ? 8 * ac : 0);
-    const __half* b_src = dY + (b_ok ? oc0 + 8 * bc : 0);
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    // Addresses: a scalar base per stage plus a per-thread byte offset computed once (this kernel is bound by
+    // its single wave's instruction stream, and per-load address arithmetic was a third of it).  A stage whose
+    // 64 tokens would pass the end of the matrices is fetched 64 tokens back from the end instead (M >= 64) and
+    // put() keeps only the rows that belong to it; stages past the range re-read the last one and store zeros.
+    using gptr = const __attribute__((address_space(1))) char*;
+    using g_u4 = const __attribute__((address_space(1))) u4;
+    uint32_t aoff[4], boff[2];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) aoff[u] = (uint32_t)(((int64_t)(ar + 16 * u) * ldxw + (a_ok ? 8 * ac : 0)) * 2);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) boff[u] = (uint32_t)(((int64_t)(br + 32 * u) * lddy + (b_ok ? oc0 + 8 * bc : 0)) * 2);
+    const bool cols_full = __builtin_amdgcn_readfirstlane((int)(k >= 8 * 16 && oc0 + WG_OC <= oc_total)) != 0;   // no thread's chunk is zeroed
+    auto first_token = [&](int st) { return min(mb + BK * min(st, nst - 1), M - BK); };   // of the 64 tokens fetched for stage st
     // three stages of fetches in flight per thread (registers), a fourth in LDS being multiplied
     u4 va[3][4], vb[3][2];
     auto fetch = [&](auto set_c, int st) {
         constexpr int SET = decltype(set_c)::value;
-        // branch-free (a fetch under a condition would be waited for at once): tokens past the range
-        // read a valid row; put() zeroes them when it consumes the registers (a select here would
-        // make every turn of the loop wait for its fetches)
-        const int m0 = mb + BK * st;
+        const int t0 = first_token(st);
+        const char* ab = reinterpret_cast<const char*>(Xw) + (int64_t)t0 * ldxw * 2;
+        const char* bb = reinterpret_cast<const char*>(dY) + (int64_t)t0 * lddy * 2;
+        asm volatile("" : "+s"(ab), "+s"(bb));
 #pragma unroll
-        for (int u = 0; u < 4; ++u) va[SET][u] = ld16(a_src + (size_t)min(m0 + ar + 16 * u, M - 1) * ldxw);
+        for (int u = 0; u < 4; ++u) va[SET][u] = *reinterpret_cast<g_u4*>((gptr)ab + aoff[u]);
 #pragma unroll
-        for (int u = 0; u < 2; ++u) vb[SET][u] = ld16(b_src + (size_t)min(m0 + br + 32 * u, M - 1) * lddy);
+        for (int u = 0; u < 2; ++u) vb[SET][u] = *reinterpret_cast<g_u4*>((gptr)bb + boff[u]);
     };
     auto put = [&](auto set_c, int st, int buf) {   // stage st, held by register set SET, into LDS buffer buf
         constexpr int SET = decltype(set_c)::value;
-        const int m0 = mb + BK * st;
+        const int m0 = mb + BK * st, t0 = first_token(st);
         unsigned char* sA = lds + buf * WG_A_BYTES;
         unsigned char* sB = lds + 2 * WG_A_BYTES + buf * WG_B_BYTES;
+        if (cols_full && st < nst && m0 + BK <= me) {   // a whole stage, whole columns (wave-uniform): the registers as they are
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-            *reinterpret_cast<u4*>(sA + (ar + 16 * u) * WG_A_PITCH + 16 * ac) = (a_ok && m0 + ar + 16 * u < me) ? va[SET][u] : zero4;
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<u4*>(sA + (ar + 16 * u) * WG_A_PITCH + 16 * ac) = va[SET][u];
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
-            *reinterpret_cast<u4*>(sB + (br + 32 * u) * WG_B_PITCH + 16 * bc) = (b_ok && m0 + br + 32 * u < me) ? vb[SET][u] : zero4;
+            for (int u = 0; u < 2; ++u) *reinterpret_cast<u4*>(sB + (br + 32 * u) * WG_B_PITCH + 16 * bc) = vb[SET][u];
+        } else if (st >= nst) {   // past the range: a tile of zeros
+#pragma unroll
+            for (int u = 0; u < 4; ++u) *reinterpret_cast<u4*>(sA + (ar + 16 * u) * WG_A_PITCH + 16 * ac) = zero4;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) *reinterpret_cast<u4*>(sB + (br + 32 * u) * WG_B_PITCH + 16 * bc) = zero4;
+        } else {
+            // fetched row r holds token t0 + r; it belongs to the stage when that lies in [m0, me), and its tile row
+            // is token - m0.  shift = m0 - t0 > 0 only for the last stage of the matrices: fetched rows [shift, 64)
+            // fill tile rows [0, 64 - shift), the rest of the tile is zero.
+            const int shift = m0 - t0;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int r = ar + 16 * u, tok = t0 + r;
+                if (r >= shift) *reinterpret_cast<u4*>(sA + (r - shift) * WG_A_PITCH + 16 * ac) = (a_ok && tok < me) ? va[SET][u] : zero4;
+                if (r >= BK - shift) *reinterpret_cast<u4*>(sA + r * WG_A_PITCH + 16 * ac) = zero4;
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int r = br + 32 * u, tok = t0 + r;
+                if (r >= shift) *reinterpret_cast<u4*>(sB + (r - shift) * WG_B_PITCH + 16 * bc) = (b_ok && tok < me) ? vb[SET][u] : zero4;
+                if (r >= BK - shift) *reinterpret_cast<u4*>(sB + r * WG_B_PITCH + 16 * bc) = zero4;
+            }
+        }
     };
 
     f16v acc[2];
@@ -1223,13 +1256,20 @@ __global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int 
         fetch(set_c, st + 3);
         __builtin_amdgcn_sched_barrier(0);   // issue the fetches first: they are what the stage waits for
         const uint32_t a0 = fa + cur * WG_A_BYTES, b0 = fb + cur * WG_B_BYTES;
+        // fragments are read one k-block ahead of the MFMAs that use them (one wave per SIMD: nothing else hides the LDS latency)
+        h8 a[2], bl[2], bh[2];
+        auto frags = [&](int ks) {
+            a[ks & 1] = frag(a0 + 16 * ks * WG_A_PITCH, WG_A_PITCH);
+            bl[ks & 1] = frag(b0 + 16 * ks * WG_B_PITCH, WG_B_PITCH);
+            bh[ks & 1] = frag(b0 + 16 * ks * WG_B_PITCH + 64, WG_B_PITCH);
+        };
+        frags(0);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const h8 a = frag(a0 + 16 * ks * WG_A_PITCH, WG_A_PITCH);
-            const h8 bl = frag(b0 + 16 * ks * WG_B_PITCH, WG_B_PITCH);
-            const h8 bh = frag(b0 + 16 * ks * WG_B_PITCH + 64, WG_B_PITCH);
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bl, acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, bh, acc[1], 0, 0, 0);
+            if (ks < 3) frags(ks + 1);
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks & 1], bl[ks & 1], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[ks & 1], bh[ks & 1], acc[1], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         put(std::integral_constant<int, (SET + 1) % 3>{}, st + 1, cur ^ 1);
         __syncthreads();
