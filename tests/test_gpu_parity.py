@@ -487,6 +487,15 @@ def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
         np.max(np.abs(copy.astype(np.float64) - h.w64)) <= np.max(np.abs(h.w64)) * 2.0 ** -11
     with pytest.raises(B.QeftError):
         B.qeft_linear_fwd(h.desc, w, xd, ws=ws[:n - 16])   # too small
+    # the weak block is trainable: a call after an update must not reuse the old copy
+    new_weak = (np.random.default_rng(3).standard_normal((oc, k)) * 0.05).astype(np.float16)
+    w.weak.copy_(torch.from_numpy(new_weak))
+    w64 = qo.dequantize(h.codes, h.scales, h.zeros, new_weak, 128)
+    y = B.qeft_linear_fwd(h.desc, w, xd, ws=ws[:n])
+    dx = B.qeft_linear_bwd_dx(h.desc, w, dyd, ws=ws[:n])
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), qo.linear_fwd(w64, x), "3-bit fwd after a weak-block update")
+    assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(w64, dy), "3-bit dX after a weak-block update")
 
 
 def test_backward_uses_current_weak_values():
