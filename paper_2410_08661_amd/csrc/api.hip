@@ -71,6 +71,23 @@ int check_matrix(const void* p, int64_t M, int64_t ld, int64_t width) {
 
 inline int hip_status(hipError_t e) { return e == hipSuccess ? QEFT_OK : QEFT_ERR_HIP; }
 
+// Between the matrix-vector kernels (16 tokens per pass, the whole layer streamed per pass) and the tiled GEMM
+// (256-token tiles: with few tokens only OC / 256 workgroups exist, a fraction of the 256 CUs, and each walks the
+// whole K range) lies a range of token counts where repeated passes are faster.  Both are modelled from
+// measurements on the Llama-2 shapes: a pass takes about 4.5 us + stored bytes / 4 TB/s + 0.85 us per 1000
+// input channels, a GEMM ceil(tiles / 256) x stages x 1.15 us + 8 us; passes are taken when the model favours them by 10 %.
+// (4096 x 4096: up to 96 tokens, 62 us against 75; 28672 x 8192: up to 32, 102 us against 152.)  Layers under
+// 4 MB keep the GEMM: either way takes microseconds there.
+bool passes_beat_gemm(const Layer& L, int64_t M) {
+    if (M <= 16 || M > 256 || L.bits != 4) return false;
+    const double bytes = (double)L.oc * ((double)L.stride * 4.0 + (double)L.gs * 4.0 + (double)L.k * 2.0);
+    if (bytes < 4.0e6) return false;
+    const double passes = (double)((M + 15) / 16), t_pass = 4.5 + bytes / 4.0e6 + 0.85e-3 * (double)L.ic;
+    const double tiles = (double)((L.oc + 255) / 256), stages = (double)((L.kq + 63) / 64 + (L.k + 63) / 64);
+    const double t_gemm = (double)((int64_t)(tiles + 255.0) / 256) * stages * 1.15 + 8.0;
+    return passes * t_pass < 0.9 * t_gemm;
+}
+
 // 3-bit layers at GEMM sizes: the tiled kernels convert 4-bit codes only, so the layer is dequantized once
 // into a caller-provided fp16 [OC][IC] workspace and multiplied as a layer whose columns are all weak
 // (the paper's own training path: dequantize, then a dense product; Sec. 4.3 / App. A.2).
@@ -176,7 +193,8 @@ int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
     hipStream_t s = (hipStream_t)stream;
     const __half* x = (const __half*)X;
     __half* y = (__half*)Y;
-    if (M > 16 && gemm_fwd_supported(L, M)) return hip_status(gemm_fwd(L, x, M, ldx, y, ldy, s));
+    if (M > 16 && gemm_fwd_supported(L, M) && !(passes_beat_gemm(L, M) && gemv_supported(L, 16, ldx)))
+        return hip_status(gemm_fwd(L, x, M, ldx, y, ldy, s));
     if (ws && dense_copy_applies(L, M)) {
         if (!aligned16(ws)) return QEFT_ERR_ALIGN;
         if (ws_bytes < dense_copy_bytes(L)) return QEFT_ERR_WORKSPACE;

@@ -73,7 +73,7 @@ def _check(actual_t, pairs, ref, what):
 
 
 DECODE = [  # config, shapes, k, bits list, M list
-    (2, synth.LLAMA_7B, 128, [4], [1, 8]),
+    (2, synth.LLAMA_7B, 128, [4], [1, 8, 40, 100]),     # 40, 100: between the matrix-vector kernels and the GEMM
     (3, synth.LLAMA_13B, 128, [3, 4], [1, 3, 5, 16]),
     (3, synth.LLAMA_13B, 128, ["3d"], [1, 5, 16]),      # the dense 3-bit layout
     (5, synth.LLAMA_70B, 256, [4], [1, 4]),
