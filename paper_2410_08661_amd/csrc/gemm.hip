@@ -1141,8 +1141,11 @@ __global__ __launch_bounds__(256) void weak_grad_kernel(int oc_total, int k, con
 // Wave w multiplies weak columns 32 w .. 32 w + 31 against the 64 channels.  With one split
 // the result goes straight to dW, otherwise into fp32 slabs as above.
 constexpr int WG_OC = 64;                             // output channels per workgroup
-constexpr int WG_A_PITCH = 128 * 2 + 32;              // bytes per token row of the Xw tile
-constexpr int WG_B_PITCH = WG_OC * 2 + 32;            // ... of the dY tile
+// Row pitches: a transposing fragment read takes, per half wave, 4 rows x 64 bytes (two 16-lane groups side by
+// side), so consecutive rows must sit 16 (or 48) banks apart: 256 + 64 and 128 + 64 bytes.  (With + 32 bytes a
+// third of the LDS cycles of this kernel were bank conflicts.)
+constexpr int WG_A_PITCH = 128 * 2 + 64;              // bytes per token row of the Xw tile
+constexpr int WG_B_PITCH = WG_OC * 2 + 64;            // ... of the dY tile
 constexpr int WG_A_BYTES = BK * WG_A_PITCH, WG_B_BYTES = BK * WG_B_PITCH;
 constexpr int WG_LDS = 2 * (WG_A_BYTES + WG_B_BYTES); // A0 A1 B0 B1
 
@@ -1431,6 +1434,12 @@ hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t ld
     const int64_t n = (int64_t)oc * k;
     if (k <= 128) {
         weak_grad_strip_split(oc, M, splits, chunk);
+        static bool strip_attr = false;
+        if (!strip_attr) {
+            hipError_t e = hipFuncSetAttribute((const void*)weak_grad_strip_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS);
+            if (e != hipSuccess) return e;
+            strip_attr = true;
+        }
         weak_grad_strip_kernel<<<ceil_div(oc, WG_OC) * splits, 256, WG_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws,
                                                                                 splits, chunk, dW, out_f32, accumulate);
         if (splits > 1)
