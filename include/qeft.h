@@ -14,7 +14,8 @@
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers owned by the caller; the library
- *     allocates nothing, keeps no state and never synchronises.  Work is enqueued
+ *     allocates nothing, keeps no state (beyond "shared-memory limit of kernel X already raised" flags) and
+ *     never synchronises.  Work is enqueued
  *     on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
  *     ordered only by that stream.
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
@@ -79,10 +80,11 @@ typedef struct {
 } qeft_layout_t;
 
 /* The stored layer: four device pointers, borrowed for the duration of a call.
- *   qweight uint32 [OC][row_stride_words]  code i of a word at bits [b*i, b*i+b), lowest
- *                                          column first; 8 codes per word for 4-bit,
- *                                          10 for 3-bit (bits 30..31 zero); row padding
- *                                          words are zero.
+ *   qweight uint32 [OC][row_stride_words]  QEFT_LAYOUT_CANONICAL: code i of a word at bits
+ *                                          [b*i, b*i+b), lowest column first; 8 codes per word
+ *                                          for 4-bit, 10 for 3-bit (bits 30..31 zero).
+ *                                          QEFT_LAYOUT_DENSE3: see above.  Row padding words
+ *                                          (and bits past the last code) are zero.
  *   scales  fp16   [OC][group_stride]      entries past G are zero
  *   zeros   fp16   [OC][group_stride]      any fp16 value; qeft_pack writes integers
  *   weak    fp16   [OC][k]                 the trainable block; the caller's optimizer
@@ -145,15 +147,18 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
 size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
 
 /* Forward of the fused layer (Sec. 3.2.1): Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . weak^T in
- * one pass.  X fp16 [M][ldx] (ldx >= IC), Y fp16 [M][ldy] (ldy >= OC).  Small M runs a
- * bandwidth-bound matrix-vector kernel, large M a tiled MFMA GEMM. */
+ * one pass.  X fp16 [M][ldx] (ldx >= IC), Y fp16 [M][ldy] (ldy >= OC).  M <= 16 runs a
+ * bandwidth-bound matrix-vector kernel, large M a tiled MFMA GEMM; for the token counts in between (up to
+ * about 100, depending on the layer) several 16-token passes of the former where a host-side time model puts
+ * them ahead of a GEMM that would fill only a fraction of the GPU.  ws / ws_bytes: see qeft_workspace_bytes
+ * (only 3-bit layers use one; NULL / 0 is always valid). */
 int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* X, int64_t M,
                     int64_t ldx, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream);
 
 /* Forward of n (1 .. QEFT_MAX_GROUP) layers that read the same input, Y_i = X . W_i^T for each:
  * the query / key / value projections, or gate and up (Sec. 3.2.1; the weak columns are chosen
  * from the statistics of the layer's input, Sec. 3.1, so layers that share an input share
- * them).  The layers must agree in in_features, n_weak, bits and group_size; out_features may
+ * them).  The layers must agree in in_features, n_weak, bits, layout and group_size; out_features may
  * differ.  descs, w, Y and ldy are host arrays of n entries (w[i]'s device pointers and the
  * device buffer Y[i] fp16 [M][ldy[i]] are borrowed for the call).  Results equal those of n
  * qeft_linear_fwd calls up to summation order; decode-sized M runs them as one launch. */
