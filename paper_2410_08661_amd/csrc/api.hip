@@ -174,8 +174,11 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
         L.bits = desc->bits;
         L.oc = desc->out_features;
         L.ic = desc->in_features;
+        L.k = desc->n_weak;
+        L.g = desc->group_size;
         L.kq = desc->in_features - desc->n_weak;
         if (dense_copy_applies(L, M)) return dense_copy_bytes(L);
+        if (op == QEFT_OP_FWD && M > 16 && gemm_fwd_supported(L, M)) return gemm_fwd_split_workspace(L, M);
     }
     return 0;
 }
@@ -193,8 +196,16 @@ int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
     hipStream_t s = (hipStream_t)stream;
     const __half* x = (const __half*)X;
     __half* y = (__half*)Y;
-    if (M > 16 && gemm_fwd_supported(L, M) && !(passes_beat_gemm(L, M) && gemv_supported(L, 16, ldx)))
-        return hip_status(gemm_fwd(L, x, M, ldx, y, ldy, s));
+    if (M > 16 && gemm_fwd_supported(L, M)) {
+        // optional workspace: K-split partial tiles for launches of few tiles
+        const size_t need = ws ? gemm_fwd_split_workspace(L, M) : 0;
+        if (need > 0) {
+            if (!aligned16(ws)) return QEFT_ERR_ALIGN;
+            if (ws_bytes < need) return QEFT_ERR_WORKSPACE;
+        }
+        if (need > 0 ? M >= 48 : !(passes_beat_gemm(L, M) && gemv_supported(L, 16, ldx)))
+            return hip_status(gemm_fwd(L, x, M, ldx, y, ldy, need > 0 ? ws : nullptr, s));
+    }
     if (ws && dense_copy_applies(L, M)) {
         if (!aligned16(ws)) return QEFT_ERR_ALIGN;
         if (ws_bytes < dense_copy_bytes(L)) return QEFT_ERR_WORKSPACE;
@@ -202,7 +213,7 @@ int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
         if (gemm_fwd_supported(D, M)) {
             hipError_t e = dequantize_fp16(L, (__half*)ws, s);
             if (e != hipSuccess) return QEFT_ERR_HIP;
-            return hip_status(gemm_fwd(D, x, M, ldx, y, ldy, s));
+            return hip_status(gemm_fwd(D, x, M, ldx, y, ldy, nullptr, s));
         }
     }
     if (gemv_supported(L, M, ldx)) {

@@ -200,20 +200,30 @@ __device__ __forceinline__ void store_f16_lds_64x256(const f16v (&acc)[2][8], un
     }
 }
 
+// K split (splits > 1): workgroup (tile, sp) multiplies the quantized stages [sp * sps, (sp + 1) * sps) only - the last
+// split also the weak block - and stores its partial tile as fp16 into part[sp] ([M][ldy_part]); a second kernel adds the
+// partials.  For launches with too few tiles to occupy the CUs.  sps is a multiple of 8 stages, so every split starts on
+// a boundary of the four-group parameter fetches.
 __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
-                                                            __half* __restrict__ Y, int64_t ldy, int tiles_oc, int wide_stores) {
+                                                            __half* __restrict__ Y, int64_t ldy, int tiles_oc, int wide_stores,
+                                                            int splits, int sps, int64_t part_stride) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tile = xcd_tile(tiles_oc * ((M + BT - 1) / BT));
-    if (tile < 0) return;
+    const int tiles_all = tiles_oc * ((M + BT - 1) / BT);
+    const int tile_sp = xcd_tile(tiles_all * splits);
+    if (tile_sp < 0) return;
+    const int sp = tile_sp / tiles_all, tile = tile_sp - sp * tiles_all;
     const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
     const int oc0 = t_oc * BT, m0 = t_m * BT;
-    const int nq = L.kq / BK;
+    const bool last_split = sp == splits - 1;
+    const int s_first = sp * sps;                                      // first quantized stage of this workgroup
+    const int nq = splits > 1 ? min(sps, L.kq / BK - s_first) : L.kq / BK;
     // weak stages: whole 64-column stages take the direct path below (A fragments straight from the fp16
     // block), a ragged block the LDS-staged stages at the end
-    const int nwf = (L.k % BK == 0) ? L.k / BK : 0;
+    const int nwf = (L.k % BK == 0 && last_split) ? L.k / BK : 0;
     const int ns = nq + nwf;
+    if (splits > 1) Y += (size_t)sp * part_stride;
     const RegConsts cst = make_reg_consts();
     using lds_u4 = __attribute__((address_space(3))) u4;
     using lds_h8 = __attribute__((address_space(3))) h8;
@@ -223,10 +233,11 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const int fr = lane & 31, fk = lane >> 5;
 
     // global addresses: wave-uniform 64-bit base (scalar registers) + 32-bit lane offset
-    const char* wt = reinterpret_cast<const char*>(L.qweight + (size_t)oc0 * L.stride);
-    const char* st_ = reinterpret_cast<const char*>(L.scales + (size_t)oc0 * L.gs);
-    const char* zt = reinterpret_cast<const char*>(L.zeros + (size_t)oc0 * L.gs);
-    const char* xt = reinterpret_cast<const char*>(X + (size_t)m0 * ldx);
+    // (a stage is 32 bytes of codes per row, half a group = one byte of each parameter array per row, 128 bytes of X per token)
+    const char* wt = reinterpret_cast<const char*>(L.qweight + (size_t)oc0 * L.stride) + 32 * s_first;
+    const char* st_ = reinterpret_cast<const char*>(L.scales + (size_t)oc0 * L.gs) + s_first;
+    const char* zt = reinterpret_cast<const char*>(L.zeros + (size_t)oc0 * L.gs) + s_first;
+    const char* xt = reinterpret_cast<const char*>(X + (size_t)m0 * ldx) + 2 * BK * s_first;
     const char* wk = reinterpret_cast<const char*>(L.weak + (size_t)oc0 * L.k);
     uint32_t aoff[2], szoff[2], xoff[8];
 #pragma unroll
@@ -298,7 +309,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
 
     // weak block operands: chunk u of this thread is tile row xr + 32 u, 16-byte column xc of the stage
     // (branch-free fetches: columns past k read the row's last 8 and are zeroed when stored)
-    const int nw = nwf ? 0 : (L.k + BK - 1) / BK;
+    const int nw = (nwf || !last_split) ? 0 : (L.k + BK - 1) / BK;
     const u4 zero4 = u4{0u, 0u, 0u, 0u};
     u4 wa[8], wb[8];
     auto load_weak = [&](int w) {
@@ -1354,7 +1365,61 @@ bool gemm_fwd_supported(const Layer& L, int64_t M) {
     return M >= 1 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0 && (L.oc % 8) == 0;
 }
 
-hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
+namespace {
+// Sum of the K-split partial tiles: 8 outputs (16 bytes) per thread, fp32 sum in split order, one rounding.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const __half* __restrict__ part, int splits, int64_t part_stride, int M,
+                                                            int oc, int64_t ldp, __half* __restrict__ Y, int64_t ldy) {
+    const int chunks = (oc + 7) >> 3;
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (int64_t)M * chunks) return;
+    const int m = (int)(t / chunks), c = (int)(t % chunks);
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int p = 0; p < splits; ++p) {
+        const u4 v = ld16(part + (size_t)p * part_stride + (size_t)m * ldp + 8 * c);
+        const h8 h = __builtin_bit_cast(h8, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += (float)h[e];
+    }
+    __half* y = Y + (size_t)m * ldy + 8 * c;
+    if (8 * c + 8 <= oc && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0) {
+        h8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (_Float16)acc[e];
+        *reinterpret_cast<u4*>(y) = __builtin_bit_cast(u4, o);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (8 * c + e < oc) y[e] = __float2half_rn(acc[e]);
+    }
+}
+}  // namespace
+
+// K split of the forward for launches that would leave most CUs idle: as many splits as bring the number of
+// workgroups to about the number of CUs, each a multiple of 8 stages (512 columns), at most 16.
+void gemm_fwd_split(const Layer& L, int64_t M, int& splits, int& sps) {
+    splits = 1;
+    sps = 0;
+    if (L.kq <= 0 || L.kq % BK != 0) return;
+    const int tiles = ceil_div(L.oc, BT) * ceil_div(M, BT), nq = L.kq / BK, chunks = nq / 8;
+    if (tiles >= 160 || chunks < 2) return;
+    int want = 256 / tiles;
+    want = want > 16 ? 16 : want;
+    want = want > chunks ? chunks : want;
+    if (want < 2) return;
+    sps = ceil_div(chunks, want) * 8;
+    splits = ceil_div(nq, sps);
+    if (splits < 2) splits = 1;
+}
+
+size_t gemm_fwd_split_workspace(const Layer& L, int64_t M) {
+    int splits, sps;
+    gemm_fwd_split(L, M, splits, sps);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)((L.oc + 7) / 8 * 8) * sizeof(__half) : 0;
+}
+
+hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, void* ws, hipStream_t s) {
     const int tiles_oc = ceil_div(L.oc, BT), tiles_m = ceil_div(M, BT);
     hipError_t e;
     if (L.kq % BK == 0 && (L.kq > 0 || (L.k > 0 && L.k % BK == 0))) {   // whole stages: weights straight into MFMA operand registers
@@ -1364,8 +1429,19 @@ hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __h
             if (e != hipSuccess) return e;
             attr = true;
         }
+        int splits = 1, sps = 0;
+        if (ws) gemm_fwd_split(L, M, splits, sps);
+        if (splits > 1) {
+            const int64_t ldp = (L.oc + 7) / 8 * 8, part_stride = M * ldp;
+            __half* part = (__half*)ws;
+            gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m * splits), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, part, ldp, tiles_oc, 1, splits,
+                                                                                            sps, part_stride);
+            const int64_t n = M * (ldp / 8);
+            splitk_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>(part, splits, part_stride, (int)M, L.oc, ldp, Y, ldy);
+            return hipGetLastError();
+        }
         const int wide = (ldy % 8 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
-        gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide);
+        gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide, 1, 0, 0);
     } else {
         static bool attr = false;
         e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);

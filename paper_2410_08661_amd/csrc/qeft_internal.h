@@ -98,7 +98,9 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M, in
 
 // ---- prefill / fine-tune path: MFMA GEMMs (gemm.hip) ---------------------------------------
 bool gemm_fwd_supported(const Layer& L, int64_t M);
-hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s);
+// ws: optional device workspace of gemm_fwd_split_workspace() bytes (16-byte aligned); with it, launches of few tiles split K
+hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, void* ws, hipStream_t s);
+size_t gemm_fwd_split_workspace(const Layer& L, int64_t M);
 bool gemm_dx_supported(const Layer& L, int64_t M);
 hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s);
 bool weak_grad_mfma_supported(int oc, int k, int64_t M);

@@ -460,6 +460,35 @@ def test_weak_grad_parity(oc, ic, k, bits, g, m, compact):
     assert_close(dw16.cpu().numpy(), ref, f"dW overwrite {oc}x{k}")
 
 
+@pytest.mark.parametrize("oc,ic,k,m", [
+    (256, 4096 + 128, 128, 300),     # 2 tiles, 64 quantized stages: 8 splits of 8 stages, the weak block in the last
+    (528, 2560 + 64, 64, 64),        # 3 tiles (one ragged), 40 stages: 5 splits
+    (200, 1088 + 72, 72, 130),       # 17 stages: splits of 16 and 1 stage, ragged weak block (LDS-staged weak stages in the last split)
+    (1000, 3072, 0, 100),            # no weak block
+])
+def test_forward_k_split_with_workspace(oc, ic, k, m):
+    """Forward launches of few tiles: with the optional workspace the K range is split over workgroups and the
+    fp16 partial tiles are summed by a second kernel; without it one workgroup per tile walks the whole range."""
+    h = HostLayer(oc, ic, k, 4, 128, seed=oc + ic)
+    w = h.to_device()
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m)
+    assert n > 0 and n % (m * ((oc + 7) // 8 * 8) * 2) == 0
+    x = synth.make_activations(m, ic, k, seed=m)
+    xv, _ = pad_cols(x)
+    ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
+    ybuf = torch.full((m, oc + 8), -5.0, dtype=torch.float16, device="cuda")
+    ref = qo.linear_fwd(h.w64, x)
+    for use_ws in (ws[:n], False):
+        ybuf.fill_(-5.0)
+        B.qeft_linear_fwd(h.desc, w, xv, ybuf[:, :oc], ws=use_ws)
+        torch.cuda.synchronize()
+        assert_close(ybuf[:, :oc].cpu().numpy(), ref, f"fwd {oc}x{ic} M{m} ws={use_ws is not False}")
+        assert torch.all(ybuf[:, oc:] == -5.0)
+    assert torch.all(ws[n:] == 0x7f)
+    with pytest.raises(B.QeftError):
+        B.qeft_linear_fwd(h.desc, w, xv, ws=ws[:n - 16])   # too small
+
+
 @pytest.mark.parametrize("dense", [False, True])
 @pytest.mark.parametrize("oc,ic,k,m", [(320, 1280 + 128, 128, 300), (264, 512 + 64, 64, 40)])
 def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
