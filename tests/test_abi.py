@@ -120,6 +120,21 @@ def test_three_bit_workspace_rules():
     assert B.qeft_workspace_bytes(B.make_desc(64, 260, 128, 3), B.QEFT_OP_FWD, 4096) == 0       # IC not a multiple of 8: general kernel
 
 
+def test_forward_k_split_workspace_rules():
+    """4-bit forward launches with few output tiles may split K over an optional workspace of fp16 partial tiles."""
+    fwd = B.raw.qeft_linear_fwd
+    X, Y, WS = 0x10000, 0x2000000, 0x40000000
+    d = B.make_desc(1024, 8192, 256, 4)                      # 4 x 8 tiles at M = 2048, 124 quantized stages: 8 splits of 16
+    need = B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 2048)
+    assert need == 8 * 2048 * 1024 * 2
+    assert B.qeft_workspace_bytes(d, B.QEFT_OP_BWD_DX, 2048) == 0
+    assert B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 16) == 0                                    # decode sizes
+    assert B.qeft_workspace_bytes(B.make_desc(4096, 4096, 128, 4), B.QEFT_OP_FWD, 4096) == 0     # 256 tiles: no split
+    assert B.qeft_workspace_bytes(B.make_desc(4096, 4096, 128, 4), B.QEFT_OP_FWD, 256) == 4 * 256 * 4096 * 2 * 2   # 16 tiles, 62 stages: 7 chunks -> 8 splits
+    assert fwd(C.byref(d), C.byref(_w()), X, 2048, 8192, Y, 1024, WS, need - 2, None) == B.QEFT_ERR_WORKSPACE
+    assert fwd(C.byref(d), C.byref(_w()), X, 2048, 8192, Y, 1024, WS + 8, need, None) == B.QEFT_ERR_ALIGN
+
+
 def test_forward_group_validation():
     grp = B.raw.qeft_linear_fwd_group
     X = 0x10000
