@@ -5,13 +5,14 @@
 //   backward   dX[M][IC]  = dY . W              contraction over OC, through the full mixed weight
 //   weak grad  dW[OC][k]  = dY^T . X[:, weak]   contraction over the M tokens (Eq. 5, weak block only)
 //
-// Two generations of kernels live here.
+// Two families of kernels live here.
 //   * gemm_fwd_rega_kernel / gemm_dx_rega_kernel: the 4-bit codes are dequantized straight into the
 //     MFMA operand registers of the wave that multiplies them; LDS carries only the fp16 activation
 //     tile (and, for dX, the raw codes transposed at 16-bit granularity).  Waves are stacked
 //     along the weight rows (64 rows x 256 tokens each) so that every code is converted once;
-//     software-pipelined in steps of one MFMA with static LDS / global addressing.  Described
-//     at each kernel.
+//     software-pipelined in steps of one MFMA with static LDS / global addressing.  The forward
+//     kernel can also split the K range over workgroups (few output tiles: fp16 partial tiles in a
+//     workspace, summed by splitk_reduce_kernel).  Described at each kernel.
 //   * gemm_fwd_kernel / gemm_dx_kernel: producer threads dequantize into an fp16 weight tile in
 //     LDS.  Simpler, LDS-bound, kept for the shapes the register kernels do not take.
 //
