@@ -271,10 +271,18 @@ def main():
     del w3
 
     # a plain device copy of known size: the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
+    # (timed as well: what a plain copy reaches on this machine, read + written bytes per second, as context for the HBM fraction)
     cal = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
     cal2 = torch.empty_like(cal)
     cal2.copy_(cal)
     torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(5):
+        cal2.copy_(cal)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * cal.numel() * 4 / (e0.elapsed_time(e1) * 1e-3 / 5) / 1e9
     del cal, cal2
 
     seg = np.array([[m[j].elapsed_time(m[j + 1]) for j in range(len(m) - 1)] for m in records])   # ms
@@ -330,6 +338,8 @@ def main():
                                "decode_us_reordered": next(dk["us"] for dk in decode_kernels if dk["launch"] == "o"),
                                "fwd_M4096_us": round(irr_ft_us, 1), "fwd_M4096_us_reordered": kernels[0]["fwd_us"]},
         "three_bit": three_bit,
+        "device_copy_gbs": round(copy_gbs, 1),
+        "pct_of_device_copy": round(100 * gemv_gbs / copy_gbs, 1),
         "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_kernel_gbs / HBM_PEAK_GBS, 4),
                           "traffic": round(TRAFFIC_GEMV_BYTES),
