@@ -141,10 +141,11 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
 /* Bytes of device workspace an operation can use for M rows (0 if none).  QEFT_OP_WEAK_GRAD and the
  * irregular operations require theirs; those of QEFT_OP_FWD / QEFT_OP_BWD_DX are optional (NULL is always valid,
  * a workspace that is given must be 16-byte aligned and large enough, else QEFT_ERR_ALIGN / QEFT_ERR_WORKSPACE).
- * QEFT_OP_FWD, 4-bit layers at M > 16 whose GEMM would have too few 256 x 256 output tiles to occupy the GPU
- * (fewer than 160): splits * M * roundup8(OC) * 2 bytes; with it the K range is split over up to 16 workgroups per
- * tile, partial tiles are stored as fp16 and summed in fp32 by a second kernel (one extra fp16 rounding per split;
- * 1024 x 8192 at M = 2048: 46 us against 150 us).
+ * QEFT_OP_FWD / QEFT_OP_BWD_DX, 4-bit layers at M > 16 whose GEMM would have too few 256 x 256 output tiles to
+ * occupy the GPU (fewer than 160): splits * M * roundup8(OC or IC) * 2 bytes; with it the contraction range (input
+ * channels for the forward, weight rows for the input gradient) is split over up to 16 workgroups per tile,
+ * partial tiles are stored as fp16 and summed in fp32 by a second kernel (one extra fp16 rounding per split;
+ * forward of 1024 x 8192 at M = 2048: 46 us against 150 us).
  * QEFT_OP_FWD / QEFT_OP_BWD_DX report OC * IC * 2 bytes for 3-bit layers
  * at M > 16: with that workspace (16-byte aligned) the call dequantizes the layer once into it as fp16 and
  * runs the tensor-core kernels on the copy - the paper's own training path, dequantize then a dense product

@@ -179,6 +179,7 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
         L.kq = desc->in_features - desc->n_weak;
         if (dense_copy_applies(L, M)) return dense_copy_bytes(L);
         if (op == QEFT_OP_FWD && M > 16 && gemm_fwd_supported(L, M)) return gemm_fwd_split_workspace(L, M);
+        if (op == QEFT_OP_BWD_DX && gemm_dx_supported(L, M)) return gemm_dx_split_workspace(L, M);
     }
     return 0;
 }
@@ -270,7 +271,14 @@ int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const vo
     if (st != QEFT_OK) return st;
     if (M == 0) return QEFT_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (gemm_dx_supported(L, M)) return hip_status(gemm_dx(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+    if (gemm_dx_supported(L, M)) {
+        const size_t need = ws ? gemm_dx_split_workspace(L, M) : 0;   // optional: partial tiles of a row split
+        if (need > 0) {
+            if (!aligned16(ws)) return QEFT_ERR_ALIGN;
+            if (ws_bytes < need) return QEFT_ERR_WORKSPACE;
+        }
+        return hip_status(gemm_dx(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, need > 0 ? ws : nullptr, s));
+    }
     if (ws && dense_copy_applies(L, M)) {
         if (!aligned16(ws)) return QEFT_ERR_ALIGN;
         if (ws_bytes < dense_copy_bytes(L)) return QEFT_ERR_WORKSPACE;
@@ -278,7 +286,7 @@ int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const vo
         if (gemm_dx_supported(D, M)) {
             hipError_t e = dequantize_fp16(L, (__half*)ws, s);
             if (e != hipSuccess) return QEFT_ERR_HIP;
-            return hip_status(gemm_dx(D, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));
+            return hip_status(gemm_dx(D, (const __half*)dY, M, lddy, (__half*)dX, lddx, nullptr, s));
         }
     }
     return hip_status(bwd_dx_generic(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));

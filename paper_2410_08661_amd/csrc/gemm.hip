@@ -1083,11 +1083,27 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
     }
 }
 
+// splits > 1: workgroup (tile, sp) contracts over the weight rows [sp * rps, (sp + 1) * rps) only (rps a multiple of
+// 64: whole stages) and stores its partial tile as fp16 into dX + sp * part_stride; splitk_reduce_kernel adds them.
+// The rows of a stored layer are independent, so a split is simply the layer made of those rows.
 __global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
-                                                           __half* __restrict__ dX, int64_t lddx, int tiles_ic) {
+                                                           __half* __restrict__ dX, int64_t lddx, int tiles_ic, int splits,
+                                                           int rps, int64_t part_stride) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
-    const int tile = xcd_tile(tiles_ic * ((M + BT - 1) / BT));
-    if (tile < 0) return;
+    const int tiles_all = tiles_ic * ((M + BT - 1) / BT);
+    const int tile_sp = xcd_tile(tiles_all * splits);
+    if (tile_sp < 0) return;
+    const int sp = tile_sp / tiles_all, tile = tile_sp - sp * tiles_all;
+    if (splits > 1) {
+        const int r0 = sp * rps;
+        L.qweight += (size_t)r0 * L.stride;
+        L.scales += (size_t)r0 * L.gs;
+        L.zeros += (size_t)r0 * L.gs;
+        L.weak += (size_t)r0 * L.k;
+        L.oc = min(rps, L.oc - r0);
+        dY += r0;
+        dX += (size_t)sp * part_stride;
+    }
     const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
     const int ic0 = t_ic * BT, m0 = t_m * BT;
     // a half is weak when it starts at or past Kq (Kq % 128 == 0); without a weak block the surplus
@@ -1457,7 +1473,29 @@ bool gemm_dx_supported(const Layer& L, int64_t M) {
            (L.ic % 8) == 0;
 }
 
-hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s) {
+// Row split of the input gradient for launches with few tiles, as for the forward: multiples of 8 stages (512 rows).
+void gemm_dx_split(const Layer& L, int64_t M, int& splits, int& rps) {
+    splits = 1;
+    rps = 0;
+    if (!(L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0)) return;
+    const int tiles = ceil_div(L.ic, BT) * ceil_div(M, BT), nst = L.oc / BK, chunks = nst / 8;
+    if (tiles >= 160 || chunks < 2) return;
+    int want = 256 / tiles;
+    want = want > 16 ? 16 : want;
+    want = want > chunks ? chunks : want;
+    if (want < 2) return;
+    rps = ceil_div(chunks, want) * 8 * BK;
+    splits = ceil_div(L.oc, rps);
+    if (splits < 2) splits = 1;
+}
+
+size_t gemm_dx_split_workspace(const Layer& L, int64_t M) {
+    int splits, rps;
+    gemm_dx_split(L, M, splits, rps);
+    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)((L.ic + 7) / 8 * 8) * sizeof(__half) : 0;
+}
+
+hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, void* ws, hipStream_t s) {
     const int tiles_m = ceil_div(M, BT), tiles_ic = ceil_div(L.ic, BT);
     hipError_t e;
     if (L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0) {
@@ -1467,7 +1505,18 @@ hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __
             if (e != hipSuccess) return e;
             attr = true;
         }
-        gemm_dx_rega_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic);
+        int splits = 1, rps = 0;
+        if (ws) gemm_dx_split(L, M, splits, rps);
+        if (splits > 1) {
+            const int64_t ldp = (L.ic + 7) / 8 * 8, part_stride = M * ldp;
+            __half* part = (__half*)ws;
+            gemm_dx_rega_kernel<<<xcd_grid(tiles_ic * tiles_m * splits), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, part, ldp, tiles_ic, splits, rps,
+                                                                                          part_stride);
+            const int64_t n = M * (ldp / 8);
+            splitk_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>(part, splits, part_stride, (int)M, L.ic, ldp, dX, lddx);
+            return hipGetLastError();
+        }
+        gemm_dx_rega_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic, 1, 0, 0);
     } else {
         static bool attr = false;
         e = raise_lds_limit((const void*)gemm_dx_kernel, attr);

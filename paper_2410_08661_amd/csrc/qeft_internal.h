@@ -102,7 +102,8 @@ bool gemm_fwd_supported(const Layer& L, int64_t M);
 hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, void* ws, hipStream_t s);
 size_t gemm_fwd_split_workspace(const Layer& L, int64_t M);
 bool gemm_dx_supported(const Layer& L, int64_t M);
-hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, hipStream_t s);
+hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, void* ws, hipStream_t s);
+size_t gemm_dx_split_workspace(const Layer& L, int64_t M);
 bool weak_grad_mfma_supported(int oc, int k, int64_t M);
 size_t weak_grad_mfma_workspace(int oc, int k, int64_t M);
 hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,

@@ -127,7 +127,12 @@ def test_forward_k_split_workspace_rules():
     d = B.make_desc(1024, 8192, 256, 4)                      # 4 x 8 tiles at M = 2048, 124 quantized stages: 8 splits of 16
     need = B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 2048)
     assert need == 8 * 2048 * 1024 * 2
-    assert B.qeft_workspace_bytes(d, B.QEFT_OP_BWD_DX, 2048) == 0
+    assert B.qeft_workspace_bytes(d, B.QEFT_OP_BWD_DX, 2048) == 0                                # 32 x 8 tiles: no split
+    d4 = B.make_desc(4096, 4096, 128, 4)                     # input gradient at M = 256: 16 tiles, 64 stages of rows: 8 splits
+    need_dx = B.qeft_workspace_bytes(d4, B.QEFT_OP_BWD_DX, 256)
+    assert need_dx == 8 * 256 * 4096 * 2
+    assert B.raw.qeft_linear_bwd_dx(C.byref(d4), C.byref(_w()), X, 256, 4096, Y, 4096, WS, need_dx - 2, None) == B.QEFT_ERR_WORKSPACE
+    assert B.raw.qeft_linear_bwd_dx(C.byref(d4), C.byref(_w()), X, 256, 4096, Y, 4096, WS + 8, need_dx, None) == B.QEFT_ERR_ALIGN
     assert B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 16) == 0                                    # decode sizes
     assert B.qeft_workspace_bytes(B.make_desc(4096, 4096, 128, 4), B.QEFT_OP_FWD, 4096) == 0     # 256 tiles: no split
     assert B.qeft_workspace_bytes(B.make_desc(4096, 4096, 128, 4), B.QEFT_OP_FWD, 256) == 4 * 256 * 4096 * 2 * 2   # 16 tiles, 62 stages: 7 chunks -> 8 splits

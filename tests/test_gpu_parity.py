@@ -489,6 +489,34 @@ def test_forward_k_split_with_workspace(oc, ic, k, m):
         B.qeft_linear_fwd(h.desc, w, xv, ws=ws[:n - 16])   # too small
 
 
+@pytest.mark.parametrize("oc,ic,k,m", [
+    (4096, 256 + 128, 128, 300),     # 2 x 2 tiles (the second half weak, then empty), 64 stages of rows: 8 splits
+    (1088, 640, 0, 64),              # 17 stages: splits of 16 and 1, no weak block
+    (2560, 1024 + 64, 64, 130),      # mixed last tile, 40 stages: 5 splits
+])
+def test_backward_dx_row_split_with_workspace(oc, ic, k, m):
+    """Input-gradient launches of few tiles: with the optional workspace the weight rows are split over workgroups
+    (fp16 partial tiles, summed by a second kernel); without it one workgroup per tile walks all rows."""
+    h = HostLayer(oc, ic, k, 4, 128, seed=oc + ic)
+    w = h.to_device()
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    assert n > 0 and n % (m * ((ic + 7) // 8 * 8) * 2) == 0
+    dy = synth.make_grad_output(m, oc, seed=m)
+    dyv, _ = pad_cols(dy)
+    ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
+    buf = torch.full((m, ic + 8), -5.0, dtype=torch.float16, device="cuda")
+    ref = qo.linear_bwd_dx(h.w64, dy)
+    for use_ws in (ws[:n], False):
+        buf.fill_(-5.0)
+        B.qeft_linear_bwd_dx(h.desc, w, dyv, buf[:, :ic], ws=use_ws)
+        torch.cuda.synchronize()
+        assert_close(buf[:, :ic].cpu().numpy(), ref, f"dX {oc}x{ic} M{m} ws={use_ws is not False}")
+        assert torch.all(buf[:, ic:] == -5.0)
+    assert torch.all(ws[n:] == 0x7f)
+    with pytest.raises(B.QeftError):
+        B.qeft_linear_bwd_dx(h.desc, w, dyv, ws=ws[:n - 16])   # too small
+
+
 @pytest.mark.parametrize("dense", [False, True])
 @pytest.mark.parametrize("oc,ic,k,m", [(320, 1280 + 128, 128, 300), (264, 512 + 64, 64, 40)])
 def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
