@@ -1116,51 +1116,13 @@ __global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half
 
 // ======================================================================================= weak gradient
 // A[i = c][k = m] = Xw[m][c], B[j = oc][k = m] = dY[m][oc]: both operands are read transposed.
-// The tokens are split over `splits` workgroups per OC tile; each writes an fp32 partial
+// The tokens are split over `splits` workgroups per strip of output channels; each writes an fp32 partial
 // [OC][k] slab, summed in slab order by a second kernel (no atomics: deterministic).
-__global__ __launch_bounds__(256) void weak_grad_kernel(int oc_total, int k, const __half* __restrict__ dY, int M,
-                                                        int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
-                                                        float* __restrict__ part, int splits, int chunk) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
-    const int split = blockIdx.x % splits, t_oc = blockIdx.x / splits;
-    const int oc0 = t_oc * BT;
-    const int mb = split * chunk, me = min(mb + chunk, M);
-    const int nst = (me - mb + BK - 1) / BK;
-
-    f16v acc[4][4];
-    zero_acc(acc);
-    ColLoader la, lb;
-    if (nst > 0) {
-        la.load(Xw, ldxw, mb, me, 0, k, tid);
-        lb.load(dY, lddy, mb, me, oc0, oc_total, tid);
-        la.store(lds, tid);
-        lb.store(lds + 2 * TILE_BYTES, tid);
-    }
-    __syncthreads();
-    for (int st = 0; st < nst; ++st) {
-        const int cur = st & 1;
-        if (st + 1 < nst) {
-            la.load(Xw, ldxw, mb + BK * (st + 1), me, 0, k, tid);
-            lb.load(dY, lddy, mb + BK * (st + 1), me, oc0, oc_total, tid);
-        }
-        compute_stage(lds + cur * TILE_BYTES, lds + (2 + cur) * TILE_BYTES, acc, wm, wn, lane);
-        if (st + 1 < nst) {
-            la.store(lds + (cur ^ 1) * TILE_BYTES, tid);
-            lb.store(lds + (2 + (cur ^ 1)) * TILE_BYTES, tid);
-        }
-        __syncthreads();
-    }
-    store_f32(acc, part + (size_t)split * oc_total * k, k, 0, k, oc0, oc_total, wm, wn, lane);
-}
-
-// The same for k <= 128 (the paper's settings), sized for what bounds it - reading dY once from
-// HBM: a workgroup owns 64 output channels x all k weak columns over a range of tokens, so the
+// The kernel is sized for what bounds it - reading dY once from
+// HBM: a workgroup owns 64 output channels x up to 128 weak columns over a range of tokens, so the
 // MFMA tiles hold no padding and a dY row contributes 128 contiguous bytes.  Both operands have
 // the contraction index (the token) as their row index; instead of transposing 8 x 8 blocks in
-// registers, the tiles go to LDS as they are ([token][column], rows padded by 32 bytes) and the
+// registers, the tiles go to LDS as they are ([token][column], rows padded by 64 bytes) and the
 // fragments are read with the transposing LDS load of gfx950 (ds_read_b64_tr_b16: the 16 lanes
 // of a group each name 4 consecutive halfs; output lane l receives element l % 4 of source
 // lanes l / 4, l / 4 + 4, l / 4 + 8, l / 4 + 12).  With source lane s pointing at row k0 + s / 4,
@@ -1177,7 +1139,9 @@ constexpr int WG_B_PITCH = WG_OC * 2 + 64;            // ... of the dY tile
 constexpr int WG_A_BYTES = BK * WG_A_PITCH, WG_B_BYTES = BK * WG_B_PITCH;
 constexpr int WG_LDS = 2 * (WG_A_BYTES + WG_B_BYTES); // A0 A1 B0 B1
 
-__global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int k, const __half* __restrict__ dY, int M,
+// A weak block wider than 128 columns is taken in halves of 128 (workgroup index = ((strip, half), split)): the two halves
+// of a strip read the same dY rows and sit next to each other in the grid.
+__global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int k_total, const __half* __restrict__ dY, int M,
                                                               int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
                                                               float* __restrict__ part, int splits, int chunk, void* dW,
                                                               int out_f32, int accumulate) {
@@ -1187,7 +1151,11 @@ __global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int 
     using lds_s4 = __attribute__((address_space(3))) s4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int split = blockIdx.x % splits, t_oc = blockIdx.x / splits;
+    const int halves = (k_total + 127) >> 7;
+    const int split = blockIdx.x % splits, rest = blockIdx.x / splits;
+    const int kh = rest % halves, t_oc = rest / halves;
+    const int k = min(128, k_total - 128 * kh);   // this workgroup's weak columns: 128 kh .. 128 kh + k - 1
+    Xw += 128 * kh;
     const int oc0 = t_oc * WG_OC;
     const int mb = split * chunk, me = min(mb + chunk, M);
     const int nst = (me - mb + BK - 1) / BK;
@@ -1328,9 +1296,9 @@ __global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int 
             const int i = 32 * wave + 8 * q + 4 * fk;
             if (i >= k) continue;
             f4 r = f4{acc[t][4 * q + 0], acc[t][4 * q + 1], acc[t][4 * q + 2], acc[t][4 * q + 3]};
-            const size_t at = (size_t)j * k + i;
+            const size_t at = (size_t)j * k_total + 128 * kh + i;
             if (splits > 1) {
-                *reinterpret_cast<f4*>(part + (size_t)split * oc_total * k + at) = r;
+                *reinterpret_cast<f4*>(part + (size_t)split * oc_total * k_total + at) = r;
             } else if (out_f32) {
                 f4* o = reinterpret_cast<f4*>((float*)dW + at);
                 *o = accumulate ? *o + r : r;
@@ -1363,17 +1331,6 @@ hipError_t raise_lds_limit(const void* fn, bool& done) {
     hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, GEMM_LDS);
     if (e == hipSuccess) done = true;
     return e;
-}
-
-// tokens per split: whole stages, enough workgroups to cover the CUs
-void weak_grad_split(int oc, int64_t M, int& splits, int& chunk) {
-    const int oc_tiles = ceil_div(oc, BT);
-    const int stages = ceil_div(M, BK);
-    int want = ceil_div(256, oc_tiles);
-    if (want > stages) want = stages;
-    if (want < 1) want = 1;
-    chunk = ceil_div(stages, want) * BK;
-    splits = ceil_div(M, chunk);
 }
 
 }  // namespace
@@ -1533,8 +1490,8 @@ bool weak_grad_mfma_supported(int oc, int k, int64_t M) {
 namespace {
 // split of the tokens for the strip kernel: about one workgroup per CU (more splits would add
 // slab traffic comparable to dY itself), every split a whole number of stages
-void weak_grad_strip_split(int oc, int64_t M, int& splits, int& chunk) {
-    const int tiles = ceil_div(oc, WG_OC);
+void weak_grad_strip_split(int oc, int k, int64_t M, int& splits, int& chunk) {
+    const int tiles = ceil_div(oc, WG_OC) * ceil_div(k, 128);
     const int stages = ceil_div(M, BK);
     int want = ceil_div(256, tiles);
     if (want > stages) want = stages;
@@ -1546,39 +1503,24 @@ void weak_grad_strip_split(int oc, int64_t M, int& splits, int& chunk) {
 
 size_t weak_grad_mfma_workspace(int oc, int k, int64_t M) {
     int splits, chunk;
-    if (k <= 128) {
-        weak_grad_strip_split(oc, M, splits, chunk);
-        return splits > 1 ? (size_t)splits * oc * k * sizeof(float) : 0;
-    }
-    weak_grad_split(oc, M, splits, chunk);
-    return (size_t)splits * oc * k * sizeof(float);
+    weak_grad_strip_split(oc, k, M, splits, chunk);
+    return splits > 1 ? (size_t)splits * oc * k * sizeof(float) : 0;
 }
 
 hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
                           void* dW, int out_f32, int accumulate, void* ws, hipStream_t s) {
     int splits, chunk;
     const int64_t n = (int64_t)oc * k;
-    if (k <= 128) {
-        weak_grad_strip_split(oc, M, splits, chunk);
-        static bool strip_attr = false;
-        if (!strip_attr) {
-            hipError_t e = hipFuncSetAttribute((const void*)weak_grad_strip_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS);
-            if (e != hipSuccess) return e;
-            strip_attr = true;
-        }
-        weak_grad_strip_kernel<<<ceil_div(oc, WG_OC) * splits, 256, WG_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws,
-                                                                                splits, chunk, dW, out_f32, accumulate);
-        if (splits > 1)
-            weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
-        return hipGetLastError();
+    weak_grad_strip_split(oc, k, M, splits, chunk);
+    static bool strip_attr = false;
+    if (!strip_attr) {
+        hipError_t e = hipFuncSetAttribute((const void*)weak_grad_strip_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, WG_LDS);
+        if (e != hipSuccess) return e;
+        strip_attr = true;
     }
-    static bool attr = false;
-    hipError_t e = raise_lds_limit((const void*)weak_grad_kernel, attr);
-    if (e != hipSuccess) return e;
-    weak_grad_split(oc, M, splits, chunk);
-    weak_grad_kernel<<<ceil_div(oc, BT) * splits, 256, GEMM_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws,
-                                                                     splits, chunk);
-    weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
+    weak_grad_strip_kernel<<<ceil_div(oc, WG_OC) * ceil_div(k, 128) * splits, 256, WG_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws, splits,
+                                                                                          chunk, dW, out_f32, accumulate);
+    if (splits > 1) weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
     return hipGetLastError();
 }
 
