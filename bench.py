@@ -34,8 +34,8 @@ MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
 # the launches of the kernel in one step
-TRAFFIC_DX_BYTES = (113.5e6 + 34.3e6 + 331.9e6 + 34.3e6 + 484.5e6 + 90.9e6) / 3
-TRAFFIC_GEMV_BYTES = (29.34e6 + 9.94e6 + 52.38e6 + 25.22e6) / 4
+TRAFFIC_DX_BYTES = (114.3e6 + 34.3e6 + 339.3e6 + 34.3e6 + 485.3e6 + 90.9e6) / 3
+TRAFFIC_GEMV_BYTES = (29.31e6 + 9.90e6 + 52.40e6 + 25.21e6) / 4
 
 
 def main():
