@@ -14,8 +14,8 @@
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers owned by the caller; the library
- *     allocates nothing, keeps no state (beyond "shared-memory limit of kernel X already raised" flags) and
- *     never synchronises.  Work is enqueued
+ *     allocates nothing, keeps no state (beyond "shared-memory limit of kernel X already raised" flags, which
+ *     assume one GPU per process, the way this library is meant to be deployed) and never synchronises.  Work is enqueued
  *     on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
  *     ordered only by that stream.
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
