@@ -141,11 +141,13 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
 /* Bytes of device workspace an operation can use for M rows (0 if none).  QEFT_OP_WEAK_GRAD and the
  * irregular operations require theirs; those of QEFT_OP_FWD / QEFT_OP_BWD_DX are optional (NULL is always valid,
  * a workspace that is given must be 16-byte aligned and large enough, else QEFT_ERR_ALIGN / QEFT_ERR_WORKSPACE).
- * QEFT_OP_FWD / QEFT_OP_BWD_DX, 4-bit layers at M > 16 whose GEMM would have too few 256 x 256 output tiles to
- * occupy the GPU (fewer than 160): splits * M * roundup8(OC or IC) * 2 bytes; with it the contraction range (input
- * channels for the forward, weight rows for the input gradient) is split over up to 16 workgroups per tile,
- * partial tiles are stored as fp16 and summed in fp32 by a second kernel (one extra fp16 rounding per split;
- * forward of 1024 x 8192 at M = 2048: 46 us against 150 us).
+ * QEFT_OP_FWD / QEFT_OP_BWD_DX, 4-bit layers at M > 16 whose GEMM would leave compute units idle: split tiles *
+ * splits * 128 KiB (one 256 x 256 fp16 partial tile per split).  With it the contraction range (input channels for
+ * the forward, weight rows for the input gradient) of those tiles is split over several workgroups, partial tiles are
+ * stored as fp16 and summed in fp32 by a second kernel (one extra fp16 rounding per split).  Two cases: fewer than
+ * 160 output tiles - every tile, up to 16 splits (forward of 1024 x 8192 at M = 2048: 46 us against 150 us); or a
+ * last round of tiles that fills at most half of the compute units - those tiles only, up to 8 splits, at most
+ * 32 MiB (forward of 5120 x 13824 at M = 4096, 320 tiles on 256 units: 515 us against 651 us).
  * QEFT_OP_FWD / QEFT_OP_BWD_DX report OC * IC * 2 bytes for 3-bit layers
  * at M > 16: with that workspace (16-byte aligned) the call dequantizes the layer once into it as fp16 and
  * runs the tensor-core kernels on the copy - the paper's own training path, dequantize then a dense product

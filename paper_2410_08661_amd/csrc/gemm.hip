@@ -201,30 +201,36 @@ __device__ __forceinline__ void store_f16_lds_64x256(const f16v (&acc)[2][8], un
     }
 }
 
-// K split (splits > 1): workgroup (tile, sp) multiplies the quantized stages [sp * sps, (sp + 1) * sps) only - the last
-// split also the weak block - and stores its partial tile as fp16 into part[sp] ([M][ldy_part]); a second kernel adds the
-// partials.  For launches with too few tiles to occupy the CUs.  sps is a multiple of 8 stages, so every split starts on
-// a boundary of the four-group parameter fetches.
+// K split (splits > 1): a workgroup (tile, sp) of a split tile multiplies the quantized stages [sp * sps, (sp + 1) * sps)
+// only - the last split also the weak block - and stores its partial tile as fp16 into its slot of `part` (BT rows of
+// BT halves); splitk_reduce_kernel adds the partials.  Either every tile is split (launches with too few tiles to occupy
+// the CUs) or only those of the last, partly filled round (split_tile).  sps is a multiple of 8 stages, so every split
+// starts on a boundary of the four-group parameter fetches.
 __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __half* __restrict__ X, int M, int64_t ldx,
                                                             __half* __restrict__ Y, int64_t ldy, int tiles_oc, int wide_stores,
-                                                            int splits, int sps, int64_t part_stride) {
+                                                            int splits, int sps, int tail_first, __half* __restrict__ part) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tiles_all = tiles_oc * ((M + BT - 1) / BT);
-    const int tile_sp = xcd_tile(tiles_all * splits);
-    if (tile_sp < 0) return;
-    const int sp = tile_sp / tiles_all, tile = tile_sp - sp * tiles_all;
+    int tile, sp, slot;
+    if (!split_tile(tiles_all, tail_first, splits, tile, sp, slot)) return;
     const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
     const int oc0 = t_oc * BT, m0 = t_m * BT;
-    const bool last_split = sp == splits - 1;
+    const bool is_split = slot >= 0;
+    const bool last_split = !is_split || sp == splits - 1;
     const int s_first = sp * sps;                                      // first quantized stage of this workgroup
-    const int nq = splits > 1 ? min(sps, L.kq / BK - s_first) : L.kq / BK;
+    const int nq = is_split ? min(sps, L.kq / BK - s_first) : L.kq / BK;
     // weak stages: whole 64-column stages take the direct path below (A fragments straight from the fp16
     // block), a ragged block the LDS-staged stages at the end
     const int nwf = (L.k % BK == 0 && last_split) ? L.k / BK : 0;
     const int ns = nq + nwf;
-    if (splits > 1) Y += (size_t)sp * part_stride;
+    if (is_split) {
+        // the epilogue addresses Y[m][oc] with absolute indices: point it at the slot's (m0, oc0)
+        Y = part + (size_t)slot * (BT * BT) - ((size_t)m0 * BT + oc0);
+        ldy = BT;
+        wide_stores = 1;
+    }
     const RegConsts cst = make_reg_consts();
     using lds_u4 = __attribute__((address_space(3))) u4;
     using lds_h8 = __attribute__((address_space(3))) h8;
@@ -1083,18 +1089,20 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
     }
 }
 
-// splits > 1: workgroup (tile, sp) contracts over the weight rows [sp * rps, (sp + 1) * rps) only (rps a multiple of
-// 64: whole stages) and stores its partial tile as fp16 into dX + sp * part_stride; splitk_reduce_kernel adds them.
-// The rows of a stored layer are independent, so a split is simply the layer made of those rows.
+// splits > 1: a workgroup (tile, sp) of a split tile contracts over the weight rows [sp * rps, (sp + 1) * rps) only (rps
+// a multiple of 64: whole stages) and stores its partial tile as fp16 into its slot of `part`; splitk_reduce_kernel
+// adds them.  Which tiles are split: split_tile.  The rows of a stored layer are independent, so a split is simply the
+// layer made of those rows.
 __global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
                                                            __half* __restrict__ dX, int64_t lddx, int tiles_ic, int splits,
-                                                           int rps, int64_t part_stride) {
+                                                           int rps, int tail_first, __half* __restrict__ part) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int tiles_all = tiles_ic * ((M + BT - 1) / BT);
-    const int tile_sp = xcd_tile(tiles_all * splits);
-    if (tile_sp < 0) return;
-    const int sp = tile_sp / tiles_all, tile = tile_sp - sp * tiles_all;
-    if (splits > 1) {
+    int tile, sp, slot;
+    if (!split_tile(tiles_all, tail_first, splits, tile, sp, slot)) return;
+    const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
+    const int ic0 = t_ic * BT, m0 = t_m * BT;
+    if (slot >= 0) {
         const int r0 = sp * rps;
         L.qweight += (size_t)r0 * L.stride;
         L.scales += (size_t)r0 * L.gs;
@@ -1102,10 +1110,10 @@ __global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half
         L.weak += (size_t)r0 * L.k;
         L.oc = min(rps, L.oc - r0);
         dY += r0;
-        dX += (size_t)sp * part_stride;
+        // the tile stores dX[m][ic] with absolute indices: point it at the slot's (m0, ic0)
+        dX = part + (size_t)slot * (BT * BT) - ((size_t)m0 * BT + ic0);
+        lddx = BT;
     }
-    const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
-    const int ic0 = t_ic * BT, m0 = t_m * BT;
     // a half is weak when it starts at or past Kq (Kq % 128 == 0); without a weak block the surplus
     // half of the last tile runs as a quantized one on clamped addresses and stores nothing
     const bool w0 = L.k > 0 && ic0 >= L.kq, w1 = L.k > 0 && ic0 + 128 >= L.kq;
@@ -1340,57 +1348,94 @@ bool gemm_fwd_supported(const Layer& L, int64_t M) {
 }
 
 namespace {
-// Sum of the K-split partial tiles: 8 outputs (16 bytes) per thread, fp32 sum in split order, one rounding.
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const __half* __restrict__ part, int splits, int64_t part_stride, int M,
-                                                            int oc, int64_t ldp, __half* __restrict__ Y, int64_t ldy) {
-    const int chunks = (oc + 7) >> 3;
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= (int64_t)M * chunks) return;
-    const int m = (int)(t / chunks), c = (int)(t % chunks);
-    float acc[8];
+// Sum of the partial tiles of the split tiles: workgroup (tail index, quarter) adds the `splits` slots of 64 rows of one
+// tile, 8 outputs (16 bytes) per thread and step, fp32 sum in split order, one rounding.  n: columns of the output
+// (tiles_n tiles of them).
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const __half* __restrict__ part, int splits, int tiles_all, int tiles_n,
+                                                            int tail_first, int M, int n, __half* __restrict__ Y, int64_t ldy) {
+    const int tt = blockIdx.x >> 2, quarter = blockIdx.x & 3;
+    const int tile = split_tail_tile(tiles_all, tail_first, tt);
+    if (tile < 0) return;
+    const int n0 = (tile % tiles_n) * BT, m0 = (tile / tiles_n) * BT;
+    const bool wide = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
+    const __half* p0 = part + (size_t)tt * splits * (BT * BT);
+#pragma unroll 2
+    for (int it = 0; it < 8; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        const int row = quarter * 64 + (idx >> 5), c = idx & 31;
+        const int m = m0 + row, col = n0 + 8 * c;
+        if (m >= M || col >= n) continue;
+        float acc[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int p = 0; p < splits; ++p) {
-        const u4 v = ld16(part + (size_t)p * part_stride + (size_t)m * ldp + 8 * c);
-        const h8 h = __builtin_bit_cast(h8, v);
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        for (int p = 0; p < splits; ++p) {
+            const u4 v = ld16(p0 + (size_t)p * (BT * BT) + row * BT + 8 * c);
+            const h8 h = __builtin_bit_cast(h8, v);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += (float)h[e];
+            for (int e = 0; e < 8; ++e) acc[e] += (float)h[e];
+        }
+        __half* y = Y + (size_t)m * ldy + col;
+        if (col + 8 <= n && wide) {
+            h8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (_Float16)acc[e];
+            *reinterpret_cast<u4*>(y) = __builtin_bit_cast(u4, o);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (col + e < n) y[e] = __float2half_rn(acc[e]);
+        }
     }
-    __half* y = Y + (size_t)m * ldy + 8 * c;
-    if (8 * c + 8 <= oc && (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0) {
-        h8 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (_Float16)acc[e];
-        *reinterpret_cast<u4*>(y) = __builtin_bit_cast(u4, o);
+}
+
+// Which tiles to split and how, for a launch of `tiles` tiles whose contraction has `chunks` units of 8 stages.
+//   fewer than 160 tiles: all of them, as many ways as bring the workgroups to about the number of CUs (at most 16);
+//   otherwise the tiles of each XCD's last round when that round fills at most half of the XCD's 32 CUs, as many ways as
+//   fill it (at most 8) - provided the time saved on that round (stage_us per stage) is well above the cost of the
+//   partial tiles' traffic and the second launch.
+struct SplitPlan {
+    int splits = 1, chunks_per_split = 0, tail_first = 0;
+};
+SplitPlan plan_split(int tiles, int stages) {
+    SplitPlan p;
+    const int chunks = stages / 8;
+    if (chunks < 2) return p;
+    int want;
+    if (tiles < 160) {
+        want = 256 / tiles;
+        want = want > 16 ? 16 : want;
     } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-            if (8 * c + e < oc) y[e] = __float2half_rn(acc[e]);
+        const int per = ceil_div(tiles, N_XCD), full = per / 32 * 32, rem = per - full;
+        if (rem == 0 || rem > 16 || full == 0) return p;
+        want = 32 / rem;
+        want = want > 8 ? 8 : want;
+        p.tail_first = full;
     }
+    want = want > chunks ? chunks : want;
+    if (want < 2) return SplitPlan();
+    p.chunks_per_split = ceil_div(chunks, want);
+    p.splits = ceil_div(stages, p.chunks_per_split * 8);
+    if (p.splits < 2) return SplitPlan();
+    if (p.tail_first > 0) {
+        const double saved = (stages - p.chunks_per_split * 8) * 1.15;                               // us
+        const double cost = 6.0 + split_tail_tiles(tiles, p.tail_first) * p.splits * 0.064;          // us: 128 KB written and read per slot
+        if (saved < 2.0 * cost) return SplitPlan();
+    }
+    return p;
+}
+size_t split_workspace(int tiles, const SplitPlan& p) {
+    return p.splits > 1 ? (size_t)split_tail_tiles(tiles, p.tail_first) * p.splits * BT * BT * sizeof(__half) : 0;
 }
 }  // namespace
 
-// K split of the forward for launches that would leave most CUs idle: as many splits as bring the number of
-// workgroups to about the number of CUs, each a multiple of 8 stages (512 columns), at most 16.
-void gemm_fwd_split(const Layer& L, int64_t M, int& splits, int& sps) {
-    splits = 1;
-    sps = 0;
-    if (L.kq <= 0 || L.kq % BK != 0) return;
-    const int tiles = ceil_div(L.oc, BT) * ceil_div(M, BT), nq = L.kq / BK, chunks = nq / 8;
-    if (tiles >= 160 || chunks < 2) return;
-    int want = 256 / tiles;
-    want = want > 16 ? 16 : want;
-    want = want > chunks ? chunks : want;
-    if (want < 2) return;
-    sps = ceil_div(chunks, want) * 8;
-    splits = ceil_div(nq, sps);
-    if (splits < 2) splits = 1;
+// K split of the forward: units of 8 stages (512 columns)
+static SplitPlan gemm_fwd_plan(const Layer& L, int64_t M) {
+    if (L.kq <= 0 || L.kq % BK != 0) return SplitPlan();
+    return plan_split(ceil_div(L.oc, BT) * ceil_div(M, BT), L.kq / BK);
 }
 
 size_t gemm_fwd_split_workspace(const Layer& L, int64_t M) {
-    int splits, sps;
-    gemm_fwd_split(L, M, splits, sps);
-    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)((L.oc + 7) / 8 * 8) * sizeof(__half) : 0;
+    return split_workspace(ceil_div(L.oc, BT) * ceil_div(M, BT), gemm_fwd_plan(L, M));
 }
 
 hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, void* ws, hipStream_t s) {
@@ -1403,19 +1448,18 @@ hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __h
             if (e != hipSuccess) return e;
             attr = true;
         }
-        int splits = 1, sps = 0;
-        if (ws) gemm_fwd_split(L, M, splits, sps);
-        if (splits > 1) {
-            const int64_t ldp = (L.oc + 7) / 8 * 8, part_stride = M * ldp;
+        const int tiles = tiles_oc * tiles_m;
+        const int wide = (ldy % 8 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
+        const SplitPlan p = ws ? gemm_fwd_plan(L, M) : SplitPlan();
+        if (p.splits > 1) {
             __half* part = (__half*)ws;
-            gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m * splits), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, part, ldp, tiles_oc, 1, splits,
-                                                                                            sps, part_stride);
-            const int64_t n = M * (ldp / 8);
-            splitk_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>(part, splits, part_stride, (int)M, L.oc, ldp, Y, ldy);
+            gemm_fwd_rega_kernel<<<split_grid(tiles, p.tail_first, p.splits), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide, p.splits,
+                                                                                                 p.chunks_per_split * 8, p.tail_first, part);
+            splitk_reduce_kernel<<<4 * split_tail_tiles(tiles, p.tail_first), 256, 0, s>>>(part, p.splits, tiles, tiles_oc, p.tail_first, (int)M,
+                                                                                           L.oc, Y, ldy);
             return hipGetLastError();
         }
-        const int wide = (ldy % 8 == 0) && (reinterpret_cast<uintptr_t>(Y) % 16 == 0);
-        gemm_fwd_rega_kernel<<<xcd_grid(tiles_oc * tiles_m), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide, 1, 0, 0);
+        gemm_fwd_rega_kernel<<<xcd_grid(tiles), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide, 1, 0, 0, nullptr);
     } else {
         static bool attr = false;
         e = raise_lds_limit((const void*)gemm_fwd_kernel, attr);
@@ -1430,26 +1474,14 @@ bool gemm_dx_supported(const Layer& L, int64_t M) {
            (L.ic % 8) == 0;
 }
 
-// Row split of the input gradient for launches with few tiles, as for the forward: multiples of 8 stages (512 rows).
-void gemm_dx_split(const Layer& L, int64_t M, int& splits, int& rps) {
-    splits = 1;
-    rps = 0;
-    if (!(L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0)) return;
-    const int tiles = ceil_div(L.ic, BT) * ceil_div(M, BT), nst = L.oc / BK, chunks = nst / 8;
-    if (tiles >= 160 || chunks < 2) return;
-    int want = 256 / tiles;
-    want = want > 16 ? 16 : want;
-    want = want > chunks ? chunks : want;
-    if (want < 2) return;
-    rps = ceil_div(chunks, want) * 8 * BK;
-    splits = ceil_div(L.oc, rps);
-    if (splits < 2) splits = 1;
+// Row split of the input gradient, as for the forward: units of 8 stages (512 rows).
+static SplitPlan gemm_dx_plan(const Layer& L, int64_t M) {
+    if (!(L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0)) return SplitPlan();
+    return plan_split(ceil_div(L.ic, BT) * ceil_div(M, BT), L.oc / BK);
 }
 
 size_t gemm_dx_split_workspace(const Layer& L, int64_t M) {
-    int splits, rps;
-    gemm_dx_split(L, M, splits, rps);
-    return splits > 1 ? (size_t)splits * (size_t)M * (size_t)((L.ic + 7) / 8 * 8) * sizeof(__half) : 0;
+    return split_workspace(ceil_div(L.ic, BT) * ceil_div(M, BT), gemm_dx_plan(L, M));
 }
 
 hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, void* ws, hipStream_t s) {
@@ -1462,18 +1494,17 @@ hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __
             if (e != hipSuccess) return e;
             attr = true;
         }
-        int splits = 1, rps = 0;
-        if (ws) gemm_dx_split(L, M, splits, rps);
-        if (splits > 1) {
-            const int64_t ldp = (L.ic + 7) / 8 * 8, part_stride = M * ldp;
+        const int tiles = tiles_ic * tiles_m;
+        const SplitPlan p = ws ? gemm_dx_plan(L, M) : SplitPlan();
+        if (p.splits > 1) {
             __half* part = (__half*)ws;
-            gemm_dx_rega_kernel<<<xcd_grid(tiles_ic * tiles_m * splits), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, part, ldp, tiles_ic, splits, rps,
-                                                                                          part_stride);
-            const int64_t n = M * (ldp / 8);
-            splitk_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>(part, splits, part_stride, (int)M, L.ic, ldp, dX, lddx);
+            gemm_dx_rega_kernel<<<split_grid(tiles, p.tail_first, p.splits), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic, p.splits,
+                                                                                              p.chunks_per_split * 8 * BK, p.tail_first, part);
+            splitk_reduce_kernel<<<4 * split_tail_tiles(tiles, p.tail_first), 256, 0, s>>>(part, p.splits, tiles, tiles_ic, p.tail_first, (int)M,
+                                                                                           L.ic, dX, lddx);
             return hipGetLastError();
         }
-        gemm_dx_rega_kernel<<<xcd_grid(tiles_ic * tiles_m), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic, 1, 0, 0);
+        gemm_dx_rega_kernel<<<xcd_grid(tiles), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic, 1, 0, 0, nullptr);
     } else {
         static bool attr = false;
         e = raise_lds_limit((const void*)gemm_dx_kernel, attr);

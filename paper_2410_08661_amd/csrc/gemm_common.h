@@ -91,6 +91,59 @@ __device__ __forceinline__ int xcd_tile(int n_tiles) {
 }
 inline int xcd_grid(int n_tiles) { return N_XCD * ((n_tiles + N_XCD - 1) / N_XCD); }
 
+// Tile order of a launch in which some tiles are split `splits` ways along the contraction (a workgroup per split, each
+// storing a partial tile of BT x BT halves into slot `slot` of a workspace; a second kernel adds them).
+//   tail_first <= 0: every tile is split (launches of few tiles); order as xcd_tile over tiles * splits.
+//   tail_first  > 0: each XCD walks its contiguous range of ceil(tiles / 8) tiles as in xcd_tile; the first tail_first of
+//     them (whole rounds of the XCD's 32 CUs) are not split, the rest - the last, partly filled round - are, all splits
+//     of one index after the other.  Slots number the tail tiles XCD by XCD.
+// Returns false for a workgroup without work; slot < 0 for a tile that is not split.
+__device__ __forceinline__ bool split_tile(int tiles_all, int tail_first, int splits, int& tile, int& sp, int& slot) {
+    if (tail_first <= 0) {
+        const int v = xcd_tile(tiles_all * splits);
+        if (v < 0) return false;
+        sp = v / tiles_all;
+        tile = v - sp * tiles_all;
+        slot = splits > 1 ? tile * splits + sp : -1;
+        return true;
+    }
+    const int per = (tiles_all + N_XCD - 1) / N_XCD;
+    const int x = (int)(blockIdx.x % N_XCD), l = (int)(blockIdx.x / N_XCD);
+    const int tf = min(tail_first, per), ntail = per - tf;
+    if (l < tf) {
+        tile = x * per + l;
+        sp = 0;
+        slot = -1;
+    } else {
+        const int j = l - tf;
+        sp = j / ntail;
+        const int r = j - sp * ntail;
+        tile = x * per + tf + r;
+        slot = (x * ntail + r) * splits + sp;
+    }
+    return tile < tiles_all;
+}
+// host side of the same order: workgroups in the grid, and partial-tile slots
+inline int split_grid(int tiles_all, int tail_first, int splits) {
+    if (tail_first <= 0) return xcd_grid(tiles_all * splits);
+    const int per = (tiles_all + N_XCD - 1) / N_XCD, tf = tail_first < per ? tail_first : per;
+    return N_XCD * (tf + (per - tf) * splits);
+}
+inline int split_tail_tiles(int tiles_all, int tail_first) {   // tail tiles, counting the empty ones of a ragged last XCD
+    if (tail_first <= 0) return tiles_all;
+    const int per = (tiles_all + N_XCD - 1) / N_XCD, tf = tail_first < per ? tail_first : per;
+    return N_XCD * (per - tf);
+}
+// tile of tail index tt (the inverse of the slot numbering), -1 if none
+__device__ __forceinline__ int split_tail_tile(int tiles_all, int tail_first, int tt) {
+    if (tail_first <= 0) return tt < tiles_all ? tt : -1;
+    const int per = (tiles_all + N_XCD - 1) / N_XCD;
+    const int tf = min(tail_first, per), ntail = per - tf;
+    const int x = tt / ntail, r = tt - x * ntail;
+    const int tile = x * per + tf + r;
+    return (x < N_XCD && tile < tiles_all) ? tile : -1;
+}
+
 __device__ __forceinline__ void zero_acc(f16v (&acc)[4][4]) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)

@@ -98,7 +98,8 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M, in
 
 // ---- prefill / fine-tune path: MFMA GEMMs (gemm.hip) ---------------------------------------
 bool gemm_fwd_supported(const Layer& L, int64_t M);
-// ws: optional device workspace of gemm_fwd_split_workspace() bytes (16-byte aligned); with it, launches of few tiles split K
+// ws: optional device workspace of gemm_fwd_split_workspace() bytes (16-byte aligned); with it, launches of few tiles, or with a
+// sparsely filled last round of tiles, split K (for dX: the weight rows) of those tiles
 hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __half* Y, int64_t ldy, void* ws, hipStream_t s);
 size_t gemm_fwd_split_workspace(const Layer& L, int64_t M);
 bool gemm_dx_supported(const Layer& L, int64_t M);

@@ -465,14 +465,17 @@ def test_weak_grad_parity(oc, ic, k, bits, g, m, compact):
     (528, 2560 + 64, 64, 64),        # 3 tiles (one ragged), 40 stages: 5 splits
     (200, 1088 + 72, 72, 130),       # 17 stages: splits of 16 and 1 stage, ragged weak block (LDS-staged weak stages in the last split)
     (1000, 3072, 0, 100),            # no weak block
+    (8448, 2048 + 128, 128, 2048),   # 264 tiles: 32 per XCD unsplit, the 33rd of each XCD in 4 splits
+    (9448, 2048 + 128, 128, 1700),   # 259 tiles (ragged both ways): the last XCD has fewer tiles and no split one
 ])
 def test_forward_k_split_with_workspace(oc, ic, k, m):
-    """Forward launches of few tiles: with the optional workspace the K range is split over workgroups and the
-    fp16 partial tiles are summed by a second kernel; without it one workgroup per tile walks the whole range."""
+    """Forward launches of few tiles, or whose last round of tiles fills few CUs: with the optional workspace the K
+    range of those tiles is split over workgroups and the fp16 partial tiles are summed by a second kernel; without it
+    one workgroup per tile walks the whole range."""
     h = HostLayer(oc, ic, k, 4, 128, seed=oc + ic)
     w = h.to_device()
     n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m)
-    assert n > 0 and n % (m * ((oc + 7) // 8 * 8) * 2) == 0
+    assert n > 0 and n % (256 * 256 * 2) == 0       # whole partial tiles
     x = synth.make_activations(m, ic, k, seed=m)
     xv, _ = pad_cols(x)
     ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
@@ -493,14 +496,17 @@ def test_forward_k_split_with_workspace(oc, ic, k, m):
     (4096, 256 + 128, 128, 300),     # 2 x 2 tiles (the second half weak, then empty), 64 stages of rows: 8 splits
     (1088, 640, 0, 64),              # 17 stages: splits of 16 and 1, no weak block
     (2560, 1024 + 64, 64, 130),      # mixed last tile, 40 stages: 5 splits
+    (2048, 8320 + 128, 128, 2048),   # 264 tiles: the 33rd of each XCD (the half-quantized, half-weak last one) in 4 splits
+    (2112, 9344 + 128, 128, 1700),   # 259 tiles (split ones all quantized), 33 stages: 5 splits, the last of one stage
 ])
 def test_backward_dx_row_split_with_workspace(oc, ic, k, m):
-    """Input-gradient launches of few tiles: with the optional workspace the weight rows are split over workgroups
-    (fp16 partial tiles, summed by a second kernel); without it one workgroup per tile walks all rows."""
+    """Input-gradient launches of few tiles, or whose last round fills few CUs: with the optional workspace the weight
+    rows of those tiles are split over workgroups (fp16 partial tiles, summed by a second kernel); without it one
+    workgroup per tile walks all rows."""
     h = HostLayer(oc, ic, k, 4, 128, seed=oc + ic)
     w = h.to_device()
     n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
-    assert n > 0 and n % (m * ((ic + 7) // 8 * 8) * 2) == 0
+    assert n > 0 and n % (256 * 256 * 2) == 0       # whole partial tiles
     dy = synth.make_grad_output(m, oc, seed=m)
     dyv, _ = pad_cols(dy)
     ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
