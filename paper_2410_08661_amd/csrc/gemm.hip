@@ -1413,7 +1413,7 @@ SplitPlan plan_split(int tiles, int stages) {
     }
     want = want > chunks ? chunks : want;
     if (want < 2) return SplitPlan();
-    p.chunks_per_split = ceil_div(chunks, want);
+    p.chunks_per_split = ceil_div(ceil_div(stages, 8), want);   // at most `want` splits, a ragged last chunk included
     p.splits = ceil_div(stages, p.chunks_per_split * 8);
     if (p.splits < 2) return SplitPlan();
     if (p.tail_first > 0) {

@@ -497,7 +497,7 @@ def test_forward_k_split_with_workspace(oc, ic, k, m):
     (1088, 640, 0, 64),              # 17 stages: splits of 16 and 1, no weak block
     (2560, 1024 + 64, 64, 130),      # mixed last tile, 40 stages: 5 splits
     (2048, 8320 + 128, 128, 2048),   # 264 tiles: the 33rd of each XCD (the half-quantized, half-weak last one) in 4 splits
-    (2112, 9344 + 128, 128, 1700),   # 259 tiles (split ones all quantized), 33 stages: 5 splits, the last of one stage
+    (2112, 9344 + 128, 128, 1700),   # 259 tiles (split ones all quantized), 33 stages: 3 splits, the last of one stage
 ])
 def test_backward_dx_row_split_with_workspace(oc, ic, k, m):
     """Input-gradient launches of few tiles, or whose last round fills few CUs: with the optional workspace the weight
