@@ -56,3 +56,39 @@ def test_random_shape(i):
             dw = B.qeft_weak_grad(h.desc, dyv, xw, out_dtype=torch.float32)
             torch.cuda.synchronize()
             assert_close(dw.cpu().numpy(), qo.weak_grad(dy, x[:, kq:]), f"{what} dW M{m}")
+
+
+def _tail_case(i):
+    """Launches of 160 - 420 tiles whose last round leaves at most half of an XCD's compute units busy and whose
+    contraction is long enough that the library splits it, for those tiles only, when given the optional workspace."""
+    rng = np.random.default_rng(2000 + i)
+    while True:
+        tn, tm = int(rng.integers(3, 40)), int(rng.integers(4, 12))
+        n = tn * 256 - int(rng.choice([0, 8, 64, 120, 200]))     # channels along the tiled dimension (ragged last tile)
+        m = tm * 256 - int(rng.choice([0, 1, 77, 255]))
+        k = int(rng.choice([0, 64, 128, 256]))
+        depth = int(rng.choice([2048, 2560, 3072, 4096]))        # length of the contraction
+        ic = (n - k) // 128 * 128 + k                            # dX: about n input channels, whole groups
+        fwd, dx = B.make_desc(n, depth + k, k, 4, 128), B.make_desc(depth, ic, k, 4, 128)
+        if tn * tm >= 160 and B.qeft_workspace_bytes(fwd, B.QEFT_OP_FWD, m) > 0 and B.qeft_workspace_bytes(dx, B.QEFT_OP_BWD_DX, m) > 0:
+            return n, m, k, depth, ic
+
+
+@pytest.mark.parametrize("i", range(4))
+def test_random_shape_with_split_last_round(i):
+    n, m, k, depth, ic = _tail_case(i)
+    # forward: n output channels, contraction over depth quantized + k weak input channels
+    h = HostLayer(n, depth + k, k, 4, 128, seed=i)
+    w = h.to_device()
+    x = synth.make_activations(m, depth + k, k, seed=i)
+    y = B.qeft_linear_fwd(h.desc, w, torch.from_numpy(x).cuda())        # the binding allocates the workspace
+    torch.cuda.synchronize()
+    assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), f"fwd {n}x{depth + k} k={k} M{m}")
+    del h, w, x, y
+    # input gradient: ic input channels, contraction over depth weight rows
+    h = HostLayer(depth, ic, k, 4, 128, seed=i + 50)
+    w = h.to_device()
+    dy = synth.make_grad_output(m, depth, seed=i)
+    dx = B.qeft_linear_bwd_dx(h.desc, w, torch.from_numpy(dy).cuda())
+    torch.cuda.synchronize()
+    assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), f"dX {depth}x{ic} k={k} M{m}")
