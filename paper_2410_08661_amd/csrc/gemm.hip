@@ -1411,9 +1411,10 @@ SplitPlan plan_split(int tiles, int stages) {
         want = want > 8 ? 8 : want;
         p.tail_first = full;
     }
-    want = want > chunks ? chunks : want;
+    const int chunks_all = ceil_div(stages, 8);   // a ragged last chunk included
+    want = want > chunks_all ? chunks_all : want;
     if (want < 2) return SplitPlan();
-    p.chunks_per_split = ceil_div(ceil_div(stages, 8), want);   // at most `want` splits, a ragged last chunk included
+    p.chunks_per_split = ceil_div(chunks_all, want);   // at most `want` splits
     p.splits = ceil_div(stages, p.chunks_per_split * 8);
     if (p.splits < 2) return SplitPlan();
     if (p.tail_first > 0) {
