@@ -270,6 +270,45 @@ def main():
         del copies, ws3
     del w3
 
+    # ---- the other models' fine-tune shapes (outside the timed step; context for the 7B figures) ---------
+    # forward and input gradient with the optional workspace (launches with few tiles, or with a sparsely filled last
+    # round of tiles, split their contraction over it), weak gradient; random stored components, one layer per shape
+    other_models = []
+    for model, shapes, k_o, m_o in (("Llama-2-13B", synth.LLAMA_13B, 128, 4096), ("Llama-2-70B", synth.LLAMA_70B, 256, 2048)):
+        for oc, ic in shapes:
+            d_o2 = B.make_desc(oc, ic, k_o, bits, g)
+            w_o2 = B.Weight(d_o2)
+            w_o2.qweight.random_(-2**31, 2**31 - 1, generator=gen)
+            w_o2.scales.copy_((torch.rand(w_o2.scales.shape, generator=gen, device=dev) * 0.008 + 0.004).half())
+            w_o2.zeros.copy_(torch.randint(0, 16, w_o2.zeros.shape, generator=gen, device=dev).half())
+            w_o2.weak.copy_((torch.randn(w_o2.weak.shape, generator=gen, device=dev) * 0.02).half())
+            x_o = torch.randn((m_o, ic), generator=gen, device=dev).half()
+            dy_o = (torch.randn((m_o, oc), generator=gen, device=dev) * 0.01).half()
+            y_o = torch.empty((m_o, oc), dtype=torch.float16, device=dev)
+            dx_o = torch.empty((m_o, ic), dtype=torch.float16, device=dev)
+            dw_o = torch.zeros((oc, k_o), dtype=torch.float32, device=dev)
+            n_ws = max(B.qeft_workspace_bytes(d_o2, op, m_o) for op in (B.QEFT_OP_FWD, B.QEFT_OP_BWD_DX, B.QEFT_OP_WEAK_GRAD))
+            ws_o = torch.empty(max(n_ws, 16), dtype=torch.uint8, device=dev)
+            calls = (lambda: B.qeft_linear_fwd(d_o2, w_o2, x_o, y_o, ws=ws_o),
+                     lambda: B.qeft_linear_bwd_dx(d_o2, w_o2, dy_o, dx_o, ws=ws_o),
+                     lambda: B.qeft_weak_grad(d_o2, dy_o, x_o[:, ic - k_o:], dW=dw_o, ws=ws_o))
+            us = []
+            for call in calls:
+                for _ in range(2):
+                    call()
+                e0, e1 = ev(), ev()
+                e0.record()
+                for _ in range(5):
+                    call()
+                e1.record()
+                torch.cuda.synchronize()
+                us.append(e0.elapsed_time(e1) * 1e3 / 5)
+            fl = 2.0 * m_o * oc * ic
+            other_models.append(dict(model=model, shape=f"{oc}x{ic}", k=k_o, M=m_o, fwd_us=round(us[0], 1), fwd_tflops=round(fl / us[0] / 1e6, 1),
+                                     dx_us=round(us[1], 1), dx_tflops=round(fl / us[1] / 1e6, 1), dw_us=round(us[2], 1),
+                                     step_tflops=round((2 * fl + 2.0 * m_o * oc * k_o) / sum(us) / 1e6, 1)))
+            del w_o2, x_o, dy_o, y_o, dx_o, dw_o, ws_o
+
     # a plain device copy of known size: the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
     # (timed as well: what a plain copy reaches on this machine, read + written bytes per second, as context for the HBM fraction)
     cal = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev)
@@ -338,6 +377,7 @@ def main():
                                "decode_us_reordered": next(dk["us"] for dk in decode_kernels if dk["launch"] == "o"),
                                "fwd_M4096_us": round(irr_ft_us, 1), "fwd_M4096_us_reordered": kernels[0]["fwd_us"]},
         "three_bit": three_bit,
+        "finetune_other_models": other_models,
         "device_copy_gbs": round(copy_gbs, 1),
         "pct_of_device_copy": round(100 * gemv_gbs / copy_gbs, 1),
         "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),

@@ -1348,23 +1348,21 @@ bool gemm_fwd_supported(const Layer& L, int64_t M) {
 }
 
 namespace {
-// Sum of the partial tiles of the split tiles: workgroup (tail index, quarter) adds the `splits` slots of 64 rows of one
-// tile, 8 outputs (16 bytes) per thread and step, fp32 sum in split order, one rounding.  n: columns of the output
+// Sum of the partial tiles of the split tiles: workgroup (tail index, r) adds the `splits` slots of rows 8 r .. 8 r + 7
+// of one tile, 8 outputs (16 bytes) per thread, fp32 sum in split order, one rounding.  n: columns of the output
 // (tiles_n tiles of them).
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const __half* __restrict__ part, int splits, int tiles_all, int tiles_n,
                                                             int tail_first, int M, int n, __half* __restrict__ Y, int64_t ldy) {
-    const int tt = blockIdx.x >> 2, quarter = blockIdx.x & 3;
+    const int tt = blockIdx.x >> 5, part32 = blockIdx.x & 31;
     const int tile = split_tail_tile(tiles_all, tail_first, tt);
     if (tile < 0) return;
     const int n0 = (tile % tiles_n) * BT, m0 = (tile / tiles_n) * BT;
     const bool wide = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
     const __half* p0 = part + (size_t)tt * splits * (BT * BT);
-#pragma unroll 2
-    for (int it = 0; it < 8; ++it) {
-        const int idx = it * 256 + threadIdx.x;
-        const int row = quarter * 64 + (idx >> 5), c = idx & 31;
+    {
+        const int row = part32 * 8 + (threadIdx.x >> 5), c = threadIdx.x & 31;
         const int m = m0 + row, col = n0 + 8 * c;
-        if (m >= M || col >= n) continue;
+        if (m >= M || col >= n) return;
         float acc[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[e] = 0.f;
@@ -1456,7 +1454,7 @@ hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __h
             __half* part = (__half*)ws;
             gemm_fwd_rega_kernel<<<split_grid(tiles, p.tail_first, p.splits), 256, REGA_LDS, s>>>(L, X, (int)M, ldx, Y, ldy, tiles_oc, wide, p.splits,
                                                                                                  p.chunks_per_split * 8, p.tail_first, part);
-            splitk_reduce_kernel<<<4 * split_tail_tiles(tiles, p.tail_first), 256, 0, s>>>(part, p.splits, tiles, tiles_oc, p.tail_first, (int)M,
+            splitk_reduce_kernel<<<32 * split_tail_tiles(tiles, p.tail_first), 256, 0, s>>>(part, p.splits, tiles, tiles_oc, p.tail_first, (int)M,
                                                                                            L.oc, Y, ldy);
             return hipGetLastError();
         }
@@ -1501,7 +1499,7 @@ hipError_t gemm_dx(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __
             __half* part = (__half*)ws;
             gemm_dx_rega_kernel<<<split_grid(tiles, p.tail_first, p.splits), 256, DX_LDS, s>>>(L, dY, (int)M, lddy, dX, lddx, tiles_ic, p.splits,
                                                                                               p.chunks_per_split * 8 * BK, p.tail_first, part);
-            splitk_reduce_kernel<<<4 * split_tail_tiles(tiles, p.tail_first), 256, 0, s>>>(part, p.splits, tiles, tiles_ic, p.tail_first, (int)M,
+            splitk_reduce_kernel<<<32 * split_tail_tiles(tiles, p.tail_first), 256, 0, s>>>(part, p.splits, tiles, tiles_ic, p.tail_first, (int)M,
                                                                                            L.ic, dX, lddx);
             return hipGetLastError();
         }
