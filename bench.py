@@ -44,6 +44,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-other-models", action="store_true", help="skip the 13B / 70B fine-tune timings (a profile of the 7B workload alone)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -274,7 +275,7 @@ def main():
     # forward and input gradient with the optional workspace (launches with few tiles, or with a sparsely filled last
     # round of tiles, split their contraction over it), weak gradient; random stored components, one layer per shape
     other_models = []
-    for model, shapes, k_o, m_o in (("Llama-2-13B", synth.LLAMA_13B, 128, 4096), ("Llama-2-70B", synth.LLAMA_70B, 256, 2048)):
+    for model, shapes, k_o, m_o in (() if args.no_other_models else (("Llama-2-13B", synth.LLAMA_13B, 128, 4096), ("Llama-2-70B", synth.LLAMA_70B, 256, 2048))):
         for oc, ic in shapes:
             d_o2 = B.make_desc(oc, ic, k_o, bits, g)
             w_o2 = B.Weight(d_o2)
