@@ -1416,9 +1416,10 @@ SplitPlan plan_split(int tiles, int stages) {
     p.splits = ceil_div(stages, p.chunks_per_split * 8);
     if (p.splits < 2) return SplitPlan();
     if (p.tail_first > 0) {
-        const double saved = (stages - p.chunks_per_split * 8) * 1.15;                               // us
-        const double cost = 6.0 + split_tail_tiles(tiles, p.tail_first) * p.splits * 0.064;          // us: 128 KB written and read per slot
-        if (saved < 2.0 * cost) return SplitPlan();
+        // measured: a stage takes 1.6 - 1.8 us with every CU busy; the second launch 7 - 9 us for 256 slots
+        const double saved = (stages - p.chunks_per_split * 8) * 1.6;                                // us
+        const double cost = 8.0 + split_tail_tiles(tiles, p.tail_first) * p.splits * 0.05;           // us: 128 KB written and read per slot
+        if (saved < 1.5 * cost) return SplitPlan();
     }
     return p;
 }
