@@ -120,6 +120,29 @@ def test_three_bit_workspace_rules():
     assert B.qeft_workspace_bytes(B.make_desc(64, 260, 128, 3), B.QEFT_OP_FWD, 4096) == 0       # IC not a multiple of 8: general kernel
 
 
+def test_last_round_split_workspace_rules():
+    """Launches of 160 tiles or more: only the tiles of a sparsely filled last round are split (per XCD: the tiles past its
+    last multiple of 32, when at most 16), each partial tile a 128 KiB slot; launches that fill their rounds need nothing."""
+    slot = 256 * 256 * 2
+
+    def slots(oc, ic, k, m, op):
+        return B.qeft_workspace_bytes(B.make_desc(oc, ic, k, 4), op, m) / slot
+
+    F, D = B.QEFT_OP_FWD, B.QEFT_OP_BWD_DX
+    # 13B, M = 4096: 20 x 16 = 320 tiles -> 8 per XCD in the last round, 4 splits; 54 x 16 = 864 -> 12 per XCD, 2 splits
+    assert slots(5120, 5120, 128, 4096, F) == 64 * 4 and slots(5120, 5120, 128, 4096, D) == 64 * 4
+    assert slots(13824, 5120, 128, 4096, F) == 96 * 2 and slots(13824, 5120, 128, 4096, D) == 64 * 4
+    assert slots(5120, 13824, 128, 4096, F) == 64 * 4 and slots(5120, 13824, 128, 4096, D) == 96 * 2
+    # 70B, M = 2048: 112 x 8 = 896 tiles -> 16 per XCD, 2 splits; 32 x 8 = 256 tiles fill one round exactly
+    assert slots(28672, 8192, 256, 2048, F) == 128 * 2 and slots(28672, 8192, 256, 2048, D) == 0
+    assert slots(8192, 28672, 256, 2048, D) == 128 * 2 and slots(8192, 28672, 256, 2048, F) == 0
+    # 7B, M = 4096: 256 tiles, or 688 = 86 per XCD with 22 in the last round (more than half of the CUs): no split
+    for oc, ic in ((4096, 4096), (11008, 4096), (4096, 11008)):
+        assert slots(oc, ic, 128, 4096, F) == 0 and slots(oc, ic, 128, 4096, D) == 0
+    # a short contraction does not pay for the second pass: 264 tiles, 16 stages against 32
+    assert slots(8448, 1024 + 128, 128, 2048, F) == 0 and slots(8448, 2048 + 128, 128, 2048, F) == 8 * 4
+
+
 def test_forward_k_split_workspace_rules():
     """4-bit forward launches with few output tiles may split K over an optional workspace of fp16 partial tiles."""
     fwd = B.raw.qeft_linear_fwd
