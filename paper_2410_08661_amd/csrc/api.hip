@@ -177,7 +177,11 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
         L.k = desc->n_weak;
         L.g = desc->group_size;
         L.kq = desc->in_features - desc->n_weak;
-        if (dense_copy_applies(L, M)) return dense_copy_bytes(L);
+        if (dense_copy_applies(L, M)) {
+            // the fp16 copy; behind it, for the input gradient, the partial tiles of a row split of the copy
+            const Layer D = dense_copy_layer(L, nullptr);
+            return dense_copy_bytes(L) + ((op == QEFT_OP_BWD_DX && gemm_dx_supported(D, M)) ? gemm_dx_split_workspace(D, M) : 0);
+        }
         if (op == QEFT_OP_FWD && M > 16 && gemm_fwd_supported(L, M)) return gemm_fwd_split_workspace(L, M);
         if (op == QEFT_OP_BWD_DX && gemm_dx_supported(L, M)) return gemm_dx_split_workspace(L, M);
     }
@@ -286,7 +290,10 @@ int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const vo
         if (gemm_dx_supported(D, M)) {
             hipError_t e = dequantize_fp16(L, (__half*)ws, s);
             if (e != hipSuccess) return QEFT_ERR_HIP;
-            return hip_status(gemm_dx(D, (const __half*)dY, M, lddy, (__half*)dX, lddx, nullptr, s));
+            // what the caller gave beyond the copy serves a row split of it (all of it or nothing)
+            const size_t need = gemm_dx_split_workspace(D, M);
+            void* split_ws = (need > 0 && ws_bytes >= dense_copy_bytes(L) + need) ? (char*)ws + dense_copy_bytes(L) : nullptr;
+            return hip_status(gemm_dx(D, (const __half*)dY, M, lddy, (__half*)dX, lddx, split_ws, s));
         }
     }
     return hip_status(bwd_dx_generic(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, s));

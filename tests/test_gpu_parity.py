@@ -524,6 +524,28 @@ def test_backward_dx_row_split_with_workspace(oc, ic, k, m):
 
 
 @pytest.mark.parametrize("dense", [False, True])
+def test_three_bit_input_gradient_splits_the_rows_of_the_copy(dense):
+    """3-bit input gradient at GEMM sizes: behind the fp16 copy the workspace may hold the partial tiles of a row split of
+    the copy (few tiles here: 3 x 2, 16 stages of rows -> 2 splits); with room for the copy only, one workgroup per tile."""
+    oc, ic, k, m = 1024, 512 + 128, 128, 300
+    h = HostLayer(oc, ic, k, 3, 128, seed=5, dense=dense)
+    w = h.to_device()
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    copy = oc * ic * 2
+    assert n > copy and (n - copy) % (256 * 256 * 2) == 0
+    assert B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m) == copy
+    dy = synth.make_grad_output(m, oc, seed=m)
+    dyv, _ = pad_cols(dy)
+    ref = qo.linear_bwd_dx(h.w64, dy)
+    ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
+    for use in (ws[:n], ws[:copy]):
+        dx = B.qeft_linear_bwd_dx(h.desc, w, dyv, ws=use)
+        torch.cuda.synchronize()
+        assert_close(dx.cpu().numpy(), ref, f"3-bit dX {oc}x{ic} M{m}, workspace {use.numel()} bytes")
+    assert torch.all(ws[n:] == 0x7f)
+
+
+@pytest.mark.parametrize("dense", [False, True])
 @pytest.mark.parametrize("oc,ic,k,m", [(320, 1280 + 128, 128, 300), (264, 512 + 64, 64, 40)])
 def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
     """3-bit layers at M > 16: dequantized once into the workspace, then the tensor-core kernels; the same
