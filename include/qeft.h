@@ -149,7 +149,7 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
  * last round of tiles that fills at most half of the compute units - those tiles only, up to 8 splits, at most
  * 32 MiB (forward of 5120 x 13824 at M = 4096, 320 tiles on 256 units: 515 us against 651 us).
  * QEFT_OP_FWD / QEFT_OP_BWD_DX report OC * IC * 2 bytes for 3-bit layers
- * at M > 16 (QEFT_OP_BWD_DX: plus the partial tiles of a split of the copy's rows as above, used when the whole
+ * at M > 16 (plus the partial tiles of a split of the copy's columns or rows as above, used when the whole
  * amount is given): with that workspace (16-byte aligned) the call dequantizes the layer once into it as fp16 and
  * runs the tensor-core kernels on the copy - the paper's own training path, dequantize then a dense product
  * (Sec. 4.3, App. A.2) - and without it (ws NULL) the slow general kernel; a workspace that is too small is

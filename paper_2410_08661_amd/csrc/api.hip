@@ -178,9 +178,10 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
         L.g = desc->group_size;
         L.kq = desc->in_features - desc->n_weak;
         if (dense_copy_applies(L, M)) {
-            // the fp16 copy; behind it, for the input gradient, the partial tiles of a row split of the copy
+            // the fp16 copy; behind it the partial tiles of a split of the copy's columns (forward) or rows (input gradient)
             const Layer D = dense_copy_layer(L, nullptr);
-            return dense_copy_bytes(L) + ((op == QEFT_OP_BWD_DX && gemm_dx_supported(D, M)) ? gemm_dx_split_workspace(D, M) : 0);
+            if (op == QEFT_OP_FWD) return dense_copy_bytes(L) + (gemm_fwd_supported(D, M) ? gemm_fwd_split_workspace(D, M) : 0);
+            return dense_copy_bytes(L) + (gemm_dx_supported(D, M) ? gemm_dx_split_workspace(D, M) : 0);
         }
         if (op == QEFT_OP_FWD && M > 16 && gemm_fwd_supported(L, M)) return gemm_fwd_split_workspace(L, M);
         if (op == QEFT_OP_BWD_DX && gemm_dx_supported(L, M)) return gemm_dx_split_workspace(L, M);
@@ -218,7 +219,10 @@ int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
         if (gemm_fwd_supported(D, M)) {
             hipError_t e = dequantize_fp16(L, (__half*)ws, s);
             if (e != hipSuccess) return QEFT_ERR_HIP;
-            return hip_status(gemm_fwd(D, x, M, ldx, y, ldy, nullptr, s));
+            // what the caller gave beyond the copy serves a split of its columns (all of it or nothing)
+            const size_t need = gemm_fwd_split_workspace(D, M);
+            void* split_ws = (need > 0 && ws_bytes >= dense_copy_bytes(L) + need) ? (char*)ws + dense_copy_bytes(L) : nullptr;
+            return hip_status(gemm_fwd(D, x, M, ldx, y, ldy, split_ws, s));
         }
     }
     if (gemv_supported(L, M, ldx)) {

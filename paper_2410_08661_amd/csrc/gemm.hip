@@ -219,11 +219,14 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const bool is_split = slot >= 0;
     const bool last_split = !is_split || sp == splits - 1;
-    const int s_first = sp * sps;                                      // first quantized stage of this workgroup
-    const int nq = is_split ? min(sps, L.kq / BK - s_first) : L.kq / BK;
+    const int s_first = sp * sps;                                      // first stage of this workgroup
+    // a layer without quantized columns (the fp16 copy of a 3-bit layer) is split along its weak stages instead:
+    // a split is then the layer whose weak block starts 64 s_first columns further on
+    const bool weak_split = is_split && L.kq == 0;
+    const int nq = weak_split ? 0 : (is_split ? min(sps, L.kq / BK - s_first) : L.kq / BK);
     // weak stages: whole 64-column stages take the direct path below (A fragments straight from the fp16
     // block), a ragged block the LDS-staged stages at the end
-    const int nwf = (L.k % BK == 0 && last_split) ? L.k / BK : 0;
+    const int nwf = weak_split ? min(sps, L.k / BK - s_first) : ((L.k % BK == 0 && last_split) ? L.k / BK : 0);
     const int ns = nq + nwf;
     if (is_split) {
         // the epilogue addresses Y[m][oc] with absolute indices: point it at the slot's (m0, oc0)
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const char* st_ = reinterpret_cast<const char*>(L.scales + (size_t)oc0 * L.gs) + s_first;
     const char* zt = reinterpret_cast<const char*>(L.zeros + (size_t)oc0 * L.gs) + s_first;
     const char* xt = reinterpret_cast<const char*>(X + (size_t)m0 * ldx) + 2 * BK * s_first;
-    const char* wk = reinterpret_cast<const char*>(L.weak + (size_t)oc0 * L.k);
+    const char* wk = reinterpret_cast<const char*>(L.weak + (size_t)oc0 * L.k) + (weak_split ? 2 * BK * s_first : 0);
     uint32_t aoff[2], szoff[2], xoff[8];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -1430,8 +1433,10 @@ size_t split_workspace(int tiles, const SplitPlan& p) {
 
 // K split of the forward: units of 8 stages (512 columns)
 static SplitPlan gemm_fwd_plan(const Layer& L, int64_t M) {
+    const int tiles = ceil_div(L.oc, BT) * ceil_div(M, BT);
+    if (L.kq == 0 && L.k > 0 && L.k % BK == 0) return plan_split(tiles, L.k / BK);   // all fp16: the weak stages are split
     if (L.kq <= 0 || L.kq % BK != 0) return SplitPlan();
-    return plan_split(ceil_div(L.oc, BT) * ceil_div(M, BT), L.kq / BK);
+    return plan_split(tiles, L.kq / BK);
 }
 
 size_t gemm_fwd_split_workspace(const Layer& L, int64_t M) {

@@ -524,24 +524,30 @@ def test_backward_dx_row_split_with_workspace(oc, ic, k, m):
 
 
 @pytest.mark.parametrize("dense", [False, True])
-def test_three_bit_input_gradient_splits_the_rows_of_the_copy(dense):
-    """3-bit input gradient at GEMM sizes: behind the fp16 copy the workspace may hold the partial tiles of a row split of
-    the copy (few tiles here: 3 x 2, 16 stages of rows -> 2 splits); with room for the copy only, one workgroup per tile."""
-    oc, ic, k, m = 1024, 512 + 128, 128, 300
+def test_three_bit_gemm_splits_the_copy(dense):
+    """3-bit layers at GEMM sizes: behind the fp16 copy the workspace may hold the partial tiles of a split of the copy
+    (few tiles here; forward: 18 stages of columns -> 3 splits, input gradient: 16 stages of rows -> 2 splits); with room
+    for the copy only, one workgroup per tile."""
+    oc, ic, k, m = 1024, 1024 + 128, 128, 300
     h = HostLayer(oc, ic, k, 3, 128, seed=5, dense=dense)
     w = h.to_device()
-    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
     copy = oc * ic * 2
-    assert n > copy and (n - copy) % (256 * 256 * 2) == 0
-    assert B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m) == copy
+    nf, nd = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m), B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    for n in (nf, nd):
+        assert n > copy and (n - copy) % (256 * 256 * 2) == 0
+    x = synth.make_activations(m, ic, k, seed=m)
+    xv, _ = pad_cols(x)
     dy = synth.make_grad_output(m, oc, seed=m)
     dyv, _ = pad_cols(dy)
-    ref = qo.linear_bwd_dx(h.w64, dy)
+    ref_y, ref_dx = qo.linear_fwd(h.w64, x), qo.linear_bwd_dx(h.w64, dy)
+    n = max(nf, nd)
     ws = torch.full((n + 64,), 0x7f, dtype=torch.uint8, device="cuda")
     for use in (ws[:n], ws[:copy]):
+        y = B.qeft_linear_fwd(h.desc, w, xv, ws=use)
         dx = B.qeft_linear_bwd_dx(h.desc, w, dyv, ws=use)
         torch.cuda.synchronize()
-        assert_close(dx.cpu().numpy(), ref, f"3-bit dX {oc}x{ic} M{m}, workspace {use.numel()} bytes")
+        assert_close(y.cpu().numpy(), ref_y, f"3-bit fwd {oc}x{ic} M{m}, workspace {use.numel()} bytes")
+        assert_close(dx.cpu().numpy(), ref_dx, f"3-bit dX {oc}x{ic} M{m}, workspace {use.numel()} bytes")
     assert torch.all(ws[n:] == 0x7f)
 
 
@@ -552,8 +558,11 @@ def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
     results (to the bar) without a workspace, from the general kernel."""
     h = HostLayer(oc, ic, k, 3, 128, seed=oc + ic, dense=dense)
     w = h.to_device()
-    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m)
-    assert n == oc * ic * 2 == B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    nbytes = oc * ic * 2                                   # the copy; behind it, partial tiles when the GEMM on the copy is split
+    n = max(B.qeft_workspace_bytes(h.desc, op, m) for op in (B.QEFT_OP_FWD, B.QEFT_OP_BWD_DX))
+    for op in (B.QEFT_OP_FWD, B.QEFT_OP_BWD_DX):
+        extra = B.qeft_workspace_bytes(h.desc, op, m) - nbytes
+        assert extra >= 0 and extra % (256 * 256 * 2) == 0
     assert B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, 16) == 0
     x = synth.make_activations(m, ic, k, seed=m)
     dy = synth.make_grad_output(m, oc, seed=m)
@@ -567,11 +576,11 @@ def test_three_bit_gemm_sizes_through_the_fp16_copy(oc, ic, k, m, dense):
         assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), f"3-bit dX M{m} ws={use_ws is not False}")
     assert torch.all(ws[n:] == 0x7f)                       # nothing written past the stated size
     # the copy is the dequantized layer, rounded once to fp16
-    copy = ws[:n].view(torch.float16).reshape(oc, ic).cpu().numpy()
+    copy = ws[:nbytes].view(torch.float16).reshape(oc, ic).cpu().numpy()
     assert np.array_equal(copy, h.w64.astype(np.float32).astype(np.float16)) or \
         np.max(np.abs(copy.astype(np.float64) - h.w64)) <= np.max(np.abs(h.w64)) * 2.0 ** -11
     with pytest.raises(B.QeftError):
-        B.qeft_linear_fwd(h.desc, w, xd, ws=ws[:n - 16])   # too small
+        B.qeft_linear_fwd(h.desc, w, xd, ws=ws[:nbytes - 16])   # too small for the copy
     # the weak block is trainable: a call after an update must not reuse the old copy
     new_weak = (np.random.default_rng(3).standard_normal((oc, k)) * 0.05).astype(np.float16)
     w.weak.copy_(torch.from_numpy(new_weak))
