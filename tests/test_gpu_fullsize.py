@@ -140,7 +140,8 @@ def test_irregular_out_proj_full_size(m):
         _check(dx, pairs, ref, f"irregular dX 4096x4096 M{m}")
 
 
-TRAIN = [(4, synth.LLAMA_7B, 128, 4096), (5, synth.LLAMA_70B, 256, 2048)]
+TRAIN = [(4, synth.LLAMA_7B, 128, 4096), (5, synth.LLAMA_70B, 256, 2048),
+         (3, synth.LLAMA_13B, 128, 4096)]   # the 13B shapes: 320 / 864 tiles, whose last round is split (4 and 2 ways)
 TRAIN_CASES = [(cfg, si, s, k, m) for cfg, shapes, k, m in TRAIN for si, s in enumerate(shapes)]
 
 
