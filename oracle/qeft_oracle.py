@@ -38,7 +38,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
-    "layout", "pack_codes", "unpack_codes", "pack_codes_dense3", "unpack_codes_dense3", "quantize_rtn", "quantize_search", "dequantize",
+    "layout", "pack_codes", "unpack_codes", "pack_codes_dense3", "unpack_codes_dense3", "quantize_rtn", "codes_for_params", "search_candidates", "quantize_search", "dequantize",
     "stored_order", "linear_fwd_irregular", "linear_bwd_dx_irregular",
     "sensitivity", "top_k", "vote", "global_weak_columns", "reorder", "merge_weak",
     "linear_fwd", "linear_bwd_dx", "weak_grad", "round_fp16",
@@ -211,74 +211,98 @@ def _group_params(lo, hi, qmax):
     return s16, z
 
 
-def quantize_search(w: np.ndarray, n_weak: int, bits: int, group_size: int, n_grid: int, shrink_step: float):
-    """Group-wise grid search with truncation [Sec. 3.1: "a grid search for each group to find the
-    quantization parameters that minimize the squared error of weights after truncation"].
+def codes_for_params(w: np.ndarray, n_weak: int, bits: int, group_size: int, scales: np.ndarray, zeros: np.ndarray) -> np.ndarray:
+    """Round-to-nearest codes of the non-weak columns under GIVEN group parameters [Sec. 3.1]:
+    q = clip(rint(w / s) + z, 0, qmax) in float32, round-half-to-even, as in quantize_rtn.
+    scales, zeros: [OC][G].  -> uint8 [OC][Kq]."""
+    w = np.asarray(w)
+    assert w.dtype == np.float16 and w.ndim == 2
+    oc, ic = w.shape
+    g = int(group_size)
+    kq = ic - int(n_weak)
+    f32 = np.float32
+    qmax = f32((1 << bits) - 1)
+    codes = np.zeros((oc, kq), dtype=np.uint8)
+    for gi in range(-(-kq // g)):
+        blk = w[:, gi * g:min((gi + 1) * g, kq)].astype(np.float32)
+        sf = np.asarray(scales)[:, gi].astype(np.float32)
+        zf = np.asarray(zeros)[:, gi].astype(np.float32)
+        q = np.rint((blk / sf[:, None]).astype(np.float32)).astype(np.float32) + zf[:, None]
+        codes[:, gi * g:gi * g + blk.shape[1]] = np.clip(q, f32(0), qmax).astype(np.uint8)
+    return codes
 
-    The paper gives neither the grid nor the error's precision.  Reading taken here: candidate i
-    (i = 0 .. n_grid-1) shrinks the group's min-max range [lo, hi] (0 included, as in
-    quantize_rtn) to [p_i lo, p_i hi] with p_i = 1 - i * shrink_step, derives (s, z) from it by
-    quantize_rtn's rules, quantizes, and scores  E_i = sum_j (w_j - s (q_j - z))^2 ; the first
-    candidate with the smallest E wins, so candidate 0 (p = 1, plain min-max) is kept on ties.
 
-    Decisions are integers taken from floating point, so everything is IEEE float32 with one
-    rounding per operation (no fused multiply-add), and the error sum has a fixed order that any
-    implementation can follow: the group's columns in octets of 8 consecutive columns, each octet
-    summed left to right, the (up to 16) octet sums combined by a balanced binary tree over 16
-    slots (absent octets are zeros).  Requires group_size % 8 == 0, group_size <= 128 and
-    Kq % 8 == 0.  Returns what quantize_rtn returns.
+def search_candidates(w: np.ndarray, n_weak: int, bits: int, group_size: int, n_grid: int, shrink_step: float):
+    """Every candidate of the group-wise grid search with truncation [Sec. 3.1], scored.
+
+    The paper names a grid search per group that minimizes the squared weight error after the
+    range is truncated; it gives neither the grid nor a precision.  Reading taken here: candidate
+    i (i = 0 .. n_grid-1) shrinks the group's min-max range [lo, hi] (0 included, as in
+    quantize_rtn) to [p_i lo, p_i hi] with p_i = 1 - i * shrink_step, derives (s, z) from that
+    range by quantize_rtn's rules and quantizes with them.  Those are integer decisions taken
+    from floating point, so they are IEEE float32 with one rounding per operation, as in
+    quantize_rtn.  The score is a real number and is taken as such:
+        E_i = sum_j (w_j - s (q_j - z))^2        in float64, a plain sum.
+    Returns (scales f16 [n_grid][OC][G], zeros f32 [n_grid][OC][G], err f64 [n_grid][OC][G]).
     """
     w = np.asarray(w)
     assert w.dtype == np.float16 and w.ndim == 2
     oc, ic = w.shape
     k, g = int(n_weak), int(group_size)
     kq = ic - k
-    assert g % 8 == 0 and g <= 128 and kq % 8 == 0 and n_grid >= 1
     f32 = np.float32
-    assert f32(n_grid - 1) * f32(shrink_step) < f32(1)
+    assert n_grid >= 1 and f32(n_grid - 1) * f32(shrink_step) < f32(1)
     n_groups = -(-kq // g)
     qmax = f32((1 << bits) - 1)
     wf = w[:, :kq].astype(np.float32)
-    codes = np.zeros((oc, kq), dtype=np.uint8)
-    scales = np.zeros((oc, n_groups), dtype=np.float16)
-    zeros = np.zeros((oc, n_groups), dtype=np.float16)
+    s_all = np.zeros((n_grid, oc, n_groups), dtype=np.float16)
+    z_all = np.zeros((n_grid, oc, n_groups), dtype=np.float32)
+    e_all = np.zeros((n_grid, oc, n_groups), dtype=np.float64)
     for gi in range(n_groups):
         blk = wf[:, gi * g:min((gi + 1) * g, kq)]
-        n = blk.shape[1]
         lo0 = np.minimum(f32(0), blk.min(axis=1)).astype(np.float32)
         hi0 = np.maximum(f32(0), blk.max(axis=1)).astype(np.float32)
-        best_e = np.full(oc, np.inf, dtype=np.float32)
-        best_s = np.zeros(oc, dtype=np.float16)
-        best_z = np.zeros(oc, dtype=np.float32)
         for i in range(n_grid):
             p = f32(f32(1) - f32(f32(i) * f32(shrink_step)))
             lo, hi = (p * lo0).astype(np.float32), (p * hi0).astype(np.float32)
             s16, z = _group_params(lo, hi, qmax)
             sf = s16.astype(np.float32)
             q = np.clip(np.rint((blk / sf[:, None]).astype(np.float32)).astype(np.float32) + z[:, None], f32(0), qmax)
-            d = (blk - (sf[:, None] * (q - z[:, None])).astype(np.float32)).astype(np.float32)
-            sq = (d * d).astype(np.float32)
-            octs = np.zeros((oc, 16), dtype=np.float32)          # octet sums, left to right
-            for o8 in range(n // 8):
-                acc = np.zeros(oc, dtype=np.float32)
-                for e in range(8):
-                    acc = (acc + sq[:, 8 * o8 + e]).astype(np.float32)
-                octs[:, o8] = acc
-            t = octs
-            while t.shape[1] > 1:                                  # balanced tree over the 16 slots
-                t = (t[:, 0::2] + t[:, 1::2]).astype(np.float32)
-            e_i = t[:, 0]
-            better = e_i < best_e
-            best_e = np.where(better, e_i, best_e)
-            best_s = np.where(better, s16, best_s)
-            best_z = np.where(better, z, best_z)
-        sf = best_s.astype(np.float32)
-        q = np.clip(np.rint((blk / sf[:, None]).astype(np.float32)).astype(np.float32) + best_z[:, None], f32(0), qmax)
-        codes[:, gi * g:gi * g + n] = q.astype(np.uint8)
-        scales[:, gi] = best_s
-        zeros[:, gi] = best_z.astype(np.float16)
+            d = blk.astype(np.float64) - sf.astype(np.float64)[:, None] * (q.astype(np.float64) - z.astype(np.float64)[:, None])
+            s_all[i, :, gi], z_all[i, :, gi], e_all[i, :, gi] = s16, z, np.sum(d * d, axis=1)
+    return s_all, z_all, e_all
+
+
+def quantize_search(w: np.ndarray, n_weak: int, bits: int, group_size: int, n_grid: int, shrink_step: float):
+    """Group-wise grid search with truncation [Sec. 3.1]: per (row, group) the candidate of
+    search_candidates with the smallest squared error; the first one on ties, so candidate 0
+    (p = 1, plain min-max) is kept unless a truncated range is strictly better.  Any group size,
+    any Kq.  Returns what quantize_rtn returns.
+
+    Two candidates whose errors differ by less than rounding are both correct answers of the
+    search; an implementation that sums in another precision or order may pick either, which is
+    why a comparison against this function checks the error reached, not only the choice.
+    """
+    w = np.asarray(w)
+    s_all, z_all, e_all = search_candidates(w, n_weak, bits, group_size, n_grid, shrink_step)
+    oc, ic = w.shape
+    k, g = int(n_weak), int(group_size)
+    kq = ic - k
+    n_groups = s_all.shape[2]
+    f32 = np.float32
+    qmax = f32((1 << bits) - 1)
+    best = np.argmin(e_all, axis=0)                          # first minimum
+    scales = np.take_along_axis(s_all, best[None], axis=0)[0]
+    zf = np.take_along_axis(z_all, best[None], axis=0)[0]
+    wf = w[:, :kq].astype(np.float32)
+    codes = np.zeros((oc, kq), dtype=np.uint8)
+    for gi in range(n_groups):
+        blk = wf[:, gi * g:min((gi + 1) * g, kq)]
+        sf = scales[:, gi].astype(np.float32)
+        q = np.clip(np.rint((blk / sf[:, None]).astype(np.float32)).astype(np.float32) + zf[:, gi][:, None], f32(0), qmax)
+        codes[:, gi * g:gi * g + blk.shape[1]] = q.astype(np.uint8)
     weak = np.ascontiguousarray(w[:, kq:])
-    return codes, scales, zeros, weak
+    return codes, scales, zf.astype(np.float16), weak
 
 
 # --------------------------------------------------------------------------- dequantize
@@ -371,9 +395,11 @@ def vote(s_local: np.ndarray, k: int, s_global: np.ndarray) -> np.ndarray:
     """One layer's contribution [App. B]: its k most sensitive channels add their sensitivity
     divided by the layer's mean sensitivity to s_global (in place); returns those channels."""
     s_local = np.asarray(s_local, dtype=np.float64)
-    ids = top_k(s_local, k)
-    s_global[ids] += s_local[ids] / s_local.mean()
-    return ids
+    chosen = top_k(s_local, k)
+    layer_mean = float(np.mean(s_local))
+    for j in chosen.tolist():
+        s_global[j] += s_local[j] / layer_mean
+    return chosen
 
 
 def global_weak_columns(layer_inputs, k: int) -> np.ndarray:

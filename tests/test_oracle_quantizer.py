@@ -113,3 +113,19 @@ def test_quantizing_twice_is_stable():
     assert np.array_equal(w2, w)
     c2, s2, z2, _ = qo.quantize_rtn(w2, 0, 4, 64)
     assert np.array_equal(c1, c2) and np.array_equal(s1, s2) and np.array_equal(z1, z2)
+
+
+def test_codes_for_given_parameters_hand_cases():
+    """Codes under parameters that did not come from min-max: s = 0.5, z = 3 on a hand-made row
+    (w / s = [-7, -2.5, 0.5, 1.5, 30] -> rint half-to-even [-7, -2, 0, 2, 30] -> + 3, clipped to 0..15),
+    and a second group with s = 0.25, z = 0."""
+    w = np.array([[-3.5, -1.25, 0.25, 0.75, 15.0, 0.5, 0.125, 3.9, -1.0, 0.0, 7.0]], dtype=np.float16)
+    s = np.array([[0.5, 0.25]], dtype=np.float16)
+    z = np.array([[3.0, 0.0]], dtype=np.float16)
+    codes = qo.codes_for_params(w, 1, 4, 5, s, z)        # Kq = 10: groups [0, 5) and [5, 10); column 10 is weak
+    assert codes.tolist() == [[0, 1, 3, 5, 15, 2, 0, 15, 0, 0]]   # 0.125/0.25 = 0.5 -> 0; 3.9/0.25 = 15.6 -> 15 (clipped from 16)
+    # the min-max quantizer's own codes are the codes under its own parameters
+    r = np.random.default_rng(2)
+    w = (r.standard_normal((9, 70)) * 0.02).astype(np.float16)
+    c, sc, zp, _ = qo.quantize_rtn(w, 6, 3, 32)
+    assert np.array_equal(qo.codes_for_params(w, 6, 3, 32, sc, zp), c)

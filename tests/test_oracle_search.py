@@ -100,3 +100,30 @@ def test_against_independent_brute_force_on_exact_cases():
     for o in range(6):
         e, s, z, qs = _brute([float(v) for v in w[o]], bits, 6, 0.125)
         assert float(scales[o, 0]) == s and float(zeros[o, 0]) == z and codes[o].tolist() == qs
+
+
+def test_candidates_are_scored_in_plain_float64_and_any_shape_is_taken():
+    """search_candidates against a per-element Python-float recomputation from its own (s, z), on a shape
+    with a ragged last group and a group size that is no multiple of 8; quantize_search picks the
+    first minimum of those scores."""
+    r = np.random.default_rng(9)
+    oc, kq, k, g, bits, n_grid, step = 3, 27, 2, 12, 3, 7, 0.0625
+    w = (r.standard_normal((oc, kq + k)) * 0.05).astype(np.float16)
+    s_all, z_all, e_all = qo.search_candidates(w, k, bits, g, n_grid, step)
+    assert s_all.shape == (n_grid, oc, 3)
+    for i in range(n_grid):
+        codes = qo.codes_for_params(w, k, bits, g, s_all[i], z_all[i])
+        for o in range(oc):
+            for gi in range(3):
+                e = 0.0
+                for j in range(gi * g, min((gi + 1) * g, kq)):
+                    e += (float(w[o, j]) - float(s_all[i, o, gi]) * (int(codes[o, j]) - float(z_all[i, o, gi]))) ** 2
+                assert abs(e - e_all[i, o, gi]) <= 1e-12 * max(e, 1e-30)
+    codes, scales, zeros, weak = qo.quantize_search(w, k, bits, g, n_grid, step)
+    best = np.argmin(e_all, axis=0)
+    for o in range(oc):
+        for gi in range(3):
+            assert scales[o, gi] == s_all[best[o, gi], o, gi] and float(zeros[o, gi]) == z_all[best[o, gi], o, gi]
+            assert np.all(e_all[:best[o, gi], o, gi] > e_all[best[o, gi], o, gi])      # the first minimum
+    assert np.array_equal(codes, qo.codes_for_params(w, k, bits, g, scales, zeros))
+    assert np.array_equal(weak, w[:, kq:])
