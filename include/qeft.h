@@ -14,8 +14,10 @@
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers owned by the caller; the library
- *     allocates nothing, keeps no state (beyond "shared-memory limit of kernel X already raised" flags, which
- *     assume one GPU per process, the way this library is meant to be deployed) and never synchronises.  Work is enqueued
+ *     allocates nothing and never synchronises.  Its only state is a set of process-wide flags "the
+ *     shared-memory limit of kernel X has been raised" (plain static booleans, set on a kernel's first
+ *     launch and never cleared; two threads racing on one write the same value; they assume one GPU per
+ *     process, the way this library is meant to be deployed).  Work is enqueued
  *     on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
  *     ordered only by that stream.
  *   - Matrices are row-major with an explicit leading dimension in ELEMENTS.
@@ -53,7 +55,9 @@ typedef enum {
  *                          sizes of the paper's Tab. 5 correspond to.  Every entry point takes either layout
  *                          (decode, M <= 16: a kernel of its own when the padded row holds whole groups, i.e.
  *                          12 * G <= row_stride_words, which every Kq that is a multiple of 128 satisfies;
- *                          larger M and the backward pass: the general kernels, as for all 3-bit layers). */
+ *                          larger M and the backward pass: as for all 3-bit layers, the tensor-core kernels on
+ *                          an fp16 copy in the caller's workspace, see qeft_workspace_bytes, or the slow
+ *                          general kernels without one). */
 enum { QEFT_LAYOUT_CANONICAL = 0, QEFT_LAYOUT_DENSE3 = 1 };
 
 /* Description of one layer (plain data, passed by pointer, host memory). */
@@ -117,12 +121,13 @@ int qeft_pack(const qeft_desc_t* desc, const void* W, int64_t ldw,
  * (row, group), candidate i = 0 .. n_grid-1 shrinks the min-max range [lo, hi] to [p lo, p hi],
  * p = 1 - i * shrink_step, derives (s, z) from it by qeft_pack's rules, and the candidate with the
  * smallest squared weight error sum (w - s (q - z))^2 is kept (the first one on ties; candidate 0 is
- * qeft_pack's result, so no group gets worse).  The paper fixes neither the grid nor the arithmetic:
- * everything is fp32 with one rounding per operation, the error summed over a group's columns in
- * octets left to right and a balanced tree over the octets.  n_grid >= 1, (n_grid - 1) * shrink_step
- * < 1.  Needs group_size % 8 == 0, group_size <= 128, Kq % 8 == 0 (else QEFT_ERR_UNSUPPORTED).  The
- * OPTQ step that follows in the paper needs calibration data and is not part of this library:
- * qeft_pack_codes takes its output. */
+ * qeft_pack's result, so no group gets worse).  The paper fixes neither the grid nor the arithmetic.
+ * (s, z, codes) of a candidate are taken in fp32 with one rounding per operation, like qeft_pack's; the
+ * error is summed in fp32 (eight consecutive columns at a time, then a tree over those sums), so between
+ * candidates whose errors agree to about 1e-5 relative either may be kept.  n_grid >= 1,
+ * (n_grid - 1) * shrink_step < 1.  This kernel needs group_size % 8 == 0, group_size <= 128 and
+ * Kq % 8 == 0 (else QEFT_ERR_UNSUPPORTED).  The OPTQ step that follows in the paper needs calibration
+ * data and is not part of this library: qeft_pack_codes takes its output. */
 int qeft_pack_search(const qeft_desc_t* desc, const void* W, int64_t ldw, int n_grid, float shrink_step,
                      const qeft_weight_t* out, void* stream);
 
@@ -160,8 +165,9 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
  * one pass.  X fp16 [M][ldx] (ldx >= IC), Y fp16 [M][ldy] (ldy >= OC).  M <= 16 runs a
  * bandwidth-bound matrix-vector kernel, large M a tiled MFMA GEMM; for the token counts in between (up to
  * about 100, depending on the layer) several 16-token passes of the former where a host-side time model puts
- * them ahead of a GEMM that would fill only a fraction of the GPU.  ws / ws_bytes: see qeft_workspace_bytes
- * (only 3-bit layers use one; NULL / 0 is always valid). */
+ * them ahead of a GEMM that would fill only a fraction of the GPU.  ws / ws_bytes: optional, see
+ * qeft_workspace_bytes (4-bit layers: partial tiles of a split launch; 3-bit layers: the fp16 copy and,
+ * beyond it, the partial tiles of its split); NULL / 0 is always valid. */
 int qeft_linear_fwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* X, int64_t M,
                     int64_t ldx, void* Y, int64_t ldy, void* ws, size_t ws_bytes, void* stream);
 

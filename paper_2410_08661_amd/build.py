@@ -27,9 +27,14 @@ FLAGS = [
 ]
 
 
+# The quantizers take integer decisions from fp32 arithmetic that is specified operation by operation
+# (one rounding each): no multiply-add fusion anywhere in that file, its inlined header functions included.
+EXTRA_FLAGS = {"pack.hip": ["-ffp-contract=off"]}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(BUILD_DIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

@@ -1346,8 +1346,14 @@ hipError_t raise_lds_limit(const void* fn, bool& done) {
 
 }  // namespace
 
+// The tiled kernels round every dequantized weight once to fp16 (relative 2^-11).  Over a long contraction these
+// roundings average out far below the parity bar; a sum of a handful of terms has no such averaging and single
+// outputs can leave the per-element bar, so contractions shorter than 64 terms (IC here, OC for the input
+// gradient) take the general kernels, which keep s (q - z) in fp32.
+constexpr int MIN_CONTRACTION = 64;
+
 bool gemm_fwd_supported(const Layer& L, int64_t M) {
-    return M >= 1 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0 && (L.oc % 8) == 0;
+    return M >= 1 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0 && (L.oc % 8) == 0 && L.ic >= MIN_CONTRACTION;
 }
 
 namespace {
@@ -1476,7 +1482,7 @@ hipError_t gemm_fwd(const Layer& L, const __half* X, int64_t M, int64_t ldx, __h
 
 bool gemm_dx_supported(const Layer& L, int64_t M) {
     return M > 16 && L.bits == 4 && L.g == 128 && (L.kq % 8) == 0 && (L.k % 8) == 0 && (L.oc % 8) == 0 &&
-           (L.ic % 8) == 0;
+           (L.ic % 8) == 0 && L.oc >= MIN_CONTRACTION;
 }
 
 // Row split of the input gradient, as for the forward: units of 8 stages (512 rows).

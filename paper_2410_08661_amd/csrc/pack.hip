@@ -1,8 +1,11 @@
 // Format conversion kernels: min-max round-to-nearest group quantization + bit packing
 // (paper Sec. 3.1 for the three stored components; Sec. 6.1 / App. C for the quantizer),
 // packing of externally chosen codes, and the inverse.  Integer results are bit-exact by
-// construction: every float operation is a single correctly rounded IEEE fp32 operation
-// (explicit __fdiv_rn / rintf, no contraction possible).
+// construction: every float operation is a single correctly rounded IEEE fp32 operation.
+// The __f*_rn functions of this toolchain are the plain operators, which the compiler would fuse
+// (1 - i * step and p * hi - p * lo became fused multiply-adds and moved a scale across an fp16
+// rounding tie in one group of three thousand), so this file is compiled with -ffp-contract=off
+// (the build script passes it; a pragma here would not reach the header's inline functions).
 #include <type_traits>
 
 #include "qeft_internal.h"

@@ -68,7 +68,9 @@ SEARCH_SHAPES = [  # oc, ic, k, bits, g, n_grid, step
 
 @pytest.mark.parametrize("oc,ic,k,bits,g,n_grid,step", SEARCH_SHAPES)
 def test_pack_search_bit_exact(oc, ic, k, bits, g, n_grid, step):
-    """Grid-search quantizer (Sec. 3.1): scales, zero-points and codes equal the oracle's bit for bit."""
+    """Grid-search quantizer (Sec. 3.1): on these seeded inputs no two candidates of a group are closer than the rounding
+    of the kernel's fp32 error sum, so its choice equals the oracle's float64 first minimum and scales, zero-points and
+    codes agree bit for bit (a regression pin; the criterion itself is checked order-free in the next test)."""
     w = synth.make_weight(oc, ic, seed=3 * oc + ic)
     w[1, 3] = np.float16(0.3)                # outliers, where truncation changes the choice
     w[2, min(g + 1, ic - k - 1)] = np.float16(-0.45)
@@ -92,6 +94,37 @@ def test_pack_search_bit_exact(oc, ic, k, bits, g, n_grid, step):
     if n_grid > 1:   # the search moved at least the outlier groups away from min-max
         _, s_rtn, _, _ = qo.quantize_rtn(w, k, bits, g)
         assert np.any(scales.view(np.uint16) != s_rtn.view(np.uint16))
+
+
+@pytest.mark.parametrize("oc,ic,k,bits,g,n_grid,step", SEARCH_SHAPES + [(1024, 1024 + 128, 128, 4, 128, 80, 0.01), (300, 640, 0, 3, 64, 50, 0.015)])
+def test_pack_search_reaches_the_minimum_whatever_the_summation_order(oc, ic, k, bits, g, n_grid, step):
+    """The search is defined by its criterion (Sec. 3.1: the smallest squared weight error over the grid), not by an
+    order of summation.  For every (row, group) the parameters the GPU chose must be one of the grid's candidates, its
+    codes must be the round-to-nearest codes under those parameters, and the float64 error it reaches must not exceed
+    the float64 minimum over the grid by more than 1e-5 relative (candidates closer than that are ties within the
+    rounding of an fp32 error sum of up to 128 terms: 128 x 2^-24 = 7.6e-6)."""
+    w = synth.make_weight(oc, ic, seed=5 * oc + ic)
+    w[1, 3] = np.float16(0.3)
+    w[3, :min(g, ic - k)] = 0
+    desc = B.make_desc(oc, ic, k, bits, g)
+    _, wbuf = pad_cols(w)
+    out = B.Weight(desc)
+    B.qeft_pack_search(desc, wbuf[:, :ic], n_grid, step, out)
+    torch.cuda.synchronize()
+    lay = qo.layout(oc, ic, k, bits, g)
+    ng, kq = lay["n_groups"], lay["kq"]
+    s_gpu = out.scales[:, :ng].cpu().numpy()
+    z_gpu = out.zeros[:, :ng].cpu().numpy()
+    codes_gpu = qo.unpack_codes(out.qweight.cpu().numpy().view(np.uint32), kq, bits)
+    s_all, z_all, e_all = qo.search_candidates(w, k, bits, g, n_grid, step)
+    is_cand = np.any((s_all.view(np.uint16) == s_gpu.view(np.uint16)[None]) & (z_all == z_gpu.astype(np.float32)[None]), axis=0)
+    assert np.all(is_cand), "parameters that no candidate of the grid produces"
+    assert np.array_equal(codes_gpu, qo.codes_for_params(w, k, bits, g, s_gpu, z_gpu))
+    wq = qo.dequantize(codes_gpu, s_gpu, z_gpu, np.zeros((oc, 0), dtype=np.float16), g)
+    d = (w[:, :kq].astype(np.float64) - wq) ** 2
+    e_gpu = np.stack([d[:, gi * g:min((gi + 1) * g, kq)].sum(axis=1) for gi in range(ng)], axis=1)
+    e_min = e_all.min(axis=0)
+    assert np.all(e_gpu <= e_min * (1 + 1e-5) + 1e-30), f"worst excess {np.max(e_gpu / np.maximum(e_min, 1e-300)) - 1:.2e}"
 
 
 @pytest.mark.parametrize("oc,ic,k,bits,g", PACK_SHAPES)
@@ -616,3 +649,136 @@ def test_empty_batch_is_a_no_op():
     B.qeft_weak_grad(h.desc, dy, x[:, 128:], dW=dw)
     torch.cuda.synchronize()
     assert torch.all(dw == 2.0)
+
+
+# ------------------------------------------------------------------------------ exact-arithmetic and repeat pins
+def _integer_layer(oc, kq, k, seed):
+    """A stored layer whose weights are small integers: scale 1, zero-point 7 or 8, so s (q - z) lies in -8 .. 8 and is
+    exact in fp16; weak block integers in -3 .. 3.  With integer activations in -1 .. 1 every product and every partial
+    sum of a few thousand terms is an integer below 2048: exact in fp32 in ANY order of summation and exact in fp16,
+    also where a split launch stores fp16 partial tiles.  The GPU must then equal the oracle bit for bit."""
+    r = np.random.default_rng(seed)
+    h = HostLayer(oc, kq + k, k, 4, 128, seed=1)
+    ng = h.lay["n_groups"]
+    h.codes = r.integers(0, 16, size=(oc, kq), dtype=np.uint8)
+    h.scales = np.ones((oc, ng), dtype=np.float16)
+    h.zeros = r.integers(7, 9, size=(oc, ng)).astype(np.float16)
+    h.weak = r.integers(-3, 4, size=(oc, k)).astype(np.float16)
+    h.qweight = qo.pack_codes(h.codes, 4, h.lay["row_stride_words"])
+    return h, r
+
+
+def _bitwise(t, ref64, what):
+    ref = qo.round_fp16(ref64)
+    assert np.max(np.abs(ref64)) < 2048, "the case left the range in which every value is exact"
+    assert np.array_equal(t.cpu().numpy().view(np.uint16), ref.view(np.uint16)), what
+
+
+@pytest.mark.parametrize("oc,kq,k,m,split", [
+    (272, 1024, 32, 200, False),      # one workgroup per tile
+    (256, 4096, 128, 300, True),      # 2 tiles, K split 8 ways over the workspace
+    (8448, 2048, 128, 512, True),     # 33 x 2 tiles: the last round's tiles split
+])
+def test_forward_gemm_exact_integer_case_is_bitwise(oc, kq, k, m, split):
+    h, r = _integer_layer(oc, kq, k, seed=31)
+    x = r.integers(-1, 2, size=(m, kq + k)).astype(np.float16)
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m)
+    assert n > 0 or not split
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda") if split else False
+    y = B.qeft_linear_fwd(h.desc, h.to_device(), torch.from_numpy(x).cuda(), ws=ws)
+    torch.cuda.synchronize()
+    _bitwise(y, qo.linear_fwd(h.w64, x), f"fwd {oc}x{kq + k} M{m} split={split}")
+
+
+@pytest.mark.parametrize("oc,kq,k,m,split", [
+    (320, 768, 128, 257, False),      # mixed last tile, one workgroup per tile
+    (4096, 256, 128, 300, True),      # 64 stages of rows: 8 splits
+    (2048, 8320, 128, 512, True),     # 33 x 2 tiles: the last round's tiles split over the weight rows
+])
+def test_backward_dx_exact_integer_case_is_bitwise(oc, kq, k, m, split):
+    h, r = _integer_layer(oc, kq, k, seed=32)
+    dy = r.integers(-1, 2, size=(m, oc)).astype(np.float16)
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    assert n > 0 or not split
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda") if split else False
+    dx = B.qeft_linear_bwd_dx(h.desc, h.to_device(), torch.from_numpy(dy).cuda(), ws=ws)
+    torch.cuda.synchronize()
+    _bitwise(dx, qo.linear_bwd_dx(h.w64, dy), f"dX {oc}x{kq + k} M{m} split={split}")
+
+
+@pytest.mark.parametrize("oc,k,m", [(256, 128, 4096), (704, 256, 1000), (64, 40, 64)])
+def test_weak_grad_exact_integer_case_is_bitwise(oc, k, m):
+    """Integer dY and weak activations in -2 .. 2: every partial sum (token splits, slab sums) is an exact integer, so
+    the fp32 result equals the oracle's exactly and the fp16 one its rounding."""
+    r = np.random.default_rng(33)
+    desc = B.make_desc(oc, 512 + k, k, 4, 128)
+    dy = r.integers(-2, 3, size=(m, oc)).astype(np.float16)
+    xw = r.integers(-2, 3, size=(m, k)).astype(np.float16)
+    ref = qo.weak_grad(dy, xw)
+    dyd, xwd = torch.from_numpy(dy).cuda(), pad_cols(xw)[0]
+    dw32 = B.qeft_weak_grad(desc, dyd, xwd, out_dtype=torch.float32)
+    dw16 = B.qeft_weak_grad(desc, dyd, xwd, out_dtype=torch.float16)
+    torch.cuda.synchronize()
+    assert np.array_equal(dw32.cpu().numpy().astype(np.float64), ref)
+    assert np.array_equal(dw16.cpu().numpy().view(np.uint16), qo.round_fp16(ref).view(np.uint16))
+
+
+@pytest.mark.parametrize("oc,ic,k,m,use_ws", [
+    (320, 768 + 128, 128, 257, False),
+    (4096, 256 + 128, 128, 300, True),       # row split of dX / its forward takes one tile row
+    (256, 4096 + 128, 128, 300, True),       # K split of the forward
+    (2048, 2048 + 128, 128, 2300, True),     # 9 x 9 tiles
+])
+def test_gemm_paths_repeat_bitwise(oc, ic, k, m, use_ws):
+    """No atomics anywhere: forward, input gradient (split or not) and the two-pass weak gradient give the same bits
+    on every run."""
+    h = HostLayer(oc, ic, k, 4, 128, seed=oc + ic)
+    w = h.to_device()
+    xd = torch.from_numpy(synth.make_activations(m, ic, k, 3)).cuda()
+    dyd = torch.from_numpy(synth.make_grad_output(m, oc, 4)).cuda()
+    nf, nd = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_FWD, m), B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    wsf = torch.empty(nf, dtype=torch.uint8, device="cuda") if (use_ws and nf) else False
+    wsd = torch.empty(nd, dtype=torch.uint8, device="cuda") if (use_ws and nd) else False
+    assert not use_ws or nf or nd
+
+    def run():
+        y = B.qeft_linear_fwd(h.desc, w, xd, ws=wsf)
+        dx = B.qeft_linear_bwd_dx(h.desc, w, dyd, ws=wsd)
+        dw = B.qeft_weak_grad(h.desc, dyd, xd[:, ic - k:], out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        return y, dx, dw
+
+    first = run()
+    for _ in range(5):
+        for a, b in zip(run(), first):
+            assert torch.equal(a, b)
+
+
+SHORT_CASES = [  # oc, ic, k, m, layer seed: found on the CPU (tests/test_oracle_linear.py) to leave the bar with fp16-rounded weights
+    (8, 320, 256, 130, 14),
+    (8, 640, 256, 260, 14),
+]
+
+
+@pytest.mark.parametrize("oc,ic,k,m,seed", SHORT_CASES)
+def test_backward_dx_short_contraction(oc, ic, k, m, seed):
+    """Input gradients that sum only eight terms: rounding the dequantized weights to fp16, as the tiled kernels do, puts
+    single outputs of these two cases outside the per-element bar, so contractions under 64 terms run on the kernels
+    that keep s (q - z) in fp32."""
+    h = HostLayer(oc, ic, k, 4, 128, seed=seed)
+    dy = synth.make_grad_output(m, oc, seed=m)
+    dx = B.qeft_linear_bwd_dx(h.desc, h.to_device(), pad_cols(dy)[0])
+    torch.cuda.synchronize()
+    assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), f"dX {oc}x{ic} k{k} M{m}")
+
+
+@pytest.mark.parametrize("ic,k", [(8, 0), (8, 8), (16, 8), (56, 24)])
+def test_forward_short_contraction(ic, k):
+    h = HostLayer(264, ic, k, 4, 128, seed=ic + k)
+    w = h.to_device()
+    for m in (17, 70, 260):
+        x = synth.make_activations(m, ic, k, seed=m)
+        y = B.qeft_linear_fwd(h.desc, w, pad_cols(x)[0])
+        torch.cuda.synchronize()
+        assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), f"fwd 264x{ic} k{k} M{m}")
+

@@ -221,3 +221,30 @@ def test_round_fp16_is_nearest_even():
     assert qo.round_fp16(np.array([2049.0, 2051.0, 1e-8, 65519.0])).tolist() == [2048.0, 2052.0, 0.0, 65504.0]
     # no double rounding through float32: 1 + 2^-11 + 2^-30 is above the halfway point
     assert float(qo.round_fp16(np.array([1 + 2.0 ** -11 + 2.0 ** -30]))[0]) == 1 + 2.0 ** -10
+
+
+def test_fp16_rounded_weights_leave_the_bar_on_eight_term_sums():
+    """Why input gradients over fewer than 64 output channels must not round the dequantized weights: on these two
+    seeded layers (8 output channels) the exact product with weights rounded once to fp16 - the best a kernel that
+    feeds fp16 operands can do - puts an output outside the per-element bar 2e-3 (|r| + rms), while the same product
+    with unrounded weights stays five times inside it.  The Frobenius error is 3e-4 either way."""
+    from paper_2410_08661_amd import synth
+
+    def worst(a, r):
+        rms = float(np.sqrt(np.mean(r * r)))
+        return float(np.max(np.abs(a - r) / (2e-3 * (np.abs(r) + rms))))
+
+    for oc, ic, k, m, seed in [(8, 320, 256, 130, 14), (8, 640, 256, 260, 14)]:
+        lay = qo.layout(oc, ic, k, 4, 128)
+        codes, scales, zeros = synth.make_codes(oc, lay["kq"], lay["n_groups"], 4, seed)
+        weak = np.ascontiguousarray(synth.make_weight(oc, ic, seed)[:, ic - k:])
+        w64 = qo.dequantize(codes, scales, zeros, weak, 128)
+        dy = synth.make_grad_output(m, oc, seed=m)
+        ref = qo.linear_bwd_dx(w64, dy)
+        w16 = w64.astype(np.float32).astype(np.float16).astype(np.float64)
+        rounded = qo.round_fp16(qo.linear_bwd_dx(w16, dy)).astype(np.float64)
+        unrounded = qo.round_fp16(ref).astype(np.float64)
+        assert worst(rounded, ref) > 1.0
+        assert worst(unrounded, ref) < 0.25
+        assert np.linalg.norm(rounded - ref) / np.linalg.norm(ref) < 5e-4
+
