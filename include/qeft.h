@@ -254,6 +254,22 @@ int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t l
                    const void* Xw, int64_t ldxw, void* dW, int out_dtype, int accumulate,
                    void* ws, size_t ws_bytes, void* stream);
 
+/* qeft_weak_grad for callers that cannot allocate and cannot hand over a workspace: code under HIP graph
+ * capture, tight training or serving loops, harnesses that forbid hipMalloc.  Same arguments without ws, same
+ * kernels and bit-identical results; the partial sums of the token split go to a device array inside the
+ * library (QEFT_NOALLOC_SCRATCH_BYTES per GPU, held until the process ends) instead.  The call allocates
+ * nothing and frees nothing.
+ *   - QEFT_ERR_WORKSPACE when qeft_workspace_bytes(desc, QEFT_OP_WEAK_GRAD, M) exceeds
+ *     QEFT_NOALLOC_SCRATCH_BYTES (all Llama-2 7B / 13B / 70B layer shapes fit); QEFT_ERR_UNSUPPORTED for the
+ *     shapes qeft_weak_grad runs on its general kernel (M < 64, k > 256, k or OC not a multiple of 8) - it
+ *     needs no workspace for those, call it instead.
+ *   - Uses the array of the device that is current at the call, which must be the stream's device.
+ *   - All calls on one GPU share that GPU's array: calls whose execution may overlap (different streams)
+ *     race on it.  Calls ordered on one stream are safe; the buffer's previous contents are never read. */
+#define QEFT_NOALLOC_SCRATCH_BYTES (14u * 1024u * 1024u)
+int qeft_weak_grad_noalloc(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy,
+                           const void* Xw, int64_t ldxw, void* dW, int out_dtype, int accumulate, void* stream);
+
 /* Static, never NULL. */
 const char* qeft_status_string(int status);
 

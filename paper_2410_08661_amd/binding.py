@@ -70,6 +70,8 @@ EXPORTS = {
                                   C.c_void_p]),
     "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_weak_grad_noalloc": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
+                                         C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "qeft_status_string": (C.c_char_p, [C.c_int]),
 }
 
@@ -336,3 +338,15 @@ def qeft_weak_grad(desc, dY: torch.Tensor, Xw: torch.Tensor, dW: torch.Tensor | 
                               Xw.stride(0) if M else max(desc.n_weak, 8), _ptr(dW), code, int(bool(accumulate)),
                               _ptr(ws), ws.numel() if ws is not None else 0, _stream()), "qeft_weak_grad")
     return dW
+
+
+def qeft_weak_grad_noalloc(desc, dY: torch.Tensor, Xw: torch.Tensor, dW: torch.Tensor, accumulate=False) -> torch.Tensor:
+    """qeft_weak_grad without a workspace argument: the library's own per-GPU scratch array takes the partial sums.
+    dW must be given (this call allocates nothing, here or in the library)."""
+    M = dY.shape[0]
+    code = {torch.float16: QEFT_DTYPE_F16, torch.float32: QEFT_DTYPE_F32}[dW.dtype]
+    _check(raw.qeft_weak_grad_noalloc(C.byref(desc), _ptr(dY), M, dY.stride(0) if M else desc.out_features, _ptr(Xw),
+                                      Xw.stride(0) if M else max(desc.n_weak, 8), _ptr(dW), code, int(bool(accumulate)),
+                                      _stream()), "qeft_weak_grad_noalloc")
+    return dW
+
