@@ -15,7 +15,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libqeft.so")
 
-SOURCES = ["api.hip", "generic.hip", "pack.hip", "irregular.hip", "reorder.hip", "gemv.hip", "gemm.hip", "noalloc.hip"]
+SOURCES = ["api.hip", "generic.hip", "pack.hip", "irregular.hip", "reorder.hip", "gemv.hip", "gemv_dot.hip", "gemm.hip", "noalloc.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

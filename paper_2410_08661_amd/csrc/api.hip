@@ -253,7 +253,7 @@ int qeft_linear_fwd_group(int n, const qeft_desc_t* descs, const qeft_weight_t* 
     if (st != QEFT_OK) return st;
     if (M == 0) return QEFT_OK;
     hipStream_t s = (hipStream_t)stream;
-    if (n > 1 && M <= 4 && gemv_supported(Ls[0], M, ldx)) {
+    if (n > 1 && M <= 16 && gemv_supported(Ls[0], M, ldx)) {
         __half* ys[QEFT_MAX_GROUP];
         for (int i = 0; i < n; ++i) ys[i] = (__half*)Y[i];
         bool handled = false;

@@ -26,8 +26,13 @@
 //     Sx), one barrier; a launch-latency-shaped prologue (see the kernel).  It also takes a
 //     group of layers that share X (query / key / value, gate / up) as one launch: its tiles
 //     are those of layer 0, then layer 1, ..., each wave picking its layer's pointers;
+//   * register kernel (5 <= M <= 16): one wave per K range keeps the A fragments of its range in registers
+//     for the whole launch (no staging, no barrier before the stream), walks several row tiles and meets the
+//     other waves' partial tiles in LDS at the end;
+//   * one activation row goes to a kernel of its own (gemv_dot.hip): whole rows per wave, two-element dot
+//     products, activations in registers;
 //   * row-batch kernel (any M <= 16): nothing staged, A fragments straight from X, Sx from the
-//     matrix core;
+//     matrix core (fallback for shapes the register kernel does not take);
 //   * 3-bit kernel (any M <= 16): weight-side dequantization, ten codes per word;
 //   * chunked kernel: each wave stages its own slice, CH steps at a time (fallback only).
 //
@@ -946,6 +951,167 @@ hipError_t launch_w3(const Layer& L, const __half* X, int M, int64_t ldx, __half
     return hipGetLastError();
 }
 
+// =============================================================================================
+// Register kernel: any M <= 16, rows up to MAXSTEPS * 128 columns per pass.  The activations never touch LDS:
+// a workgroup has one wave per K range of S steps, and lane (n, kb) of a wave keeps, for the whole launch, the A
+// fragments of activation row n for its range (4 S registers of 8 halfs, fetched straight from X with 128-bit
+// loads and permuted once), together with the group sums Sx of its steps in accumulator layout (from MFMAs
+// against an all-ones operand).  The launch therefore starts streaming weights at once - no staging pass, no
+// barrier - and costs the same for M = 1 and M = 16.  A workgroup walks T row tiles (compile-time, so every
+// load is unconditional) with D tiles of weight loads in flight; the K-split partial tiles stay in registers
+// and meet in LDS once, at the end.  Several layers that share X run as one launch (tiles of layer 0, 1, ...).
+// =============================================================================================
+struct RegsArgs {
+    const uint32_t* qweight[MAX_GROUP];
+    const __half* scales[MAX_GROUP];
+    const __half* zeros[MAX_GROUP];
+    const __half* weak[MAX_GROUP];
+    __half* Y[MAX_GROUP];
+    int64_t ldy[MAX_GROUP];
+    int oc[MAX_GROUP];
+    int tile_begin[MAX_GROUP];   // first 16-row tile of layer i; INT_MAX when absent
+    int n_tiles;
+    const __half* X;
+    int64_t ldx;
+    int M, kq, k, nq, stride, gs;
+};
+
+// S: steps per wave and pass; D: tiles in flight; T: tiles per workgroup; XM: activation rows fetched (1, 4: one
+// 128-bit load per row covers the wave's whole range and the fragments are dealt out through a wave-private piece
+// of LDS; 16: every lane fetches the fragments of its own row); MAXW: waves per workgroup at most (register
+// budget); MULTI: rows longer than one pass of the workgroup (KS * S steps) take `passes` passes - the
+// accumulators stay, the activation registers are refilled at each pass boundary and the weight requests run on
+// across it.  LDS: per wave max(XM, T) KB - first the activation bounce, at the end this wave's partial tiles.
+template <int S, int D, int T, int XM, int MAXW, bool MULTI>
+__global__ __launch_bounds__(64 * MAXW) void gemv_w4_regs_kernel(RegsArgs A, int passes) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    static_assert(S == 4, "a wave's range is 4 steps = 512 columns = 64 pieces of 16 bytes");
+    constexpr int WKB = XM == 16 ? T : (XM > T ? XM : T);   // KB of LDS per wave
+    const int lane = threadIdx.x & 63;
+    const int KS = blockDim.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, kb = lane >> 4;
+    const int nweak = (A.k + 31) >> 5;
+    const int wt = min(wave, nweak - 1);            // weak step of this wave (waves past the block repeat the last, with zero activations)
+    const u4 zero4 = u4{0u, 0u, 0u, 0u};
+    const int C = MULTI ? passes : 1;
+    unsigned char* mine = lds + (size_t)wave * (WKB * 1024);
+
+    // ---- per-tile pointers (wave-uniform) and requests --------------------------------------------------------
+    u4 wq[D][S], wk[D];
+    u2 sb[D], zb[D];
+    auto issue = [&](int d, int t, int c) {   // t: tile of this workgroup (compile-time), clamped to the launch's last tile; c: pass
+        const int tile_g = min((int)blockIdx.x * T + t, A.n_tiles - 1);
+        const int li = (tile_g >= A.tile_begin[1]) + (tile_g >= A.tile_begin[2]) + (tile_g >= A.tile_begin[3]);
+        const int row0 = (tile_g - A.tile_begin[li]) * 16;
+        const size_t orow = (size_t)min(row0 + n, A.oc[li] - 1);
+        const int js0 = (min(c, C - 1) * KS + wave) * S;
+        const unsigned char* wp = reinterpret_cast<const unsigned char*>(A.qweight[li] + orow * A.stride) + 16 * kb;
+#pragma unroll
+        for (int j = 0; j < S; ++j) wq[d][j] = load16(wp + 64 * min(js0 + j, (A.stride >> 4) - 1));
+        const int g0 = min(js0, A.gs - S);
+        sb[d] = load8(A.scales[li] + orow * A.gs + g0);
+        zb[d] = load8(A.zeros[li] + orow * A.gs + g0);
+        wk[d] = load16(A.weak[li] + orow * A.k + min(32 * wt + 8 * kb, A.k - 8));
+    };
+
+    const __half* xrow = A.X + (size_t)min(n, A.M - 1) * A.ldx;
+    u4 xw = load16(xrow + A.kq + min(32 * wt + 8 * kb, A.k - 8));
+    u4 ones = u4{0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+    asm volatile("" : "+v"(ones.x), "+v"(ones.y), "+v"(ones.z), "+v"(ones.w));
+    const Consts magic = make_consts();
+    f4 acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
+
+    for (int c = 0; c < C; ++c) {
+        const int js0 = (c * KS + wave) * S;   // first step of this wave in this pass
+        // ---- requests: the activations of this wave's range first (L2 hits), then (first pass) the first D tiles -----
+        u4 xa[S][4];
+        u4 xrows[XM == 16 ? 1 : XM];
+        if (XM == 16) {
+#pragma unroll
+            for (int j = 0; j < S; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xa[j][i] = load16(xrow + min(128 * (js0 + j) + 32 * kb + 8 * i, A.kq - 8));
+        } else {   // lane l: piece l (8 columns) of the wave's 512 columns, for each of the XM rows
+#pragma unroll
+            for (int m = 0; m < XM; ++m)
+                xrows[m] = load16(A.X + (size_t)min(m, A.M - 1) * A.ldx + min(128 * js0 + 8 * lane, A.kq - 8));
+        }
+        if (c == 0) {
+#pragma unroll
+            for (int d = 0; d < D; ++d)
+                if (d < T) issue(d, d, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
+
+        // ---- this wave's activations for the pass: nibble order, zeros past M / Kq, group sums ---------------------
+        if (XM != 16) {
+#pragma unroll
+            for (int m = 0; m < XM; ++m) *reinterpret_cast<u4*>(mine + 1024 * m + 16 * lane) = xrows[m];
+            wave_lds_fence();
+            const unsigned char* src = mine + 1024 * min(n, XM - 1) + 64 * kb;
+#pragma unroll
+            for (int j = 0; j < S; ++j)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) xa[j][i] = *reinterpret_cast<const u4*>(src + 256 * j + 16 * i);
+            wave_lds_fence();
+        }
+        f4 sx[S];
+#pragma unroll
+        for (int j = 0; j < S; ++j) {
+            sx[j] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool live = n < A.M && 128 * (js0 + j) + 32 * kb + 8 * i < A.kq;
+                xa[j][i] = permute_x(live ? xa[j][i] : zero4);
+                sx[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[j][i]), as_h8(ones), sx[j], 0, 0, 0);
+            }
+        }
+        const u4 xwc = (c == 0 && n < A.M && wave < nweak && 32 * wave + 8 * kb < A.k) ? xw : zero4;
+
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const int d = t % D;
+#pragma unroll
+            for (int j = 0; j < S; ++j) {
+                const float sf = half_at(sb[d], j), cz = 1024.f + half_at(zb[d], j);
+                step_tile(acc[t], xa[j], wq[d][j], sx[j], sf, cz, magic);
+            }
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xwc), as_h8(wk[d]), acc[t], 0, 0, 0);
+            if (t + D < T) issue(d, t + D, c);
+            else if (MULTI) issue(d, t + D - T, c + 1);   // the next pass's first tiles (after the last pass: repeats, never used)
+            __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its tile
+        }
+    }
+
+    // ---- K split: partial tiles meet in LDS, wave t sums and stores tile t -----------------------------------------
+#pragma unroll
+    for (int t = 0; t < T; ++t) *reinterpret_cast<f4*>(mine + 1024 * t + 16 * lane) = acc[t];
+    __syncthreads();
+    for (int t = wave; t < T; t += KS) {
+        const int tile_g = (int)blockIdx.x * T + t;
+        if (tile_g >= A.n_tiles) break;
+        f4 y = f4{0.f, 0.f, 0.f, 0.f};
+        for (int w = 0; w < KS; ++w) {
+            const f4 p = *reinterpret_cast<const f4*>(lds + (size_t)w * (WKB * 1024) + 1024 * t + 16 * lane);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) y[e] += p[e];
+        }
+        const int li = (tile_g >= A.tile_begin[1]) + (tile_g >= A.tile_begin[2]) + (tile_g >= A.tile_begin[3]);
+        const int o = (tile_g - A.tile_begin[li]) * 16 + n;
+        __half* Y = A.Y[li];
+        const int64_t ldy = A.ldy[li];
+        // accumulator element e of lane l is row 4 * (l / 16) + e, column l % 16 of the 16 x 16 tile
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int m = 4 * kb + e;
+            if (m < A.M && o < A.oc[li]) Y[(size_t)m * ldy + o] = __float2half_rn(y[e]);
+        }
+    }
+}
+
 constexpr int SMALL_LDS_LIMIT = 144 * 1024;   // of the 160 KB a CU has
 
 }  // namespace
@@ -1027,6 +1193,63 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
     return true;
 }
 
+// The register kernel over the 16-row tiles of n layers that share X.  Returns false (nothing launched) when the
+// shape does not fit it: not 4-bit / group 128, or a weak block wider than 32 columns per wave of the workgroup.
+bool launch_regs(const Layer* Ls, int n, const __half* X, int M, int64_t ldx, __half* const* Y, const int64_t* ldy, hipStream_t s,
+                 hipError_t* err) {
+    const Layer& L = Ls[0];
+    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || L.k < 8 || (L.kq % 8) != 0 || (L.k % 8) != 0 || M < 1 || M > 16) return false;
+    constexpr int S = 4;
+    // passes over K and waves per workgroup: at most 8 waves (two per SIMD keep the whole register file), rows longer
+    // than 8 x 4 steps in the fewest passes
+    const int units = ceil_div(L.ng, S);
+    const int passes = ceil_div(units, 8), ks = ceil_div(units, passes);
+    if (ceil_div(L.k, 32) > ks) return false;
+    RegsArgs A = {};
+    int tiles = 0;
+    for (int i = 0; i < MAX_GROUP; ++i) {
+        const Layer& Li = Ls[i < n ? i : 0];
+        A.qweight[i] = Li.qweight;
+        A.scales[i] = Li.scales;
+        A.zeros[i] = Li.zeros;
+        A.weak[i] = Li.weak;
+        A.Y[i] = Y[i < n ? i : 0];
+        A.ldy[i] = ldy[i < n ? i : 0];
+        A.oc[i] = Li.oc;
+        A.tile_begin[i] = i < n ? tiles : INT_MAX;
+        if (i < n) tiles += ceil_div(Li.oc, 16);
+    }
+    A.n_tiles = tiles;
+    A.X = X;
+    A.ldx = ldx;
+    A.M = M;
+    A.kq = L.kq;
+    A.k = L.k;
+    A.nq = L.ng;
+    A.stride = L.stride;
+    A.gs = L.gs;
+    // tiles per workgroup (they share the activation registers): the fewest for which all workgroups are resident at
+    // once - the register use of each variant sets the waves a CU holds (16 / 12 / 8)
+    int T = 1;
+    for (; T < 4; ++T) {
+        const int waves_cu = passes > 1 ? (T == 1 ? 12 : 8) : (T == 1 ? 16 : 12);
+        const int per_cu = waves_cu / ks < 1 ? 1 : waves_cu / ks;
+        if (ceil_div(tiles, T) <= 256 * per_cu) break;
+    }
+    const int grid = ceil_div(tiles, T);
+    const int xm = M == 1 ? 1 : (M <= 4 ? 4 : 16), xi = M == 1 ? 0 : (M <= 4 ? 1 : 2);
+    const int wkb = xm == 16 ? T : (xm > T ? xm : T);
+    const size_t lds_bytes = (size_t)ks * wkb * 1024;
+    using Kern = void (*)(RegsArgs, int);
+#define QEFT_REGS_ROW(XM, MU) {gemv_w4_regs_kernel<S, 1, 1, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 2, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 3, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 4, XM, 8, MU>}
+    static const Kern table[2][3][4] = {{QEFT_REGS_ROW(1, false), QEFT_REGS_ROW(4, false), QEFT_REGS_ROW(16, false)},
+                                        {QEFT_REGS_ROW(1, true), QEFT_REGS_ROW(4, true), QEFT_REGS_ROW(16, true)}};
+#undef QEFT_REGS_ROW
+    table[passes > 1 ? 1 : 0][xi][T - 1]<<<grid, 64 * ks, lds_bytes, s>>>(A, passes);
+    *err = hipGetLastError();
+    return true;
+}
+
 GroupTail no_tail() {
     GroupTail t = {};
     for (int i = 0; i < MAX_GROUP - 1; ++i) t.tile_begin[i] = INT_MAX;
@@ -1038,7 +1261,16 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, 
                           const int64_t* ldy, hipStream_t s, bool* handled) {
     *handled = false;
     const Layer& L = Ls[0];
-    if (n < 1 || n > MAX_GROUP || M64 > 4 || !(L.bits == 4 || L.dense) || L.kq < 8 || L.k < 8) return hipSuccess;
+    if (n < 1 || n > MAX_GROUP || M64 > 16 || !(L.bits == 4 || L.dense) || L.kq < 8 || L.k < 8) return hipSuccess;
+    if (M64 == 1) {   // one activation row: rows per wave, activations in registers
+        hipError_t e = gemv_dot_fwd(Ls, n, nullptr, X, Y, s, handled);
+        if (e != hipSuccess || *handled) return e;
+    }
+    if (M64 > 4) {    // 5 .. 16 rows: the register kernel (the small-M kernel below stages at most 4 rows)
+        hipError_t e = hipSuccess;
+        *handled = launch_regs(Ls, n, X, (int)M64, ldx, Y, ldy, s, &e);
+        return e;
+    }
     GroupTail tail = no_tail();
     int tiles = ceil_div(L.oc, 16);
     for (int i = 1; i < n; ++i) {
@@ -1061,6 +1293,10 @@ hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64
                          hipStream_t s, bool* handled) {
     *handled = false;
     if (M64 > 4 || L.bits != 4 || L.kq < 8 || L.k < 8) return hipSuccess;
+    if (M64 == 1) {
+        hipError_t e = gemv_dot_fwd(&L, 1, perm, X, &Y, s, handled);
+        if (e != hipSuccess || *handled) return e;
+    }
     hipError_t err = hipSuccess;
     *handled = launch_small(L, ceil_div(L.oc, 16), no_tail(), perm, X, (int)M64, ldx, Y, ldy, s, &err);
     return err;
@@ -1068,6 +1304,15 @@ hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64
 
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int M = (int)M64;
+    if (M > 4) {      // 5 .. 16 rows: activations in registers, any row length
+        hipError_t e = hipSuccess;
+        if (launch_regs(&L, 1, X, M, ldx, &Y, &ldy, s, &e)) return e;
+    }
+    if (M == 1) {
+        bool handled = false;
+        hipError_t e = gemv_dot_fwd(&L, 1, nullptr, X, &Y, s, &handled);
+        if (e != hipSuccess || handled) return e;
+    }
     if (M <= 4 && L.kq >= 8 && L.k >= 8 && (L.bits == 4 || L.dense)) {   // (dense 3-bit: gemv_supported has checked that rows hold whole steps)
         hipError_t err = hipSuccess;
         if (launch_small(L, ceil_div(L.oc, 16), no_tail(), nullptr, X, M, ldx, Y, ldy, s, &err)) return err;

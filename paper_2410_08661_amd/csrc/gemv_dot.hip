@@ -1,0 +1,396 @@
+// Decode at M = 1 (paper Sec. 3.2.1): Y = x . W^T for one activation row, every stored byte of the layer
+// streamed once.  A matrix-vector product has no reuse of the weights, so this kernel is shaped by the memory
+// system alone:
+//
+//   * a wavefront owns whole weight rows.  One 128-bit load per lane covers 1 KB of contiguous codes of a row
+//     (2048 columns, lane l the 32 columns 32 l .. 32 l + 31: a quarter of one 128-column group), so every
+//     request is a full, contiguous kilobyte of one DRAM page;
+//   * the activations live in registers for the whole launch: lane l keeps the 32 values of each of its column
+//     ranges (NL ranges per wave), already in the order the nibbles leave the conversion, together with their
+//     sums.  They are staged once per workgroup through LDS (coalesced read, transposed so that the per-lane
+//     reads are conflict-free); after that the row loop touches neither LDS nor a barrier;
+//   * dequantization is on the accumulator side: nibble pairs become the exact fp16 numbers 1024 + q (bits 0..3
+//     of each half) and 64 + q (bits 4..7, no shift needed: the exponent of 64 gives mantissa bit 4 the weight 1),
+//     two-element dot products accumulate x (base + q) in fp32, and the group's scale and zero-point are applied
+//     to the lane's partial sum: s ((sum x (base + q) - sum base x) - z sum x).  Nothing is rounded to fp16;
+//   * rows are dealt to the wavefronts in equal contiguous runs (DEPTH rows in flight, B batches per wave), the
+//     loads of the next batch are issued as each row of the current one is consumed; there are no conditional
+//     loads anywhere (rows past the end are clamped and never stored);
+//   * a row's 64 lane sums are added with data-parallel-primitive moves; the wave's results are stored together.
+//   * K can be split over KS waves of a workgroup when a row is too long for one wave's registers (the 70B
+//     down projection); their partial results meet in LDS once, at the end.
+//   * several layers that read the same input (q / k / v, gate / up) run as one launch: their rows are
+//     concatenated and each row looks up its layer with scalar compares.
+#include <climits>
+#include <cstdlib>
+#include <type_traits>
+
+#include "qeft_internal.h"
+
+namespace qeft {
+namespace {
+
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+
+constexpr int DOT_THREADS = 512;   // 8 waves: two per SIMD
+constexpr int DOT_WAVES = DOT_THREADS / 64;
+
+struct DotLayers {   // up to MAX_GROUP layers that share the input
+    const uint32_t* qweight[MAX_GROUP];
+    const __half* scales[MAX_GROUP];
+    const __half* zeros[MAX_GROUP];
+    const __half* weak[MAX_GROUP];
+    __half* Y[MAX_GROUP];
+    int oc[MAX_GROUP];
+    int set_begin[MAX_GROUP];   // first row set (a wave's run of rows) of layer i; INT_MAX when absent
+    int n_sets;
+};
+
+// a.x * b.x + a.y * b.y + c with fp32 products and sums
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, a), __builtin_bit_cast(h2, b), c, false);
+}
+
+// sum over the 64 lanes, valid in lane 63
+__device__ __forceinline__ float wave_sum_to_lane63(float t) {
+    auto dpp = [](float v, auto ctrl, auto rmask) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), decltype(ctrl)::value,
+                                                                     decltype(rmask)::value, 0xf, false));
+    };
+    t += dpp(t, std::integral_constant<int, 0xB1>{}, std::integral_constant<int, 0xf>{});    // quad_perm [1,0,3,2]
+    t += dpp(t, std::integral_constant<int, 0x4E>{}, std::integral_constant<int, 0xf>{});    // quad_perm [2,3,0,1]
+    t += dpp(t, std::integral_constant<int, 0x141>{}, std::integral_constant<int, 0xf>{});   // row_half_mirror
+    t += dpp(t, std::integral_constant<int, 0x140>{}, std::integral_constant<int, 0xf>{});   // row_mirror: every lane holds its row's sum
+    t += dpp(t, std::integral_constant<int, 0x142>{}, std::integral_constant<int, 0xa>{});   // row_bcast15 into rows 1 and 3
+    t += dpp(t, std::integral_constant<int, 0x143>{}, std::integral_constant<int, 0xc>{});   // row_bcast31 into rows 2 and 3
+    return t;
+}
+
+// NSCW: column ranges of 4096 per wave (two 1 KB loads each); DEPTH: rows in flight; NKW: weak dwords per lane.
+// LDS: pair-ordered activations [KS * NL][4 pieces][64 lanes] 16 B | (sum base x, sum x) float2 [KS * NL][64] |
+//      weak activations fp16 [KS * NKW * 128] | K-split exchange float [8 waves][64]
+template <int NSCW, int DEPTH, int NKW, bool PERM>
+__global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, int kq, int k, int row_bytes, int gs,
+                                                                   const __half* __restrict__ X, const int* __restrict__ perm, int ic,
+                                                                   int B, int ks_log2) {
+    constexpr int NL = 2 * NSCW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int KS = 1 << ks_log2;
+    const int kpart = wave & (KS - 1), wset = wave >> ks_log2;
+    const int nl_all = NL * KS;                       // 1 KB ranges of a row, all waves of a K split together
+    const int rpw = DEPTH * B;
+    const int li0 = kpart * NL;
+    // the wave's row set lies in ONE layer (each layer's rows are cut into sets of rpw on their own), looked up once
+    const int sidx_raw = blockIdx.x * (DOT_WAVES >> ks_log2) + wset;
+    const bool live = sidx_raw < R.n_sets;
+    const int sidx = min(sidx_raw, R.n_sets - 1);
+    const int li = (sidx >= R.set_begin[1]) + (sidx >= R.set_begin[2]) + (sidx >= R.set_begin[3]);
+    const int row_first = (sidx - R.set_begin[li]) * rpw, n_rows = R.oc[li];
+    const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(R.qweight[li]);
+    const unsigned char* const sbase = reinterpret_cast<const unsigned char*>(R.scales[li]);
+    const unsigned char* const zbase = reinterpret_cast<const unsigned char*>(R.zeros[li]);
+    const unsigned char* const kbase_p = reinterpret_cast<const unsigned char*>(R.weak[li]);
+    __half* const yout = R.Y[li];
+
+    // ---- per-lane offsets of the wave's loads within a row (clamped: lanes past the row read its last bytes, their x is 0)
+    // Group parameters: the four lanes of a quad share a group, so after a quad sum only one of them needs (s, z).
+    // Lane 4 g + m takes range 4 j + m of parameter set j: one 2-byte load per array and set fetches the parameters
+    // of up to four ranges (64 groups) of a row.
+    constexpr int NP = (NL + 3) / 4;
+    const int qm = lane & 3;
+    int woff[NL], goff[NP], koff[NKW];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) woff[i] = min(1024 * (li0 + i) + 16 * lane, row_bytes - 16);
+#pragma unroll
+    for (int j = 0; j < NP; ++j) goff[j] = 2 * min(16 * (li0 + 4 * j + qm) + (lane >> 2), gs - 1);
+#pragma unroll
+    for (int t = 0; t < NKW; ++t) koff[t] = 4 * min(lane + 64 * (t * KS + kpart), (k >> 1) - 1);
+
+    u4 wq[DEPTH][NL];
+    uint32_t sq[DEPTH][NP], zq[DEPTH][NP], wk[DEPTH][NKW];
+    auto issue = [&](int d, int row_in) {
+        const size_t lr = (size_t)min(row_in, n_rows - 1);
+        const unsigned char* wrow = wbase + lr * (size_t)row_bytes;
+        const unsigned char* srow = sbase + lr * (size_t)(2 * gs);
+        const unsigned char* zrow = zbase + lr * (size_t)(2 * gs);
+        const unsigned char* krow = kbase_p + lr * (size_t)(2 * k);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
+#pragma unroll
+        for (int j = 0; j < NP; ++j) {
+            sq[d][j] = *reinterpret_cast<const unsigned short*>(srow + goff[j]);
+            zq[d][j] = *reinterpret_cast<const unsigned short*>(zrow + goff[j]);
+        }
+#pragma unroll
+        for (int t = 0; t < NKW; ++t) wk[d][t] = *reinterpret_cast<const uint32_t*>(krow + koff[t]);
+    };
+
+    // ---- requests: the activations this thread stages, then the first DEPTH rows ----------------------------
+    // unit u = 8 columns of the padded quantized range [0, 2048 nl_all); XU units per thread and pass
+    constexpr int XU = 4;
+    const int n_units = 256 * nl_all;
+    u4 xv[XU];
+    auto load_units = [&](int base) {
+#pragma unroll
+        for (int t = 0; t < XU; ++t) {
+            const int u = base + t * DOT_THREADS + tid;
+            const int c0 = min(8 * u, kq - 8);
+            if (PERM) {
+                const u4 lo = *reinterpret_cast<const u4*>(perm + c0), hi = *reinterpret_cast<const u4*>(perm + c0 + 4);
+                const unsigned short* xr = reinterpret_cast<const unsigned short*>(X);
+                uint32_t h[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] = xr[min(max((int)(e < 4 ? lo[e] : hi[e - 4]), 0), ic - 1)];
+                xv[t] = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+            } else {
+                xv[t] = *reinterpret_cast<const u4*>(X + c0);
+            }
+        }
+    };
+    // pair order of a word's conversion: (x0, x4) (x1, x5) (x2, x6) (x3, x7); with it the unit's sums
+    // sum base x (base 1024 for the pairs at bits 0..3, 64 for those at bits 4..7) and sum x, added over the four
+    // units of a lane's 32 columns (threads 4 j .. 4 j + 3 of the staging pass hold them)
+    float2* ksum = reinterpret_cast<float2*>(lds + 4096 * nl_all);
+    unsigned char* xweak = lds + 4096 * nl_all + 512 * nl_all;
+    auto store_units = [&](int base) {
+#pragma unroll
+        for (int t = 0; t < XU; ++t) {
+            const int u = base + t * DOT_THREADS + tid;
+            u4 v = xv[t];
+            if (8 * u >= kq) v = u4{0u, 0u, 0u, 0u};
+            u4 p;
+            p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);   // (x0, x4)   base 1024
+            p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);   // (x1, x5)   base 64
+            p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);   // (x2, x6)   base 1024
+            p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);   // (x3, x7)   base 64
+            // (copies first: a bit cast applied directly to a vector component read the first component every time)
+            const uint32_t px = p.x, py = p.y, pz = p.z, pw = p.w;
+            const h2 a = __builtin_bit_cast(h2, px), b = __builtin_bit_cast(h2, py), c = __builtin_bit_cast(h2, pz),
+                     d = __builtin_bit_cast(h2, pw);
+            float se = ((float)a.x + (float)a.y) + ((float)c.x + (float)c.y);
+            float so = ((float)b.x + (float)b.y) + ((float)d.x + (float)d.y);
+            auto quad = [](float f) {
+                f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0xB1, 0xf, 0xf, false));
+                f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0x4E, 0xf, 0xf, false));
+                return f;
+            };
+            se = quad(se);
+            so = quad(so);
+            if (u < n_units) {
+                // range i = u / 256, lane l = (u % 256) / 4, piece q = u % 4  ->  [i][q][l]
+                const int i = u >> 8, l = (u & 255) >> 2, q = u & 3;
+                *reinterpret_cast<u4*>(lds + 4096 * i + 1024 * q + 16 * l) = p;
+                if (q == 0) ksum[64 * i + l] = float2{1024.f * se + 64.f * so, se + so};
+            }
+        }
+    };
+    load_units(0);
+    // the weak activations: one 16-byte unit per thread (k <= 8 * DOT_THREADS)
+    u4 xwv;
+    {
+        const int c0 = min(8 * tid, k - 8);
+        if (PERM) {
+            const u4 lo = *reinterpret_cast<const u4*>(perm + kq + c0), hi = *reinterpret_cast<const u4*>(perm + kq + c0 + 4);
+            const unsigned short* xr = reinterpret_cast<const unsigned short*>(X);
+            uint32_t h[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) h[e] = xr[min(max((int)(e < 4 ? lo[e] : hi[e - 4]), 0), ic - 1)];
+            xwv = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+        } else {
+            xwv = *reinterpret_cast<const u4*>(X + kq + c0);
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) issue(d, row_first + d);
+    __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
+
+    // ---- stage the activations --------------------------------------------------------------------------------
+    store_units(0);
+    if (8 * tid < k) *reinterpret_cast<u4*>(xweak + 16 * tid) = xwv;
+    for (int base = XU * DOT_THREADS; base < n_units; base += XU * DOT_THREADS) {   // rows longer than 16384 columns
+        load_units(base);
+        store_units(base);
+    }
+    __syncthreads();
+
+    // ---- this lane's activations, for the rest of the launch ----------------------------------------------------
+    uint32_t xr[NL][16];
+    float kbase[NL], ssum[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const u4 v = *reinterpret_cast<const u4*>(lds + 4096 * (li0 + i) + 1024 * q + 16 * lane);
+            xr[i][4 * q + 0] = v.x;
+            xr[i][4 * q + 1] = v.y;
+            xr[i][4 * q + 2] = v.z;
+            xr[i][4 * q + 3] = v.w;
+        }
+        const float2 ks2 = ksum[64 * (li0 + i) + lane];
+        kbase[i] = ks2.x;
+        ssum[i] = ks2.y;
+    }
+    auto quad_sum = [](float f) {
+        f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0xB1, 0xf, 0xf, false));
+        f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0x4E, 0xf, 0xf, false));
+        return f;
+    };
+    float ssel[NP];   // sum x of the group this lane applies the parameters of set j to (0: none)
+#pragma unroll
+    for (int j = 0; j < NP; ++j) ssel[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        const float sg = quad_sum(ssum[i]);
+        if (qm == (i & 3)) ssel[i >> 2] = sg;
+    }
+    uint32_t xw[NKW];
+#pragma unroll
+    for (int t = 0; t < NKW; ++t) {
+        const int dw = lane + 64 * (t * KS + kpart);
+        xw[t] = (2 * dw < k) ? *reinterpret_cast<const uint32_t*>(xweak + 4 * dw) : 0u;
+    }
+
+    uint32_t m_lo = 0x000f000fu, m_hi = 0x00f000f0u, g_lo = 0x64006400u, g_hi = 0x54005400u;
+    asm volatile("" : "+v"(m_lo), "+v"(m_hi), "+v"(g_lo), "+v"(g_hi));   // in registers: (w & m) | g is then one v_and_or_b32
+
+    float res = 0.f;   // lane j: the wave's result for its row j
+    auto compute = [&](int d, int j) {
+        float y = 0.f;
+        float tsel[NP];
+#pragma unroll
+        for (int jj = 0; jj < NP; ++jj) tsel[jj] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            float a0 = 0.f, a1 = 0.f;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t w = wq[d][i][q], w8 = w >> 8;
+                const uint32_t p0 = (w & m_lo) | g_lo, p1 = (w & m_hi) | g_hi, p2 = (w8 & m_lo) | g_lo, p3 = (w8 & m_hi) | g_hi;
+                a0 = dot2(p0, xr[i][4 * q + 0], a0);
+                a1 = dot2(p1, xr[i][4 * q + 1], a1);
+                a0 = dot2(p2, xr[i][4 * q + 2], a0);
+                a1 = dot2(p3, xr[i][4 * q + 3], a1);
+            }
+            const float tg = quad_sum((a0 + a1) - kbase[i]);   // sum x q of the group, in its four lanes
+            if (qm == (i & 3)) tsel[i >> 2] = tg;
+        }
+#pragma unroll
+        for (int jj = 0; jj < NP; ++jj) {
+            const float sc = (float)__builtin_bit_cast(_Float16, (unsigned short)sq[d][jj]);
+            const float z = (float)__builtin_bit_cast(_Float16, (unsigned short)zq[d][jj]);
+            y = fmaf(sc, fmaf(-z, ssel[jj], tsel[jj]), y);
+        }
+#pragma unroll
+        for (int t = 0; t < NKW; ++t)
+            y = dot2(wk[d][t], xw[t], y);
+        const float tot = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(y)), 63));
+        res = (lane == j) ? tot : res;
+    };
+
+    for (int b = 0; b + 1 < B; ++b) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            compute(d, b * DEPTH + d);
+            issue(d, row_first + (b + 1) * DEPTH + d);
+            __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its row
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) compute(d, (B - 1) * DEPTH + d);
+
+    // ---- K split: partial results meet in LDS; then one store per row ----------------------------------------------
+    if (KS > 1) {
+        float* xch = reinterpret_cast<float*>(xweak + 256 * KS * NKW);
+        if (kpart > 0) xch[64 * wave + lane] = res;
+        __syncthreads();
+        if (kpart == 0)
+            for (int p = 1; p < KS; ++p) res += xch[64 * (wave + p) + lane];
+    }
+    if (live && kpart == 0 && lane < rpw && row_first + lane < n_rows) yout[row_first + lane] = __float2half_rn(res);
+}
+
+struct DotPlan {
+    int nscw, depth, nkw, ks_log2, B;
+    size_t lds;
+    bool ok;
+};
+
+// Shapes the kernel takes, and how a launch is cut: column ranges per wave from the row length (a wave keeps at
+// most 4 x 4096 columns of activations in registers, longer rows are split over 2 or 4 waves), rows in flight so
+// that a wave has 4 - 8 KB of requests outstanding, batches so that the row sets fill the resident waves once.
+DotPlan dot_plan(const Layer& L, int n_rows) {
+    DotPlan p = {};
+    p.ok = false;
+    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || (L.kq % 8) != 0 || L.k < 8 || (L.k % 8) != 0) return p;
+    const int nl_all = ceil_div(L.kq, 2048);
+    int ks_log2 = 0;
+    while (ks_log2 < 2 && ceil_div(nl_all, 2 << ks_log2) > 4) ++ks_log2;
+    const int KS = 1 << ks_log2;
+    const int nscw = ceil_div(nl_all, 2 * KS);
+    if (nscw > 4) return p;
+    const int nkw = ceil_div(L.k, 128 * KS);
+    if (nkw > 2 || L.k > 8 * DOT_THREADS) return p;
+    p.nscw = nscw;
+    p.nkw = nkw;
+    p.ks_log2 = ks_log2;
+    p.depth = nscw == 1 ? 2 : 1;
+    const int occ_wg = nscw == 1 ? 2 : 1;                       // resident workgroups per CU the register budget allows
+    const int slots = 256 * occ_wg * (DOT_WAVES / KS);          // row sets resident at once
+    p.B = ceil_div(n_rows, p.depth * slots);
+    if (p.depth * p.B > 64) return p;                           // a wave keeps its rows' results one per lane
+    const int nl_pad = 2 * nscw * KS;
+    p.lds = (size_t)4096 * nl_pad + 512 * nl_pad + 256 * KS * nkw + (KS > 1 ? DOT_WAVES * 64 * sizeof(float) : 0);
+    p.ok = p.lds <= 64 * 1024;
+    return p;
+}
+
+using DotKern = void (*)(DotLayers, int, int, int, int, const __half*, const int*, int, int, int);
+
+template <bool PERM>
+DotKern dot_kernel(int nscw, int depth, int nkw) {
+#define QEFT_DOT(N, D) (nkw == 1 ? (DotKern)gemv_w4_dot_kernel<N, D, 1, PERM> : (DotKern)gemv_w4_dot_kernel<N, D, 2, PERM>)
+    if (nscw == 1) return depth == 2 ? QEFT_DOT(1, 2) : QEFT_DOT(1, 4);
+    if (nscw == 2) return depth == 2 ? QEFT_DOT(2, 2) : QEFT_DOT(2, 1);
+    if (nscw == 3) return QEFT_DOT(3, 1);
+    return QEFT_DOT(4, 1);
+#undef QEFT_DOT
+}
+
+}  // namespace
+
+// Layers Ls[0 .. n) share the input (same IC, k, bits, group size).  *handled = false, nothing launched, when
+// the shapes do not fit this kernel.
+hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X, __half* const* Y, hipStream_t s, bool* handled) {
+    *handled = false;
+    if (n < 1 || n > MAX_GROUP) return hipSuccess;
+    DotLayers R = {};
+    int rows = 0;
+    for (int i = 0; i < n; ++i) rows += Ls[i].oc;
+    const Layer& L = Ls[0];
+    DotPlan p = dot_plan(L, rows);
+    if (!p.ok) return hipSuccess;
+    const int rpw = p.depth * p.B;
+    int sets = 0;
+    for (int i = 0; i < MAX_GROUP; ++i) {
+        const Layer& Li = Ls[i < n ? i : 0];
+        R.qweight[i] = Li.qweight;
+        R.scales[i] = Li.scales;
+        R.zeros[i] = Li.zeros;
+        R.weak[i] = Li.weak;
+        R.Y[i] = Y[i < n ? i : 0];
+        R.oc[i] = Li.oc;
+        R.set_begin[i] = i < n ? sets : INT_MAX;
+        if (i < n) sets += ceil_div(Li.oc, rpw);
+    }
+    R.n_sets = sets;
+    const int blocks = ceil_div(sets, DOT_WAVES >> p.ks_log2);
+    const DotKern kern = perm ? dot_kernel<true>(p.nscw, p.depth, p.nkw) : dot_kernel<false>(p.nscw, p.depth, p.nkw);
+    kern<<<blocks, DOT_THREADS, p.lds, s>>>(R, L.kq, L.k, 4 * L.stride, L.gs, X, perm, L.ic, p.B, p.ks_log2);
+    *handled = true;
+    return hipGetLastError();
+}
+
+}  // namespace qeft

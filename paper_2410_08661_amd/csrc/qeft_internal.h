@@ -96,6 +96,10 @@ hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64
 hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M, int64_t ldx, __half* const* Y,
                           const int64_t* ldy, hipStream_t s, bool* handled);
 
+// Decode at M = 1: rows per wavefront, activations in registers (gemv_dot.hip).  Ls[0 .. n) share the input;
+// perm (or nullptr) gathers the activations from original channel order.  *handled = false: not this kernel's shape.
+hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X, __half* const* Y, hipStream_t s, bool* handled);
+
 // ---- prefill / fine-tune path: MFMA GEMMs (gemm.hip) ---------------------------------------
 bool gemm_fwd_supported(const Layer& L, int64_t M);
 // ws: optional device workspace of gemm_fwd_split_workspace() bytes (16-byte aligned); with it, launches of few tiles, or with a

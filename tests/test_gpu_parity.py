@@ -169,6 +169,10 @@ FWD_CASES = [  # oc, ic, k, bits, g, Ms
     (256, 2560 + 256, 256, 4, 128, [33]),            # GEMM path, 20 groups (three reloads of the group parameters)
     (2064, 2176 + 64, 64, 4, 128, [5, 16]),          # unstaged decode kernel with a K split, 17 groups
     (2064, 2000 + 64, 64, 3, 128, [1, 6, 16]),       # 3-bit decode kernel with a K split, ragged OC
+    (304, 4600 + 40, 40, 4, 128, [1, 7, 16]),        # 36 groups (the last partial): two passes of the register kernel, the second short
+    (96, 10880 + 128, 128, 4, 128, [1, 6]),          # the 7B down projection's row length: three passes of eight waves
+    (4112, 1024 + 256, 256, 4, 128, [1, 9]),         # 257 tiles, two waves per workgroup; weak block as wide as the register kernel takes
+    (64, 512 + 288, 288, 4, 128, [1, 5]),            # weak block too wide for the register kernel: the unstaged kernel
 ]
 
 
