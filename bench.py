@@ -20,7 +20,6 @@ events on the stream the kernels run on.  Prints one JSON line.
 """
 import argparse
 import json
-import math
 import os
 import sys
 import time
@@ -33,9 +32,13 @@ HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
 MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
-# the launches of the kernel in one step
+# the launches of the kernel in one step.  They are NOT measured in this run (counters need the profiler).
 TRAFFIC_DX_BYTES = (114.3e6 + 34.3e6 + 339.3e6 + 34.3e6 + 485.3e6 + 90.9e6) / 3
 TRAFFIC_GEMV_BYTES = (29.31e6 + 9.90e6 + 52.40e6 + 25.21e6) / 4
+TRAFFIC_SOURCE = "profiles/bench_7b_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script; not measured in this run)"
+# every stored byte of one 7B block with rows padded to 4 words and unpadded group parameters: the figure a
+# reader derives from the format alone; block_bytes below is what this build stores (rows padded to 16 words)
+ALGORITHMIC_BLOCK_BYTES = 115501056
 
 
 def main():
@@ -44,7 +47,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-other-models", action="store_true", help="skip the 13B / 70B fine-tune timings (a profile of the 7B workload alone)")
+    ap.add_argument("--no-other-models", action="store_true", help="skip the 13B / 70B timings (a profile of the 7B workload alone)")
+    ap.add_argument("--sustained-seconds", type=float, default=2.0, help="length of the back-to-back fine-tune leg")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -187,6 +191,41 @@ def main():
                                    gbs=round(nb / us / 1e3, 1)))
     gemv_kernel_gbs = gemv_bytes / (gemv_ms * 1e-3) / 1e9
 
+    def graph_period_us(fn, n_copies):
+        """fn(c) enqueues one launch on copy c; period of one launch inside a graph over all copies."""
+        fn(0)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=cap_stream):
+            for c in range(n_copies):
+                fn(c)
+        gr.replay()
+        torch.cuda.synchronize()
+        a, b = ev(), ev()
+        a.record()
+        for _ in range(n_rep):
+            gr.replay()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / (n_rep * n_copies)
+
+    # the same four launches at M = 8 (config 2 names M = 1 and M = 8)
+    x8 = {ic: synth_x(8, ic) for ic in {s[1] for s in block_shapes}}
+    y8 = [torch.empty((8, s[0]), dtype=torch.float16, device=dev) for s in block_shapes]
+    groups8 = [[B.Group([descs[block_shapes[i]] for i in idx], [layers[i] for i in idx], [y8[i] for i in idx])
+                for _, idx in launches] for layers in blocks]
+    decode_m8 = []
+    for li, (name, idx) in enumerate(launches):
+        def l8(c, li=li, idx=idx):
+            x = x8[block_shapes[idx[0]][1]]
+            if len(idx) == 1:
+                B.qeft_linear_fwd(descs[block_shapes[idx[0]]], blocks[c][idx[0]], x, y8[idx[0]])
+            else:
+                B.qeft_linear_fwd_group(None, None, x, group=groups8[c][li])
+        us = graph_period_us(l8, n_blocks)
+        decode_m8.append(dict(launch=name, us=round(us, 2), vs_M1=round(us / decode_kernels[li]["us"], 2)))
+    del x8, y8, groups8
+
     # ---- the attention output projection with its weak columns left in place (the layout the offline
     # reordering cannot reach): the same stored layer behind an on-the-fly gather of the activations
     d_o = descs[(4096, 4096)]
@@ -271,6 +310,50 @@ def main():
         del copies, ws3
     del w3
 
+    # ---- decode at M = 1 on the other models' blocks (outside the timed step): one graph per launch over enough
+    # distinct copies to exceed the last-level cache; random stored components
+    def rand_weight(desc_):
+        w_ = B.Weight(desc_)
+        w_.qweight.random_(-2**31, 2**31 - 1, generator=gen)
+        if desc_.bits == 3 and desc_.layout == B.QEFT_LAYOUT_CANONICAL:
+            w_.qweight.bitwise_and_(0x3fffffff)
+        w_.scales.copy_((torch.rand(w_.scales.shape, generator=gen, device=dev) * 0.008 + 0.004).half())
+        w_.zeros.copy_(torch.randint(0, 2 ** desc_.bits, w_.zeros.shape, generator=gen, device=dev).half())
+        w_.weak.copy_((torch.randn(w_.weak.shape, generator=gen, device=dev) * 0.02).half())
+        return w_
+
+    decode_other = []
+    other_blocks = [] if args.no_other_models else [
+        ("Llama-2-13B", 128, 4, B.QEFT_LAYOUT_CANONICAL, [("q/k/v", [(5120, 5120)] * 3), ("o", [(5120, 5120)]), ("gate/up", [(13824, 5120)] * 2), ("down", [(5120, 13824)])]),
+        ("Llama-2-13B", 128, 3, B.QEFT_LAYOUT_CANONICAL, [("q/k/v", [(5120, 5120)] * 3), ("o", [(5120, 5120)]), ("gate/up", [(13824, 5120)] * 2), ("down", [(5120, 13824)])]),
+        ("Llama-2-13B", 128, 3, B.QEFT_LAYOUT_DENSE3, [("q/k/v", [(5120, 5120)] * 3), ("o", [(5120, 5120)]), ("gate/up", [(13824, 5120)] * 2), ("down", [(5120, 13824)])]),
+        ("Llama-2-70B", 256, 4, B.QEFT_LAYOUT_CANONICAL, [("q/k/v", [(8192, 8192), (1024, 8192), (1024, 8192)]), ("o", [(8192, 8192)]), ("gate/up", [(28672, 8192)] * 2), ("down", [(8192, 28672)])]),
+    ]
+    for model, k_o, bits_o, lay_o, launches_o in other_blocks:
+        tot_us, tot_b, per_launch = 0.0, 0, []
+        for name, shapes in launches_o:
+            ds = [B.make_desc(oc, ic, k_o, bits_o, g, layout=lay_o) for oc, ic in shapes]
+            one = sum(B.Weight(d_).nbytes() for d_ in ds)
+            n_c = max(2, min(n_blocks * 2, int(1.1e9 // one)))
+            copies = [[rand_weight(d_) for d_ in ds] for _ in range(n_c)]
+            xo = torch.randn((1, shapes[0][1]), generator=gen, device=dev).half()
+            yo = [torch.empty((1, oc), dtype=torch.float16, device=dev) for oc, _ in shapes]
+            grp = [B.Group(ds, cw, yo) for cw in copies] if len(shapes) > 1 else None
+
+            def lo(c, ds=ds, copies=copies, xo=xo, yo=yo, grp=grp):
+                if grp is None:
+                    B.qeft_linear_fwd(ds[0], copies[c][0], xo, yo[0])
+                else:
+                    B.qeft_linear_fwd_group(None, None, xo, group=grp[c])
+            us = graph_period_us(lo, n_c)
+            per_launch.append(dict(launch=name, bytes=one, us=round(us, 2), gbs=round(one / us / 1e3, 1)))
+            tot_us += us
+            tot_b += one
+            del copies, grp
+        decode_other.append(dict(model=model, bits=bits_o, layout="dense" if lay_o == B.QEFT_LAYOUT_DENSE3 else "canonical", k=k_o,
+                                 block_bytes=tot_b, block_us=round(tot_us, 2), gbs=round(tot_b / tot_us / 1e3, 1),
+                                 pct_hbm_peak=round(100 * tot_b / tot_us / 1e3 / HBM_PEAK_GBS, 2), launches=per_launch))
+
     # ---- the other models' fine-tune shapes (outside the timed step; context for the 7B figures) ---------
     # forward and input gradient with the optional workspace (launches with few tiles, or with a sparsely filled last
     # round of tiles, split their contraction over it), weak gradient; random stored components, one layer per shape
@@ -309,6 +392,29 @@ def main():
                                      dx_us=round(us[1], 1), dx_tflops=round(fl / us[1] / 1e6, 1), dw_us=round(us[2], 1),
                                      step_tflops=round((2 * fl + 2.0 * m_o * oc * k_o) / sum(us) / 1e6, 1)))
             del w_o2, x_o, dy_o, y_o, dx_o, dw_o, ws_o
+
+    # ---- sustained: the fine-tune calls of the 7B shapes back to back for a few seconds (the timed step above lasts
+    # milliseconds; the chip is power-managed, so a short burst may not show the clock a long run settles at)
+    ft_flops_step = sum(4.0 * M_ft * f["shape"][0] * f["shape"][1] + 2.0 * M_ft * f["shape"][0] * k for f in ft)
+
+    def ft_calls():
+        for f in ft:
+            B.qeft_linear_fwd(f["desc"], f["w"], f["x"], f["y"])
+            B.qeft_linear_bwd_dx(f["desc"], f["w"], f["dy"], f["dx"])
+            B.qeft_weak_grad(f["desc"], f["dy"], f["x"][:, f["shape"][1] - k:], dW=f["dw"], ws=f["ws"])
+
+    sustained = None
+    if args.sustained_seconds > 0:
+        n_sus = max(20, int(args.sustained_seconds / 1.8e-3))
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(n_sus):
+            ft_calls()
+        e1.record()
+        torch.cuda.synchronize()
+        sus_ms = e0.elapsed_time(e1)
+        sustained = dict(seconds=round(sus_ms * 1e-3, 2), steps=n_sus, finetune_tflops=round(ft_flops_step * n_sus / sus_ms / 1e9, 1))
 
     # a plain device copy of known size: the reference for scaling rocprofv3's FETCH_SIZE / WRITE_SIZE
     # (timed as well: what a plain copy reaches on this machine, read + written bytes per second, as context for the HBM fraction)
@@ -362,7 +468,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": "Llama-2-7B layer shapes, w4 g128 k=128: decode M=1 over "
                                f"{n_blocks} distinct packed blocks (7 layers in 4 launches each: q/k/v, o, gate/up, down; one graph) + fine-tune M=4096 fwd+dX+dW_weak + pack",
-                   "block_bytes": block_bytes, "M_decode": 1, "M_finetune": M_ft},
+                   "block_bytes": block_bytes, "algorithmic_block_bytes": ALGORITHMIC_BLOCK_BYTES, "M_decode": 1, "M_finetune": M_ft},
         "pct_hbm_peak": round(100 * gemv_gbs / HBM_PEAK_GBS, 2),
         "decode_us_per_block": round(decode_ms * 1e3, 2),
         "finetune_tflops": round(ft_tflops, 1),
@@ -371,8 +477,13 @@ def main():
         "pack_search_us": round(pack_search_us, 1),
         "finetune_kernels": kernels,
         "roofline": {"kernel": "gemm_dx_rega_kernel", "bound": "mfma", "achieved": round(dx_tf, 1), "peak": MFMA_F16_PEAK_TF,
-                     "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": round(TRAFFIC_DX_BYTES)},
+                     "unit": "TFLOP/s", "frac": round(dx_tf / MFMA_F16_PEAK_TF, 4), "traffic": round(TRAFFIC_DX_BYTES),
+                     "traffic_source": TRAFFIC_SOURCE},
         "decode_kernels": decode_kernels,
+        "decode_M8": decode_m8,
+        "decode_other_models": decode_other,
+        "sustained": sustained,
+        "value_algorithmic_bytes_gbs": round(ALGORITHMIC_BLOCK_BYTES / (decode_ms * 1e-3) / 1e9, 1),
         "irregular_out_proj": {"layer": "4096x4096, weak columns at arbitrary channels (decode: gather inside the matrix-vector kernel; M=4096: a gather pass, then the same GEMM)",
                                "decode_us": round(irr_decode_us, 2),
                                "decode_us_reordered": next(dk["us"] for dk in decode_kernels if dk["launch"] == "o"),
@@ -381,9 +492,9 @@ def main():
         "finetune_other_models": other_models,
         "device_copy_gbs": round(copy_gbs, 1),
         "pct_of_device_copy": round(100 * gemv_gbs / copy_gbs, 1),
-        "roofline_gemv": {"kernel": "gemv_w4_small_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
+        "roofline_gemv": {"kernel": "gemv_w4_dot_kernel", "bound": "hbm", "achieved": round(gemv_kernel_gbs, 1),
                           "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gemv_kernel_gbs / HBM_PEAK_GBS, 4),
-                          "traffic": round(TRAFFIC_GEMV_BYTES),
+                          "traffic": round(TRAFFIC_GEMV_BYTES), "traffic_source": TRAFFIC_SOURCE,
                           "note": "stored bytes of the block's 7 layers / sum of its 4 launch periods, each launch "
                                   "replayed from a graph of its own (HIP events; gaps between launches included, "
                                   "host overhead not)"},
@@ -395,7 +506,10 @@ def main():
 
 def cpu_baseline(np, synth, k, bits, g):
     """The oracle as it stands, timed on the host: one 4096 x 4096 layer at M = 1
-    (unpack -> dequantize -> float64 product), scaled to the metric's unit."""
+    (unpack -> dequantize -> float64 product), scaled to the metric's unit; and, as a second leg, its
+    forward product at M = 256 on the same layer in GFLOP/s.  `cores` is what the host offers the process
+    (os.cpu_count(), capped by OMP_NUM_THREADS when that is set): the float64 product runs on the BLAS's
+    threads, the unpack / dequantize loops on one."""
     from oracle import qeft_oracle as qo
     oc, ic = 4096, 4096
     seed = synth.seed_for(2, 0)
@@ -405,18 +519,29 @@ def cpu_baseline(np, synth, k, bits, g):
     codes, scales, zeros, weak = qo.quantize_rtn(w16, k, bits, g)
     qweight = qo.pack_codes(codes, bits, lay["row_stride_words"])
     nbytes = lay["qweight_bytes"] + lay["scales_bytes"] + lay["zeros_bytes"] + lay["weak_bytes"]
-    reps, t_wall, t_cpu = 0, 0.0, 0.0
+    reps, t_wall = 0, 0.0
     while t_wall < 10.0 and reps < 50:
-        c0, w0 = time.process_time(), time.perf_counter()
+        w0 = time.perf_counter()
         w64 = qo.dequantize(qo.unpack_codes(qweight, lay["kq"], bits), scales, zeros, weak, g)
         y = qo.round_fp16(qo.linear_fwd(w64, x))
         t_wall += time.perf_counter() - w0
-        t_cpu += time.process_time() - c0
         reps += 1
+    x256 = synth.make_activations(256, ic, k, seed + 1)
+    g_reps, g_wall = 0, 0.0
+    while g_wall < 5.0 and g_reps < 200:
+        w0 = time.perf_counter()
+        y = qo.linear_fwd(w64, x256)
+        g_wall += time.perf_counter() - w0
+        g_reps += 1
+    cores = os.cpu_count() or 1
+    if os.environ.get("OMP_NUM_THREADS", "").isdigit():
+        cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
     return {"value": round(nbytes * reps / t_wall / 1e9, 4), "unit": "GB/s",
-            "cores": max(1, int(math.ceil(t_cpu / t_wall - 0.05))), "kind": "oracle",
+            "cores": cores, "kind": "oracle",
             "sample": f"{reps} x (unpack + dequantize + fp64 product) of one 4096x4096 w4 g128 k128 layer at M=1, "
-                      f"{t_wall:.1f} s of host time"}
+                      f"{t_wall:.1f} s of host time",
+            "gemm_gflops": round(2.0 * 256 * oc * ic * g_reps / g_wall / 1e9, 1),
+            "gemm_sample": f"{g_reps} x the oracle's fp64 forward product of the dequantized layer at M=256, {g_wall:.1f} s"}
 
 
 if __name__ == "__main__":
