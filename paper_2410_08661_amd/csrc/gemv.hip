@@ -1261,7 +1261,7 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, 
                           const int64_t* ldy, hipStream_t s, bool* handled) {
     *handled = false;
     const Layer& L = Ls[0];
-    if (n < 1 || n > MAX_GROUP || M64 > 16 || !(L.bits == 4 || L.dense) || L.kq < 8 || L.k < 8) return hipSuccess;
+    if (n < 1 || n > MAX_GROUP || M64 > 16 || L.kq < 8 || L.k < 8) return hipSuccess;
     if (M64 == 1) {   // one activation row: rows per wave, activations in registers
         hipError_t e = gemv_dot_fwd(Ls, n, nullptr, X, Y, s, handled);
         if (e != hipSuccess || *handled) return e;
@@ -1271,6 +1271,7 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, 
         *handled = launch_regs(Ls, n, X, (int)M64, ldx, Y, ldy, s, &e);
         return e;
     }
+    if (!(L.bits == 4 || L.dense)) return hipSuccess;   // ten 3-bit codes per word: per-layer calls
     GroupTail tail = no_tail();
     int tiles = ceil_div(L.oc, 16);
     for (int i = 1; i < n; ++i) {

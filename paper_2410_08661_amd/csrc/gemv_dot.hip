@@ -312,6 +312,177 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
     if (live && kpart == 0 && lane < rpw && row_first + lane < n_rows) yout[row_first + lane] = __float2half_rn(res);
 }
 
+// =============================================================================================
+// Three-bit codes, ten to a 32-bit word (the canonical layout), one activation row.  Same shape as the 4-bit kernel
+// above - whole rows per wave in contiguous 1 KB requests, activations in registers - with the group structure
+// read off the layout: 1 KB = 256 words = 2560 codes = exactly 20 groups of 128, and a lane's 16 bytes = 40 codes
+// = five chunks of 8.  Inside each run of 16 lanes (640 codes = 5 groups) the boundaries 128, 256, 384, 512 fall on
+// chunk boundaries of lanes 3, 6, 9 and 12; every other lane lies in one group.  So a lane keeps five chunk sums
+// (four two-element dot products each, codes as the exact fp16 numbers 1024 + q), splits them into "its first
+// group" and "its second group" by a per-lane prefix select, and applies the two groups' scales and zero-points
+// to those two sums: s (sum x (1024 + q) - (1024 + z) sum x).  A pair of codes never straddles words (ten per
+// word): one 6-bit field extract and one multiplication by 2^13 + 1 put its codes at bits 0..2 and 16..18.
+// The four parameters of a lane's two groups come with one 8-byte load per array (four consecutive groups
+// starting at an even one) and one byte permute.
+// LDS: activation chunks [NL][5][64 lanes] 16 B | chunk sums float [NL][5][64] | weak activations fp16 [128 NKW]
+// =============================================================================================
+template <int NL, int DEPTH, int NKW>
+__global__ __launch_bounds__(DOT_THREADS) void gemv_w3_dot_kernel(DotLayers R, int kq, int k, int row_bytes, int gs,
+                                                                   const __half* __restrict__ X, int B) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+    typedef uint32_t u2 __attribute__((ext_vector_type(2)));
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rpw = DEPTH * B;
+    const int sidx_raw = blockIdx.x * DOT_WAVES + wave;
+    const bool live = sidx_raw < R.n_sets;
+    const int sidx = min(sidx_raw, R.n_sets - 1);
+    const int li = (sidx >= R.set_begin[1]) + (sidx >= R.set_begin[2]) + (sidx >= R.set_begin[3]);
+    const int row_first = (sidx - R.set_begin[li]) * rpw, n_rows = R.oc[li];
+    const unsigned char* const wbase = reinterpret_cast<const unsigned char*>(R.qweight[li]);
+    const unsigned char* const sbase = reinterpret_cast<const unsigned char*>(R.scales[li]);
+    const unsigned char* const zbase = reinterpret_cast<const unsigned char*>(R.zeros[li]);
+    const unsigned char* const kbase_p = reinterpret_cast<const unsigned char*>(R.weak[li]);
+    __half* const yout = R.Y[li];
+
+    // ---- per-lane offsets; the lane's first group of range i is 20 i + 5 lane / 16, its parameters are halfs sel, sel + 1
+    // of the four fetched from the even group g' <= gs - 4
+    int woff[NL], goff[NL], koff[NKW];
+    uint32_t selb[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        woff[i] = min(1024 * i + 16 * lane, row_bytes - 16);
+        const int g_lo = 20 * i + ((5 * lane) >> 4);
+        const int gp = max(min(g_lo & ~1, gs - 4), 0);
+        const int sl = min(max(g_lo - gp, 0), 3), sh = min(sl + 1, 3);
+        goff[i] = 2 * gp;
+        selb[i] = (uint32_t)(2 * sl) | ((uint32_t)(2 * sl + 1) << 8) | ((uint32_t)(2 * sh) << 16) | ((uint32_t)(2 * sh + 1) << 24);
+    }
+#pragma unroll
+    for (int t = 0; t < NKW; ++t) koff[t] = 4 * min(lane + 64 * t, (k >> 1) - 1);
+
+    u4 wq[DEPTH][NL];
+    u2 sq[DEPTH][NL], zq[DEPTH][NL];
+    uint32_t wk[DEPTH][NKW];
+    auto issue = [&](int d, int row_in) {
+        const size_t lr = (size_t)min(row_in, n_rows - 1);
+        const unsigned char* wrow = wbase + lr * (size_t)row_bytes;
+        const unsigned char* srow = sbase + lr * (size_t)(2 * gs);
+        const unsigned char* zrow = zbase + lr * (size_t)(2 * gs);
+        const unsigned char* krow = kbase_p + lr * (size_t)(2 * k);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
+            sq[d][i] = *reinterpret_cast<const u2*>(srow + goff[i]);
+            zq[d][i] = *reinterpret_cast<const u2*>(zrow + goff[i]);
+        }
+#pragma unroll
+        for (int t = 0; t < NKW; ++t) wk[d][t] = *reinterpret_cast<const uint32_t*>(krow + koff[t]);
+    };
+
+    // ---- requests: the activations this thread stages, then the first DEPTH rows ----------------------------
+    // unit u = 8 columns: chunk u % 5 of lane position u / 5 (range (u / 5) / 64, lane (u / 5) % 64)
+    constexpr int XU = 4;
+    constexpr int n_units = 320 * NL;
+    static_assert(n_units <= XU * DOT_THREADS, "one staging pass");
+    u4 xv[XU];
+#pragma unroll
+    for (int t = 0; t < XU; ++t) xv[t] = *reinterpret_cast<const u4*>(X + min(8 * (t * DOT_THREADS + tid), kq - 8));
+    u4 xwv = *reinterpret_cast<const u4*>(X + kq + min(8 * tid, k - 8));
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) issue(d, row_first + d);
+    __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
+
+    float* csum = reinterpret_cast<float*>(lds + 5120 * NL);
+    unsigned char* xweak = lds + 5120 * NL + 1280 * NL;
+#pragma unroll
+    for (int t = 0; t < XU; ++t) {
+        const int u = t * DOT_THREADS + tid;
+        u4 v = xv[t];
+        if (8 * u >= kq) v = u4{0u, 0u, 0u, 0u};
+        const uint32_t vx = v.x, vy = v.y, vz = v.z, vw = v.w;
+        const h2 a = __builtin_bit_cast(h2, vx), b = __builtin_bit_cast(h2, vy), c = __builtin_bit_cast(h2, vz), d = __builtin_bit_cast(h2, vw);
+        const float su = (((float)a.x + (float)a.y) + ((float)b.x + (float)b.y)) + (((float)c.x + (float)c.y) + ((float)d.x + (float)d.y));
+        if (u < n_units) {
+            const int pos = u / 5, ch = u - 5 * pos, i = pos >> 6, l = pos & 63;
+            *reinterpret_cast<u4*>(lds + 5120 * i + 1024 * ch + 16 * l) = v;
+            csum[(5 * i + ch) * 64 + l] = su;
+        }
+    }
+    if (8 * tid < k) *reinterpret_cast<u4*>(xweak + 16 * tid) = xwv;
+    __syncthreads();
+
+    // ---- this lane's activations and group sums, for the rest of the launch ---------------------------------------
+    const int j16 = lane & 15;
+    const int bc = j16 == 3 ? 1 : (j16 == 6 ? 2 : (j16 == 9 ? 3 : (j16 == 12 ? 4 : 5)));   // chunks of the lane's first group
+    uint32_t xr[NL][20];
+    float s_lo[NL], s_hi[NL];
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+        float lo = 0.f, all = 0.f;
+#pragma unroll
+        for (int ch = 0; ch < 5; ++ch) {
+            const u4 v = *reinterpret_cast<const u4*>(lds + 5120 * i + 1024 * ch + 16 * lane);
+            xr[i][4 * ch + 0] = v.x;
+            xr[i][4 * ch + 1] = v.y;
+            xr[i][4 * ch + 2] = v.z;
+            xr[i][4 * ch + 3] = v.w;
+            const float sc = csum[(5 * i + ch) * 64 + lane];
+            all += sc;
+            if (ch < bc) lo += sc;
+        }
+        s_lo[i] = lo;
+        s_hi[i] = all - lo;
+    }
+    uint32_t xw[NKW];
+#pragma unroll
+    for (int t = 0; t < NKW; ++t) {
+        const int dw = lane + 64 * t;
+        xw[t] = (2 * dw < k) ? *reinterpret_cast<const uint32_t*>(xweak + 4 * dw) : 0u;
+    }
+    uint32_t cmask = 0x00070007u, cmagic = 0x64006400u;
+    asm volatile("" : "+v"(cmask), "+v"(cmagic));   // in registers: (v & m) | g is then one v_and_or_b32
+
+    float res = 0.f;   // lane j: the wave's result for its row j
+    auto compute = [&](int d, int j) {
+        float y = 0.f;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+            float c[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int P = 0; P < 20; ++P) {   // pair P: codes 2 P, 2 P + 1 of the lane's 40 = pair P % 5 of word P / 5
+                const uint32_t six = __builtin_amdgcn_ubfe(wq[d][i][P / 5], 6 * (P % 5), 6);
+                const uint32_t cp = ((six * 0x2001u) & cmask) | cmagic;
+                c[P / 4] = dot2(cp, xr[i][P], c[P / 4]);
+            }
+            const float p1 = c[0], p2 = p1 + c[1], p3 = p2 + c[2], p4 = p3 + c[3], all = p4 + c[4];
+            const float a_lo = bc == 1 ? p1 : (bc == 2 ? p2 : (bc == 3 ? p3 : (bc == 4 ? p4 : all)));
+            const float a_hi = all - a_lo;
+            const h2 sp = __builtin_bit_cast(h2, __builtin_amdgcn_perm(sq[d][i].y, sq[d][i].x, selb[i]));
+            const h2 zp = __builtin_bit_cast(h2, __builtin_amdgcn_perm(zq[d][i].y, zq[d][i].x, selb[i]));
+            y = fmaf((float)sp.x, fmaf(-(1024.f + (float)zp.x), s_lo[i], a_lo), y);
+            y = fmaf((float)sp.y, fmaf(-(1024.f + (float)zp.y), s_hi[i], a_hi), y);
+        }
+#pragma unroll
+        for (int t = 0; t < NKW; ++t) y = dot2(wk[d][t], xw[t], y);
+        const float tot = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(y)), 63));
+        res = (lane == j) ? tot : res;
+    };
+
+    for (int b = 0; b + 1 < B; ++b) {
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            compute(d, b * DEPTH + d);
+            issue(d, row_first + (b + 1) * DEPTH + d);
+            __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its row
+        }
+    }
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) compute(d, (B - 1) * DEPTH + d);
+
+    if (live && lane < rpw && row_first + lane < n_rows) yout[row_first + lane] = __float2half_rn(res);
+}
+
 struct DotPlan {
     int nscw, depth, nkw, ks_log2, B;
     size_t lds;
@@ -347,6 +518,28 @@ DotPlan dot_plan(const Layer& L, int n_rows) {
     return p;
 }
 
+// The 3-bit kernel: nscw holds NL, the 1 KB ranges of a row (at most 6: 15360 columns); no K split, no gather.
+DotPlan dot_plan_w3(const Layer& L, int n_rows, bool perm) {
+    DotPlan p = {};
+    p.ok = false;
+    if (perm || L.bits != 3 || L.dense || L.g != 128 || L.kq < 8 || (L.kq % 8) != 0 || L.k < 8 || (L.k % 8) != 0 || L.gs < 8) return p;
+    const int nl = ceil_div(L.stride, 256);
+    if (nl > 6) return p;
+    const int nkw = ceil_div(L.k, 128);
+    if (nkw > 2) return p;
+    p.nscw = nl;
+    p.nkw = nkw;
+    p.ks_log2 = 0;
+    p.depth = nl <= 2 ? 2 : 1;
+    const int occ_wg = nl <= 2 ? 2 : 1;
+    const int slots = 256 * occ_wg * DOT_WAVES;
+    p.B = ceil_div(n_rows, p.depth * slots);
+    if (p.depth * p.B > 64) return p;
+    p.lds = (size_t)5120 * nl + 1280 * nl + 256 * nkw;
+    p.ok = p.lds <= 64 * 1024;
+    return p;
+}
+
 using DotKern = void (*)(DotLayers, int, int, int, int, const __half*, const int*, int, int, int);
 
 template <bool PERM>
@@ -370,7 +563,8 @@ hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X
     int rows = 0;
     for (int i = 0; i < n; ++i) rows += Ls[i].oc;
     const Layer& L = Ls[0];
-    DotPlan p = dot_plan(L, rows);
+    const bool w3 = L.bits == 3 && !L.dense;
+    DotPlan p = w3 ? dot_plan_w3(L, rows, perm != nullptr) : dot_plan(L, rows);
     if (!p.ok) return hipSuccess;
     const int rpw = p.depth * p.B;
     int sets = 0;
@@ -386,6 +580,15 @@ hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X
         if (i < n) sets += ceil_div(Li.oc, rpw);
     }
     R.n_sets = sets;
+    if (w3) {
+        using W3Kern = void (*)(DotLayers, int, int, int, int, const __half*, int);
+#define QEFT_W3(N, D) (p.nkw == 1 ? (W3Kern)gemv_w3_dot_kernel<N, D, 1> : (W3Kern)gemv_w3_dot_kernel<N, D, 2>)
+        const W3Kern k3 = p.nscw == 1 ? QEFT_W3(1, 2) : (p.nscw == 2 ? QEFT_W3(2, 2) : (p.nscw == 3 ? QEFT_W3(3, 1) : (p.nscw == 4 ? QEFT_W3(4, 1) : (p.nscw == 5 ? QEFT_W3(5, 1) : QEFT_W3(6, 1)))));
+#undef QEFT_W3
+        k3<<<ceil_div(sets, DOT_WAVES), DOT_THREADS, p.lds, s>>>(R, L.kq, L.k, 4 * L.stride, L.gs, X, p.B);
+        *handled = true;
+        return hipGetLastError();
+    }
     const int blocks = ceil_div(sets, DOT_WAVES >> p.ks_log2);
     const DotKern kern = perm ? dot_kernel<true>(p.nscw, p.depth, p.nkw) : dot_kernel<false>(p.nscw, p.depth, p.nkw);
     kern<<<blocks, DOT_THREADS, p.lds, s>>>(R, L.kq, L.k, 4 * L.stride, L.gs, X, perm, L.ic, p.B, p.ks_log2);
