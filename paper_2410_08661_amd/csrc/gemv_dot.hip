@@ -67,24 +67,30 @@ __device__ __forceinline__ float wave_sum_to_lane63(float t) {
     return t;
 }
 
-// NSCW: column ranges of 4096 per wave (two 1 KB loads each); DEPTH: rows in flight; NKW: weak dwords per lane.
+// NL: 1 KB ranges of a row per wave (2048 columns each); DEPTH: rows in flight; NKW: weak columns per lane, in units of
+// two (DEPTH 1) or four (DEPTH 2); PERM: gather the activations through the table while staging.
+// With two rows in flight the rows go in pairs that share their small requests: the weak block of a pair comes
+// with one load (lanes 0 .. 31 hold row 0's columns, lanes 32 .. 63 row 1's), and when a pair has at most four
+// (row, range) slots, lane 4 g + m takes the parameters of slot m, so one 2-byte load per array serves both rows.
 // LDS: pair-ordered activations [KS * NL][4 pieces][64 lanes] 16 B | (sum base x, sum x) float2 [KS * NL][64] |
-//      weak activations fp16 [KS * NKW * 128] | K-split exchange float [8 waves][64]
-template <int NSCW, int DEPTH, int NKW, bool PERM>
+//      weak activations fp16 | K-split exchange float [8 waves][64]
+template <int NL, int DEPTH, int NKW, bool PERM>
 __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, int kq, int k, int row_bytes, int gs,
                                                                    const __half* __restrict__ X, const int* __restrict__ perm, int ic,
                                                                    int B, int ks_log2) {
-    constexpr int NL = 2 * NSCW;
+    static_assert(DEPTH == 1 || DEPTH == 2, "one row or a pair of rows in flight");
+    constexpr bool PAIR = DEPTH == 2;          // one weak load per pair of rows (no K split in these variants)
+    constexpr bool PAIRP = PAIR && NL <= 2;    // one parameter load per array and pair
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KS = 1 << ks_log2;
-    const int kpart = wave & (KS - 1), wset = wave >> ks_log2;
+    const int KS = PAIR ? 1 : (1 << ks_log2);
+    const int kpart = PAIR ? 0 : (wave & (KS - 1)), wset = PAIR ? wave : (wave >> ks_log2);
     const int nl_all = NL * KS;                       // 1 KB ranges of a row, all waves of a K split together
     const int rpw = DEPTH * B;
     const int li0 = kpart * NL;
     // the wave's row set lies in ONE layer (each layer's rows are cut into sets of rpw on their own), looked up once
-    const int sidx_raw = blockIdx.x * (DOT_WAVES >> ks_log2) + wset;
+    const int sidx_raw = blockIdx.x * (PAIR ? DOT_WAVES : (DOT_WAVES >> ks_log2)) + wset;
     const bool live = sidx_raw < R.n_sets;
     const int sidx = min(sidx_raw, R.n_sets - 1);
     const int li = (sidx >= R.set_begin[1]) + (sidx >= R.set_begin[2]) + (sidx >= R.set_begin[3]);
@@ -97,35 +103,68 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
 
     // ---- per-lane offsets of the wave's loads within a row (clamped: lanes past the row read its last bytes, their x is 0)
     // Group parameters: the four lanes of a quad share a group, so after a quad sum only one of them needs (s, z).
-    // Lane 4 g + m takes range 4 j + m of parameter set j: one 2-byte load per array and set fetches the parameters
-    // of up to four ranges (64 groups) of a row.
-    constexpr int NP = (NL + 3) / 4;
+    // Per row: lane 4 g + m takes range 4 j + m of parameter set j.  Per pair (PAIRP): lane 4 g + m takes slot m =
+    // (row m / NL of the pair, range m % NL).
+    constexpr int NP = PAIRP ? 1 : (NL + 3) / 4;
     const int qm = lane & 3;
-    int woff[NL], goff[NP], koff[NKW];
+    const int p_row = PAIRP ? (qm >= NL ? 1 : 0) : 0, p_rng = PAIRP ? (qm >= NL ? qm - NL : qm) : 0;   // this lane's slot of a pair
+    int woff[NL], goff[NP];
 #pragma unroll
     for (int i = 0; i < NL; ++i) woff[i] = min(1024 * (li0 + i) + 16 * lane, row_bytes - 16);
 #pragma unroll
-    for (int j = 0; j < NP; ++j) goff[j] = 2 * min(16 * (li0 + 4 * j + qm) + (lane >> 2), gs - 1);
+    for (int j = 0; j < NP; ++j) goff[j] = 2 * min(16 * (li0 + (PAIRP ? min(p_rng, NL - 1) : 4 * j + qm)) + (lane >> 2), gs - 1);
+    // weak columns: DEPTH 1: dword t of the lane = columns 2 (lane + 64 (t KS + kpart)), + 1; pairs: the 4 NKW columns from
+    // 4 NKW (lane % 32) on, of row lane / 32 of the pair
+    constexpr int WKN = PAIR ? 2 * NKW : NKW;   // dwords of weak block per lane and load
+    int koff[PAIR ? 1 : NKW];
+    if (PAIR) {
+        koff[0] = min(8 * NKW * (lane & 31), 2 * k - 8 * NKW);
+    } else {
 #pragma unroll
-    for (int t = 0; t < NKW; ++t) koff[t] = 4 * min(lane + 64 * (t * KS + kpart), (k >> 1) - 1);
+        for (int t = 0; t < NKW; ++t) koff[t] = 4 * min(lane + 64 * (t * KS + kpart), (k >> 1) - 1);
+    }
 
     u4 wq[DEPTH][NL];
-    uint32_t sq[DEPTH][NP], zq[DEPTH][NP], wk[DEPTH][NKW];
-    auto issue = [&](int d, int row_in) {
-        const size_t lr = (size_t)min(row_in, n_rows - 1);
-        const unsigned char* wrow = wbase + lr * (size_t)row_bytes;
-        const unsigned char* srow = sbase + lr * (size_t)(2 * gs);
-        const unsigned char* zrow = zbase + lr * (size_t)(2 * gs);
-        const unsigned char* krow = kbase_p + lr * (size_t)(2 * k);
+    uint32_t sq[PAIRP ? 1 : DEPTH][NP], zq[PAIRP ? 1 : DEPTH][NP], wk[PAIR ? 1 : DEPTH][WKN];
+    auto issue_w = [&](int d, int row_in) {   // the codes of one row
+        const unsigned char* wrow = wbase + (size_t)min(row_in, n_rows - 1) * (size_t)row_bytes;
 #pragma unroll
         for (int i = 0; i < NL; ++i) wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
+    };
+    auto issue_small = [&](int d, int row_in) {   // group parameters and weak block: of row d (DEPTH 1, or the per-row parameters of a pair) ...
+        const size_t lr = (size_t)min(row_in, n_rows - 1);
+        if (!PAIRP) {
 #pragma unroll
-        for (int j = 0; j < NP; ++j) {
-            sq[d][j] = *reinterpret_cast<const unsigned short*>(srow + goff[j]);
-            zq[d][j] = *reinterpret_cast<const unsigned short*>(zrow + goff[j]);
+            for (int j = 0; j < NP; ++j) {
+                sq[d][j] = *reinterpret_cast<const unsigned short*>(sbase + lr * (size_t)(2 * gs) + goff[j]);
+                zq[d][j] = *reinterpret_cast<const unsigned short*>(zbase + lr * (size_t)(2 * gs) + goff[j]);
+            }
         }
+        if (!PAIR) {
 #pragma unroll
-        for (int t = 0; t < NKW; ++t) wk[d][t] = *reinterpret_cast<const uint32_t*>(krow + koff[t]);
+            for (int t = 0; t < NKW; ++t) wk[d][t] = *reinterpret_cast<const uint32_t*>(kbase_p + lr * (size_t)(2 * k) + koff[t]);
+        }
+    };
+    auto issue_pair = [&](int row_in) {   // ... or of the pair that starts at row_in
+        if (PAIRP) {
+            const size_t lr = (size_t)min(row_in + p_row, n_rows - 1);
+            sq[0][0] = *reinterpret_cast<const unsigned short*>(sbase + lr * (size_t)(2 * gs) + goff[0]);
+            zq[0][0] = *reinterpret_cast<const unsigned short*>(zbase + lr * (size_t)(2 * gs) + goff[0]);
+        }
+        if (PAIR) {
+            const unsigned char* kp = kbase_p + (size_t)min(row_in + (lane >> 5), n_rows - 1) * (size_t)(2 * k) + koff[0];
+            if (NKW == 1) {
+                const uint2 v = *reinterpret_cast<const uint2*>(kp);
+                wk[0][0] = v.x;
+                wk[0][1] = v.y;
+            } else {
+                const u4 v = *reinterpret_cast<const u4*>(kp);
+                wk[0][0] = v.x;
+                wk[0][1] = v.y;
+                wk[0][WKN > 2 ? 2 : 0] = v.z;
+                wk[0][WKN > 2 ? 3 : 1] = v.w;
+            }
+        }
     };
 
     // ---- requests: the activations this thread stages, then the first DEPTH rows ----------------------------
@@ -133,21 +172,19 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
     constexpr int XU = 4;
     const int n_units = 256 * nl_all;
     u4 xv[XU];
+    auto gather8 = [&](int c0) {   // 8 activations at stored columns c0 .. c0 + 7 through the table
+        const u4 lo = *reinterpret_cast<const u4*>(perm + c0), hi = *reinterpret_cast<const u4*>(perm + c0 + 4);
+        const unsigned short* xs = reinterpret_cast<const unsigned short*>(X);
+        uint32_t h[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) h[e] = xs[min(max((int)(e < 4 ? lo[e] : hi[e - 4]), 0), ic - 1)];
+        return u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
+    };
     auto load_units = [&](int base) {
 #pragma unroll
         for (int t = 0; t < XU; ++t) {
-            const int u = base + t * DOT_THREADS + tid;
-            const int c0 = min(8 * u, kq - 8);
-            if (PERM) {
-                const u4 lo = *reinterpret_cast<const u4*>(perm + c0), hi = *reinterpret_cast<const u4*>(perm + c0 + 4);
-                const unsigned short* xr = reinterpret_cast<const unsigned short*>(X);
-                uint32_t h[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) h[e] = xr[min(max((int)(e < 4 ? lo[e] : hi[e - 4]), 0), ic - 1)];
-                xv[t] = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-            } else {
-                xv[t] = *reinterpret_cast<const u4*>(X + c0);
-            }
+            const int c0 = min(8 * (base + t * DOT_THREADS + tid), kq - 8);
+            xv[t] = PERM ? gather8(c0) : *reinterpret_cast<const u4*>(X + c0);
         }
     };
     // pair order of a word's conversion: (x0, x4) (x1, x5) (x2, x6) (x3, x7); with it the unit's sums
@@ -155,6 +192,11 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
     // units of a lane's 32 columns (threads 4 j .. 4 j + 3 of the staging pass hold them)
     float2* ksum = reinterpret_cast<float2*>(lds + 4096 * nl_all);
     unsigned char* xweak = lds + 4096 * nl_all + 512 * nl_all;
+    auto quad_sum = [](float f) {
+        f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0xB1, 0xf, 0xf, false));
+        f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0x4E, 0xf, 0xf, false));
+        return f;
+    };
     auto store_units = [&](int base) {
 #pragma unroll
         for (int t = 0; t < XU; ++t) {
@@ -170,15 +212,8 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
             const uint32_t px = p.x, py = p.y, pz = p.z, pw = p.w;
             const h2 a = __builtin_bit_cast(h2, px), b = __builtin_bit_cast(h2, py), c = __builtin_bit_cast(h2, pz),
                      d = __builtin_bit_cast(h2, pw);
-            float se = ((float)a.x + (float)a.y) + ((float)c.x + (float)c.y);
-            float so = ((float)b.x + (float)b.y) + ((float)d.x + (float)d.y);
-            auto quad = [](float f) {
-                f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0xB1, 0xf, 0xf, false));
-                f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0x4E, 0xf, 0xf, false));
-                return f;
-            };
-            se = quad(se);
-            so = quad(so);
+            const float se = quad_sum(((float)a.x + (float)a.y) + ((float)c.x + (float)c.y));
+            const float so = quad_sum(((float)b.x + (float)b.y) + ((float)d.x + (float)d.y));
             if (u < n_units) {
                 // range i = u / 256, lane l = (u % 256) / 4, piece q = u % 4  ->  [i][q][l]
                 const int i = u >> 8, l = (u & 255) >> 2, q = u & 3;
@@ -189,22 +224,12 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
     };
     load_units(0);
     // the weak activations: one 16-byte unit per thread (k <= 8 * DOT_THREADS)
-    u4 xwv;
-    {
-        const int c0 = min(8 * tid, k - 8);
-        if (PERM) {
-            const u4 lo = *reinterpret_cast<const u4*>(perm + kq + c0), hi = *reinterpret_cast<const u4*>(perm + kq + c0 + 4);
-            const unsigned short* xr = reinterpret_cast<const unsigned short*>(X);
-            uint32_t h[8];
+    const u4 xwv = PERM ? gather8(kq + min(8 * tid, k - 8)) : *reinterpret_cast<const u4*>(X + kq + min(8 * tid, k - 8));
+    issue_pair(row_first);   // the small requests first: they return first and nothing waits behind a kilobyte for them
 #pragma unroll
-            for (int e = 0; e < 8; ++e) h[e] = xr[min(max((int)(e < 4 ? lo[e] : hi[e - 4]), 0), ic - 1)];
-            xwv = u4{h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)};
-        } else {
-            xwv = *reinterpret_cast<const u4*>(X + kq + c0);
-        }
-    }
+    for (int d = 0; d < DEPTH; ++d) issue_small(d, row_first + d);
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) issue(d, row_first + d);
+    for (int d = 0; d < DEPTH; ++d) issue_w(d, row_first + d);
     __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
 
     // ---- stage the activations --------------------------------------------------------------------------------
@@ -233,35 +258,37 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
         kbase[i] = ks2.x;
         ssum[i] = ks2.y;
     }
-    auto quad_sum = [](float f) {
-        f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0xB1, 0xf, 0xf, false));
-        f += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, f), 0x4E, 0xf, 0xf, false));
-        return f;
-    };
     float ssel[NP];   // sum x of the group this lane applies the parameters of set j to (0: none)
 #pragma unroll
     for (int j = 0; j < NP; ++j) ssel[j] = 0.f;
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
         const float sg = quad_sum(ssum[i]);
-        if (qm == (i & 3)) ssel[i >> 2] = sg;
+        if (PAIRP) {
+            if (p_rng == i && qm < 2 * NL) ssel[0] = sg;
+        } else {
+            if (qm == (i & 3)) ssel[i >> 2] = sg;
+        }
     }
-    uint32_t xw[NKW];
+    uint32_t xw[WKN];
+    if (PAIR) {
+        const int c0 = 4 * NKW * (lane & 31);   // columns c0 .. c0 + 4 NKW - 1 (k is a multiple of 8: whole or nothing)
 #pragma unroll
-    for (int t = 0; t < NKW; ++t) {
-        const int dw = lane + 64 * (t * KS + kpart);
-        xw[t] = (2 * dw < k) ? *reinterpret_cast<const uint32_t*>(xweak + 4 * dw) : 0u;
+        for (int t = 0; t < WKN; ++t) xw[t] = (c0 + 2 * t < k) ? *reinterpret_cast<const uint32_t*>(xweak + 2 * c0 + 4 * t) : 0u;
+    } else {
+#pragma unroll
+        for (int t = 0; t < NKW; ++t) {
+            const int dw = lane + 64 * (t * KS + kpart);
+            xw[t] = (2 * dw < k) ? *reinterpret_cast<const uint32_t*>(xweak + 4 * dw) : 0u;
+        }
     }
 
     uint32_t m_lo = 0x000f000fu, m_hi = 0x00f000f0u, g_lo = 0x64006400u, g_hi = 0x54005400u;
     asm volatile("" : "+v"(m_lo), "+v"(m_hi), "+v"(g_lo), "+v"(g_hi));   // in registers: (w & m) | g is then one v_and_or_b32
 
     float res = 0.f;   // lane j: the wave's result for its row j
-    auto compute = [&](int d, int j) {
-        float y = 0.f;
-        float tsel[NP];
-#pragma unroll
-        for (int jj = 0; jj < NP; ++jj) tsel[jj] = 0.f;
+    // sum x q of every group of one row's ranges, each in the four lanes of its quad
+    auto row_sums = [&](int d, float (&tg)[NL]) {
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             float a0 = 0.f, a1 = 0.f;
@@ -274,32 +301,94 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
                 a0 = dot2(p2, xr[i][4 * q + 2], a0);
                 a1 = dot2(p3, xr[i][4 * q + 3], a1);
             }
-            const float tg = quad_sum((a0 + a1) - kbase[i]);   // sum x q of the group, in its four lanes
-            if (qm == (i & 3)) tsel[i >> 2] = tg;
+            tg[i] = quad_sum((a0 + a1) - kbase[i]);
         }
+    };
+    // the parameters of one row applied to its group sums (the per-row sets)
+    auto row_scaled = [&](int d, const float (&tg)[NL]) {
+        float tsel[NP], y = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < NP; ++jj) tsel[jj] = 0.f;
+#pragma unroll
+        for (int i = 0; i < NL; ++i)
+            if (qm == (i & 3)) tsel[i >> 2] = tg[i];
 #pragma unroll
         for (int jj = 0; jj < NP; ++jj) {
             const float sc = (float)__builtin_bit_cast(_Float16, (unsigned short)sq[d][jj]);
             const float z = (float)__builtin_bit_cast(_Float16, (unsigned short)zq[d][jj]);
             y = fmaf(sc, fmaf(-z, ssel[jj], tsel[jj]), y);
         }
-#pragma unroll
-        for (int t = 0; t < NKW; ++t)
-            y = dot2(wk[d][t], xw[t], y);
+        return y;
+    };
+    auto finish = [&](float y, int j) {
         const float tot = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, wave_sum_to_lane63(y)), 63));
         res = (lane == j) ? tot : res;
     };
 
-    for (int b = 0; b + 1 < B; ++b) {
+    // One pair / one row; REFILL: request the next one behind it.  The last one is peeled off so that no request
+    // stands under a condition (the compiler would wait for every outstanding load at the join).
+    auto pair_step = [&](int b, auto refill) {
+        constexpr bool REFILL = decltype(refill)::value;
+        const int next = row_first + (b + 1) * 2;
+        float t0[NL], t1[NL];
+        row_sums(0, t0);
+        if (REFILL) issue_w(0, next);
+        __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its row
+        row_sums(1, t1);
+        if (REFILL) issue_w(1, next + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        float y0, y1;
+        if (PAIRP) {
+            float tsel = 0.f;
 #pragma unroll
-        for (int d = 0; d < DEPTH; ++d) {
-            compute(d, b * DEPTH + d);
-            issue(d, row_first + (b + 1) * DEPTH + d);
-            __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its row
+            for (int i = 0; i < NL; ++i) {
+                if (qm == i) tsel = t0[i];
+                if (qm == NL + i) tsel = t1[i];
+            }
+            const float sc = (float)__builtin_bit_cast(_Float16, (unsigned short)sq[0][0]);
+            const float z = (float)__builtin_bit_cast(_Float16, (unsigned short)zq[0][0]);
+            const float c = sc * fmaf(-z, ssel[0], tsel);
+            y0 = p_row == 0 ? c : 0.f;
+            y1 = p_row == 1 ? c : 0.f;
+        } else {
+            y0 = row_scaled(0, t0);
+            y1 = row_scaled(1, t1);
         }
-    }
+        float yw = 0.f;
 #pragma unroll
-    for (int d = 0; d < DEPTH; ++d) compute(d, (B - 1) * DEPTH + d);
+        for (int t = 0; t < WKN; ++t) yw = dot2(wk[0][t], xw[t], yw);
+        y0 += lane < 32 ? yw : 0.f;
+        y1 += lane < 32 ? 0.f : yw;
+        if (REFILL) {
+            issue_small(0, next);
+            issue_small(1, next + 1);
+            issue_pair(next);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        finish(y0, 2 * b);
+        finish(y1, 2 * b + 1);
+    };
+    auto row_step = [&](int b, auto refill) {
+        constexpr bool REFILL = decltype(refill)::value;
+        float t0[NL];
+        row_sums(0, t0);
+        float y = row_scaled(0, t0);
+#pragma unroll
+        for (int t = 0; t < NKW; ++t) y = dot2(wk[0][t], xw[t], y);
+        if (REFILL) {
+            issue_small(0, row_first + b + 1);
+            issue_w(0, row_first + b + 1);
+        }
+        __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its row
+        finish(y, b);
+    };
+    if constexpr (PAIR) {
+        for (int b = 0; b + 1 < B; ++b) pair_step(b, std::true_type{});
+        pair_step(B - 1, std::false_type{});
+    } else {
+        for (int b = 0; b + 1 < B; ++b) row_step(b, std::true_type{});
+        row_step(B - 1, std::false_type{});
+    }
 
     // ---- K split: partial results meet in LDS; then one store per row ----------------------------------------------
     if (KS > 1) {
@@ -370,14 +459,16 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w3_dot_kernel(DotLayers R, i
         const unsigned char* srow = sbase + lr * (size_t)(2 * gs);
         const unsigned char* zrow = zbase + lr * (size_t)(2 * gs);
         const unsigned char* krow = kbase_p + lr * (size_t)(2 * k);
+        // the small requests first: they return first and nothing waits behind a kilobyte for them
+#pragma unroll
+        for (int t = 0; t < NKW; ++t) wk[d][t] = *reinterpret_cast<const uint32_t*>(krow + koff[t]);
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
-            wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
             sq[d][i] = *reinterpret_cast<const u2*>(srow + goff[i]);
             zq[d][i] = *reinterpret_cast<const u2*>(zrow + goff[i]);
         }
 #pragma unroll
-        for (int t = 0; t < NKW; ++t) wk[d][t] = *reinterpret_cast<const uint32_t*>(krow + koff[t]);
+        for (int i = 0; i < NL; ++i) wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
     };
 
     // ---- requests: the activations this thread stages, then the first DEPTH rows ----------------------------
@@ -484,35 +575,36 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w3_dot_kernel(DotLayers R, i
 }
 
 struct DotPlan {
-    int nscw, depth, nkw, ks_log2, B;
+    int nscw, depth, nkw, ks_log2, B;   // nscw: 1 KB ranges of a row per wave
     size_t lds;
     bool ok;
 };
 
-// Shapes the kernel takes, and how a launch is cut: column ranges per wave from the row length (a wave keeps at
-// most 4 x 4096 columns of activations in registers, longer rows are split over 2 or 4 waves), rows in flight so
-// that a wave has 4 - 8 KB of requests outstanding, batches so that the row sets fill the resident waves once.
+// Shapes the kernel takes, and how a launch is cut: ranges per wave from the row length (a wave keeps at most 8 x 2048
+// columns of activations in registers, longer rows are split over 2 or 4 waves), two rows in flight for rows of up
+// to three ranges, batches so that the row sets fill the resident waves once.
 DotPlan dot_plan(const Layer& L, int n_rows) {
     DotPlan p = {};
     p.ok = false;
     if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || (L.kq % 8) != 0 || L.k < 8 || (L.k % 8) != 0) return p;
     const int nl_all = ceil_div(L.kq, 2048);
     int ks_log2 = 0;
-    while (ks_log2 < 2 && ceil_div(nl_all, 2 << ks_log2) > 4) ++ks_log2;
+    while (ks_log2 < 2 && ceil_div(nl_all, 1 << ks_log2) > 8) ++ks_log2;
     const int KS = 1 << ks_log2;
-    const int nscw = ceil_div(nl_all, 2 * KS);
-    if (nscw > 4) return p;
+    int nl = ceil_div(nl_all, KS);
+    if (nl > 8) return p;
+    nl = nl < 2 ? 2 : (nl == 7 ? 8 : nl);   // (seven ranges spill registers; the eighth is clamped and multiplies zeros)
     const int nkw = ceil_div(L.k, 128 * KS);
     if (nkw > 2 || L.k > 8 * DOT_THREADS) return p;
-    p.nscw = nscw;
+    p.nscw = nl;
     p.nkw = nkw;
     p.ks_log2 = ks_log2;
-    p.depth = nscw == 1 ? 2 : 1;
-    const int occ_wg = nscw == 1 ? 2 : 1;                       // resident workgroups per CU the register budget allows
+    p.depth = (nl <= 3 && KS == 1) ? 2 : 1;
+    const int occ_wg = nl <= 3 ? 2 : 1;                         // resident workgroups per CU the register budget allows
     const int slots = 256 * occ_wg * (DOT_WAVES / KS);          // row sets resident at once
     p.B = ceil_div(n_rows, p.depth * slots);
     if (p.depth * p.B > 64) return p;                           // a wave keeps its rows' results one per lane
-    const int nl_pad = 2 * nscw * KS;
+    const int nl_pad = nl * KS;
     p.lds = (size_t)4096 * nl_pad + 512 * nl_pad + 256 * KS * nkw + (KS > 1 ? DOT_WAVES * 64 * sizeof(float) : 0);
     p.ok = p.lds <= 64 * 1024;
     return p;
@@ -543,12 +635,16 @@ DotPlan dot_plan_w3(const Layer& L, int n_rows, bool perm) {
 using DotKern = void (*)(DotLayers, int, int, int, int, const __half*, const int*, int, int, int);
 
 template <bool PERM>
-DotKern dot_kernel(int nscw, int depth, int nkw) {
+DotKern dot_kernel(int nl, int nkw) {
 #define QEFT_DOT(N, D) (nkw == 1 ? (DotKern)gemv_w4_dot_kernel<N, D, 1, PERM> : (DotKern)gemv_w4_dot_kernel<N, D, 2, PERM>)
-    if (nscw == 1) return depth == 2 ? QEFT_DOT(1, 2) : QEFT_DOT(1, 4);
-    if (nscw == 2) return depth == 2 ? QEFT_DOT(2, 2) : QEFT_DOT(2, 1);
-    if (nscw == 3) return QEFT_DOT(3, 1);
-    return QEFT_DOT(4, 1);
+    switch (nl) {
+        case 2: return QEFT_DOT(2, 2);
+        case 3: return QEFT_DOT(3, 2);
+        case 4: return QEFT_DOT(4, 1);
+        case 5: return QEFT_DOT(5, 1);
+        case 6: return QEFT_DOT(6, 1);
+        default: return QEFT_DOT(8, 1);
+    }
 #undef QEFT_DOT
 }
 
@@ -590,7 +686,7 @@ hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X
         return hipGetLastError();
     }
     const int blocks = ceil_div(sets, DOT_WAVES >> p.ks_log2);
-    const DotKern kern = perm ? dot_kernel<true>(p.nscw, p.depth, p.nkw) : dot_kernel<false>(p.nscw, p.depth, p.nkw);
+    const DotKern kern = perm ? dot_kernel<true>(p.nscw, p.nkw) : dot_kernel<false>(p.nscw, p.nkw);
     kern<<<blocks, DOT_THREADS, p.lds, s>>>(R, L.kq, L.k, 4 * L.stride, L.gs, X, perm, L.ic, p.B, p.ks_log2);
     *handled = true;
     return hipGetLastError();
