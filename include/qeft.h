@@ -101,7 +101,8 @@ typedef struct {
     void* weak;
 } qeft_weight_t;
 
-enum { QEFT_OP_FWD = 0, QEFT_OP_BWD_DX = 1, QEFT_OP_WEAK_GRAD = 2, QEFT_OP_FWD_IRREGULAR = 3, QEFT_OP_BWD_DX_IRREGULAR = 4 };
+enum { QEFT_OP_FWD = 0, QEFT_OP_BWD_DX = 1, QEFT_OP_WEAK_GRAD = 2, QEFT_OP_FWD_IRREGULAR = 3, QEFT_OP_BWD_DX_IRREGULAR = 4,
+       QEFT_OP_BWD = 5 };
 enum { QEFT_DTYPE_F16 = 0, QEFT_DTYPE_F32 = 1 };
 
 /* Component sizes of the stored form (Sec. 3.1).  Host only, pure. */
@@ -253,6 +254,26 @@ int qeft_merge_weak(const void* tuned, const void* base, int64_t out_features, i
 int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t lddy,
                    const void* Xw, int64_t ldxw, void* dW, int out_dtype, int accumulate,
                    void* ws, size_t ws_bytes, void* stream);
+
+/* The backward pass of one layer in one call (Sec. 3.3, Eq. 5): dX = dY . W through the full mixed weight and
+ * dW (+)= dY^T . Xw for the weak block, arguments as in qeft_linear_bwd_dx and qeft_weak_grad.  The same kernels
+ * run as in those two calls, and the results equal theirs bit for bit; what the call chooses is how they go out:
+ *   - with room in ws for the partial tiles of a row split of dX (qeft_workspace_bytes(desc, QEFT_OP_BWD, M), the
+ *     larger of the two steps' amounts; 4-bit layers only) and a layer whose dX that split applies to: dX with the
+ *     split, then the weak gradient, as qeft_linear_bwd_dx with its workspace followed by qeft_weak_grad (the
+ *     workspace serves one after the other);
+ *   - else, where both steps take the tensor-core path, the weak block is at most 128 wide and the dX tiles do not
+ *     fill their last round of 256 compute units: ONE launch - the weak gradient's workgroups follow the tiles in
+ *     the grid and are dispatched as compute units fall free, so they run in what the last round leaves idle (dX of
+ *     11008 x 4096 at M = 4096: 688 tiles on 256 units; 368 us against 343 + 46 us for the two calls); results as
+ *     qeft_linear_bwd_dx without workspace followed by qeft_weak_grad;
+ *   - else the two calls one after the other, dX without workspace.
+ * ws / ws_bytes: at least qeft_workspace_bytes(desc, QEFT_OP_WEAK_GRAD, M) bytes, 16-byte aligned, required as for
+ * qeft_weak_grad (QEFT_ERR_WORKSPACE before anything is launched); more than that is optional.
+ * n_weak == 0: only dX is computed, without workspace (Xw, dW, ws may be NULL). */
+int qeft_linear_bwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M, int64_t lddy,
+                    void* dX, int64_t lddx, const void* Xw, int64_t ldxw, void* dW, int out_dtype, int accumulate,
+                    void* ws, size_t ws_bytes, void* stream);
 
 /* qeft_weak_grad for callers that cannot allocate and cannot hand over a workspace: code under HIP graph
  * capture, tight training or serving loops, harnesses that forbid hipMalloc.  Same arguments without ws, same

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libqeft.so")
 QEFT_OK = 0
 QEFT_ERR_NULL, QEFT_ERR_SHAPE, QEFT_ERR_BITS, QEFT_ERR_ALIGN = -1, -2, -3, -4
 QEFT_ERR_WORKSPACE, QEFT_ERR_UNSUPPORTED, QEFT_ERR_HIP = -5, -6, -7
-QEFT_OP_FWD, QEFT_OP_BWD_DX, QEFT_OP_WEAK_GRAD, QEFT_OP_FWD_IRREGULAR, QEFT_OP_BWD_DX_IRREGULAR = 0, 1, 2, 3, 4
+QEFT_OP_FWD, QEFT_OP_BWD_DX, QEFT_OP_WEAK_GRAD, QEFT_OP_FWD_IRREGULAR, QEFT_OP_BWD_DX_IRREGULAR, QEFT_OP_BWD = 0, 1, 2, 3, 4, 5
 QEFT_DTYPE_F16, QEFT_DTYPE_F32 = 0, 1
 QEFT_LAYOUT_CANONICAL, QEFT_LAYOUT_DENSE3 = 0, 1
 
@@ -70,6 +70,8 @@ EXPORTS = {
                                   C.c_void_p]),
     "qeft_weak_grad": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                  C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "qeft_linear_bwd": (C.c_int, [C.POINTER(qeft_desc_t), C.POINTER(qeft_weight_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
+                                  C.c_int64, C.c_void_p, C.c_int64, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p]),
     "qeft_weak_grad_noalloc": (C.c_int, [C.POINTER(qeft_desc_t), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64,
                                          C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "qeft_status_string": (C.c_char_p, [C.c_int]),
@@ -349,4 +351,24 @@ def qeft_weak_grad_noalloc(desc, dY: torch.Tensor, Xw: torch.Tensor, dW: torch.T
                                       Xw.stride(0) if M else max(desc.n_weak, 8), _ptr(dW), code, int(bool(accumulate)),
                                       _stream()), "qeft_weak_grad_noalloc")
     return dW
+
+
+def qeft_linear_bwd(desc, w: Weight, dY: torch.Tensor, Xw: torch.Tensor, dX: torch.Tensor | None = None,
+                    dW: torch.Tensor | None = None, accumulate=False, out_dtype=torch.float32, ws=None):
+    """dX and dW_weak of one layer in one call; returns (dX, dW).  ws: None allocates the weak gradient's workspace;
+    a tensor of qeft_workspace_bytes(desc, QEFT_OP_BWD, M) bytes also lets dX split its rows where that pays."""
+    M = dY.shape[0]
+    if dX is None:
+        dX = _empty_rows(M, desc.in_features, torch.float16, dY.device)
+    if dW is None:
+        dW = torch.zeros((desc.out_features, desc.n_weak), dtype=out_dtype, device=dY.device)
+    code = {torch.float16: QEFT_DTYPE_F16, torch.float32: QEFT_DTYPE_F32}[dW.dtype]
+    if ws is None:
+        ws, _ = _workspace(desc, QEFT_OP_WEAK_GRAD, M, dY.device)
+    wst = w.c_struct()
+    _check(raw.qeft_linear_bwd(C.byref(desc), C.byref(wst), _ptr(dY), M, dY.stride(0) if M else desc.out_features, _ptr(dX),
+                               dX.stride(0) if M else desc.in_features, _ptr(Xw), Xw.stride(0) if M else max(desc.n_weak, 8),
+                               _ptr(dW), code, int(bool(accumulate)), _ptr(ws), ws.numel() if ws is not None else 0, _stream()),
+           "qeft_linear_bwd")
+    return dX, dW
 

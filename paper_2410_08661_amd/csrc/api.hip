@@ -168,6 +168,12 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
     if (check_desc(desc) != QEFT_OK || M <= 0) return 0;
     if (op == QEFT_OP_WEAK_GRAD && weak_grad_mfma_supported(desc->out_features, desc->n_weak, M))
         return weak_grad_mfma_workspace(desc->out_features, desc->n_weak, M);
+    if (op == QEFT_OP_BWD) {
+        const size_t a = qeft_workspace_bytes(desc, QEFT_OP_WEAK_GRAD, M);
+        size_t b = 0;
+        if (desc->bits == 4) b = qeft_workspace_bytes(desc, QEFT_OP_BWD_DX, M);   // the row split; never the 3-bit fp16 copy
+        return a > b ? a : b;
+    }
     if (op == QEFT_OP_FWD_IRREGULAR || op == QEFT_OP_BWD_DX_IRREGULAR) return irregular_workspace(desc->in_features, M);
     if (op == QEFT_OP_FWD || op == QEFT_OP_BWD_DX) {
         Layer L = {};
@@ -429,6 +435,38 @@ int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t l
     }
     return hip_status(weak_grad_generic(oc, k, (const __half*)dY, M, lddy, (const __half*)Xw, ldxw, dW,
                                         out_dtype == QEFT_DTYPE_F32, accumulate != 0, s));
+}
+
+int qeft_linear_bwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void* dY, int64_t M, int64_t lddy, void* dX,
+                    int64_t lddx, const void* Xw, int64_t ldxw, void* dW, int out_dtype, int accumulate, void* ws,
+                    size_t ws_bytes, void* stream) {
+    Layer L;
+    int st = make_layer(desc, w, &L);
+    if (st != QEFT_OK) return st;
+    if (out_dtype != QEFT_DTYPE_F16 && out_dtype != QEFT_DTYPE_F32) return QEFT_ERR_UNSUPPORTED;
+    st = check_matrix(dY, M, lddy, L.oc);
+    if (st != QEFT_OK) return st;
+    st = check_matrix(dX, M, lddx, L.ic);
+    if (st != QEFT_OK) return st;
+    if (M == 0) return QEFT_OK;
+    if (L.k == 0) return qeft_linear_bwd_dx(desc, w, dY, M, lddy, dX, lddx, nullptr, 0, stream);
+    st = check_matrix(Xw, M, ldxw, L.k);
+    if (st != QEFT_OK) return st;
+    if (!dW) return QEFT_ERR_NULL;
+    if (!aligned16(dW)) return QEFT_ERR_ALIGN;
+    // the weak gradient's workspace is required whichever way the two steps run; checked before any launch
+    const size_t need_dw = weak_grad_mfma_supported(L.oc, L.k, M) ? weak_grad_mfma_workspace(L.oc, L.k, M) : 0;
+    if (need_dw > 0 && (!ws || ws_bytes < need_dw || !aligned16(ws))) return QEFT_ERR_WORKSPACE;
+    // room for the partial tiles of a row split of dX: that split fills a sparse last round of tiles better than the
+    // weak gradient's strips do, so it goes first (the strips' partial sums reuse the same bytes afterwards)
+    const size_t need_dx = gemm_dx_supported(L, M) ? gemm_dx_split_workspace(L, M) : 0;
+    const bool split = need_dx > 0 && ws && aligned16(ws) && ws_bytes >= need_dx;
+    if (!split && gemm_dx_dw_supported(L, M))
+        return hip_status(gemm_dx_dw(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, (const __half*)Xw, ldxw, dW,
+                                     out_dtype == QEFT_DTYPE_F32, accumulate != 0, ws, (hipStream_t)stream));
+    st = qeft_linear_bwd_dx(desc, w, dY, M, lddy, dX, lddx, split ? ws : nullptr, split ? ws_bytes : 0, stream);
+    if (st != QEFT_OK) return st;
+    return qeft_weak_grad(desc, dY, M, lddy, Xw, ldxw, dW, out_dtype, accumulate, ws, ws_bytes, stream);
 }
 
 const char* qeft_status_string(int status) {

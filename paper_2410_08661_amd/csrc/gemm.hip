@@ -1096,10 +1096,9 @@ __device__ __forceinline__ void dx_tile(const Layer& L, const __half* __restrict
 // a multiple of 64: whole stages) and stores its partial tile as fp16 into its slot of `part`; splitk_reduce_kernel
 // adds them.  Which tiles are split: split_tile.  The rows of a stored layer are independent, so a split is simply the
 // layer made of those rows.
-__global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
-                                                           __half* __restrict__ dX, int64_t lddx, int tiles_ic, int splits,
-                                                           int rps, int tail_first, __half* __restrict__ part) {
-    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+__device__ __forceinline__ void dx_rega_body(unsigned char* lds, Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
+                                             __half* __restrict__ dX, int64_t lddx, int tiles_ic, int splits,
+                                             int rps, int tail_first, __half* __restrict__ part) {
     const int tiles_all = tiles_ic * ((M + BT - 1) / BT);
     int tile, sp, slot;
     if (!split_tile(tiles_all, tail_first, splits, tile, sp, slot)) return;
@@ -1123,6 +1122,12 @@ __global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half
     if (w0) dx_tile<1, 1>(L, dY, M, lddy, dX, lddx, ic0, m0, lds);
     else if (w1) dx_tile<0, 1>(L, dY, M, lddy, dX, lddx, ic0, m0, lds);
     else dx_tile<0, 0>(L, dY, M, lddy, dX, lddx, ic0, m0, lds);
+}
+__global__ __launch_bounds__(256) void gemm_dx_rega_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
+                                                           __half* __restrict__ dX, int64_t lddx, int tiles_ic, int splits,
+                                                           int rps, int tail_first, __half* __restrict__ part) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    dx_rega_body(lds, L, dY, M, lddy, dX, lddx, tiles_ic, splits, rps, tail_first, part);
 }
 
 // ======================================================================================= weak gradient
@@ -1152,18 +1157,18 @@ constexpr int WG_LDS = 2 * (WG_A_BYTES + WG_B_BYTES); // A0 A1 B0 B1
 
 // A weak block wider than 128 columns is taken in halves of 128 (workgroup index = ((strip, half), split)): the two halves
 // of a strip read the same dY rows and sit next to each other in the grid.
-__global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int k_total, const __half* __restrict__ dY, int M,
-                                                              int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
-                                                              float* __restrict__ part, int splits, int chunk, void* dW,
-                                                              int out_f32, int accumulate) {
-    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+// (bid: the workgroup's index among the strip workgroups; lds: its dynamic shared memory, WG_LDS bytes)
+__device__ __forceinline__ void weak_grad_strip_body(unsigned char* lds, int bid, int oc_total, int k_total, const __half* __restrict__ dY, int M,
+                                                     int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
+                                                     float* __restrict__ part, int splits, int chunk, void* dW,
+                                                     int out_f32, int accumulate) {
     typedef short s4 __attribute__((ext_vector_type(4)));
     typedef short s8 __attribute__((ext_vector_type(8)));
     using lds_s4 = __attribute__((address_space(3))) s4;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int halves = (k_total + 127) >> 7;
-    const int split = blockIdx.x % splits, rest = blockIdx.x / splits;
+    const int split = bid % splits, rest = bid / splits;
     const int kh = rest % halves, t_oc = rest / halves;
     const int k = min(128, k_total - 128 * kh);   // this workgroup's weak columns: 128 kh .. 128 kh + k - 1
     Xw += 128 * kh;
@@ -1320,6 +1325,30 @@ __global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int 
             }
         }
     }
+}
+
+__global__ __launch_bounds__(256) void weak_grad_strip_kernel(int oc_total, int k_total, const __half* __restrict__ dY, int M,
+                                                              int64_t lddy, const __half* __restrict__ Xw, int64_t ldxw,
+                                                              float* __restrict__ part, int splits, int chunk, void* dW,
+                                                              int out_f32, int accumulate) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    weak_grad_strip_body(lds, (int)blockIdx.x, oc_total, k_total, dY, M, lddy, Xw, ldxw, part, splits, chunk, dW, out_f32, accumulate);
+}
+
+// The input gradient and the weak block's gradient of one layer in ONE launch: the first n_dx workgroups are the
+// tiles of gemm_dx_rega_kernel (no split), the rest the strips of weak_grad_strip_kernel.  Both read dY; the
+// strips are dispatched as compute units fall free, i.e. into the partly empty last round of tiles (688 tiles on
+// 256 units leave 80 of them idle for a third of the launch), where they cost nothing.
+__global__ __launch_bounds__(256) void gemm_dx_dw_kernel(Layer L, const __half* __restrict__ dY, int M, int64_t lddy,
+                                                         __half* __restrict__ dX, int64_t lddx, int tiles_ic, int n_dx,
+                                                         const __half* __restrict__ Xw, int64_t ldxw, float* __restrict__ part,
+                                                         int splits, int chunk, void* dW, int out_f32, int accumulate) {
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    if ((int)blockIdx.x >= n_dx) {
+        weak_grad_strip_body(lds, (int)blockIdx.x - n_dx, L.oc, L.k, dY, M, lddy, Xw, ldxw, part, splits, chunk, dW, out_f32, accumulate);
+        return;
+    }
+    dx_rega_body(lds, L, dY, M, lddy, dX, lddx, tiles_ic, 1, 0, 0, nullptr);
 }
 
 __global__ __launch_bounds__(256) void weak_grad_reduce_kernel(const float* __restrict__ part, int splits, int64_t n,
@@ -1562,6 +1591,42 @@ hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t ld
     }
     weak_grad_strip_kernel<<<ceil_div(oc, WG_OC) * ceil_div(k, 128) * splits, 256, WG_LDS, s>>>(oc, k, dY, (int)M, lddy, Xw, ldxw, (float*)ws, splits,
                                                                                           chunk, dW, out_f32, accumulate);
+    if (splits > 1) weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
+    return hipGetLastError();
+}
+
+// dX and dW_weak of one layer in one launch (see gemm_dx_dw_kernel); false when the shapes do not fit both
+// register kernels (the caller then makes the two calls one after the other).
+// Taken when the last round of dX tiles leaves compute units idle (the tile count is no multiple of 256) and the weak
+// block is one strip wide (k <= 128).  Inside the combined launch a strip workgroup has a compute unit to itself (the
+// launch reserves the tile kernel's LDS and registers for every workgroup; on its own the strip kernel runs two per
+// unit), so a weak gradient that is heavy next to the idle capacity loses more than it gains: measured at M = 4096,
+// both calls against one: 11008 x 4096 376 -> 359 us, 4096 x 11008 363 -> 350, 5120 x 5120 281 -> 262, 13824 x 5120
+// 699 -> 670; with a 256-wide weak block (two half strips per strip of channels) 8192 x 8192 at M = 2048 257 -> 252
+// but 28672 x 8192 862 -> 877.
+bool gemm_dx_dw_supported(const Layer& L, int64_t M) {
+    if (!(gemm_dx_supported(L, M) && L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0 && L.k > 0 && weak_grad_mfma_supported(L.oc, L.k, M)))
+        return false;
+    const int tiles = ceil_div(L.ic, BT) * ceil_div(M, BT);
+    return L.k <= 128 && tiles % 256 != 0;
+}
+
+hipError_t gemm_dx_dw(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, const __half* Xw,
+                      int64_t ldxw, void* dW, int out_f32, int accumulate, void* ws, hipStream_t s) {
+    const int tiles = ceil_div(L.ic, BT) * ceil_div(M, BT), n_dx = xcd_grid(tiles);
+    int splits, chunk;
+    const int64_t n = (int64_t)L.oc * L.k;
+    weak_grad_strip_split(L.oc, L.k, M, splits, chunk);
+    static bool attr = false;
+    constexpr int LDS_BYTES = DX_LDS > WG_LDS ? DX_LDS : WG_LDS;
+    if (!attr) {
+        hipError_t e = hipFuncSetAttribute((const void*)gemm_dx_dw_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
+        if (e != hipSuccess) return e;
+        attr = true;
+    }
+    const int n_dw = ceil_div(L.oc, WG_OC) * ceil_div(L.k, 128) * splits;
+    gemm_dx_dw_kernel<<<n_dx + n_dw, 256, LDS_BYTES, s>>>(L, dY, (int)M, lddy, dX, lddx, ceil_div(L.ic, BT), n_dx, Xw, ldxw, (float*)ws, splits,
+                                                         chunk, dW, out_f32, accumulate);
     if (splits > 1) weak_grad_reduce_kernel<<<ceil_div(n, 256), 256, 0, s>>>((const float*)ws, splits, n, dW, out_f32, accumulate);
     return hipGetLastError();
 }

@@ -114,4 +114,9 @@ size_t weak_grad_mfma_workspace(int oc, int k, int64_t M);
 hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t lddy, const __half* Xw, int64_t ldxw,
                           void* dW, int out_f32, int accumulate, void* ws, hipStream_t s);
 
+// input gradient and weak-block gradient of one layer in one launch (ws: the weak gradient's workspace)
+bool gemm_dx_dw_supported(const Layer& L, int64_t M);
+hipError_t gemm_dx_dw(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, const __half* Xw,
+                      int64_t ldxw, void* dW, int out_f32, int accumulate, void* ws, hipStream_t s);
+
 }  // namespace qeft

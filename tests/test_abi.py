@@ -279,3 +279,39 @@ def test_pack_and_weak_grad_validation():
         assert wg(C.byref(d4), dY, 4096, 4096, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_WORKSPACE
         assert wg(C.byref(d4), dY, 4096, 4096, Xw, 128, dW, 1, 0, 0x40000, need - 1, None) == B.QEFT_ERR_WORKSPACE
     assert B.qeft_workspace_bytes(d, B.QEFT_OP_FWD, 0) == 0
+
+
+def test_backward_in_one_call_validation():
+    """qeft_linear_bwd: every error comes before a launch, also the weak gradient's when the two steps
+    would run one after the other."""
+    bw = B.raw.qeft_linear_bwd
+    d = B.make_desc(64, 256, 128, 4)
+    w = _w()
+    dY, dX, Xw, dW, WS = 0x10000, 0x20000, 0x30000, 0x40000, 0x4000000
+    assert bw(C.byref(d), None, dY, 4, 64, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 256, Xw, 128, dW, 2, 0, None, 0, None) == B.QEFT_ERR_UNSUPPORTED  # dtype
+    assert bw(C.byref(d), C.byref(w), None, 4, 64, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert bw(C.byref(d), C.byref(w), dY, 4, 56, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE       # lddy < OC
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, None, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 248, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE       # lddx < IC
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 256, None, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 256, Xw, 120, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE       # ldxw < k
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 256, Xw, 128, None, 1, 0, None, 0, None) == B.QEFT_ERR_NULL
+    assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 256, Xw, 128, dW + 4, 1, 0, None, 0, None) == B.QEFT_ERR_ALIGN
+    assert bw(C.byref(d), C.byref(w), dY, -1, 64, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE
+    assert bw(C.byref(d), C.byref(w), dY, 0, 64, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_OK              # M = 0: no-op
+    # the weak gradient's workspace is asked for whichever way the two steps run: 11008 x 4096 goes out as one
+    # launch, 4096 x 4096 as two
+    for oc, ic in ((11008, 4096), (4096, 4096)):
+        d4 = B.make_desc(oc, ic, 128, 4)
+        need = B.qeft_workspace_bytes(d4, B.QEFT_OP_WEAK_GRAD, 4096)
+        if need:
+            assert bw(C.byref(d4), C.byref(w), dY, 4096, oc, dX, ic, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_WORKSPACE
+            assert bw(C.byref(d4), C.byref(w), dY, 4096, oc, dX, ic, Xw, 128, dW, 1, 0, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
+            assert bw(C.byref(d4), C.byref(w), dY, 4096, oc, dX, ic, Xw, 128, dW, 1, 0, WS + 8, need, None) == B.QEFT_ERR_WORKSPACE
+    # QEFT_OP_BWD: the larger of the two steps' amounts (13824 x 5120: the last round's 96 tiles split two ways)
+    d5 = B.make_desc(13824, 5120, 128, 4)
+    a, b = B.qeft_workspace_bytes(d5, B.QEFT_OP_BWD_DX, 4096), B.qeft_workspace_bytes(d5, B.QEFT_OP_WEAK_GRAD, 4096)
+    assert a > 0 and b > 0 and B.qeft_workspace_bytes(d5, B.QEFT_OP_BWD, 4096) == max(a, b)
+    d6 = B.make_desc(13824, 5120, 128, 3)      # 3-bit: never the fp16 copy, the weak gradient's amount only
+    assert B.qeft_workspace_bytes(d6, B.QEFT_OP_BWD, 4096) == B.qeft_workspace_bytes(d6, B.QEFT_OP_WEAK_GRAD, 4096)

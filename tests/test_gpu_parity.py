@@ -497,6 +497,74 @@ def test_weak_grad_parity(oc, ic, k, bits, g, m, compact):
     assert_close(dw16.cpu().numpy(), ref, f"dW overwrite {oc}x{k}")
 
 
+@pytest.mark.parametrize("oc,ic,k,bits,g,m", BWD_CASES + [
+    (704, 1024 + 128, 128, 4, 128, 600),      # 5 x 3 tiles and 11 strips x 8 token splits in one launch
+    (2816, 512 + 256, 256, 4, 128, 1024),     # a weak block of two halves; more strips than tiles
+    (1088, 8320 + 128, 128, 4, 128, 300),     # 33 x 2 tiles: the strips fill the second round
+])
+def test_backward_in_one_call_equals_the_two_calls(oc, ic, k, bits, g, m):
+    """qeft_linear_bwd: dX and dW_weak of a layer in one call (one launch where both take the tensor-core path): bit for
+    bit what qeft_linear_bwd_dx (no workspace) and qeft_weak_grad give, and the oracle's values to the bar."""
+    h = HostLayer(oc, ic, k, bits, g, seed=oc + 7 * ic)
+    w = h.to_device()
+    x = synth.make_activations(m, ic, k, seed=m + 3)
+    dy = synth.make_grad_output(m, oc, seed=m + 4)
+    dyv, _ = pad_cols(dy)
+    kq = ic - k
+    xw = pad_cols(x[:, kq:])[0] if k else None
+    for dtype, acc in ((torch.float32, False), (torch.float16, True)):
+        base = (np.random.default_rng(2).standard_normal((oc, k)) * 0.05).astype(np.float16)
+        dw_a = torch.from_numpy(base).cuda().to(dtype) if k else None
+        dw_b = dw_a.clone() if k else None
+        dx_a = B.qeft_linear_bwd_dx(h.desc, w, dyv, ws=False)
+        if k:
+            B.qeft_weak_grad(h.desc, dyv, xw, dW=dw_a, accumulate=acc)
+        if k:
+            dx_b, _ = B.qeft_linear_bwd(h.desc, w, dyv, xw, dW=dw_b, accumulate=acc)
+        else:
+            dx_b = torch.empty_like(dx_a)
+            B._check(B.raw.qeft_linear_bwd(B.C.byref(h.desc), B.C.byref(w.c_struct()), dyv.data_ptr(), m, dyv.stride(0), dx_b.data_ptr(),
+                                           dx_b.stride(0), None, 0, None, 1, 0, None, 0, None), "qeft_linear_bwd")
+        torch.cuda.synchronize()
+        assert torch.equal(dx_a, dx_b)
+        if k:
+            assert torch.equal(dw_a, dw_b)
+    assert_close(dx_b.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), f"dX {oc}x{ic} (one call)")
+    if k:
+        assert_close(dw_b.float().cpu().numpy(), base.astype(np.float64) + qo.weak_grad(dy, x[:, kq:]), f"dW {oc}x{k} (one call)")
+
+
+@pytest.mark.parametrize("oc,ic,k,m", [
+    (2048, 1024 + 128, 128, 512),    # 5 x 2 tiles: every tile's rows split
+    (4096, 5120, 128, 4096),         # 20 x 16 tiles: the 64 of the last round split four ways
+])
+def test_backward_in_one_call_with_room_for_a_row_split(oc, ic, k, m):
+    """qeft_linear_bwd with a workspace of QEFT_OP_BWD's size: dX takes the row split, the weak gradient follows in the
+    same bytes: bit for bit qeft_linear_bwd_dx with its workspace, then qeft_weak_grad."""
+    h = HostLayer(oc, ic, k, 4, 128, seed=oc + ic)
+    w = h.to_device()
+    gen = torch.Generator(device="cuda").manual_seed(m)
+    x = torch.randn((m, ic), generator=gen, device="cuda").half()
+    dy = (torch.randn((m, oc), generator=gen, device="cuda") * 0.01).half()
+    n_dx = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD_DX, m)
+    n_dw = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_WEAK_GRAD, m)
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD, m)
+    assert n_dx > 0 and n == max(n_dx, n_dw)
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dx_a = B.qeft_linear_bwd_dx(h.desc, w, dy, ws=ws)
+    dw_a = B.qeft_weak_grad(h.desc, dy, x[:, ic - k:], ws=ws)
+    ws.fill_(0xFF)
+    dx_b, dw_b = B.qeft_linear_bwd(h.desc, w, dy, x[:, ic - k:], ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dx_a, dx_b) and torch.equal(dw_a, dw_b)
+    # the split really ran (the unsplit kernel rounds once less), and it is the room that decides: with the weak
+    # gradient's amount alone the call splits only where that amount happens to be enough
+    dx_u = B.qeft_linear_bwd_dx(h.desc, w, dy, ws=False)
+    assert not torch.equal(dx_u, dx_b)
+    dx_c, _ = B.qeft_linear_bwd(h.desc, w, dy, x[:, ic - k:], ws=torch.empty(max(n_dw, 16), dtype=torch.uint8, device="cuda"))
+    assert torch.equal(dx_c, dx_b if n_dw >= n_dx else dx_u)
+
+
 @pytest.mark.parametrize("oc,ic,k,m", [
     (256, 4096 + 128, 128, 300),     # 2 tiles, 64 quantized stages: 8 splits of 8 stages, the weak block in the last
     (528, 2560 + 64, 64, 64),        # 3 tiles (one ragged), 40 stages: 5 splits
