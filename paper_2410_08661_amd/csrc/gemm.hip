@@ -48,7 +48,8 @@ __global__ __launch_bounds__(256) void gemm_fwd_kernel(Layer L, const __half* __
     const int wm = wave >> 1, wn = wave & 1;
     const int tile = xcd_tile(tiles_oc * ((M + BT - 1) / BT));
     if (tile < 0) return;
-    const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
+    int t_oc, t_m;
+    tile_coords(tile, tiles_oc, (M + BT - 1) / BT, t_oc, t_m);
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const int nq_st = (L.kq + BK - 1) / BK, nw_st = (L.k + BK - 1) / BK, nst = nq_st + nw_st;
     const Consts cst = make_consts();
@@ -215,7 +216,8 @@ __global__ __launch_bounds__(256) void gemm_fwd_rega_kernel(Layer L, const __hal
     const int tiles_all = tiles_oc * ((M + BT - 1) / BT);
     int tile, sp, slot;
     if (!split_tile(tiles_all, tail_first, splits, tile, sp, slot)) return;
-    const int t_oc = tile % tiles_oc, t_m = tile / tiles_oc;
+    int t_oc, t_m;
+    tile_coords(tile, tiles_oc, (M + BT - 1) / BT, t_oc, t_m);
     const int oc0 = t_oc * BT, m0 = t_m * BT;
     const bool is_split = slot >= 0;
     const bool last_split = !is_split || sp == splits - 1;
@@ -634,7 +636,8 @@ __global__ __launch_bounds__(256) void gemm_dx_kernel(Layer L, const __half* __r
     const int wm = wave >> 1, wn = wave & 1;
     const int tile = xcd_tile(tiles_ic * ((M + BT - 1) / BT));
     if (tile < 0) return;
-    const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
+    int t_ic, t_m;
+    tile_coords(tile, tiles_ic, (M + BT - 1) / BT, t_ic, t_m);
     const int ic0 = ic_start + t_ic * BT, m0 = t_m * BT;
     const int nst = (L.oc + BK - 1) / BK;
     const Consts cst = make_consts();
@@ -1102,7 +1105,8 @@ __device__ __forceinline__ void dx_rega_body(unsigned char* lds, Layer L, const 
     const int tiles_all = tiles_ic * ((M + BT - 1) / BT);
     int tile, sp, slot;
     if (!split_tile(tiles_all, tail_first, splits, tile, sp, slot)) return;
-    const int t_ic = tile % tiles_ic, t_m = tile / tiles_ic;
+    int t_ic, t_m;
+    tile_coords(tile, tiles_ic, (M + BT - 1) / BT, t_ic, t_m);
     const int ic0 = t_ic * BT, m0 = t_m * BT;
     if (slot >= 0) {
         const int r0 = sp * rps;
@@ -1394,7 +1398,9 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const __half* __rest
     const int tt = blockIdx.x >> 5, part32 = blockIdx.x & 31;
     const int tile = split_tail_tile(tiles_all, tail_first, tt);
     if (tile < 0) return;
-    const int n0 = (tile % tiles_n) * BT, m0 = (tile / tiles_n) * BT;
+    int t_n, t_m;
+    tile_coords(tile, tiles_n, (M + BT - 1) / BT, t_n, t_m);
+    const int n0 = t_n * BT, m0 = t_m * BT;
     const bool wide = (ldy & 7) == 0 && (reinterpret_cast<uintptr_t>(Y) & 15) == 0;
     const __half* p0 = part + (size_t)tt * splits * (BT * BT);
     {

@@ -91,6 +91,21 @@ __device__ __forceinline__ int xcd_tile(int n_tiles) {
 }
 inline int xcd_grid(int n_tiles) { return N_XCD * ((n_tiles + N_XCD - 1) / N_XCD); }
 
+// Tile index -> (weight tile t_n, activation panel t_m).  Panels are taken in bands of TILE_BAND: inside a band the
+// panel index runs fastest, so the 32 consecutive tiles that are resident on an XCD at a time cover TILE_BAND panels x
+// 32 / TILE_BAND weight tiles instead of one panel x 32 weight tiles.  With 4-bit weights a weight tile holds a quarter
+// of a panel's bytes, and two panels x 16 weight tiles is what an XCD's L2 has to fetch least for per round of tiles.
+#ifndef QEFT_TILE_BAND
+#define QEFT_TILE_BAND 4
+#endif
+__device__ __forceinline__ void tile_coords(int tile, int tiles_n, int tiles_m, int& t_n, int& t_m) {
+    constexpr int P = QEFT_TILE_BAND;
+    const int band = tile / (P * tiles_n), r = tile - band * (P * tiles_n);
+    const int pb = min(P, tiles_m - band * P);
+    t_n = r / pb;
+    t_m = band * P + (r - t_n * pb);
+}
+
 // Tile order of a launch in which some tiles are split `splits` ways along the contraction (a workgroup per split, each
 // storing a partial tile of BT x BT halves into slot `slot` of a workspace; a second kernel adds them).
 //   tail_first <= 0: every tile is split (launches of few tiles); order as xcd_tile over tiles * splits.
