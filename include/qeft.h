@@ -262,11 +262,11 @@ int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t l
  *     larger of the two steps' amounts; 4-bit layers only) and a layer whose dX that split applies to: dX with the
  *     split, then the weak gradient, as qeft_linear_bwd_dx with its workspace followed by qeft_weak_grad (the
  *     workspace serves one after the other);
- *   - else, where both steps take the tensor-core path, the weak block is at most 128 wide and the dX tiles do not
- *     fill their last round of 256 compute units: ONE launch - the weak gradient's workgroups follow the tiles in
- *     the grid and are dispatched as compute units fall free, so they run in what the last round leaves idle (dX of
- *     11008 x 4096 at M = 4096: 688 tiles on 256 units; 368 us against 343 + 46 us for the two calls); results as
- *     qeft_linear_bwd_dx without workspace followed by qeft_weak_grad;
+ *   - else, where both steps take the tensor-core path and the weak block is at most 128 wide: ONE launch - the
+ *     weak gradient's workgroups follow the dX tiles in the grid and are dispatched as compute units fall free, so
+ *     they run in what the last round of tiles leaves idle (dX of 4096 x 11008 at M = 4096: 688 tiles on 256 units;
+ *     350 us against 363 us for the two calls); results as qeft_linear_bwd_dx without workspace followed by
+ *     qeft_weak_grad;
  *   - else the two calls one after the other, dX without workspace.
  * ws / ws_bytes: at least qeft_workspace_bytes(desc, QEFT_OP_WEAK_GRAD, M) bytes, 16-byte aligned, required as for
  * qeft_weak_grad (QEFT_ERR_WORKSPACE before anything is launched); more than that is optional.

@@ -1603,18 +1603,18 @@ hipError_t weak_grad_mfma(int oc, int k, const __half* dY, int64_t M, int64_t ld
 
 // dX and dW_weak of one layer in one launch (see gemm_dx_dw_kernel); false when the shapes do not fit both
 // register kernels (the caller then makes the two calls one after the other).
-// Taken when the last round of dX tiles leaves compute units idle (the tile count is no multiple of 256) and the weak
-// block is one strip wide (k <= 128).  Inside the combined launch a strip workgroup has a compute unit to itself (the
-// launch reserves the tile kernel's LDS and registers for every workgroup; on its own the strip kernel runs two per
-// unit), so a weak gradient that is heavy next to the idle capacity loses more than it gains: measured at M = 4096,
-// both calls against one: 11008 x 4096 376 -> 359 us, 4096 x 11008 363 -> 350, 5120 x 5120 281 -> 262, 13824 x 5120
+// Taken when the weak block is one strip wide (k <= 128).  The strips follow the tiles in the grid, so they start on
+// whichever compute units finish their last tile first: in the idle part of a partly empty last round, or, when the
+// tiles fill their rounds, in the few microseconds by which the tiles' ends differ.  Inside the combined launch a strip
+// workgroup has a compute unit to itself (the launch reserves the tile kernel's LDS and registers for every workgroup;
+// on its own the strip kernel runs two per unit), so a weak gradient that is heavy next to that idle time loses more
+// than it gains.  Measured at M = 4096, the two calls against the one: 11008 x 4096 (256 tiles) 388 -> 382 us,
+// 4096 x 4096 (256 tiles) 165 -> 163, 4096 x 11008 (688 tiles) 363 -> 350, 5120 x 5120 281 -> 262, 13824 x 5120
 // 699 -> 670; with a 256-wide weak block (two half strips per strip of channels) 8192 x 8192 at M = 2048 257 -> 252
 // but 28672 x 8192 862 -> 877.
 bool gemm_dx_dw_supported(const Layer& L, int64_t M) {
-    if (!(gemm_dx_supported(L, M) && L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0 && L.k > 0 && weak_grad_mfma_supported(L.oc, L.k, M)))
-        return false;
-    const int tiles = ceil_div(L.ic, BT) * ceil_div(M, BT);
-    return L.k <= 128 && tiles % 256 != 0;
+    return gemm_dx_supported(L, M) && L.oc % BK == 0 && L.kq % 128 == 0 && L.k % 8 == 0 && L.k > 0 && L.k <= 128 &&
+           weak_grad_mfma_supported(L.oc, L.k, M);
 }
 
 hipError_t gemm_dx_dw(const Layer& L, const __half* dY, int64_t M, int64_t lddy, __half* dX, int64_t lddx, const __half* Xw,

@@ -300,15 +300,15 @@ def test_backward_in_one_call_validation():
     assert bw(C.byref(d), C.byref(w), dY, 4, 64, dX, 256, Xw, 128, dW + 4, 1, 0, None, 0, None) == B.QEFT_ERR_ALIGN
     assert bw(C.byref(d), C.byref(w), dY, -1, 64, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_SHAPE
     assert bw(C.byref(d), C.byref(w), dY, 0, 64, dX, 256, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_OK              # M = 0: no-op
-    # the weak gradient's workspace is asked for whichever way the two steps run: 11008 x 4096 goes out as one
-    # launch, 4096 x 4096 as two
-    for oc, ic in ((11008, 4096), (4096, 4096)):
-        d4 = B.make_desc(oc, ic, 128, 4)
-        need = B.qeft_workspace_bytes(d4, B.QEFT_OP_WEAK_GRAD, 4096)
-        if need:
-            assert bw(C.byref(d4), C.byref(w), dY, 4096, oc, dX, ic, Xw, 128, dW, 1, 0, None, 0, None) == B.QEFT_ERR_WORKSPACE
-            assert bw(C.byref(d4), C.byref(w), dY, 4096, oc, dX, ic, Xw, 128, dW, 1, 0, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
-            assert bw(C.byref(d4), C.byref(w), dY, 4096, oc, dX, ic, Xw, 128, dW, 1, 0, WS + 8, need, None) == B.QEFT_ERR_WORKSPACE
+    # the weak gradient's workspace is asked for whichever way the two steps run: 11008 x 4096 with 128 weak columns
+    # goes out as one launch, 4096 x 8192 with 256 as two
+    for oc, ic, k, m in ((11008, 4096, 128, 4096), (4096, 8192, 256, 2048)):
+        d4 = B.make_desc(oc, ic, k, 4)
+        need = B.qeft_workspace_bytes(d4, B.QEFT_OP_WEAK_GRAD, m)
+        assert need > 0
+        assert bw(C.byref(d4), C.byref(w), dY, m, oc, dX, ic, Xw, k, dW, 1, 0, None, 0, None) == B.QEFT_ERR_WORKSPACE
+        assert bw(C.byref(d4), C.byref(w), dY, m, oc, dX, ic, Xw, k, dW, 1, 0, WS, need - 1, None) == B.QEFT_ERR_WORKSPACE
+        assert bw(C.byref(d4), C.byref(w), dY, m, oc, dX, ic, Xw, k, dW, 1, 0, WS + 8, need, None) == B.QEFT_ERR_WORKSPACE
     # QEFT_OP_BWD: the larger of the two steps' amounts (13824 x 5120: the last round's 96 tiles split two ways)
     d5 = B.make_desc(13824, 5120, 128, 4)
     a, b = B.qeft_workspace_bytes(d5, B.QEFT_OP_BWD_DX, 4096), B.qeft_workspace_bytes(d5, B.QEFT_OP_WEAK_GRAD, 4096)
