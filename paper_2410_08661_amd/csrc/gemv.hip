@@ -976,17 +976,21 @@ struct RegsArgs {
     int M, kq, k, nq, stride, gs;
 };
 
-// S: steps per wave and pass; D: tiles in flight; T: tiles per workgroup; XM: activation rows fetched (1, 4: one
-// 128-bit load per row covers the wave's whole range and the fragments are dealt out through a wave-private piece
-// of LDS; 16: every lane fetches the fragments of its own row); MAXW: waves per workgroup at most (register
-// budget); MULTI: rows longer than one pass of the workgroup (KS * S steps) take `passes` passes - the
-// accumulators stay, the activation registers are refilled at each pass boundary and the weight requests run on
-// across it.  LDS: per wave max(XM, T) KB - first the activation bounce, at the end this wave's partial tiles.
+// S: steps per wave and pass; D: tiles in flight; T: tiles per workgroup; XM: activation rows fetched (8 or 16: one
+// 128-bit load per row covers the wave's whole range - a contiguous kilobyte per request - and the fragments are
+// dealt out through a wave-private piece of LDS; fetching every lane's fragments of its own row directly took 16
+// requests of sixteen 64-byte pieces each and was 10 - 25 % slower on rows of more than one pass); MAXW: waves per
+// workgroup at most (register budget); MULTI: rows longer than one pass of the workgroup (KS * S steps) take
+// `passes` passes - the accumulators stay, the next pass's activation rows are requested as soon as this pass's
+// sit in LDS, and the weight requests run on across the pass boundary (with several passes the tiles in flight
+// must divide the tiles of a workgroup, because the slots are reused pass after pass: three tiles keep one in
+// flight).  LDS: per wave max(XM, T) KB - first the activation bounce, at the end this wave's partial tiles.
 template <int S, int D, int T, int XM, int MAXW, bool MULTI>
 __global__ __launch_bounds__(64 * MAXW) void gemv_w4_regs_kernel(RegsArgs A, int passes) {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     static_assert(S == 4, "a wave's range is 4 steps = 512 columns = 64 pieces of 16 bytes");
-    constexpr int WKB = XM == 16 ? T : (XM > T ? XM : T);   // KB of LDS per wave
+    static_assert(D == 1 || T % D == 0 || !MULTI, "with several passes the slots are reused pass after pass");
+    constexpr int WKB = XM > T ? XM : T;   // KB of LDS per wave
     const int lane = threadIdx.x & 63;
     const int KS = blockDim.x >> 6;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -1001,7 +1005,10 @@ __global__ __launch_bounds__(64 * MAXW) void gemv_w4_regs_kernel(RegsArgs A, int
     u4 wq[D][S], wk[D];
     u2 sb[D], zb[D];
     auto issue = [&](int d, int t, int c) {   // t: tile of this workgroup (compile-time), clamped to the launch's last tile; c: pass
-        const int tile_g = min((int)blockIdx.x * T + t, A.n_tiles - 1);
+        int tile_g = min((int)blockIdx.x * T + t, A.n_tiles - 1);
+        // (opaque: with several passes the compiler would otherwise keep every tile's row addresses in registers
+        // across the pass loop - 8 registers per tile - and spill the accumulators instead)
+        if (MULTI) asm volatile("" : "+s"(tile_g));
         const int li = (tile_g >= A.tile_begin[1]) + (tile_g >= A.tile_begin[2]) + (tile_g >= A.tile_begin[3]);
         const int row0 = (tile_g - A.tile_begin[li]) * 16;
         const size_t orow = (size_t)min(row0 + n, A.oc[li] - 1);
@@ -1024,40 +1031,45 @@ __global__ __launch_bounds__(64 * MAXW) void gemv_w4_regs_kernel(RegsArgs A, int
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
 
-    for (int c = 0; c < C; ++c) {
-        const int js0 = (c * KS + wave) * S;   // first step of this wave in this pass
-        // ---- requests: the activations of this wave's range first (L2 hits), then (first pass) the first D tiles -----
-        u4 xa[S][4];
-        u4 xrows[XM == 16 ? 1 : XM];
-        if (XM == 16) {
+    // The activation rows of a pass: lane l fetches piece l (8 columns) of the wave's 512 columns, for each of the XM rows.
+    // The registers are free again once the pieces sit in LDS, so with up to 8 rows the next pass's rows are requested
+    // right there, ahead of this pass's products (columns past Kq: clamped, zeroed when used).
+    u4 xrows[XM];
+    auto fetch_x = [&](int c) {
+        const int js0 = (c * KS + wave) * S;
 #pragma unroll
-            for (int j = 0; j < S; ++j)
+        for (int m = 0; m < XM; ++m) xrows[m] = load16(A.X + (size_t)min(m, A.M - 1) * A.ldx + min(128 * js0 + 8 * lane, A.kq - 8));
+    };
+    // requests: the activations of this wave's first range (L2 hits), then the first D tiles of weights
+    fetch_x(0);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) xa[j][i] = load16(xrow + min(128 * (js0 + j) + 32 * kb + 8 * i, A.kq - 8));
-        } else {   // lane l: piece l (8 columns) of the wave's 512 columns, for each of the XM rows
-#pragma unroll
-            for (int m = 0; m < XM; ++m)
-                xrows[m] = load16(A.X + (size_t)min(m, A.M - 1) * A.ldx + min(128 * js0 + 8 * lane, A.kq - 8));
-        }
-        if (c == 0) {
-#pragma unroll
-            for (int d = 0; d < D; ++d)
-                if (d < T) issue(d, d, 0);
-        }
-        __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
+    for (int d = 0; d < D; ++d)
+        if (d < T) issue(d, d, 0);
+    __builtin_amdgcn_sched_barrier(0);   // nothing below may move above the requests
 
+    // (with 16 rows the 64 registers of a second set of rows cost more in spilled accumulators than the fetch ahead
+    // saves - 25 to 30 % on every 13B / 70B shape - so those fetch at the start of each pass)
+    constexpr bool PREFETCH = MULTI && XM <= 8;
+    // One pass over the workgroup's tiles with this wave's K range of pass c.
+    auto pass = [&](int c, auto first_c) {
+        constexpr bool FIRST = decltype(first_c)::value;   // the launch's first pass (it alone multiplies the weak block)
+        const int js0 = (c * KS + wave) * S;   // first step of this wave in this pass
         // ---- this wave's activations for the pass: nibble order, zeros past M / Kq, group sums ---------------------
-        if (XM != 16) {
+        // piece l of row m sits at chunk l ^ m of the row's KB: the 16 rows a fragment read touches at one chunk index
+        // then spread over the banks (rows m and m + 8 share a bank group: the native two passes of a 128-bit read)
+        u4 xa[S][4];
+        if (MULTI && !PREFETCH && !FIRST) fetch_x(c);
 #pragma unroll
-            for (int m = 0; m < XM; ++m) *reinterpret_cast<u4*>(mine + 1024 * m + 16 * lane) = xrows[m];
-            wave_lds_fence();
-            const unsigned char* src = mine + 1024 * min(n, XM - 1) + 64 * kb;
+        for (int m = 0; m < XM; ++m) *reinterpret_cast<u4*>(mine + 1024 * m + 16 * (lane ^ m)) = xrows[m];
+        wave_lds_fence();
+        if (PREFETCH) fetch_x(c + 1);
+        const int nn = min(n, XM - 1);
+        const unsigned char* src = mine + 1024 * nn;
 #pragma unroll
-            for (int j = 0; j < S; ++j)
+        for (int j = 0; j < S; ++j)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) xa[j][i] = *reinterpret_cast<const u4*>(src + 256 * j + 16 * i);
-            wave_lds_fence();
-        }
+            for (int i = 0; i < 4; ++i) xa[j][i] = *reinterpret_cast<const u4*>(src + 16 * ((4 * kb + 16 * j + i) ^ nn));
+        wave_lds_fence();
         f4 sx[S];
 #pragma unroll
         for (int j = 0; j < S; ++j) {
@@ -1069,7 +1081,7 @@ __global__ __launch_bounds__(64 * MAXW) void gemv_w4_regs_kernel(RegsArgs A, int
                 sx[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xa[j][i]), as_h8(ones), sx[j], 0, 0, 0);
             }
         }
-        const u4 xwc = (c == 0 && n < A.M && wave < nweak && 32 * wave + 8 * kb < A.k) ? xw : zero4;
+        const u4 xwc = (FIRST && n < A.M && wave < nweak && 32 * wave + 8 * kb < A.k) ? xw : zero4;
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -1081,10 +1093,13 @@ __global__ __launch_bounds__(64 * MAXW) void gemv_w4_regs_kernel(RegsArgs A, int
             }
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(as_h8(xwc), as_h8(wk[d]), acc[t], 0, 0, 0);
             if (t + D < T) issue(d, t + D, c);
-            else if (MULTI) issue(d, t + D - T, c + 1);   // the next pass's first tiles (after the last pass: repeats, never used)
+            else if (MULTI) issue(d, t + D - T, c + 1);   // the next pass's first tiles (D divides T; after the last pass: repeats, never used)
             __builtin_amdgcn_sched_barrier(0);   // keep the refill right behind its tile
         }
-    }
+    };
+    pass(0, std::true_type{});
+#pragma clang loop unroll(disable)
+    for (int c = 1; c < C; ++c) pass(c, std::false_type{});
 
     // ---- K split: partial tiles meet in LDS, wave t sums and stores tile t -----------------------------------------
 #pragma unroll
@@ -1198,7 +1213,7 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
 bool launch_regs(const Layer* Ls, int n, const __half* X, int M, int64_t ldx, __half* const* Y, const int64_t* ldy, hipStream_t s,
                  hipError_t* err) {
     const Layer& L = Ls[0];
-    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || L.k < 8 || (L.kq % 8) != 0 || (L.k % 8) != 0 || M < 1 || M > 16) return false;
+    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || L.k < 8 || (L.kq % 8) != 0 || (L.k % 8) != 0 || M < 5 || M > 16) return false;   // (one to four rows: the rows-per-wave and the staged kernels)
     constexpr int S = 4;
     // passes over K and waves per workgroup: at most 8 waves (two per SIMD keep the whole register file), rows longer
     // than 8 x 4 steps in the fewest passes
@@ -1229,23 +1244,35 @@ bool launch_regs(const Layer* Ls, int n, const __half* X, int M, int64_t ldx, __
     A.stride = L.stride;
     A.gs = L.gs;
     // tiles per workgroup (they share the activation registers): the fewest for which all workgroups are resident at
-    // once - the register use of each variant sets the waves a CU holds (16 / 12 / 8)
-    int T = 1;
-    for (; T < 4; ++T) {
-        const int waves_cu = passes > 1 ? (T == 1 ? 12 : 8) : (T == 1 ? 16 : 12);
-        const int per_cu = waves_cu / ks < 1 ? 1 : waves_cu / ks;
+    // once - the register use of each variant and the LDS of a workgroup set how many a CU holds.
+    static const int T_CHOICES[6] = {1, 2, 3, 4, 6, 8};
+    // activation rows come as whole kilobytes per row and wave (8 or 16 requests) and are dealt out through LDS
+    const int xi = M <= 8 ? 0 : 1, xm = M <= 8 ? 8 : 16;
+    int ti = 0;
+    for (; ti < 5; ++ti) {
+        const int T = T_CHOICES[ti];
+        const int waves_cu = passes > 1 ? 8 : (T <= 6 ? 12 : 8);   // from the variants' register counts (132 .. 166: three waves per SIMD; 186 .. 256: two)
+        const int by_lds = (160 * 1024) / (ks * (xm > T ? xm : T) * 1024);
+        int per_cu = waves_cu / ks < by_lds ? waves_cu / ks : by_lds;
+        per_cu = per_cu < 1 ? 1 : per_cu;
         if (ceil_div(tiles, T) <= 256 * per_cu) break;
     }
+    const int T = T_CHOICES[ti];
     const int grid = ceil_div(tiles, T);
-    const int xm = M == 1 ? 1 : (M <= 4 ? 4 : 16), xi = M == 1 ? 0 : (M <= 4 ? 1 : 2);
-    const int wkb = xm == 16 ? T : (xm > T ? xm : T);
-    const size_t lds_bytes = (size_t)ks * wkb * 1024;
+    const size_t lds_bytes = (size_t)ks * (xm > T ? xm : T) * 1024;
     using Kern = void (*)(RegsArgs, int);
-#define QEFT_REGS_ROW(XM, MU) {gemv_w4_regs_kernel<S, 1, 1, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 2, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 3, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 4, XM, 8, MU>}
-    static const Kern table[2][3][4] = {{QEFT_REGS_ROW(1, false), QEFT_REGS_ROW(4, false), QEFT_REGS_ROW(16, false)},
-                                        {QEFT_REGS_ROW(1, true), QEFT_REGS_ROW(4, true), QEFT_REGS_ROW(16, true)}};
+#define QEFT_REGS_ROW(XM, MU) {gemv_w4_regs_kernel<S, 1, 1, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 2, XM, 8, MU>, gemv_w4_regs_kernel<S, MU ? 1 : 2, 3, XM, 8, MU>, \
+                               gemv_w4_regs_kernel<S, 2, 4, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 6, XM, 8, MU>, gemv_w4_regs_kernel<S, 2, 8, XM, 8, MU>}
+    static const Kern table[2][2][6] = {{QEFT_REGS_ROW(8, false), QEFT_REGS_ROW(16, false)}, {QEFT_REGS_ROW(8, true), QEFT_REGS_ROW(16, true)}};
 #undef QEFT_REGS_ROW
-    table[passes > 1 ? 1 : 0][xi][T - 1]<<<grid, 64 * ks, lds_bytes, s>>>(A, passes);
+    static bool attr_set[2][2][6] = {};
+    const Kern kern = table[passes > 1 ? 1 : 0][xi][ti];
+    if (lds_bytes > 64 * 1024 && !attr_set[passes > 1 ? 1 : 0][xi][ti]) {
+        *err = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        if (*err != hipSuccess) return true;
+        attr_set[passes > 1 ? 1 : 0][xi][ti] = true;
+    }
+    kern<<<grid, 64 * ks, lds_bytes, s>>>(A, passes);
     *err = hipGetLastError();
     return true;
 }

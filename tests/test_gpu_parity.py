@@ -173,6 +173,7 @@ FWD_CASES = [  # oc, ic, k, bits, g, Ms
     (96, 10880 + 128, 128, 4, 128, [1, 6]),          # the 7B down projection's row length: three passes of eight waves
     (4112, 1024 + 256, 256, 4, 128, [1, 9]),         # 257 tiles, two waves per workgroup; weak block as wide as the register kernel takes
     (64, 512 + 288, 288, 4, 128, [1, 5]),            # weak block too wide for the register kernel: the unstaged kernel
+    (8208, 4224 + 128, 128, 4, 128, [6, 16]),        # register kernel: 513 tiles with two passes over K - several tiles per workgroup, each in two passes
 ]
 
 
