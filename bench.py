@@ -33,8 +33,8 @@ MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
 # the launches of the kernel in one step.  They are NOT measured in this run (counters need the profiler).
-TRAFFIC_DX_BYTES = (114.3e6 + 34.3e6 + 339.3e6 + 34.3e6 + 485.3e6 + 90.9e6) / 3
-TRAFFIC_GEMV_BYTES = (29.31e6 + 9.90e6 + 52.40e6 + 25.21e6) / 4
+TRAFFIC_DX_BYTES = (438.6e6 + 45.6e6 + 373.7e6 + 99.3e6) / 2      # gemm_dx_dw_kernel, read + written, mean of the two MLP shapes
+TRAFFIC_GEMV_BYTES = (29.24e6 + 9.84e6 + 52.28e6 + 25.09e6) / 4    # gemv_w4_dot_kernel, mean of the four launches of a block
 TRAFFIC_SOURCE = "profiles/bench_7b_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script; not measured in this run)"
 # every stored byte of one 7B block with rows padded to 4 words and unpadded group parameters: the figure a
 # reader derives from the format alone; block_bytes below is what this build stores (rows padded to 16 words)
@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--no-other-models", action="store_true", help="skip the 13B / 70B timings (a profile of the 7B workload alone)")
     ap.add_argument("--sustained-seconds", type=float, default=2.0, help="length of the back-to-back fine-tune leg")
     args = ap.parse_args()
+
+    def progress(what):   # one line per leg on stderr: a profiled run is slow, and a silent one looks hung
+        print(f"[bench] {what}", file=sys.stderr, flush=True)
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -78,6 +81,7 @@ def main():
         x[:, ic - k:] *= 20.0                      # the outlier channels that make columns weak
         return x.half()
 
+    progress("packing the decode blocks")
     # ---- decode: enough distinct packed blocks to exceed 1 GB ------------------------------------
     descs = {s: B.make_desc(s[0], s[1], k, bits, g) for s in set(block_shapes)}
     block_bytes = 0
@@ -118,6 +122,7 @@ def main():
         for b in range(n_blocks):
             decode_block(b)
 
+    progress("fine-tune operands")
     # ---- fine-tune operands -----------------------------------------------------------------------
     ft = []
     for s in ft_shapes:
@@ -168,6 +173,7 @@ def main():
         if timed:
             records.append(marks)
 
+    progress("timed steps")
     for i in range(args.warmup):
         one_step(i, False)
     torch.cuda.synchronize()
@@ -177,6 +183,7 @@ def main():
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
 
+    progress("decode launches, one graph each")
     # ---- the decode kernel by launch: one graph per launch of the block holding that launch of every
     # rotating block, so that the launch periods can be told apart (host launch overhead would
     # dominate eager launches this short)
@@ -240,6 +247,7 @@ def main():
         decode_m8.append(dict(launch=name, us=round(us, 2), vs_M1=round(us / decode_kernels[li]["us"], 2)))
     del x8, y8, groups8
 
+    progress("irregular projection, 3-bit layouts")
     # ---- the attention output projection with its weak columns left in place (the layout the offline
     # reordering cannot reach): the same stored layer behind an on-the-fly gather of the activations
     d_o = descs[(4096, 4096)]
@@ -324,6 +332,7 @@ def main():
         del copies, ws3
     del w3
 
+    progress("decode on the 13B / 70B blocks")
     # ---- decode at M = 1 on the other models' blocks (outside the timed step): one graph per launch over enough
     # distinct copies to exceed the last-level cache; random stored components
     def rand_weight(desc_):
@@ -368,6 +377,7 @@ def main():
                                  block_bytes=tot_b, block_us=round(tot_us, 2), gbs=round(tot_b / tot_us / 1e3, 1),
                                  pct_hbm_peak=round(100 * tot_b / tot_us / 1e3 / HBM_PEAK_GBS, 2), launches=per_launch))
 
+    progress("fine-tune on the 13B / 70B shapes")
     # ---- the other models' fine-tune shapes (outside the timed step; context for the 7B figures) ---------
     # forward and input gradient with the optional workspace (launches with few tiles, or with a sparsely filled last
     # round of tiles, split their contraction over it), weak gradient; random stored components, one layer per shape
@@ -399,6 +409,7 @@ def main():
                                      step_tflops=round((2 * fl + 2.0 * m_o * oc * k_o) / (us[0] + min(us[1] + us[2], us[3])) / 1e6, 1)))
             del w_o2, x_o, dy_o, y_o, dx_o, dw_o, ws_o
 
+    progress("sustained fine-tune leg")
     # ---- sustained: the fine-tune calls of the 7B shapes back to back for a few seconds (the timed step above lasts
     # milliseconds; the chip is power-managed, so a short burst may not show the clock a long run settles at)
     ft_flops_step = sum(4.0 * M_ft * f["shape"][0] * f["shape"][1] + 2.0 * M_ft * f["shape"][0] * k for f in ft)
