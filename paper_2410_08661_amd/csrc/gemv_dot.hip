@@ -32,6 +32,7 @@ namespace {
 
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u3 __attribute__((ext_vector_type(3)));
 
 constexpr int DOT_THREADS = 512;   // 8 waves: two per SIMD
 constexpr int DOT_WAVES = DOT_THREADS / 64;
@@ -74,7 +75,11 @@ __device__ __forceinline__ float wave_sum_to_lane63(float t) {
 // (row, range) slots, lane 4 g + m takes the parameters of slot m, so one 2-byte load per array serves both rows.
 // LDS: pair-ordered activations [KS * NL][4 pieces][64 lanes] 16 B | (sum base x, sum x) float2 [KS * NL][64] |
 //      weak activations fp16 | K-split exchange float [8 waves][64]
-template <int NL, int DEPTH, int NKW, bool PERM>
+// W3D: three-bit codes in the dense layout (a row is one bit string, code j at bits 3 j .. 3 j + 2).  A lane's 32 columns
+// are then 96 bits = three whole words (12-byte requests, 768 bytes per range and wave), its pairs (x_2P, x_2P+1) lie at
+// bits 6 P of them - so the activations stay in column order - and both codes of a pair become 1024 + q: one 6-bit field
+// extract (pairs 5 and 10 straddle words: a funnel shift first), one multiplication by 2^13 + 1, one and-or.
+template <int NL, int DEPTH, int NKW, bool PERM, bool W3D>
 __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, int kq, int k, int row_bytes, int gs,
                                                                    const __half* __restrict__ X, const int* __restrict__ perm, int ic,
                                                                    int B, int ks_log2) {
@@ -110,7 +115,7 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
     const int p_row = PAIRP ? (qm >= NL ? 1 : 0) : 0, p_rng = PAIRP ? (qm >= NL ? qm - NL : qm) : 0;   // this lane's slot of a pair
     int woff[NL], goff[NP];
 #pragma unroll
-    for (int i = 0; i < NL; ++i) woff[i] = min(1024 * (li0 + i) + 16 * lane, row_bytes - 16);
+    for (int i = 0; i < NL; ++i) woff[i] = W3D ? min(768 * (li0 + i) + 12 * lane, row_bytes - 12) : min(1024 * (li0 + i) + 16 * lane, row_bytes - 16);
 #pragma unroll
     for (int j = 0; j < NP; ++j) goff[j] = 2 * min(16 * (li0 + (PAIRP ? min(p_rng, NL - 1) : 4 * j + qm)) + (lane >> 2), gs - 1);
     // weak columns: DEPTH 1: dword t of the lane = columns 2 (lane + 64 (t KS + kpart)), + 1; pairs: the 4 NKW columns from
@@ -129,7 +134,14 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
     auto issue_w = [&](int d, int row_in) {   // the codes of one row
         const unsigned char* wrow = wbase + (size_t)min(row_in, n_rows - 1) * (size_t)row_bytes;
 #pragma unroll
-        for (int i = 0; i < NL; ++i) wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
+        for (int i = 0; i < NL; ++i) {
+            if (W3D) {
+                const u3 v = *reinterpret_cast<const u3*>(wrow + woff[i]);
+                wq[d][i] = u4{v.x, v.y, v.z, 0u};
+            } else {
+                wq[d][i] = *reinterpret_cast<const u4*>(wrow + woff[i]);
+            }
+        }
     };
     auto issue_small = [&](int d, int row_in) {   // group parameters and weak block: of row d (DEPTH 1, or the per-row parameters of a pair) ...
         const size_t lr = (size_t)min(row_in, n_rows - 1);
@@ -204,10 +216,14 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
             u4 v = xv[t];
             if (8 * u >= kq) v = u4{0u, 0u, 0u, 0u};
             u4 p;
-            p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);   // (x0, x4)   base 1024
-            p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);   // (x1, x5)   base 64
-            p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);   // (x2, x6)   base 1024
-            p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);   // (x3, x7)   base 64
+            if (W3D) {
+                p = v;   // column order; every code gets the base 1024, so "se" below is the whole sum
+            } else {
+                p.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);   // (x0, x4)   base 1024
+                p.y = __builtin_amdgcn_perm(v.z, v.x, 0x07060302u);   // (x1, x5)   base 64
+                p.z = __builtin_amdgcn_perm(v.w, v.y, 0x05040100u);   // (x2, x6)   base 1024
+                p.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);   // (x3, x7)   base 64
+            }
             // (copies first: a bit cast applied directly to a vector component read the first component every time)
             const uint32_t px = p.x, py = p.y, pz = p.z, pw = p.w;
             const h2 a = __builtin_bit_cast(h2, px), b = __builtin_bit_cast(h2, py), c = __builtin_bit_cast(h2, pz),
@@ -218,7 +234,7 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
                 // range i = u / 256, lane l = (u % 256) / 4, piece q = u % 4  ->  [i][q][l]
                 const int i = u >> 8, l = (u & 255) >> 2, q = u & 3;
                 *reinterpret_cast<u4*>(lds + 4096 * i + 1024 * q + 16 * l) = p;
-                if (q == 0) ksum[64 * i + l] = float2{1024.f * se + 64.f * so, se + so};
+                if (q == 0) ksum[64 * i + l] = float2{1024.f * se + (W3D ? 1024.f : 64.f) * so, se + so};
             }
         }
     };
@@ -283,8 +299,8 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
         }
     }
 
-    uint32_t m_lo = 0x000f000fu, m_hi = 0x00f000f0u, g_lo = 0x64006400u, g_hi = 0x54005400u;
-    asm volatile("" : "+v"(m_lo), "+v"(m_hi), "+v"(g_lo), "+v"(g_hi));   // in registers: (w & m) | g is then one v_and_or_b32
+    uint32_t m_lo = 0x000f000fu, m_hi = 0x00f000f0u, g_lo = 0x64006400u, g_hi = 0x54005400u, m3 = 0x00070007u;
+    asm volatile("" : "+v"(m_lo), "+v"(m_hi), "+v"(g_lo), "+v"(g_hi), "+v"(m3));   // in registers: (w & m) | g is then one v_and_or_b32
 
     float res = 0.f;   // lane j: the wave's result for its row j
     // sum x q of every group of one row's ranges, each in the four lanes of its quad
@@ -292,14 +308,31 @@ __global__ __launch_bounds__(DOT_THREADS) void gemv_w4_dot_kernel(DotLayers R, i
 #pragma unroll
         for (int i = 0; i < NL; ++i) {
             float a0 = 0.f, a1 = 0.f;
+            if (W3D) {
+                const uint32_t w0 = wq[d][i].x, w1 = wq[d][i].y, w2 = wq[d][i].z;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t w = wq[d][i][q], w8 = w >> 8;
-                const uint32_t p0 = (w & m_lo) | g_lo, p1 = (w & m_hi) | g_hi, p2 = (w8 & m_lo) | g_lo, p3 = (w8 & m_hi) | g_hi;
-                a0 = dot2(p0, xr[i][4 * q + 0], a0);
-                a1 = dot2(p1, xr[i][4 * q + 1], a1);
-                a0 = dot2(p2, xr[i][4 * q + 2], a0);
-                a1 = dot2(p3, xr[i][4 * q + 3], a1);
+                for (int P = 0; P < 16; ++P) {
+                    constexpr uint32_t spread = 0x2001u;
+                    uint32_t f;   // the pair's six bits
+                    if (P < 5) f = __builtin_amdgcn_ubfe(w0, 6 * P, 6);
+                    else if (P == 5) f = __builtin_amdgcn_alignbit(w1, w0, 30) & 63u;
+                    else if (P < 10) f = __builtin_amdgcn_ubfe(w1, 6 * P - 32, 6);
+                    else if (P == 10) f = __builtin_amdgcn_alignbit(w2, w1, 28) & 63u;
+                    else f = __builtin_amdgcn_ubfe(w2, 6 * P - 64, 6);
+                    const uint32_t pr = ((f * spread) & m3) | g_lo;
+                    if (P & 1) a1 = dot2(pr, xr[i][P], a1);
+                    else a0 = dot2(pr, xr[i][P], a0);
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t w = wq[d][i][q], w8 = w >> 8;
+                    const uint32_t p0 = (w & m_lo) | g_lo, p1 = (w & m_hi) | g_hi, p2 = (w8 & m_lo) | g_lo, p3 = (w8 & m_hi) | g_hi;
+                    a0 = dot2(p0, xr[i][4 * q + 0], a0);
+                    a1 = dot2(p1, xr[i][4 * q + 1], a1);
+                    a0 = dot2(p2, xr[i][4 * q + 2], a0);
+                    a1 = dot2(p3, xr[i][4 * q + 3], a1);
+                }
             }
             tg[i] = quad_sum((a0 + a1) - kbase[i]);
         }
@@ -586,7 +619,9 @@ struct DotPlan {
 DotPlan dot_plan(const Layer& L, int n_rows) {
     DotPlan p = {};
     p.ok = false;
-    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || (L.kq % 8) != 0 || L.k < 8 || (L.k % 8) != 0) return p;
+    const bool w3d = L.bits == 3 && L.dense;   // (the dense layout's rows hold whole 12-byte lane pieces when Kq is a multiple of 32)
+    if (!(L.bits == 4 || w3d) || L.g != 128 || L.kq < 8 || (L.kq % 8) != 0 || L.k < 8 || (L.k % 8) != 0) return p;
+    if (w3d && ((L.kq % 32) != 0 || L.stride < 3)) return p;
     const int nl_all = ceil_div(L.kq, 2048);
     int ks_log2 = 0;
     while (ks_log2 < 2 && ceil_div(nl_all, 1 << ks_log2) > 8) ++ks_log2;
@@ -634,9 +669,9 @@ DotPlan dot_plan_w3(const Layer& L, int n_rows, bool perm) {
 
 using DotKern = void (*)(DotLayers, int, int, int, int, const __half*, const int*, int, int, int);
 
-template <bool PERM>
+template <bool PERM, bool W3D>
 DotKern dot_kernel(int nl, int nkw) {
-#define QEFT_DOT(N, D) (nkw == 1 ? (DotKern)gemv_w4_dot_kernel<N, D, 1, PERM> : (DotKern)gemv_w4_dot_kernel<N, D, 2, PERM>)
+#define QEFT_DOT(N, D) (nkw == 1 ? (DotKern)gemv_w4_dot_kernel<N, D, 1, PERM, W3D> : (DotKern)gemv_w4_dot_kernel<N, D, 2, PERM, W3D>)
     switch (nl) {
         case 2: return QEFT_DOT(2, 2);
         case 3: return QEFT_DOT(3, 2);
@@ -686,7 +721,8 @@ hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X
         return hipGetLastError();
     }
     const int blocks = ceil_div(sets, DOT_WAVES >> p.ks_log2);
-    const DotKern kern = perm ? dot_kernel<true>(p.nscw, p.nkw) : dot_kernel<false>(p.nscw, p.nkw);
+    if (L.dense && perm) return hipSuccess;   // no gathering variant for 3-bit codes
+    const DotKern kern = L.dense ? dot_kernel<false, true>(p.nscw, p.nkw) : (perm ? dot_kernel<true, false>(p.nscw, p.nkw) : dot_kernel<false, false>(p.nscw, p.nkw));
     kern<<<blocks, DOT_THREADS, p.lds, s>>>(R, L.kq, L.k, 4 * L.stride, L.gs, X, perm, L.ic, p.B, p.ks_log2);
     *handled = true;
     return hipGetLastError();
