@@ -624,7 +624,9 @@ DotPlan dot_plan(const Layer& L, int n_rows) {
     if (w3d && ((L.kq % 32) != 0 || L.stride < 3)) return p;
     const int nl_all = ceil_div(L.kq, 2048);
     int ks_log2 = 0;
-    while (ks_log2 < 2 && ceil_div(nl_all, 1 << ks_log2) > 8) ++ks_log2;
+    // one wave for rows of up to 8 ranges; longer rows over 4 waves
+    // (28416 columns: 27.2 us with 4 x 4 ranges, two workgroups per CU, against 28.5 us with 2 x 8)
+    if (nl_all > 8) ks_log2 = 2;
     const int KS = 1 << ks_log2;
     int nl = ceil_div(nl_all, KS);
     if (nl > 8) return p;
@@ -635,13 +637,13 @@ DotPlan dot_plan(const Layer& L, int n_rows) {
     p.nkw = nkw;
     p.ks_log2 = ks_log2;
     p.depth = (nl <= 3 && KS == 1) ? 2 : 1;
-    const int occ_wg = nl <= 3 ? 2 : 1;                         // resident workgroups per CU the register budget allows
+    const int occ_wg = nl <= 4 ? 2 : 1;                         // resident workgroups per CU the register budget allows (87 / 119 / 116 registers at 2 / 3 / 4 ranges)
     const int slots = 256 * occ_wg * (DOT_WAVES / KS);          // row sets resident at once
     p.B = ceil_div(n_rows, p.depth * slots);
     if (p.depth * p.B > 64) return p;                           // a wave keeps its rows' results one per lane
     const int nl_pad = nl * KS;
     p.lds = (size_t)4096 * nl_pad + 512 * nl_pad + 256 * KS * nkw + (KS > 1 ? DOT_WAVES * 64 * sizeof(float) : 0);
-    p.ok = p.lds <= 64 * 1024;
+    p.ok = p.lds <= 80 * 1024;
     return p;
 }
 
@@ -723,6 +725,10 @@ hipError_t gemv_dot_fwd(const Layer* Ls, int n, const int* perm, const __half* X
     const int blocks = ceil_div(sets, DOT_WAVES >> p.ks_log2);
     if (L.dense && perm) return hipSuccess;   // no gathering variant for 3-bit codes
     const DotKern kern = L.dense ? dot_kernel<false, true>(p.nscw, p.nkw) : (perm ? dot_kernel<true, false>(p.nscw, p.nkw) : dot_kernel<false, false>(p.nscw, p.nkw));
+    if (p.lds > 64 * 1024) {   // (rows of more than 24 K columns; idempotent, so set on every such launch)
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 80 * 1024);
+        if (e != hipSuccess) return e;
+    }
     kern<<<blocks, DOT_THREADS, p.lds, s>>>(R, L.kq, L.k, 4 * L.stride, L.gs, X, perm, L.ic, p.B, p.ks_log2);
     *handled = true;
     return hipGetLastError();
