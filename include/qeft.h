@@ -39,13 +39,18 @@ extern "C" {
 typedef enum {
     QEFT_OK = 0,
     QEFT_ERR_NULL = -1,        /* a required pointer is NULL                                   */
-    QEFT_ERR_SHAPE = -2,       /* OC, IC, g <= 0; k outside [0, IC]; M < 0; ld < row width      */
+    QEFT_ERR_SHAPE = -2,       /* OC, IC, g <= 0 or above QEFT_MAX_DIM; k outside [0, IC]; M < 0 or above QEFT_MAX_DIM; ld < row width */
     QEFT_ERR_BITS = -3,        /* bits is not 3 or 4                                           */
     QEFT_ERR_ALIGN = -4,       /* pointer not 16-byte aligned, or ld not a multiple of 8       */
     QEFT_ERR_WORKSPACE = -5,   /* workspace missing or smaller than qeft_workspace_bytes()     */
     QEFT_ERR_UNSUPPORTED = -6, /* unknown layout / dtype / op, or a combination not implemented */
     QEFT_ERR_HIP = -7          /* the HIP runtime reported an error at launch                  */
 } qeft_status;
+
+/* Largest OC, IC, group size and number of rows M a call accepts (index arithmetic in the kernels is 32-bit per tile
+ * and the host's tile and workspace counts are kept well inside 64 bits); larger values are QEFT_ERR_SHAPE, and
+ * qeft_workspace_bytes / qeft_sensitivity_workspace report 0 for them.  (qeft_sensitivity takes up to 2^31 tokens.) */
+#define QEFT_MAX_DIM (1 << 24)
 
 /* How the codes of a row are laid out in its 32-bit words.
  *   QEFT_LAYOUT_CANONICAL  whole codes per word: 8 four-bit or 10 three-bit codes (bits 30..31 zero).

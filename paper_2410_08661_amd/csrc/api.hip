@@ -14,6 +14,7 @@ int check_desc(const qeft_desc_t* d) {
     if (d->out_features <= 0 || d->in_features <= 0 || d->group_size <= 0 || d->n_weak < 0 ||
         d->n_weak > d->in_features)
         return QEFT_ERR_SHAPE;
+    if (d->out_features > QEFT_MAX_DIM || d->in_features > QEFT_MAX_DIM || d->group_size > QEFT_MAX_DIM) return QEFT_ERR_SHAPE;
     if (d->layout != QEFT_LAYOUT_CANONICAL && !(d->layout == QEFT_LAYOUT_DENSE3 && d->bits == 3)) return QEFT_ERR_UNSUPPORTED;
     return QEFT_OK;
 }
@@ -61,7 +62,7 @@ int make_layer(const qeft_desc_t* d, const qeft_weight_t* w, Layer* L) {
 }
 
 int check_matrix(const void* p, int64_t M, int64_t ld, int64_t width) {
-    if (M < 0) return QEFT_ERR_SHAPE;
+    if (M < 0 || M > QEFT_MAX_DIM) return QEFT_ERR_SHAPE;
     if (M == 0) return QEFT_OK;
     if (!p) return QEFT_ERR_NULL;
     if (ld < width) return QEFT_ERR_SHAPE;
@@ -165,7 +166,7 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
 }
 
 size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
-    if (check_desc(desc) != QEFT_OK || M <= 0) return 0;
+    if (check_desc(desc) != QEFT_OK || M <= 0 || M > QEFT_MAX_DIM) return 0;
     if (op == QEFT_OP_WEAK_GRAD && weak_grad_mfma_supported(desc->out_features, desc->n_weak, M))
         return weak_grad_mfma_workspace(desc->out_features, desc->n_weak, M);
     if (op == QEFT_OP_BWD) {
@@ -362,13 +363,13 @@ int qeft_linear_bwd_dx_irregular(const qeft_desc_t* desc, const qeft_weight_t* w
 }
 
 size_t qeft_sensitivity_workspace(int32_t d, int64_t tokens) {
-    if (d <= 0 || tokens <= 0) return 0;
+    if (d <= 0 || tokens <= 0 || d > QEFT_MAX_DIM || tokens > ((int64_t)1 << 31)) return 0;
     return sens_workspace(d, tokens);
 }
 
 int qeft_sensitivity(const void* X, int64_t tokens, int64_t ldx, int32_t d, int32_t n_batch, float* out, void* ws,
                      size_t ws_bytes, void* stream) {
-    if (d <= 0 || (d & 7) != 0 || tokens <= 0 || n_batch <= 0) return QEFT_ERR_SHAPE;
+    if (d <= 0 || (d & 7) != 0 || tokens <= 0 || n_batch <= 0 || d > QEFT_MAX_DIM || tokens > ((int64_t)1 << 31)) return QEFT_ERR_SHAPE;
     int st = check_matrix(X, tokens, ldx, d);
     if (st != QEFT_OK) return st;
     if (!out) return QEFT_ERR_NULL;

@@ -315,3 +315,24 @@ def test_backward_in_one_call_validation():
     assert a > 0 and b > 0 and B.qeft_workspace_bytes(d5, B.QEFT_OP_BWD, 4096) == max(a, b)
     d6 = B.make_desc(13824, 5120, 128, 3)      # 3-bit: never the fp16 copy, the weak gradient's amount only
     assert B.qeft_workspace_bytes(d6, B.QEFT_OP_BWD, 4096) == B.qeft_workspace_bytes(d6, B.QEFT_OP_WEAK_GRAD, 4096)
+
+
+def test_dimension_limits():
+    """QEFT_MAX_DIM: larger shapes and row counts are refused before any size arithmetic could overflow (a workspace
+    query for 2^40 rows used to end in a division by zero)."""
+    lim = 1 << 24
+    lay = B.qeft_layout_t()
+    assert B.raw.qeft_layout(C.byref(B.make_desc(lim, lim, 128, 4)), C.byref(lay)) == B.QEFT_OK
+    assert lay.qweight_bytes == lim * ((lim - 128) // 8) * 4
+    for d in (B.make_desc(lim + 8, 4096, 128, 4), B.make_desc(4096, lim + 8, 128, 4), B.make_desc(4096, 4096, 128, 4, lim + 8)):
+        assert B.raw.qeft_layout(C.byref(d), C.byref(lay)) == B.QEFT_ERR_SHAPE
+        assert B.qeft_workspace_bytes(d, B.QEFT_OP_WEAK_GRAD, 4096) == 0
+    d = B.make_desc(4096, 4096, 128, 4)
+    for op in (B.QEFT_OP_FWD, B.QEFT_OP_BWD_DX, B.QEFT_OP_WEAK_GRAD, B.QEFT_OP_FWD_IRREGULAR, B.QEFT_OP_BWD):
+        assert B.qeft_workspace_bytes(d, op, 1 << 40) == 0
+        assert B.qeft_workspace_bytes(d, op, lim + 1) == 0
+    assert B.qeft_workspace_bytes(d, B.QEFT_OP_WEAK_GRAD, lim) > 0
+    w = _w()
+    assert B.raw.qeft_linear_fwd(C.byref(d), C.byref(w), 0x10000, lim + 1, 4096, 0x20000, 4096, None, 0, None) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_linear_bwd_dx(C.byref(d), C.byref(w), 0x10000, 1 << 40, 4096, 0x20000, 4096, None, 0, None) == B.QEFT_ERR_SHAPE
+    assert B.raw.qeft_sensitivity_workspace(4096, 1 << 40) == 0 and B.raw.qeft_sensitivity_workspace(lim + 8, 4096) == 0
