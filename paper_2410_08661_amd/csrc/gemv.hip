@@ -1213,13 +1213,16 @@ bool launch_small(const Layer& L, int tiles, const GroupTail& tail, const int* p
 bool launch_regs(const Layer* Ls, int n, const __half* X, int M, int64_t ldx, __half* const* Y, const int64_t* ldy, hipStream_t s,
                  hipError_t* err) {
     const Layer& L = Ls[0];
-    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || L.k < 8 || (L.kq % 8) != 0 || (L.k % 8) != 0 || M < 5 || M > 16) return false;   // (one to four rows: the rows-per-wave and the staged kernels)
+    if (L.bits != 4 || L.dense || L.g != 128 || L.kq < 8 || L.k < 8 || (L.kq % 8) != 0 || (L.k % 8) != 0 || M < 3 || M > 16) return false;   // (one and two rows: the rows-per-wave and the staged kernels)
     constexpr int S = 4;
     // passes over K and waves per workgroup: at most 8 waves (two per SIMD keep the whole register file), rows longer
     // than 8 x 4 steps in the fewest passes
     const int units = ceil_div(L.ng, S);
     const int passes = ceil_div(units, 8), ks = ceil_div(units, passes);
     if (ceil_div(L.k, 32) > ks) return false;
+    // three and four rows: only rows of a single pass (7B block at M = 4: 42.1 us with this kernel on q/k/v, o and
+    // gate/up against 46.0 us on the staged kernel throughout; rows of several passes are faster there: 11.7 against 13.1 us)
+    if (M < 5 && passes > 1) return false;
     RegsArgs A = {};
     int tiles = 0;
     for (int i = 0; i < MAX_GROUP; ++i) {
@@ -1293,10 +1296,10 @@ hipError_t gemv_fwd_group(const Layer* Ls, int n, const __half* X, int64_t M64, 
         hipError_t e = gemv_dot_fwd(Ls, n, nullptr, X, Y, s, handled);
         if (e != hipSuccess || *handled) return e;
     }
-    if (M64 > 4) {    // 5 .. 16 rows: the register kernel (the small-M kernel below stages at most 4 rows)
+    if (M64 > 2) {    // 5 .. 16 rows: the register kernel (the small-M kernel below stages at most 4 rows); 3 and 4: where it is faster
         hipError_t e = hipSuccess;
         *handled = launch_regs(Ls, n, X, (int)M64, ldx, Y, ldy, s, &e);
-        return e;
+        if (*handled || M64 > 4) return e;
     }
     if (!(L.bits == 4 || L.dense)) return hipSuccess;   // ten 3-bit codes per word: per-layer calls
     GroupTail tail = no_tail();
@@ -1332,7 +1335,7 @@ hipError_t gemv_fwd_perm(const Layer& L, const int* perm, const __half* X, int64
 
 hipError_t gemv_fwd(const Layer& L, const __half* X, int64_t M64, int64_t ldx, __half* Y, int64_t ldy, hipStream_t s) {
     const int M = (int)M64;
-    if (M > 4) {      // 5 .. 16 rows: activations in registers, any row length
+    if (M > 2) {      // 5 .. 16 rows: activations in registers, any row length; 3 and 4 rows: short rows only
         hipError_t e = hipSuccess;
         if (launch_regs(&L, 1, X, M, ldx, &Y, &ldy, s, &e)) return e;
     }
