@@ -624,13 +624,14 @@ DotPlan dot_plan(const Layer& L, int n_rows) {
     if (w3d && ((L.kq % 32) != 0 || L.stride < 3)) return p;
     const int nl_all = ceil_div(L.kq, 2048);
     int ks_log2 = 0;
-    // one wave for rows of up to 8 ranges; longer rows over 4 waves
+    // one wave for rows of up to 8 ranges; longer rows over 2 waves, or over 4 when that leaves a wave at least 4 ranges
     // (28416 columns: 27.2 us with 4 x 4 ranges, two workgroups per CU, against 28.5 us with 2 x 8)
-    if (nl_all > 8) ks_log2 = 2;
+    if (nl_all > 8) ks_log2 = nl_all > 12 ? 2 : 1;
     const int KS = 1 << ks_log2;
     int nl = ceil_div(nl_all, KS);
     if (nl > 8) return p;
     nl = nl < 2 ? 2 : (nl == 7 ? 8 : nl);   // (seven ranges spill registers; the eighth is clamped and multiplies zeros)
+    if (KS > 1 && nl < 4) nl = 4;           // (the variants of 2 and 3 ranges run pairs of rows and take no K split)
     const int nkw = ceil_div(L.k, 128 * KS);
     if (nkw > 2 || L.k > 8 * DOT_THREADS) return p;
     p.nscw = nl;

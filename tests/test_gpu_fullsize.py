@@ -14,43 +14,9 @@ import torch
 from oracle import qeft_oracle as qo
 from paper_2410_08661_amd import binding as B
 from paper_2410_08661_amd import synth
-from parity_util import assert_close
+from parity_util import BigLayer, assert_close
 
 pytestmark = pytest.mark.gpu
-
-
-class BigLayer:
-    def __init__(self, oc, ic, k, bits, seed):
-        # bits "3d": 3-bit codes in the dense layout
-        dense = bits == "3d"
-        nbits = 3 if dense else bits
-        self.oc, self.ic, self.k, self.bits, self.nbits, self.g = oc, ic, k, bits, nbits, 128
-        self.lay = qo.layout(oc, ic, k, nbits, 128, dense=dense)
-        self.kq = self.lay["kq"]
-        codes, self.scales, self.zeros = synth.make_codes(oc, self.kq, self.lay["n_groups"], nbits, seed)
-        if dense:
-            self.qweight = qo.pack_codes_dense3(codes, self.lay["row_stride_words"])
-        else:
-            self.qweight = qo.pack_codes(codes, bits, self.lay["row_stride_words"])
-        del codes
-        self.weak = (np.random.default_rng(seed).standard_normal((oc, k), dtype=np.float32) * 0.02).astype(np.float16)
-        self.desc = B.make_desc(oc, ic, k, nbits, 128, layout=B.QEFT_LAYOUT_DENSE3 if dense else B.QEFT_LAYOUT_CANONICAL)
-        w = B.Weight(self.desc)
-        ng = self.lay["n_groups"]
-        w.qweight.copy_(torch.from_numpy(self.qweight.view(np.int32)))
-        w.scales[:, :ng].copy_(torch.from_numpy(self.scales))
-        w.zeros[:, :ng].copy_(torch.from_numpy(self.zeros))
-        w.weak.copy_(torch.from_numpy(self.weak))
-        self.dev = w
-        self._w64 = None
-
-    @property
-    def w64(self):
-        """The whole mixed weight in float64, from the PACKED words (the oracle's unpack, then its dequantize)."""
-        if self._w64 is None:
-            codes = qo.unpack_codes_dense3(self.qweight, self.kq) if self.bits == "3d" else qo.unpack_codes(self.qweight, self.kq, self.nbits)
-            self._w64 = qo.dequantize(codes, self.scales, self.zeros, self.weak, self.g)
-        return self._w64
 
 
 def _check(actual_t, ref64, what):

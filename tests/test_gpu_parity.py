@@ -174,6 +174,9 @@ FWD_CASES = [  # oc, ic, k, bits, g, Ms
     (4112, 1024 + 256, 256, 4, 128, [1, 9]),         # 257 tiles, two waves per workgroup; weak block as wide as the register kernel takes
     (64, 512 + 288, 288, 4, 128, [1, 5]),            # weak block too wide for the register kernel: the unstaged kernel
     (8208, 4224 + 128, 128, 4, 128, [6, 16]),        # register kernel: 513 tiles with two passes over K - several tiles per workgroup, each in two passes
+    (136, 17408 + 24, 24, 4, 128, [1, 3]),           # rows of 9 ranges of 2048 columns: the rows-per-wave kernel with two waves per row
+    (360, 23552 + 16, 16, 4, 128, [1, 2]),           # 12 ranges: two waves of six
+    (72, 26624 + 64, 64, 4, 128, [1, 5]),            # 13 ranges: four waves of four (three clamped)
 ]
 
 
