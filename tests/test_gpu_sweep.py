@@ -82,3 +82,50 @@ def test_backward_in_one_call_random_shapes(case, oc, ic, k, m):
         torch.cuda.synchronize()
         assert_close(dx.float().cpu().numpy(), dy.astype(np.float64) @ L.w64, f"dX {oc}x{ic} k{k} M={m}")
         assert_close(dw.float().cpu().numpy(), dy.astype(np.float64).T @ x[:, ic - k:].astype(np.float64), f"dW {oc}x{k} M={m}")
+
+
+def _gemm_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for case in range(n):
+        bits = [4, 4, 4, 3, "3d"][case % 5]
+        r = rng.random()
+        kq = 0 if r < 0.05 else (64 * int(rng.integers(1, 100)) if r < 0.6 else 8 * int(rng.integers(1, 800)))
+        k = int(rng.choice([0, 8, 24, 64, 128, 192, 256, 320]))
+        if kq + k < 64:
+            k = 64
+        if kq == 0:
+            bits = 4
+        oc = 8 * int(rng.integers(1, 500))
+        m = int(rng.choice([17, 33, 48, 64, 100, 255, 256, 257, 300, 511, 700, 1024, 1500, 2100]))
+        cases.append((case, oc, kq + k, k, bits, m))
+    return cases
+
+
+@pytest.mark.parametrize("case,oc,ic,k,bits,m", _gemm_cases(20, seed=5))
+def test_gemm_paths_random_shapes(case, oc, ic, k, bits, m):
+    """Forward and input gradient at more than 16 rows, without and with the optional workspace (split launches; the
+    fp16 copy of a 3-bit layer), and the weak gradient in both output types and on a view into X."""
+    L = BigLayer(oc, ic, k, bits, 100 + case)
+    kq = ic - k
+    x = synth.make_activations(m, ic, k, seed=case)
+    dy = synth.make_grad_output(m, oc, seed=case + 1)
+    xt, dyt = torch.from_numpy(x).cuda(), torch.from_numpy(dy).cuda()
+    x64, dy64 = x.astype(np.float64), dy.astype(np.float64)
+    yref, dxref = x64 @ L.w64.T, dy64 @ L.w64
+    for ws in (False, None):      # False: no workspace; None: the binding allocates what qeft_workspace_bytes reports
+        y = B.qeft_linear_fwd(L.desc, L.dev, xt, ws=ws)
+        dx = B.qeft_linear_bwd_dx(L.desc, L.dev, dyt, ws=ws)
+        torch.cuda.synchronize()
+        assert_close(y.float().cpu().numpy(), yref, f"fwd {oc}x{ic} k{k} w{bits} M={m} ws={ws}")
+        assert_close(dx.float().cpu().numpy(), dxref, f"dX {oc}x{ic} k{k} w{bits} M={m} ws={ws}")
+    if k:
+        dwref = dy64.T @ x64[:, kq:]
+        xw = torch.from_numpy(np.ascontiguousarray(x[:, kq:])).cuda()
+        for dt in (torch.float32, torch.float16):
+            dw = B.qeft_weak_grad(L.desc, dyt, xw, out_dtype=dt)
+            torch.cuda.synchronize()
+            assert_close(dw.float().cpu().numpy(), dwref, f"dW {oc}x{k} M={m} {dt}")
+        dw = B.qeft_weak_grad(L.desc, dyt, xt[:, kq:], out_dtype=torch.float32)
+        torch.cuda.synchronize()
+        assert_close(dw.float().cpu().numpy(), dwref, f"dW {oc}x{k} M={m} on a view into X")
