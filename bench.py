@@ -552,6 +552,20 @@ def cpu_baseline(np, synth, k, bits, g):
         y = qo.linear_fwd(w64, x256)
         g_wall += time.perf_counter() - w0
         g_reps += 1
+    # the same product on one thread (the unpack / dequantize part of the decode sample is single-threaded anyway)
+    one_gflops = None
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            o_reps, o_wall = 0, 0.0
+            while o_wall < 3.0 and o_reps < 40:
+                w0 = time.perf_counter()
+                y = qo.linear_fwd(w64, x256)
+                o_wall += time.perf_counter() - w0
+                o_reps += 1
+        one_gflops = round(2.0 * 256 * oc * ic * o_reps / o_wall / 1e9, 1)
+    except ImportError:
+        pass
     cores = os.cpu_count() or 1
     if os.environ.get("OMP_NUM_THREADS", "").isdigit():
         cores = min(cores, int(os.environ["OMP_NUM_THREADS"]))
@@ -560,6 +574,7 @@ def cpu_baseline(np, synth, k, bits, g):
             "sample": f"{reps} x (unpack + dequantize + fp64 product) of one 4096x4096 w4 g128 k128 layer at M=1, "
                       f"{t_wall:.1f} s of host time",
             "gemm_gflops": round(2.0 * 256 * oc * ic * g_reps / g_wall / 1e9, 1),
+            "gemm_gflops_one_thread": one_gflops,
             "gemm_sample": f"{g_reps} x the oracle's fp64 forward product of the dequantized layer at M=256, {g_wall:.1f} s"}
 
 
