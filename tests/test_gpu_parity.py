@@ -271,12 +271,13 @@ def test_forward_group_parity(ic, k, bits, ocs, Ms):
             assert_close(y.cpu().numpy(), qo.linear_fwd(h.w64, x), f"group layer {i} (OC {h.oc}) M={m}")
 
 
-def test_forward_group_writes_only_its_outputs_and_repeats_bitwise():
+@pytest.mark.parametrize("m", [1, 3, 8])
+def test_forward_group_writes_only_its_outputs_and_repeats_bitwise(m):
     ic, k = 1024 + 128, 128
     hs = [HostLayer(oc, ic, k, 4, 128, seed=40 + oc) for oc in (200, 72)]
     ws = [h.to_device() for h in hs]
-    x = torch.from_numpy(synth.make_activations(1, ic, k, 5)).cuda()
-    bufs = [torch.full((1, h.oc + 16), -3.0, dtype=torch.float16, device="cuda") for h in hs]
+    x = torch.from_numpy(synth.make_activations(m, ic, k, 5)).cuda()
+    bufs = [torch.full((m, h.oc + 16), -3.0, dtype=torch.float16, device="cuda") for h in hs]
     grp = B.Group([h.desc for h in hs], ws, [b[:, :h.oc] for b, h in zip(bufs, hs)])
     B.qeft_linear_fwd_group(None, None, x, group=grp)
     torch.cuda.synchronize()
@@ -292,10 +293,13 @@ def test_forward_group_writes_only_its_outputs_and_repeats_bitwise():
             assert torch.equal(b, f)
 
 
-def test_forward_respects_leading_dimensions_and_is_deterministic():
-    h = HostLayer(320, 640 + 128, 128, 4, 128, seed=9)
+@pytest.mark.parametrize("bits,dense", [(4, False), (3, False), (3, True)])
+@pytest.mark.parametrize("m", [1, 2, 4, 6, 16, 40])
+def test_forward_respects_leading_dimensions_and_is_deterministic(m, bits, dense):
+    """Every forward kernel (one row, two to four, five to sixteen, the GEMM; 4-bit and both 3-bit layouts) on operands
+    with leading dimensions larger than their widths: right values, nothing written past OC, bitwise repeatable."""
+    h = HostLayer(320, 640 + 128, 128, bits, 128, seed=9, dense=dense)
     w = h.to_device()
-    m = 6
     x = synth.make_activations(m, h.ic, h.k, 9)
     xbuf = torch.full((m, h.ic + 24), 7.0, dtype=torch.float16, device="cuda")
     xbuf[:, :h.ic].copy_(torch.from_numpy(x))
