@@ -22,13 +22,14 @@
 // the K steps into contiguous ranges and are reduced through LDS in a fixed order (no
 // atomics: run-to-run deterministic).  Weight loads run several steps ahead in loops without
 // branches (rows are padded to whole steps and rows past OC are clamped, never stored).
-//   * small-M kernel (M <= 4 and X fits in LDS): the workgroup stages X once (permuted, with
+//   * small-M kernel (M <= 4 and X fits in LDS; today M = 2, M = 3 and 4 on rows of several passes, and the dense
+//     3-bit layout at 2 <= M <= 4): the workgroup stages X once (permuted, with
 //     Sx), one barrier; a launch-latency-shaped prologue (see the kernel).  It also takes a
 //     group of layers that share X (query / key / value, gate / up) as one launch: its tiles
 //     are those of layer 0, then layer 1, ..., each wave picking its layer's pointers;
-//   * register kernel (5 <= M <= 16): one wave per K range keeps the A fragments of its range in registers
-//     for the whole launch (no staging, no barrier before the stream), walks several row tiles and meets the
-//     other waves' partial tiles in LDS at the end;
+//   * register kernel (5 <= M <= 16; M = 3 and 4 on rows of a single pass): one wave per K range keeps the A
+//     fragments of its range in registers for the whole launch (no workgroup staging, no barrier before the
+//     stream), walks several row tiles and meets the other waves' partial tiles in LDS at the end;
 //   * one activation row goes to a kernel of its own (gemv_dot.hip): whole rows per wave, two-element dot
 //     products, activations in registers;
 //   * row-batch kernel (any M <= 16): nothing staged, A fragments straight from X, Sx from the
@@ -952,12 +953,12 @@ hipError_t launch_w3(const Layer& L, const __half* X, int M, int64_t ldx, __half
 }
 
 // =============================================================================================
-// Register kernel: any M <= 16, rows up to MAXSTEPS * 128 columns per pass.  The activations never touch LDS:
-// a workgroup has one wave per K range of S steps, and lane (n, kb) of a wave keeps, for the whole launch, the A
-// fragments of activation row n for its range (4 S registers of 8 halfs, fetched straight from X with 128-bit
-// loads and permuted once), together with the group sums Sx of its steps in accumulator layout (from MFMAs
-// against an all-ones operand).  The launch therefore starts streaming weights at once - no staging pass, no
-// barrier - and costs the same for M = 1 and M = 16.  A workgroup walks T row tiles (compile-time, so every
+// Register kernel: 3 <= M <= 16, rows of any length in passes of (waves x S) steps.  A workgroup has one wave per K
+// range of S steps, and lane (n, kb) of a wave keeps, for a whole pass, the A fragments of activation row n for its
+// range (4 S registers of 8 halfs: the wave fetches its rows' 512 columns as whole kilobytes, deals them out through
+// a private piece of LDS and permutes them once), together with the group sums Sx of its steps in accumulator layout
+// (from MFMAs against an all-ones operand).  No workgroup-wide staging pass and no barrier before the stream: the
+// weight requests go out with the first activation requests.  A workgroup walks T row tiles (compile-time, so every
 // load is unconditional) with D tiles of weight loads in flight; the K-split partial tiles stay in registers
 // and meet in LDS once, at the end.  Several layers that share X run as one launch (tiles of layer 0, 1, ...).
 // =============================================================================================
