@@ -164,7 +164,10 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
  * amount is given): with that workspace (16-byte aligned) the call dequantizes the layer once into it as fp16 and
  * runs the tensor-core kernels on the copy - the paper's own training path, dequantize then a dense product
  * (Sec. 4.3, App. A.2) - and without it (ws NULL) the slow general kernel; a workspace that is too small is
- * QEFT_ERR_WORKSPACE.  The copy is rewritten by every call (the weak block may have changed). */
+ * QEFT_ERR_WORKSPACE.  The copy is rewritten by every call (the weak block may have changed).
+ * QEFT_OP_BWD (qeft_linear_bwd): the larger of QEFT_OP_WEAK_GRAD's amount, which that call requires, and - for 4-bit
+ * layers - QEFT_OP_BWD_DX's, which it uses when given (3-bit layers: the weak gradient's amount only; the call never
+ * takes an fp16 copy). */
 size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
 
 /* Forward of the fused layer (Sec. 3.2.1): Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . weak^T in
