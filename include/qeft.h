@@ -165,9 +165,8 @@ int qeft_unpack(const qeft_desc_t* desc, const qeft_weight_t* w, uint8_t* codes,
  * runs the tensor-core kernels on the copy - the paper's own training path, dequantize then a dense product
  * (Sec. 4.3, App. A.2) - and without it (ws NULL) the slow general kernel; a workspace that is too small is
  * QEFT_ERR_WORKSPACE.  The copy is rewritten by every call (the weak block may have changed).
- * QEFT_OP_BWD (qeft_linear_bwd): the larger of QEFT_OP_WEAK_GRAD's amount, which that call requires, and - for 4-bit
- * layers - QEFT_OP_BWD_DX's, which it uses when given (3-bit layers: the weak gradient's amount only; the call never
- * takes an fp16 copy). */
+ * QEFT_OP_BWD (qeft_linear_bwd): the larger of QEFT_OP_WEAK_GRAD's amount, which that call requires, and
+ * QEFT_OP_BWD_DX's, which it uses when given (the two steps use the workspace one after the other). */
 size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M);
 
 /* Forward of the fused layer (Sec. 3.2.1): Y = X[:, :Kq] . dq(Q)^T + X[:, Kq:] . weak^T in
@@ -266,10 +265,11 @@ int qeft_weak_grad(const qeft_desc_t* desc, const void* dY, int64_t M, int64_t l
 /* The backward pass of one layer in one call (Sec. 3.3, Eq. 5): dX = dY . W through the full mixed weight and
  * dW (+)= dY^T . Xw for the weak block, arguments as in qeft_linear_bwd_dx and qeft_weak_grad.  The same kernels
  * run as in those two calls, and the results equal theirs bit for bit; what the call chooses is how they go out:
- *   - with room in ws for the partial tiles of a row split of dX (qeft_workspace_bytes(desc, QEFT_OP_BWD, M), the
- *     larger of the two steps' amounts; 4-bit layers only) and a layer whose dX that split applies to: dX with the
- *     split, then the weak gradient, as qeft_linear_bwd_dx with its workspace followed by qeft_weak_grad (the
- *     workspace serves one after the other);
+ *   - with room in ws for what qeft_linear_bwd_dx can use (qeft_workspace_bytes(desc, QEFT_OP_BWD, M), the larger
+ *     of the two steps' amounts: the partial tiles of a row split of dX where that split applies, the fp16 copy of
+ *     a 3-bit layer - without which its dX takes the slow general kernel): dX with that workspace, then the weak
+ *     gradient, as qeft_linear_bwd_dx with its workspace followed by qeft_weak_grad (the workspace serves one after
+ *     the other);
  *   - else, where both steps take the tensor-core path and the weak block is at most 128 wide: ONE launch - the
  *     weak gradient's workgroups follow the dX tiles in the grid and are dispatched as compute units fall free, so
  *     they run in what the last round of tiles leaves idle (dX of 4096 x 11008 at M = 4096: 688 tiles on 256 units;

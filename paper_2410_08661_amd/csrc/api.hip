@@ -169,10 +169,8 @@ size_t qeft_workspace_bytes(const qeft_desc_t* desc, int op, int64_t M) {
     if (check_desc(desc) != QEFT_OK || M <= 0 || M > QEFT_MAX_DIM) return 0;
     if (op == QEFT_OP_WEAK_GRAD && weak_grad_mfma_supported(desc->out_features, desc->n_weak, M))
         return weak_grad_mfma_workspace(desc->out_features, desc->n_weak, M);
-    if (op == QEFT_OP_BWD) {
-        const size_t a = qeft_workspace_bytes(desc, QEFT_OP_WEAK_GRAD, M);
-        size_t b = 0;
-        if (desc->bits == 4) b = qeft_workspace_bytes(desc, QEFT_OP_BWD_DX, M);   // the row split; never the 3-bit fp16 copy
+    if (op == QEFT_OP_BWD) {   // the two steps use the workspace one after the other
+        const size_t a = qeft_workspace_bytes(desc, QEFT_OP_WEAK_GRAD, M), b = qeft_workspace_bytes(desc, QEFT_OP_BWD_DX, M);
         return a > b ? a : b;
     }
     if (op == QEFT_OP_FWD_IRREGULAR || op == QEFT_OP_BWD_DX_IRREGULAR) return irregular_workspace(desc->in_features, M);
@@ -460,7 +458,10 @@ int qeft_linear_bwd(const qeft_desc_t* desc, const qeft_weight_t* w, const void*
     if (need_dw > 0 && (!ws || ws_bytes < need_dw || !aligned16(ws))) return QEFT_ERR_WORKSPACE;
     // room for the partial tiles of a row split of dX: that split fills a sparse last round of tiles better than the
     // weak gradient's strips do, so it goes first (the strips' partial sums reuse the same bytes afterwards)
-    const size_t need_dx = gemm_dx_supported(L, M) ? gemm_dx_split_workspace(L, M) : 0;
+    // (a 3-bit layer: room for its fp16 copy - without it dX would take the slow general kernel - and, beyond that, for
+    // the copy's own split; qeft_linear_bwd_dx uses what it is given)
+    size_t need_dx = gemm_dx_supported(L, M) ? gemm_dx_split_workspace(L, M) : 0;
+    if (dense_copy_applies(L, M)) need_dx = dense_copy_bytes(L);
     const bool split = need_dx > 0 && ws && aligned16(ws) && ws_bytes >= need_dx;
     if (!split && gemm_dx_dw_supported(L, M))
         return hip_status(gemm_dx_dw(L, (const __half*)dY, M, lddy, (__half*)dX, lddx, (const __half*)Xw, ldxw, dW,

@@ -573,6 +573,32 @@ def test_backward_in_one_call_with_room_for_a_row_split(oc, ic, k, m):
     assert torch.equal(dx_c, dx_b if n_dw >= n_dx else dx_u)
 
 
+@pytest.mark.parametrize("dense", [False, True])
+def test_backward_in_one_call_three_bit(dense):
+    """qeft_linear_bwd on a 3-bit layer: with a workspace of QEFT_OP_BWD's size dX runs the tensor-core kernels on the fp16
+    copy (bit for bit qeft_linear_bwd_dx with that workspace, then qeft_weak_grad); with the weak gradient's amount alone
+    it still gives the right values, through the general kernel."""
+    oc, ic, k, m = 528, 1280 + 128, 128, 300
+    h = HostLayer(oc, ic, k, 3, 128, seed=77, dense=dense)
+    w = h.to_device()
+    x = synth.make_activations(m, ic, k, seed=5)
+    dy = synth.make_grad_output(m, oc, seed=6)
+    dyt, xw = torch.from_numpy(dy).cuda(), torch.from_numpy(np.ascontiguousarray(x[:, ic - k:])).cuda()
+    n = B.qeft_workspace_bytes(h.desc, B.QEFT_OP_BWD, m)
+    assert n >= oc * ic * 2
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dx_a = B.qeft_linear_bwd_dx(h.desc, w, dyt, ws=ws)
+    dw_a = B.qeft_weak_grad(h.desc, dyt, xw, ws=ws)
+    dx_b, dw_b = B.qeft_linear_bwd(h.desc, w, dyt, xw, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(dx_a, dx_b) and torch.equal(dw_a, dw_b)
+    dx_c, dw_c = B.qeft_linear_bwd(h.desc, w, dyt, xw)                       # the weak gradient's workspace only
+    torch.cuda.synchronize()
+    for dx, dw, what in ((dx_b, dw_b, "copy"), (dx_c, dw_c, "general")):
+        assert_close(dx.cpu().numpy(), qo.linear_bwd_dx(h.w64, dy), f"dX 3-bit one call ({what})")
+        assert_close(dw.cpu().numpy(), qo.weak_grad(dy, x[:, ic - k:]), f"dW 3-bit one call ({what})")
+
+
 @pytest.mark.parametrize("oc,ic,k,m", [
     (256, 4096 + 128, 128, 300),     # 2 tiles, 64 quantized stages: 8 splits of 8 stages, the weak block in the last
     (528, 2560 + 64, 64, 64),        # 3 tiles (one ragged), 40 stages: 5 splits
