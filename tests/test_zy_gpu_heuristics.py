@@ -7,7 +7,8 @@ choice and the alternative that the boundary lets a caller force (the passes as 
 without the workspace) with HIP events and require the choice to be at most 10 % slower than that alternative.
 No numerics here (the parity tests cover every path); a failure means a heuristic needs refitting, not a wrong
 result.  Timings on a shared machine wobble, so a miss is measured a second time, and only a miss of more than 25 %
-fails the test; one between 10 % and 25 % is reported as an expected-failure note with the figures.
+fails the test; one between 10 % and 25 % is reported as an expected-failure note with the figures.  The file is named
+to be collected after the parity tests: a run that stops at the first failure has then compared every result first.
 """
 import pytest
 import torch
