@@ -33,7 +33,7 @@ MFMA_F16_PEAK_TF = 2500.0   # MI355X dense fp16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script, scaled by the
 # same counters' reading for its 256 MiB device copy (profiles/bench_7b_hbm_traffic.md): averages over
 # the launches of the kernel in one step.  They are NOT measured in this run (counters need the profiler).
-TRAFFIC_DX_BYTES = (438.6e6 + 45.6e6 + 373.7e6 + 99.3e6) / 2      # gemm_dx_dw_kernel, read + written, mean of the two MLP shapes
+TRAFFIC_DX_BYTES = (439.7e6 + 45.6e6 + 374.0e6 + 99.3e6) / 2      # gemm_dx_dw_kernel, read + written, mean of the two MLP shapes
 TRAFFIC_GEMV_BYTES = (29.24e6 + 9.84e6 + 52.28e6 + 25.09e6) / 4    # gemv_w4_dot_kernel, mean of the four launches of a block
 TRAFFIC_SOURCE = "profiles/bench_7b_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script; not measured in this run)"
 # every stored byte of one 7B block with rows padded to 4 words and unpadded group parameters: the figure a
