@@ -207,8 +207,8 @@ int qeft_linear_bwd_dx(const qeft_desc_t* desc, const qeft_weight_t* w, const vo
  * not a permutation gives unspecified values, never an access outside X / dX).  Both calls
  * need qeft_workspace_bytes(desc, QEFT_OP_FWD_IRREGULAR / QEFT_OP_BWD_DX_IRREGULAR, M) bytes of
  * device workspace, 16-byte aligned, for the gathered activations / the un-scattered gradient
- * (the forward with M <= 4 gathers inside the matrix-vector kernel and uses none; perm must be
- * 16-byte aligned).
+ * (the forward of a 4-bit layer with M <= 4 gathers inside the matrix-vector kernel and does not touch it;
+ * perm must be 16-byte aligned).
  * For the weak block's gradient, call qeft_weak_grad on the weak activations gathered by the
  * caller (X[:, perm[Kq:]], compact [M][k]). */
 int qeft_linear_fwd_irregular(const qeft_desc_t* desc, const qeft_weight_t* w, const int32_t* perm,
